@@ -1,0 +1,285 @@
+"""Seeded synthetic inputs shaped like the paper's workloads (Section V: a 169,343-node citation graph
+with 1,166,243 edges and 128 features; a 2,449,029-node co-purchase graph with 61,859,140 edges and 100
+features; random and low-cut equal-sized partitions, Appendix "Partitioning Details").
+
+This module only *draws inputs*: graphs, node-to-partition maps, features, weights and upstream gradients.
+It holds none of the method's arithmetic (no masks, no compression, no layer math, no halo indexing), so
+both the CPU oracle's tests and the HIP path may be fed from it.
+
+Everything is a pure function of its integer seed (numpy Philox streams), independent of thread count.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+
+import numpy as np
+import scipy.sparse as sp
+
+# Seeds of the benchmark configurations.
+SEED_GRAPH = 17611
+SEED_PART = 17612
+SEED_FEAT = 17613
+SEED_WEIGHT = 17614
+SEED_GRAD = 17615
+MASK_KEY = 0x240617611
+
+
+def _rng(seed: int, stream: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[seed, stream]))
+
+
+@dataclasses.dataclass
+class Graph:
+    """Global shift operator S as CSR (sorted columns), fp32 values, int64 rowptr, int32 colidx."""
+    n: int
+    rowptr: np.ndarray
+    colidx: np.ndarray
+    vals: np.ndarray
+    n_undirected: int          # undirected edges without self-loops
+    self_loops: bool
+
+    @property
+    def nnz(self) -> int:
+        return int(self.colidx.shape[0])
+
+
+# --------------------------------------------------------------------------------------------------
+# undirected edge lists
+# --------------------------------------------------------------------------------------------------
+
+def sbm_edges(block_sizes, p_in: float, p_out: float, seed: int) -> tuple[int, np.ndarray, np.ndarray]:
+    """Stochastic block model: each unordered pair is an edge with prob. p_in (same block) or p_out."""
+    n = int(sum(block_sizes))
+    block = np.repeat(np.arange(len(block_sizes)), block_sizes)
+    rng = _rng(seed)
+    us, vs = [], []
+    for i in range(n - 1):  # row-at-a-time keeps memory O(n); n is a few thousand here
+        same = block[i + 1:] == block[i]
+        p = np.where(same, p_in, p_out)
+        hit = np.nonzero(rng.random(n - 1 - i) < p)[0]
+        us.append(np.full(hit.shape, i, dtype=np.int64))
+        vs.append(hit.astype(np.int64) + i + 1)
+    return n, np.concatenate(us), np.concatenate(vs)
+
+
+def chung_lu_edges(n: int, n_edges: int, exponent: float, seed: int) -> tuple[np.ndarray, np.ndarray]:
+    """Chung-Lu style power-law graph with exactly `n_edges` distinct undirected edges, no loops.
+
+    Expected-degree weights w_i ~ (i+1)^(-1/(exponent-1)), scaled to sum 2*n_edges and capped at
+    sqrt(2*n_edges) (so that w_u*w_v/sum(w) <= 1). Endpoints are drawn independently in proportion to w,
+    loops and repeats are dropped, and the surplus is thinned uniformly to the exact edge count. Node
+    ids are shuffled so that id order carries no degree information.
+    """
+    rng = _rng(seed)
+    alpha = 1.0 / (exponent - 1.0)
+    w = (np.arange(n, dtype=np.float64) + 1.0) ** (-alpha)
+    cap = math.sqrt(2.0 * n_edges)
+    for _ in range(8):
+        w *= (2.0 * n_edges) / w.sum()
+        np.minimum(w, cap, out=w)
+    cdf = np.cumsum(w)
+    cdf /= cdf[-1]
+    relabel = rng.permutation(n).astype(np.int64)
+
+    have = np.empty(0, dtype=np.int64)
+    want = n_edges
+    over = 1.12
+    while have.shape[0] < want:
+        m = int((want - have.shape[0]) * over) + 1024
+        u = np.searchsorted(cdf, rng.random(m), side="right")
+        v = np.searchsorted(cdf, rng.random(m), side="right")
+        np.minimum(u, n - 1, out=u)
+        np.minimum(v, n - 1, out=v)
+        keep = u != v
+        u, v = u[keep], v[keep]
+        lo = np.minimum(u, v).astype(np.int64)
+        hi = np.maximum(u, v).astype(np.int64)
+        have = np.union1d(have, lo * n + hi)  # sorted unique keys
+        over *= 1.5
+    if have.shape[0] > want:
+        drop = rng.choice(have.shape[0], size=have.shape[0] - want, replace=False)
+        mask = np.ones(have.shape[0], dtype=bool)
+        mask[drop] = False
+        have = have[mask]
+    u = relabel[have // n]
+    v = relabel[have % n]
+    return u, v
+
+
+# --------------------------------------------------------------------------------------------------
+# shift operators
+# --------------------------------------------------------------------------------------------------
+
+def _symmetric_csr(n: int, u: np.ndarray, v: np.ndarray, self_loops: bool) -> sp.csr_matrix:
+    rows = [u, v]
+    cols = [v, u]
+    if self_loops:
+        d = np.arange(n, dtype=np.int64)
+        rows.append(d)
+        cols.append(d)
+    r = np.concatenate(rows)
+    c = np.concatenate(cols)
+    a = sp.coo_matrix((np.ones(r.shape[0], dtype=np.float32), (r, c)), shape=(n, n)).tocsr()
+    a.sum_duplicates()
+    a.sort_indices()
+    return a
+
+
+def gcn_operator(n: int, u: np.ndarray, v: np.ndarray) -> Graph:
+    """S = D~^{-1/2} (A + I) D~^{-1/2}, degrees of the whole graph (self-loop included)."""
+    a = _symmetric_csr(n, u, v, self_loops=True)
+    deg = np.diff(a.indptr).astype(np.float64)
+    dinv = 1.0 / np.sqrt(deg)
+    row_of = np.repeat(np.arange(n, dtype=np.int64), np.diff(a.indptr))
+    vals = (dinv[row_of] * dinv[a.indices]).astype(np.float32)
+    return Graph(n, a.indptr.astype(np.int64), a.indices.astype(np.int32), vals, int(u.shape[0]), True)
+
+
+def sage_mean_operator(n: int, u: np.ndarray, v: np.ndarray) -> Graph:
+    """S = D^{-1} A (mean over neighbours, no self-loop; isolated nodes have an empty row)."""
+    a = _symmetric_csr(n, u, v, self_loops=False)
+    deg = np.diff(a.indptr).astype(np.float64)
+    row_of = np.repeat(np.arange(n, dtype=np.int64), np.diff(a.indptr))
+    vals = (1.0 / deg[row_of]).astype(np.float32)
+    return Graph(n, a.indptr.astype(np.int64), a.indices.astype(np.int32), vals, int(u.shape[0]), False)
+
+
+# --------------------------------------------------------------------------------------------------
+# node -> partition maps (equal-sized parts, sizes differ by at most one)
+# --------------------------------------------------------------------------------------------------
+
+def _equal_chunks(order: np.ndarray, n_parts: int) -> np.ndarray:
+    n = order.shape[0]
+    part = np.empty(n, dtype=np.int32)
+    bounds = (np.arange(n_parts + 1, dtype=np.int64) * n) // n_parts
+    for q in range(n_parts):
+        part[order[bounds[q]:bounds[q + 1]]] = q
+    return part
+
+
+def random_partition(n: int, n_parts: int, seed: int) -> np.ndarray:
+    return _equal_chunks(_rng(seed).permutation(n), n_parts)
+
+
+def block_partition(block_sizes) -> np.ndarray:
+    return np.repeat(np.arange(len(block_sizes), dtype=np.int32), block_sizes)
+
+
+def bfs_contiguous_partition(g: Graph, n_parts: int) -> np.ndarray:
+    """Breadth-first visiting order (restarted at the lowest unvisited id), cut into equal chunks:
+    a cheap low-cut stand-in for a min-cut partitioner."""
+    n = g.n
+    seen = np.zeros(n, dtype=bool)
+    order = np.empty(n, dtype=np.int64)
+    filled = 0
+    next_root = 0
+    while filled < n:
+        while seen[next_root]:
+            next_root += 1
+        frontier = np.array([next_root], dtype=np.int64)
+        seen[next_root] = True
+        while frontier.shape[0]:
+            order[filled:filled + frontier.shape[0]] = frontier
+            filled += frontier.shape[0]
+            starts = g.rowptr[frontier]
+            lens = g.rowptr[frontier + 1] - starts
+            total = int(lens.sum())
+            if total == 0:
+                break
+            offs = np.repeat(starts - np.concatenate(([0], np.cumsum(lens)[:-1])), lens) + np.arange(total)
+            nb = g.colidx[offs].astype(np.int64)
+            nb = nb[~seen[nb]]
+            # first occurrence order, deterministic
+            _, first = np.unique(nb, return_index=True)
+            frontier = nb[np.sort(first)]
+            seen[frontier] = True
+    return _equal_chunks(order, n_parts)
+
+
+# --------------------------------------------------------------------------------------------------
+# dense inputs
+# --------------------------------------------------------------------------------------------------
+
+def features(n: int, width: int, seed: int) -> np.ndarray:
+    return _rng(seed).standard_normal((n, width), dtype=np.float32)
+
+
+def glorot(fan_in: int, fan_out: int, seed: int, stream: int = 0) -> np.ndarray:
+    lim = math.sqrt(6.0 / (fan_in + fan_out))
+    return ((_rng(seed, stream).random((fan_in, fan_out), dtype=np.float32) * 2.0 - 1.0) * lim).astype(np.float32)
+
+
+def upstream_grad(n: int, width: int, seed: int) -> np.ndarray:
+    return (_rng(seed).standard_normal((n, width), dtype=np.float32) / np.float32(n)).astype(np.float32)
+
+
+# --------------------------------------------------------------------------------------------------
+# the benchmark configurations
+# --------------------------------------------------------------------------------------------------
+
+@dataclasses.dataclass
+class Workload:
+    name: str
+    graph: Graph
+    part: np.ndarray
+    n_parts: int
+    conv: str                  # "gcn" | "sage"
+    widths: tuple              # F_0 .. F_L
+    ratios: tuple              # (num, den) pairs the configuration is run at
+    dtype: str = "f32"
+
+
+def _arxiv_like_edges():
+    return chung_lu_edges(169_343, 1_166_243, 2.5, SEED_GRAPH)
+
+
+def _products_like_edges():
+    return chung_lu_edges(2_449_029, 61_859_140, 2.3, SEED_GRAPH)
+
+
+def linear_schedule_config3(t: int) -> tuple[int, int]:
+    """Ratio of the 16 -> 1 linear schedule over 100 steps as an exact rational (num, den)."""
+    return 1584 - 15 * t, 99
+
+
+def make_workload(name: str) -> Workload:
+    if name == "tiny":
+        sizes = (1000, 1000)
+        n, u, v = sbm_edges(sizes, 0.01, 0.0005, SEED_GRAPH)
+        g = gcn_operator(n, u, v)
+        return Workload(name, g, block_partition(sizes), 2, "gcn", (16, 32, 8), ((4, 1),))
+    if name == "medium":
+        u, v = _arxiv_like_edges()
+        g = gcn_operator(169_343, u, v)
+        return Workload(name, g, random_partition(g.n, 4, SEED_PART), 4, "gcn", (128, 256, 256, 40),
+                        ((1, 1), (2, 1), (4, 1), (8, 1), (16, 1)))
+    if name == "medium_bfs16":
+        u, v = _arxiv_like_edges()
+        g = gcn_operator(169_343, u, v)
+        return Workload(name, g, bfs_contiguous_partition(g, 16), 16, "gcn", (128, 256, 256, 40),
+                        tuple(linear_schedule_config3(t) for t in range(100)))
+    if name == "large_sage":
+        u, v = _products_like_edges()
+        g = sage_mean_operator(2_449_029, u, v)
+        return Workload(name, g, random_partition(g.n, 8, SEED_PART), 8, "sage", (100, 256, 256, 47), ((8, 1),))
+    if name == "large_gcn_bf16":
+        u, v = _products_like_edges()
+        g = gcn_operator(2_449_029, u, v)
+        return Workload(name, g, random_partition(g.n, 32, SEED_PART), 32, "gcn", (100, 512, 512, 47),
+                        ((1, 1), (4, 1), (32, 1)), dtype="bf16")
+    raise ValueError(f"unknown workload {name!r}")
+
+
+def small_random_graph(n: int, avg_deg: float, conv: str, seed: int) -> Graph:
+    """Erdos-Renyi-like helper for unit tests (a few hundred nodes)."""
+    rng = _rng(seed)
+    m = int(n * avg_deg / 2)
+    u = rng.integers(0, n, size=m * 2)
+    v = rng.integers(0, n, size=m * 2)
+    keep = u != v
+    lo = np.minimum(u[keep], v[keep]).astype(np.int64)
+    hi = np.maximum(u[keep], v[keep]).astype(np.int64)
+    key = np.unique(lo * n + hi)[:m]
+    u, v = key // n, key % n
+    return gcn_operator(n, u, v) if conv == "gcn" else sage_mean_operator(n, u, v)

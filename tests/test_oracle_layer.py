@@ -1,0 +1,254 @@
+"""Pins of the oracle's layer forward / backward against brute force and calculus.
+
+  * ratio 1 (lossless, Definition 1 with delta = 0): the partitioned layer equals eq. (2) on the
+    unpartitioned graph with a dense adjacency, for any partition count;
+  * any ratio: equals the partition-free global-mask formula (tests/dense_reference.py);
+  * backward: central finite differences of <X_L, R> in fp64; adjoint identity of the aggregation;
+  * no cross edges => the result does not depend on the ratio;
+  * exchanged element counts = (node, destination) pairs x k.
+"""
+import numpy as np
+import pytest
+
+import dense_reference as dref
+from oracle import layer as olayer
+from oracle import mask as omask
+from oracle import partition as opart
+from paper_2406_17611_amd import synth
+
+KEY = 0x240617611
+
+
+def _setup(conv, n, n_parts, widths, seed, part=None):
+    g = synth.small_random_graph(n, 5.0, conv, seed=seed)
+    part = synth.random_partition(g.n, n_parts, seed + 1) if part is None else part
+    parts = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, part, n_parts)
+    rng = np.random.default_rng(seed + 2)
+    x = rng.standard_normal((g.n, widths[0]))
+    weights = []
+    for l in range(len(widths) - 1):
+        h1 = rng.standard_normal((widths[l], widths[l + 1])) * 0.4
+        h0 = rng.standard_normal((widths[l], widths[l + 1])) * 0.4 if conv == "sage" else None
+        weights.append((h1, h0))
+    r = rng.standard_normal((g.n, widths[-1]))
+    return g, part, parts, x, weights, r
+
+
+def _gather(parts, per_part, n):
+    out = np.empty((n, per_part[0].shape[1]))
+    for p in parts:
+        out[p.local_gid] = per_part[p.q]
+    return out
+
+
+def _run_oracle(g, parts, x, weights, r, keep, step=0):
+    acts = [olayer.RELU] * (len(weights) - 1) + [olayer.IDENTITY]
+    res = olayer.network_step(parts, [x[p.local_gid] for p in parts], weights, acts, keep, KEY, step,
+                              [r[p.local_gid] for p in parts])
+    return res, acts
+
+
+def _run_dense(g, part, x, weights, r, keep, step=0):
+    s = dref.dense_operator(g)
+    s_in, s_x = dref.split_operator(s, part)
+    n_layers = len(weights)
+    xs, ms, masks = [x], [], []
+    for l, (h1, h0) in enumerate(weights):
+        mask = omask.keep_mask(np.arange(g.n), xs[l].shape[1], keep[l], KEY, step, l)
+        xo, m = dref.forward(s_in, s_x, mask, xs[l], h1, h0, relu=l < n_layers - 1)
+        xs.append(xo), ms.append(m), masks.append(mask)
+    dh = [None] * n_layers
+    dx = r
+    dxs = {n_layers: r}
+    for l in range(n_layers - 1, -1, -1):
+        h1, h0 = weights[l]
+        dh1, dh0, dxn = dref.backward(s_in, s_x, masks[l], xs[l], ms[l], xs[l + 1], dx, h1, h0,
+                                      relu=l < n_layers - 1)
+        dh[l] = (dh1, dh0)
+        dx = dxn
+        dxs[l] = dxn
+    return xs, ms, dh, dxs
+
+
+def _close(a, b, tol=1e-11):
+    return np.abs(a - b).max() <= tol * max(1.0, np.abs(b).max())
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("n_parts", [1, 2, 3, 7])
+def test_ratio_one_equals_unpartitioned_dense_layer(conv, n_parts):
+    widths = (12, 20, 6)
+    g, part, parts, x, weights, r = _setup(conv, 150, n_parts, widths, seed=21)
+    res, _ = _run_oracle(g, parts, x, weights, r, keep=list(widths[:-1]))
+    # textbook unpartitioned network, written out here: rho(S X H1 + X H0)
+    s = dref.dense_operator(g)
+    h = x
+    for l, (h1, h0) in enumerate(weights):
+        zpre = s @ h @ h1 + (h @ h0 if h0 is not None else 0.0)
+        h = np.maximum(zpre, 0.0) if l < len(weights) - 1 else zpre
+    assert _close(_gather(parts, res["x"][-1], g.n), h)
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+def test_ratio_one_gradients_do_not_depend_on_partition_count(conv):
+    widths = (10, 16, 16, 5)
+    outs = []
+    for n_parts in (1, 2, 5):
+        g, part, parts, x, weights, r = _setup(conv, 120, n_parts, widths, seed=33)
+        res, _ = _run_oracle(g, parts, x, weights, r, keep=list(widths[:-1]))
+        outs.append((res, parts, g))
+    ref, ref_parts, g = outs[0]
+    for res, parts, _ in outs[1:]:
+        for l in range(3):
+            assert _close(res["dh"][l][0], ref["dh"][l][0])
+            if conv == "sage":
+                assert _close(res["dh"][l][1], ref["dh"][l][1])
+        for l in (1, 2):
+            assert _close(_gather(parts, res["dx"][l], g.n), _gather(ref_parts, ref["dx"][l], g.n))
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("n_parts,ratio", [(2, 4), (3, 2), (4, 8), (7, 3)])
+def test_any_ratio_equals_global_mask_formula(conv, n_parts, ratio):
+    widths = (16, 24, 24, 7)
+    g, part, parts, x, weights, r = _setup(conv, 140, n_parts, widths, seed=40 + n_parts)
+    keep = [omask.keep_count(w, ratio, 1) for w in widths[:-1]]
+    res, _ = _run_oracle(g, parts, x, weights, r, keep, step=5)
+    xs, ms, dh, dxs = _run_dense(g, part, x, weights, r, keep, step=5)
+    for l in range(3):
+        assert _close(_gather(parts, res["x"][l + 1], g.n), xs[l + 1])
+        assert _close(_gather(parts, res["m"][l], g.n), ms[l])
+        assert _close(res["dh"][l][0], dh[l][0])
+        if conv == "sage":
+            assert _close(res["dh"][l][1], dh[l][1])
+    for l in (1, 2):
+        assert _close(_gather(parts, res["dx"][l], g.n), dxs[l])
+    # compression really changed something
+    full, _ = _run_oracle(g, parts, x, weights, r, keep=list(widths[:-1]), step=5)
+    assert not _close(_gather(parts, res["x"][-1], g.n), _gather(parts, full["x"][-1], g.n), 1e-3)
+
+
+def test_exchanged_element_counts():
+    widths = (16, 24, 24, 7)
+    g, part, parts, x, weights, r = _setup("gcn", 140, 4, widths, seed=50)
+    rows_g = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    cross = part[rows_g] != part[g.colidx]
+    pairs = len({(int(c), int(part[i])) for i, c in zip(rows_g[cross], g.colidx[cross])})
+    for ratio in (1, 2, 8):
+        keep = [omask.keep_count(w, ratio, 1) for w in widths[:-1]]
+        res, _ = _run_oracle(g, parts, x, weights, r, keep)
+        assert res["fwd_elems"] == [pairs * k for k in keep]
+        assert res["bwd_elems"] == [0] + [pairs * k for k in keep[1:]]     # no exchange below layer 1
+        for l, k in enumerate(keep):
+            assert res["z"][l].shape == (sum(p.n_boundary for p in parts), k)
+            if widths[l] % ratio == 0:
+                assert res["fwd_elems"][l] * ratio == pairs * widths[l]       # Definition 1: n / r
+
+
+def test_no_cross_edges_means_ratio_is_irrelevant():
+    # two disconnected blocks, one per partition
+    sizes = (60, 60)
+    n, u, v = synth.sbm_edges(sizes, 0.08, 0.0, seed=3)
+    g = synth.gcn_operator(n, u, v)
+    part = synth.block_partition(sizes)
+    parts = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, part, 2)
+    assert all(p.n_halo == 0 for p in parts)
+    rng = np.random.default_rng(0)
+    widths = (8, 12, 4)
+    x = rng.standard_normal((n, 8))
+    weights = [(rng.standard_normal((8, 12)), None), (rng.standard_normal((12, 4)), None)]
+    r = rng.standard_normal((n, 4))
+    a, _ = _run_oracle(g, parts, x, weights, r, keep=[8, 12])
+    b, _ = _run_oracle(g, parts, x, weights, r, keep=[1, 2])
+    assert _close(_gather(parts, a["x"][-1], n), _gather(parts, b["x"][-1], n), 0.0)
+    assert _close(a["dh"][0][0], b["dh"][0][0], 0.0)
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+def test_backward_matches_finite_differences(conv):
+    widths = (6, 9, 4)
+    g, part, parts, x, weights, r = _setup(conv, 40, 3, widths, seed=60)
+    keep = [3, 4]
+    # shift inputs away from ReLU kinks: a smooth-enough point for central differences
+    res, acts = _run_oracle(g, parts, x, weights, r, keep, step=2)
+
+    def objective(xv, wts):
+        out, _ = _run_oracle(g, parts, xv, wts, r, keep, step=2)
+        return sum((out["x"][-1][p.q] * r[p.local_gid]).sum() for p in parts)
+
+    eps = 1e-6
+    rng = np.random.default_rng(7)
+    # weights of both layers
+    for l in range(2):
+        for tap in range(2 if conv == "sage" else 1):
+            for _ in range(6):
+                i, j = rng.integers(0, widths[l]), rng.integers(0, widths[l + 1])
+                wp = [[w.copy() if w is not None else None for w in pair] for pair in weights]
+                wm = [[w.copy() if w is not None else None for w in pair] for pair in weights]
+                wp[l][tap][i, j] += eps
+                wm[l][tap][i, j] -= eps
+                fd = (objective(x, [tuple(a) for a in wp]) - objective(x, [tuple(a) for a in wm])) / (2 * eps)
+                an = res["dh"][l][tap][i, j]
+                assert abs(fd - an) <= 1e-6 * max(1.0, abs(an))
+    # input of layer 2 (= output of layer 1): perturb through a one-layer network
+    x1 = _gather(parts, res["x"][1], g.n)
+    # the second layer alone, with the mask of layer index 1
+    def second_layer(xv):
+        tot = 0.0
+        z_all = np.vstack([olayer.compress(xv[p.local_gid], p.boundary_rows,
+                                           omask.kept_columns(p.local_gid[p.boundary_rows], 9, 4, KEY, 2, 1))
+                           for p in parts])
+        for p in parts:
+            cols = omask.kept_columns(p.halo_gid, 9, 4, KEY, 2, 1)
+            xo, _ = olayer.layer_forward(p, xv[p.local_gid], z_all, cols, weights[1][0], weights[1][1],
+                                         olayer.IDENTITY)
+            tot += (xo * r[p.local_gid]).sum()
+        return tot
+    dx1 = _gather(parts, res["dx"][1], g.n)
+    for _ in range(12):
+        i, j = rng.integers(0, g.n), rng.integers(0, 9)
+        xp, xm = x1.copy(), x1.copy()
+        xp[i, j] += eps
+        xm[i, j] -= eps
+        fd = (second_layer(xp) - second_layer(xm)) / (2 * eps)
+        assert abs(fd - dx1[i, j]) <= 1e-6 * max(1.0, abs(dx1[i, j]))
+
+
+def test_aggregation_adjoint_identity():
+    g, part, parts, x, weights, r = _setup("gcn", 100, 3, (5, 5), seed=70)
+    rng = np.random.default_rng(1)
+    for p in parts:
+        xc = rng.standard_normal((p.n_local + p.n_halo, 5))
+        y = rng.standard_normal((p.n_local, 5))
+        s = olayer._block(p)
+        lhs = ((s @ xc) * y).sum()
+        # transpose arrays built independently by the partition oracle
+        st = np.zeros((p.n_local + p.n_halo, p.n_local))
+        for c in range(p.n_local + p.n_halo):
+            for e in range(p.t_rowptr[c], p.t_rowptr[c + 1]):
+                st[c, p.t_colidx[e]] += p.t_vals[e]
+        rhs = (xc * (st @ y)).sum()
+        assert abs(lhs - rhs) <= 1e-12 * max(1.0, abs(lhs))
+
+
+def test_tiny_config_shapes_and_single_layer_against_dense():
+    """The 2,000-node block-model configuration, first layer, ratio 4 (k = 4 of 16)."""
+    w = synth.make_workload("tiny")
+    g = w.graph
+    parts = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, w.part, w.n_parts)
+    x = synth.features(g.n, 16, synth.SEED_FEAT).astype(np.float64)
+    h1 = synth.glorot(16, 32, synth.SEED_WEIGHT, 0).astype(np.float64)
+    k = omask.keep_count(16, 4, 1)
+    z_all = np.vstack([olayer.compress(x[p.local_gid], p.boundary_rows,
+                                       omask.kept_columns(p.local_gid[p.boundary_rows], 16, k, KEY, 0, 0))
+                       for p in parts])
+    s = np.zeros((g.n, g.n))
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    s[rows, g.colidx] = g.vals
+    s_in, s_x = dref.split_operator(s, w.part)
+    mask = omask.keep_mask(np.arange(g.n), 16, k, KEY, 0, 0)
+    want, _ = dref.forward(s_in, s_x, mask, x, h1, None, relu=True)
+    for p in parts:
+        cols = omask.kept_columns(p.halo_gid, 16, k, KEY, 0, 0)
+        xo, _ = olayer.layer_forward(p, x[p.local_gid], z_all, cols, h1, None, olayer.RELU)
+        assert _close(xo, want[p.local_gid])

@@ -1,0 +1,85 @@
+"""Planted mistakes in the oracle (on the CPU) must trip the pins: a dropped term, a wrong sign or index,
+a transposed operand, a rescaled decoder, a backward mask that differs from the forward one."""
+import numpy as np
+import pytest
+
+import test_oracle_layer as tl
+import test_oracle_mask as tm
+from oracle import layer as olayer
+from oracle import mask as omask
+
+
+def _expect_failure(fn, *args):
+    with pytest.raises(AssertionError):
+        fn(*args)
+
+
+def test_rescaled_decoder_is_caught(monkeypatch):
+    orig = olayer.decompress
+    monkeypatch.setattr(olayer, "decompress", lambda z, cols, width: orig(z, cols, width) * (width / z.shape[1]))
+    _expect_failure(tm.test_decompress_of_compress_is_masking_without_rescale)
+    _expect_failure(tl.test_any_ratio_equals_global_mask_formula, "gcn", 3, 2)
+
+
+def test_dropped_self_tap_in_backward_is_caught(monkeypatch):
+    orig = olayer.layer_backward
+
+    def broken(p, dx_out, x_out, x_local, m, halo_cols, h1, h0, act, need=True):
+        dh1, dh0, dxl, dzh = orig(p, dx_out, x_out, x_local, m, halo_cols, h1, h0, act, need)
+        if dxl is not None and h0 is not None:
+            dz = dx_out * (x_out > 0) if act == olayer.RELU else dx_out
+            dxl = dxl - dz @ h0.T
+        return dh1, dh0, dxl, dzh
+    monkeypatch.setattr(olayer, "layer_backward", broken)
+    _expect_failure(tl.test_any_ratio_equals_global_mask_formula, "sage", 3, 2)
+    _expect_failure(tl.test_backward_matches_finite_differences, "sage")
+
+
+def test_transposed_weight_in_backward_is_caught(monkeypatch):
+    orig = olayer.layer_backward
+
+    def broken(p, dx_out, x_out, x_local, m, halo_cols, h1, h0, act, need=True):
+        dh1, dh0, dxl, dzh = orig(p, dx_out, x_out, x_local, m, halo_cols, h1, h0, act, need)
+        return dh1.T.copy().reshape(dh1.shape), dh0, dxl, dzh
+    monkeypatch.setattr(olayer, "layer_backward", broken)
+    _expect_failure(tl.test_backward_matches_finite_differences, "gcn")
+
+
+def test_backward_mask_from_another_step_is_caught(monkeypatch):
+    orig = omask.kept_columns
+    calls = {"n": 0}
+
+    def broken(gids, width, k, key, step, layer):
+        calls["n"] += 1
+        return orig(gids, width, k, key, step + (1 if calls["n"] > 24 else 0), layer)
+    monkeypatch.setattr(omask, "kept_columns", broken)
+    _expect_failure(tl.test_any_ratio_equals_global_mask_formula, "gcn", 4, 8)
+
+
+def test_off_by_one_position_is_caught(monkeypatch):
+    orig = omask.affine_params
+
+    def broken(gids, width, s0, s1):
+        a, b = orig(gids, width, s0, s1)
+        return np.full_like(a, 2), b                          # 2 is not a unit of even widths
+    monkeypatch.setattr(omask, "affine_params", broken)
+    _expect_failure(tm.test_kept_columns_are_k_distinct_in_range, 16)
+
+
+def test_relu_mask_ignored_is_caught(monkeypatch):
+    orig = olayer.layer_backward
+
+    def broken(p, dx_out, x_out, x_local, m, halo_cols, h1, h0, act, need=True):
+        return orig(p, dx_out, x_out, x_local, m, halo_cols, h1, h0, olayer.IDENTITY, need)
+    monkeypatch.setattr(olayer, "layer_backward", broken)
+    _expect_failure(tl.test_backward_matches_finite_differences, "gcn")
+    _expect_failure(tl.test_any_ratio_equals_global_mask_formula, "gcn", 2, 4)
+
+
+def test_halo_read_from_wrong_owner_row_is_caught(monkeypatch):
+    orig = olayer.layer_forward
+
+    def broken(p, x_local, z_all, halo_cols, h1, h0, act):
+        return orig(p, x_local, np.roll(z_all, 1, axis=0), halo_cols, h1, h0, act)
+    monkeypatch.setattr(olayer, "layer_forward", broken)
+    _expect_failure(tl.test_ratio_one_equals_unpartitioned_dense_layer, "gcn", 3)

@@ -1,0 +1,128 @@
+"""Pins of the oracle's partition / halo / boundary indexing (Section III; Table 1)."""
+import numpy as np
+import pytest
+
+from oracle import partition as opart
+from paper_2406_17611_amd import synth
+
+
+def _check_structure(g, part, n_parts, parts):
+    n = g.n
+    seen = np.zeros(n, dtype=int)
+    for p in parts:
+        seen[p.local_gid] += 1
+        assert (np.diff(p.local_gid) > 0).all()
+        assert (part[p.local_gid] == p.q).all()
+    assert (seen == 1).all()                               # every node owned exactly once
+
+    total_b = 0
+    for p in parts:
+        nl, nh = p.n_local, p.n_halo
+        assert p.rowptr[0] == 0 and p.rowptr[-1] == p.nnz and len(p.rowptr) == nl + 1
+        assert p.colidx.min() >= 0 and p.colidx.max() < nl + nh
+        # halo: remote, distinct, ordered by (owner, gid), owner_ptr consistent
+        owners = part[p.halo_gid]
+        assert (owners != p.q).all()
+        keys = owners.astype(np.int64) * n + p.halo_gid
+        assert (np.diff(keys) > 0).all()
+        for o in range(n_parts):
+            seg = owners[p.halo_owner_ptr[o]:p.halo_owner_ptr[o + 1]]
+            assert (seg == o).all()
+        assert p.halo_owner_ptr[0] == 0 and p.halo_owner_ptr[-1] == nh
+        # row block reproduces the global rows entry by entry
+        cat_gid = np.concatenate([p.local_gid, p.halo_gid]).astype(np.int64)
+        for i in np.random.default_rng(p.q).integers(0, nl, size=min(nl, 200)):
+            v = p.local_gid[i]
+            glob = dict(zip(g.colidx[g.rowptr[v]:g.rowptr[v + 1]].tolist(),
+                            g.vals[g.rowptr[v]:g.rowptr[v + 1]].tolist()))
+            cols = p.colidx[p.rowptr[i]:p.rowptr[i + 1]]
+            assert (np.diff(cols) > 0).all()
+            mine = dict(zip(cat_gid[cols].tolist(), p.vals[p.rowptr[i]:p.rowptr[i + 1]].tolist()))
+            assert mine == glob
+        # every halo slot is referenced
+        used = np.zeros(nl + nh, dtype=bool)
+        used[p.colidx] = True
+        assert used[nl:].all()
+        # transpose holds the same triplets
+        rows = np.repeat(np.arange(nl), np.diff(p.rowptr))
+        trows = np.repeat(np.arange(nl + nh), np.diff(p.t_rowptr))
+        a = sorted(zip(rows.tolist(), p.colidx.tolist(), p.vals.tolist()))
+        b = sorted(zip(p.t_colidx.tolist(), trows.tolist(), p.t_vals.tolist()))
+        assert a == b
+        for c in range(0, nl + nh, max(1, (nl + nh) // 50)):
+            assert (np.diff(p.t_colidx[p.t_rowptr[c]:p.t_rowptr[c + 1]]) > 0).all()
+        # boundary rows: exactly the local nodes some other partition's rows reference
+        assert (np.diff(p.boundary_rows) > 0).all()
+        assert p.z_row_offset == total_b
+        total_b += p.n_boundary
+    # set-based recount of boundary nodes and of (node, destination) pairs
+    rows_g = np.repeat(np.arange(n), np.diff(g.rowptr))
+    cross = part[rows_g] != part[g.colidx]
+    pairs = {(int(c), int(part[r])) for r, c in zip(rows_g[cross], g.colidx[cross])}
+    assert opart.exchanged_rows(parts) == len(pairs)
+    needed = {c for c, _ in pairs}
+    for p in parts:
+        assert set(p.local_gid[p.boundary_rows].tolist()) == {v for v in needed if part[v] == p.q}
+    # halo_src_row / halo_zrow resolve to the same node on the owner
+    bg_all = np.concatenate([p.local_gid[p.boundary_rows] for p in parts])
+    for p in parts:
+        assert np.array_equal(bg_all[p.halo_zrow], p.halo_gid)
+        for o in range(n_parts):
+            s0, s1 = p.halo_owner_ptr[o], p.halo_owner_ptr[o + 1]
+            own = parts[o]
+            assert np.array_equal(own.local_gid[own.boundary_rows[p.halo_src_row[s0:s1]]], p.halo_gid[s0:s1])
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("n_parts", [1, 2, 3, 7])
+def test_partition_structures_on_small_graphs(conv, n_parts):
+    g = synth.small_random_graph(300, 6.0, conv, seed=5)
+    part = synth.random_partition(g.n, n_parts, seed=6)
+    parts = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, part, n_parts)
+    _check_structure(g, part, n_parts, parts)
+    if n_parts == 1:
+        assert parts[0].n_halo == 0 and parts[0].n_boundary == 0
+
+
+def test_tiny_workload_partition():
+    w = synth.make_workload("tiny")
+    parts = opart.build_partitions(w.graph.n, w.graph.rowptr, w.graph.colidx, w.graph.vals, w.part, w.n_parts)
+    _check_structure(w.graph, w.part, w.n_parts, parts)
+    assert [p.n_local for p in parts] == [1000, 1000]
+
+
+def test_scatter_back_to_global_order():
+    g = synth.small_random_graph(500, 5.0, "gcn", seed=8)
+    part = synth.random_partition(g.n, 4, seed=9)
+    parts = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, part, 4)
+    x = np.random.default_rng(0).standard_normal((g.n, 3))
+    back = np.empty_like(x)
+    for p in parts:
+        back[p.local_gid] = x[p.local_gid]
+    assert np.array_equal(back, x)
+
+
+def test_random_partition_self_edge_share_follows_table_1():
+    """Table 1 counts directed entries of the symmetrised graph with self-loops (the co-purchase graph's
+    rows sum to 2*61,859,140 + 2,449,029). For equal random parts the expected share of entries inside
+    a partition is (2E/P + n) / (2E + n), which reproduces the printed "Self / Random" percentages; the
+    synthetic stand-in must follow the same law."""
+    e_big, n_big = 61_859_140, 2_449_029
+    assert 64_302_907 + 61_864_402 == 2 * e_big + n_big                      # Table 1, P=2 row sums
+    for n_parts, printed in ((2, 50.97), (4, 26.46), (8, 14.2), (16, 8.07)):
+        law = 100.0 * (2 * e_big / n_parts + n_big) / (2 * e_big + n_big)
+        assert abs(law - printed) < 0.02
+
+    e, n = 1_166_243, 169_343
+    u, v = synth.chung_lu_edges(n, e, 2.5, synth.SEED_GRAPH)
+    g = synth.gcn_operator(n, u, v)
+    assert g.nnz == 2 * e + n and g.n_undirected == e
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    for n_parts, printed in ((2, 53.38), (4, 30.16), (8, 18.48), (16, 12.68)):
+        part = synth.random_partition(g.n, n_parts, synth.SEED_PART)
+        sizes = np.bincount(part)
+        assert sizes.max() - sizes.min() <= 1                 # equal-sized parts (Appendix B)
+        share = 100.0 * (part[rows] == part[g.colidx]).mean()
+        law = 100.0 * (2 * e / n_parts + n) / (2 * e + n)
+        assert abs(share - law) < 0.35
+        assert abs(law - printed) < 0.3                       # printed values are of the real dataset

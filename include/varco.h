@@ -1,0 +1,193 @@
+/*
+ * varco.h - C ABI of the MI355X (gfx950) library for the hot path of VARCO: one partition's step of a
+ * partitioned GNN layer, forward and backward, with compressed exchange of boundary activations.
+ *
+ * Paper passages the calls follow
+ *   eq. (1)-(2), Section II      X_l = rho( sum_k S^k X_{l-1} H_{l,k} ): aggregation, transform, nonlinearity
+ *   Section III, Algorithm 1     each worker owns a node subset; per layer the owners compress the
+ *                                activations of their boundary nodes, consumers decompress them and run
+ *                                the forward pass on uncompressed local + compressed remote rows; errors
+ *                                flow back through the same compression; weight gradients are summed
+ *   Definition 1, Appendix A     compression keeps n/r elements chosen at random with a key shared
+ *                                beforehand; the decoder writes them in place and zeros the rest
+ *   Section IV, Appendix A       the ratio is set per training step by a decreasing scheduler
+ *
+ * Conventions
+ *   - Every function returns a status code (VARCO_OK = 0); nothing throws or aborts. varco_last_error()
+ *     gives the text of the last failure on that context (or of the last failed varco_create /
+ *     varco_partition_build when ctx is NULL).
+ *   - "device" pointers are HIP device memory owned by the caller; the library borrows them while the
+ *     enqueued work runs and never frees them. "host" pointers are ordinary host memory.
+ *   - All device work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL is the
+ *     default stream). No call synchronises the device except varco_register_partition.
+ *   - Matrices are row-major and dense (leading dimension = width) unless a leading dimension is given.
+ *   - Node ids, row ids and counts are int32 (graphs below 2^31 nodes / entries per partition); element
+ *     offsets are 64-bit inside the library.
+ *   - A context is not thread-safe. Calls on one context must be issued on one stream at a time, because
+ *     they share the context's workspace.
+ *   - Layers are numbered 0..L-1; layer l maps width[l] -> width[l+1]. k_l is the number of elements of a
+ *     width[l] vector that is communicated at the current ratio of layer l.
+ */
+#ifndef VARCO_H
+#define VARCO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct varco_ctx varco_ctx;
+typedef struct varco_host_parts varco_host_parts;
+typedef void* varco_stream;
+
+enum {
+    VARCO_OK = 0,
+    VARCO_ERR_INVALID_ARG = 1, /* null pointer, index out of range, ratio < 1 */
+    VARCO_ERR_SHAPE = 2,       /* sizes that do not fit together or exceed the supported range */
+    VARCO_ERR_STATE = 3,       /* call order violated (unregistered partition, ratio change mid-step) */
+    VARCO_ERR_UNSUPPORTED = 4, /* dtype / conv / width the kernels do not implement */
+    VARCO_ERR_HIP = 5          /* a HIP runtime call failed; text in varco_last_error */
+};
+
+enum { VARCO_CONV_GCN = 0 /* single tap S */, VARCO_CONV_SAGE = 1 /* taps I (H0) and S (H1) */ };
+enum { VARCO_ACT_IDENTITY = 0, VARCO_ACT_RELU = 1 };
+enum { VARCO_F32 = 0 };
+
+#define VARCO_MAX_LAYERS 16
+#define VARCO_MAX_WIDTH 2048
+
+/* Network description (eq. (2); Section V uses 3 layers, 256 hidden units, ReLU). Host pointers, copied. */
+typedef struct {
+    int32_t n_layers;       /* L, 1..VARCO_MAX_LAYERS */
+    int32_t n_partitions;   /* Q of Section III */
+    int32_t conv;           /* VARCO_CONV_* */
+    int32_t dtype;          /* VARCO_F32 */
+    uint64_t mask_key;      /* the key shared a priori between encoder and decoder (Appendix A) */
+    const int32_t* widths;  /* L+1 widths F_0..F_L, each 1..VARCO_MAX_WIDTH */
+    const int32_t* act;     /* L activation codes VARCO_ACT_* */
+} varco_config;
+
+/*
+ * One partition's index structures (Section III: local nodes, remote neighbours, boundary nodes).
+ * Used twice: varco_partition_view fills it with HOST pointers owned by the varco_host_parts handle;
+ * varco_register_partition reads it with DEVICE pointers owned by the caller, which must stay valid and
+ * unchanged until the context is destroyed or the partition is registered again.
+ *
+ *   row block   rowptr[n_local+1], colidx[nnz], vals[nnz]: CSR of S restricted to the partition's rows;
+ *               column c < n_local is local row c, column n_local+s is halo slot s; ascending in a row
+ *   transpose   t_rowptr[n_local+n_halo+1], t_colidx[nnz], t_vals[nnz]: row c lists local rows i with
+ *               S[i,c] != 0, ascending
+ *   local_gid[n_local] ascending global ids; halo_gid[n_halo] ordered by (owner, global id)
+ *   halo_owner_ptr[n_partitions+1]: slots of owner p are [halo_owner_ptr[p], halo_owner_ptr[p+1])
+ *   boundary_rows[n_boundary]: ascending local rows referenced by some other partition
+ *   halo_src_row[n_halo]: position of the halo node in its owner's boundary_rows
+ *   halo_zrow[n_halo]: halo_src_row + (boundary rows of all partitions before the owner) = row in the
+ *               concatenated compressed buffer; z_row_offset: first row of this partition's own slice
+ */
+typedef struct {
+    int32_t n_local, n_halo, n_boundary, z_row_offset;
+    int64_t nnz;
+    const int32_t* rowptr;
+    const int32_t* colidx;
+    const float* vals;
+    const int32_t* t_rowptr;
+    const int32_t* t_colidx;
+    const float* t_vals;
+    const int32_t* local_gid;
+    const int32_t* halo_gid;
+    const int32_t* halo_owner_ptr;
+    const int32_t* boundary_rows;
+    const int32_t* halo_src_row;
+    const int32_t* halo_zrow;
+} varco_partition_desc;
+
+/* Compressed elements handed off between partitions since creation (or the last reset): the quantity
+ * Section V-B plots accuracy against. full_* is what ratio 1 would have moved on the same calls. */
+typedef struct {
+    int64_t fwd_elems[VARCO_MAX_LAYERS], bwd_elems[VARCO_MAX_LAYERS];
+    int64_t full_fwd_elems[VARCO_MAX_LAYERS], full_bwd_elems[VARCO_MAX_LAYERS];
+    int32_t bytes_per_elem;
+} varco_stats;
+
+/* ------------------------------------------------------------------------------------------------
+ * Host-side partition builder (Section III; Appendix B: any node->partition map is accepted).
+ * All pointers are host memory. rowptr[n+1] int64, colidx/vals[rowptr[n]] with ascending columns in a
+ * row, part[n] in [0, n_parts). The result is owned by *out until varco_partition_free.
+ * Errors: INVALID_ARG (null, part out of range, unsorted row), SHAPE (a partition with >= 2^31 entries).
+ */
+int32_t varco_partition_build(int32_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
+                              const int32_t* part, int32_t n_parts, varco_host_parts** out);
+int32_t varco_partition_view(const varco_host_parts* h, int32_t q, varco_partition_desc* out);
+void varco_partition_free(varco_host_parts* h);
+
+/* ------------------------------------------------------------------------------------------------
+ * Context. varco_create copies cfg, sets every layer's ratio to 1 and the step to 0.
+ * varco_register_partition copies the row pointers to the host once (synchronising), builds the
+ * library's own work lists for that partition and grows the context's device workspace; it may be called
+ * again for the same q to replace a partition.
+ */
+int32_t varco_create(const varco_config* cfg, varco_ctx** out);
+int32_t varco_destroy(varco_ctx* ctx);
+int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const varco_partition_desc* dev);
+const char* varco_last_error(const varco_ctx* ctx);
+
+/* Algorithm 1's iteration counter t: part of the mask key, so that the kept positions are redrawn every
+ * step. Also closes the previous step (ratios may change again). */
+int32_t varco_begin_step(varco_ctx* ctx, uint64_t step);
+
+/* Section IV / Algorithm 1 ("update compression rate"): ratio r = num/den >= 1 of layer `layer`'s input
+ * (-1 = every layer). k = max(1, ceil(width*den/num)); r = 1 keeps everything (lossless). STATE error if
+ * the layer's positions are already in use in the current step (by compress, decompress or a forward
+ * call; its backward must see the same positions). */
+int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, uint32_t den);
+/* k_l currently in force (negative status on error is not used: returns status, k through *k). */
+int32_t varco_get_keep(const varco_ctx* ctx, int32_t layer, int32_t* k);
+
+/* Definition 1, encoder: z[i, j] = x[rows[i], pi_v(j)], j < k_l, v = gids[i].
+ * gids[n_rows] device; rows[n_rows] device or NULL (then row i); x device with leading dimension ldx >=
+ * width[layer]; z device, n_rows x k_l dense. No index bytes are produced. */
+int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
+                       int64_t n_rows, const void* x, int64_t ldx, void* z, varco_stream stream);
+
+/* Definition 1 / Appendix A, decoder. accumulate = 0: x[rows[i], :] = 0 except x[rows[i], pi_v(j)] =
+ * z[i, j]. accumulate = 1: x[rows[i], pi_v(j)] += z[i, j] (the owner-side sum of returned errors); rows
+ * must be distinct within one call. */
+int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
+                         int64_t n_rows, const void* z, void* x, int64_t ldx, int32_t accumulate,
+                         varco_stream stream);
+
+/* Forward of layer `layer` on partition q (Algorithm 1, "compute forward pass by using non-compressed
+ * activations for local nodes and compressed activations for non-local nodes"):
+ *   m      = S_q [x_local ; decompress(z_in[halo_zrow])]      n_local x width[layer]
+ *   x_out  = act( m h1 (+ x_local h0) )                       n_local x width[layer+1]
+ *   z_out rows [z_row_offset, +n_boundary) = compress(x_out[boundary_rows]) at layer+1's k   (optional)
+ * x_local: n_local x width[layer]; z_in: (all partitions' boundary rows) x k_layer, owners' slices in
+ * partition order (the on-device stand-in for the exchange; may be NULL when n_halo = 0); h1, h0:
+ * width[layer] x width[layer+1] (h0 NULL for GCN, required for SAGE); m_saved is written and must be kept
+ * for the backward call; z_out may be NULL (must be NULL on the last layer).
+ * Counts n_halo * k_layer elements as handed off forward. */
+int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_local, const void* z_in,
+                        const void* h1, const void* h0, void* x_out, void* z_out, void* m_saved,
+                        varco_stream stream);
+
+/* Backward of layer `layer` on partition q ("back-propagating errors across machines and through the
+ * differentiable compression routine"):
+ *   dz = dx_out * [x_out > 0] (ReLU) or dx_out;  dh1 += m_saved^T dz;  dh0 += x_local^T dz
+ *   if dx_local != NULL:  dm = dz h1^T;  [dx_local ; dx_halo] = S_q^T dm;  dx_local += dz h0^T;
+ *                         dz_halo[s, j] = dx_halo[s, pi_v(j)], j < k_layer, v = halo_gid[s]
+ * dh1/dh0 are accumulated into (the sum over partitions is the cross-machine sum of Section III); dx_local
+ * (n_local x width[layer]) and dz_halo (n_halo x k_layer) are overwritten. dx_local = NULL skips the input
+ * gradient (first layer); dz_halo must then be NULL too. The owners add dz_halo with varco_decompress
+ * (accumulate = 1). Counts n_halo * k_layer elements as handed off backward when dz_halo is produced. */
+int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx_out, const void* x_out,
+                        const void* x_local, const void* m_saved, const void* h1, const void* h0, void* dh1,
+                        void* dh0, void* dx_local, void* dz_halo, varco_stream stream);
+
+int32_t varco_get_stats(const varco_ctx* ctx, varco_stats* out);
+int32_t varco_reset_stats(varco_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARCO_H */

@@ -1,0 +1,256 @@
+"""Thin ctypes binding of libvarco.so: argument marshalling only. Every step of the hot path runs in the
+library's HIP kernels; torch tensors serve as device memory and torch streams as hipStream_t handles.
+
+The library must have been built (python -m paper_2406_17611_amd.build, or __graft_entry__.build());
+loading fails loudly otherwise - there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvarco.so")
+
+OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP = range(6)
+CONV_GCN, CONV_SAGE = 0, 1
+ACT_IDENTITY, ACT_RELU = 0, 1
+F32 = 0
+MAX_LAYERS = 16
+
+EXPORTS = [
+    "varco_partition_build", "varco_partition_view", "varco_partition_free",
+    "varco_create", "varco_destroy", "varco_register_partition", "varco_last_error",
+    "varco_begin_step", "varco_set_ratio", "varco_get_keep",
+    "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
+    "varco_get_stats", "varco_reset_stats",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_partitions", C.c_int32), ("conv", C.c_int32), ("dtype", C.c_int32),
+                ("mask_key", C.c_uint64), ("widths", C.POINTER(C.c_int32)), ("act", C.POINTER(C.c_int32))]
+
+
+_DESC_ARRAYS = [("rowptr", np.int32), ("colidx", np.int32), ("vals", np.float32), ("t_rowptr", np.int32),
+                ("t_colidx", np.int32), ("t_vals", np.float32), ("local_gid", np.int32), ("halo_gid", np.int32),
+                ("halo_owner_ptr", np.int32), ("boundary_rows", np.int32), ("halo_src_row", np.int32),
+                ("halo_zrow", np.int32)]
+
+
+class PartitionDesc(C.Structure):
+    _fields_ = ([("n_local", C.c_int32), ("n_halo", C.c_int32), ("n_boundary", C.c_int32),
+                 ("z_row_offset", C.c_int32), ("nnz", C.c_int64)] + [(name, C.c_void_p) for name, _ in _DESC_ARRAYS])
+
+
+class Stats(C.Structure):
+    _fields_ = [("fwd_elems", C.c_int64 * MAX_LAYERS), ("bwd_elems", C.c_int64 * MAX_LAYERS),
+                ("full_fwd_elems", C.c_int64 * MAX_LAYERS), ("full_bwd_elems", C.c_int64 * MAX_LAYERS),
+                ("bytes_per_elem", C.c_int32)]
+
+
+class VarcoError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"varco status {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2406_17611_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u32, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_uint64
+        L.varco_partition_build.argtypes = [i32, vp, vp, vp, vp, i32, C.POINTER(vp)]
+        L.varco_partition_view.argtypes = [vp, i32, C.POINTER(PartitionDesc)]
+        L.varco_partition_free.argtypes = [vp]
+        L.varco_partition_free.restype = None
+        L.varco_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+        L.varco_destroy.argtypes = [vp]
+        L.varco_register_partition.argtypes = [vp, i32, C.POINTER(PartitionDesc)]
+        L.varco_last_error.argtypes = [vp]
+        L.varco_last_error.restype = C.c_char_p
+        L.varco_begin_step.argtypes = [vp, u64]
+        L.varco_set_ratio.argtypes = [vp, i32, u32, u32]
+        L.varco_get_keep.argtypes = [vp, i32, C.POINTER(i32)]
+        L.varco_compress.argtypes = [vp, i32, vp, vp, i64, vp, i64, vp, vp]
+        L.varco_decompress.argtypes = [vp, i32, vp, vp, i64, vp, vp, i64, i32, vp]
+        L.varco_layer_fwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.varco_layer_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.varco_get_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.varco_reset_stats.argtypes = [vp]
+        for name in EXPORTS:
+            if name not in ("varco_partition_free", "varco_last_error"):
+                getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(code: int, ctx=None):
+    if code != OK:
+        text = lib().varco_last_error(ctx)
+        raise VarcoError(code, text.decode() if text else "")
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array, None -> NULL."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
+# ---------------------------------------------------------------------------------------------------------
+# host-side partition builder
+# ---------------------------------------------------------------------------------------------------------
+
+class HostPartition:
+    """numpy copies of one partition's index structures, as built by varco_partition_build."""
+
+    def __init__(self, desc: PartitionDesc):
+        self.n_local, self.n_halo, self.n_boundary = desc.n_local, desc.n_halo, desc.n_boundary
+        self.z_row_offset, self.nnz = desc.z_row_offset, desc.nnz
+        sizes = {"rowptr": self.n_local + 1, "colidx": self.nnz, "vals": self.nnz,
+                 "t_rowptr": self.n_local + self.n_halo + 1, "t_colidx": self.nnz, "t_vals": self.nnz,
+                 "local_gid": self.n_local, "halo_gid": self.n_halo, "halo_owner_ptr": None,
+                 "boundary_rows": self.n_boundary, "halo_src_row": self.n_halo, "halo_zrow": self.n_halo}
+        self._sizes = sizes
+
+    def _fill(self, desc, n_parts):
+        self._sizes["halo_owner_ptr"] = n_parts + 1
+        for name, dt in _DESC_ARRAYS:
+            n = self._sizes[name]
+            addr = getattr(desc, name)
+            if n == 0 or not addr:
+                arr = np.empty(0, dtype=dt)
+            else:
+                arr = np.ctypeslib.as_array(C.cast(addr, C.POINTER(np.ctypeslib.as_ctypes_type(dt))), shape=(n,)).copy()
+            setattr(self, name, arr)
+
+
+def partition_build(n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray, part: np.ndarray,
+                    n_parts: int) -> list[HostPartition]:
+    """Runs the library's host-side builder and returns numpy copies of every partition's arrays."""
+    L = lib()
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    part = np.ascontiguousarray(part, dtype=np.int32)
+    if rowptr.shape[0] != n + 1 or part.shape[0] != n or colidx.shape[0] != vals.shape[0]:
+        raise VarcoError(ERR_SHAPE, "partition_build: array lengths do not match n")
+    h = C.c_void_p()
+    _check(L.varco_partition_build(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data, part.ctypes.data,
+                                   n_parts, C.byref(h)))
+    try:
+        out = []
+        for q in range(n_parts):
+            d = PartitionDesc()
+            _check(L.varco_partition_view(h, q, C.byref(d)))
+            hp = HostPartition(d)
+            hp._fill(d, n_parts)
+            out.append(hp)
+        return out
+    finally:
+        L.varco_partition_free(h)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# context
+# ---------------------------------------------------------------------------------------------------------
+
+class Context:
+    def __init__(self, widths, act, conv: int, n_partitions: int, mask_key: int, dtype: int = F32):
+        L = lib()
+        self._widths = (C.c_int32 * len(widths))(*widths)
+        self._act = (C.c_int32 * len(act))(*act)
+        cfg = Config(len(act), n_partitions, conv, dtype, mask_key, self._widths, self._act)
+        self._h = C.c_void_p()
+        _check(L.varco_create(C.byref(cfg), C.byref(self._h)))
+        self.widths = list(widths)
+        self.n_layers = len(act)
+        self.n_partitions = n_partitions
+        self._keep = {}          # device tensors of registered partitions (kept alive)
+        self.parts = {}
+
+    def close(self):
+        if self._h:
+            lib().varco_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def register_partition(self, q: int, hp: HostPartition, device="cuda"):
+        """Uploads a HostPartition's arrays (torch tensors, kept alive by this object) and registers them."""
+        import torch
+        dev = {}
+        d = PartitionDesc()
+        d.n_local, d.n_halo, d.n_boundary = hp.n_local, hp.n_halo, hp.n_boundary
+        d.z_row_offset, d.nnz = hp.z_row_offset, hp.nnz
+        for name, _ in _DESC_ARRAYS:
+            t = torch.from_numpy(getattr(hp, name)).to(device)
+            dev[name] = t
+            setattr(d, name, t.data_ptr() if t.numel() else None)
+        _check(lib().varco_register_partition(self._h, q, C.byref(d)), self._h)
+        self._keep[q] = dev
+        self.parts[q] = hp
+        return dev
+
+    def register_raw(self, q: int, desc: PartitionDesc):
+        _check(lib().varco_register_partition(self._h, q, C.byref(desc)), self._h)
+
+    def begin_step(self, step: int):
+        _check(lib().varco_begin_step(self._h, step), self._h)
+
+    def set_ratio(self, layer: int, num: int, den: int = 1):
+        _check(lib().varco_set_ratio(self._h, layer, num, den), self._h)
+
+    def keep(self, layer: int) -> int:
+        k = C.c_int32()
+        _check(lib().varco_get_keep(self._h, layer, C.byref(k)), self._h)
+        return k.value
+
+    def compress(self, layer, gids, rows, n_rows, x, ldx, z, stream=None):
+        _check(lib().varco_compress(self._h, layer, _ptr(gids), _ptr(rows), n_rows, _ptr(x), ldx, _ptr(z),
+                                    _stream(stream)), self._h)
+
+    def decompress(self, layer, gids, rows, n_rows, z, x, ldx, accumulate, stream=None):
+        _check(lib().varco_decompress(self._h, layer, _ptr(gids), _ptr(rows), n_rows, _ptr(z), _ptr(x), ldx,
+                                      int(accumulate), _stream(stream)), self._h)
+
+    def layer_fwd(self, layer, q, x_local, z_in, h1, h0, x_out, z_out, m_saved, stream=None):
+        _check(lib().varco_layer_fwd(self._h, layer, q, _ptr(x_local), _ptr(z_in), _ptr(h1), _ptr(h0), _ptr(x_out),
+                                     _ptr(z_out), _ptr(m_saved), _stream(stream)), self._h)
+
+    def layer_bwd(self, layer, q, dx_out, x_out, x_local, m_saved, h1, h0, dh1, dh0, dx_local, dz_halo, stream=None):
+        _check(lib().varco_layer_bwd(self._h, layer, q, _ptr(dx_out), _ptr(x_out), _ptr(x_local), _ptr(m_saved),
+                                     _ptr(h1), _ptr(h0), _ptr(dh1), _ptr(dh0), _ptr(dx_local), _ptr(dz_halo),
+                                     _stream(stream)), self._h)
+
+    def stats(self) -> dict:
+        s = Stats()
+        _check(lib().varco_get_stats(self._h, C.byref(s)), self._h)
+        n = self.n_layers
+        return dict(fwd_elems=list(s.fwd_elems)[:n], bwd_elems=list(s.bwd_elems)[:n],
+                    full_fwd_elems=list(s.full_fwd_elems)[:n], full_bwd_elems=list(s.full_bwd_elems)[:n],
+                    bytes_per_elem=s.bytes_per_elem)
+
+    def reset_stats(self):
+        _check(lib().varco_reset_stats(self._h), self._h)

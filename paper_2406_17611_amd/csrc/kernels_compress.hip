@@ -1,0 +1,120 @@
+// Encoder and decoder of Definition 1 / Appendix "Compression Mechanism": keep k keyed-random elements of
+// each node vector; decode by writing them in place and zero elsewhere (no rescale). Pure data movement:
+// HBM-bound, no index bytes are stored or read. A power-of-two group of lanes serves one row, so that
+// narrow messages (k of 4..32) still fill the 64-wide wavefront with several rows.
+#include "mask_device.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+
+__device__ __forceinline__ int64_t group_row(int g_log2) {
+    return (int64_t(blockIdx.x) * kBlock + threadIdx.x) >> g_log2;
+}
+
+__global__ __launch_bounds__(kBlock) void compress_kernel(MaskRule rule, const int32_t* __restrict__ gids,
+                                                          const int32_t* __restrict__ rows, int64_t n_rows,
+                                                          const float* __restrict__ x, int64_t ldx,
+                                                          float* __restrict__ z, int g_log2) {
+    const uint32_t g = 1u << g_log2;
+    const uint32_t gl = threadIdx.x & (g - 1);
+    const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
+    for (int64_t row = group_row(g_log2); row < n_rows; row += stride) {
+        const int64_t src = rows ? int64_t(rows[row]) : row;
+        const float* xr = x + src * ldx;
+        float* zr = z + row * int64_t(rule.k);
+        if (rule.k == rule.width) {
+            for (uint32_t j = gl; j < rule.k; j += g) zr[j] = xr[j];
+        } else {
+            const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
+            for (uint32_t j = gl; j < rule.k; j += g) zr[j] = xr[varco_position(rule, m, j)];
+        }
+    }
+}
+
+// Full rows are written in one coalesced pass: column c holds z[j] when its inverse position j is kept.
+__global__ __launch_bounds__(kBlock) void decompress_kernel(MaskRule rule, const int32_t* __restrict__ gids,
+                                                            const int32_t* __restrict__ rows, int64_t n_rows,
+                                                            const float* __restrict__ z, float* __restrict__ x,
+                                                            int64_t ldx, int g_log2) {
+    const uint32_t g = 1u << g_log2;
+    const uint32_t gl = threadIdx.x & (g - 1);
+    const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
+    for (int64_t row = group_row(g_log2); row < n_rows; row += stride) {
+        const int64_t dst = rows ? int64_t(rows[row]) : row;
+        float* xr = x + dst * ldx;
+        const float* zr = z + row * int64_t(rule.k);
+        if (rule.k == rule.width) {
+            for (uint32_t c = gl; c < rule.width; c += g) xr[c] = zr[c];
+        } else {
+            const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
+            for (uint32_t c = gl; c < rule.width; c += g) {
+                const uint32_t j = varco_inverse_position(rule, m, c);
+                xr[c] = j < rule.k ? zr[j] : 0.0f;
+            }
+        }
+    }
+}
+
+// Owner-side sum of returned errors: rows are distinct within a call and positions are distinct within a
+// row, so plain read-modify-write is race-free and the result does not depend on scheduling.
+__global__ __launch_bounds__(kBlock) void decompress_add_kernel(MaskRule rule, const int32_t* __restrict__ gids,
+                                                                const int32_t* __restrict__ rows, int64_t n_rows,
+                                                                const float* __restrict__ z, float* __restrict__ x,
+                                                                int64_t ldx, int g_log2) {
+    const uint32_t g = 1u << g_log2;
+    const uint32_t gl = threadIdx.x & (g - 1);
+    const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
+    for (int64_t row = group_row(g_log2); row < n_rows; row += stride) {
+        const int64_t dst = rows ? int64_t(rows[row]) : row;
+        float* xr = x + dst * ldx;
+        const float* zr = z + row * int64_t(rule.k);
+        if (rule.k == rule.width) {
+            for (uint32_t j = gl; j < rule.k; j += g) xr[j] += zr[j];
+        } else {
+            const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
+            for (uint32_t j = gl; j < rule.k; j += g) xr[varco_position(rule, m, j)] += zr[j];
+        }
+    }
+}
+
+int group_log2(uint32_t elems) {
+    int l = 0;
+    while ((1u << l) < elems && l < 6) ++l;
+    return l;
+}
+
+unsigned grid_for(int64_t n_rows, int g_log2) {
+    const int64_t threads = n_rows << g_log2;
+    int64_t blocks = (threads + kBlock - 1) / kBlock;
+    const int64_t cap = 256 * 16;  // 16 resident blocks on each of the 256 compute units, grid-stride beyond
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return unsigned(blocks);
+}
+
+}  // namespace
+
+hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                                 const float* x, int64_t ldx, float* z, hipStream_t stream) {
+    if (n_rows == 0) return hipSuccess;
+    const int gl = group_log2(rule.k);
+    hipLaunchKernelGGL(compress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows, n_rows,
+                       x, ldx, z, gl);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream) {
+    if (n_rows == 0) return hipSuccess;
+    if (accumulate) {
+        const int gl = group_log2(rule.k);
+        hipLaunchKernelGGL(decompress_add_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids,
+                           rows, n_rows, z, x, ldx, gl);
+    } else {
+        const int gl = group_log2(rule.width);
+        hipLaunchKernelGGL(decompress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
+                           n_rows, z, x, ldx, gl);
+    }
+    return hipGetLastError();
+}

@@ -1,0 +1,291 @@
+// Dense feature transform of eq. (2) and its gradients on the CDNA matrix cores, in true fp32
+// (v_mfma_f32_32x32x2_f32): X_out = act(M H1 + X H0), dM = dZ H1^T, dH += M^T dZ.
+//
+// One 256-thread workgroup (4 wavefronts, 2 x 2) computes a 128 x 128 tile of C; each wavefront owns a
+// 64 x 64 sub-tile as 2 x 2 MFMA blocks of 32 x 32 (64 accumulator registers per lane). Operand tiles of
+// 16 reduction steps are staged through LDS in k-major order (so that an MFMA operand is one conflict-free
+// 32-float row read) and double-buffered against the global loads of the next tile. The ReLU mask of the
+// backward pass is applied while an operand is loaded ("gate"), the activation in the epilogue. A second
+// (A2, B2) product can be chained into the same accumulators (the two taps of a SAGE layer). Reductions
+// over the node dimension (weight gradients) are split over workgroups into a partial buffer and summed
+// by a second kernel in a fixed order.
+#include "varco_internal.h"
+
+namespace {
+
+constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int PAD = 4;
+constexpr int kThreads = 256;
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct OperandDev {
+    const float* ptr;
+    const float* gate;
+    int64_t ld;
+    int32_t k_contig;   // 1: element (i, kk) at ptr[i * ld + kk]; 0: at ptr[kk * ld + i]
+    int32_t vec_ok;     // 16-byte loads are legal (aligned base, ld % 4 == 0)
+};
+
+struct GemmDev {
+    int32_t m, n, k, k2;
+    OperandDev a, b, a2, b2;
+    float* c;
+    int64_t ldc;
+    int32_t accumulate, relu;
+    int32_t split_k, tiles_per_split;   // reduction tiles (of BK) handled by one split
+    float* partial;
+    int32_t tiles_m, tiles_n;
+    int32_t inner, outer;               // see the workgroup -> tile mapping in the kernel
+};
+
+// Registers holding this thread's share (2 x 4 floats) of one operand tile.
+struct TileRegs {
+    float v[2][4];
+};
+
+// Loads the thread's share of a (rows x BK) operand tile whose row index is `i0 + ...` (M or N side).
+// `extent` bounds the row index, `kmax` the reduction index.
+__device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int32_t extent, int32_t k0, int32_t kmax,
+                                          TileRegs& r) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int f = tid + h * kThreads;   // index of a group of 4 floats in the tile
+        int32_t i, kk;
+        int64_t off;
+        bool in4, in[4];
+        if (op.k_contig) {                  // 4 consecutive reduction indices of one row
+            i = i0 + (f >> 2);
+            kk = k0 + ((f & 3) << 2);
+            off = int64_t(i) * op.ld + kk;
+            in4 = i < extent && kk + 3 < kmax;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) in[u] = i < extent && kk + u < kmax;
+        } else {                            // 4 consecutive rows of one reduction index
+            kk = k0 + (f >> 5);
+            i = i0 + ((f & 31) << 2);
+            off = int64_t(kk) * op.ld + i;
+            in4 = kk < kmax && i + 3 < extent;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) in[u] = kk < kmax && i + u < extent;
+        }
+        if (in4 && op.vec_ok) {
+            const float4 x = *reinterpret_cast<const float4*>(op.ptr + off);
+            r.v[h][0] = x.x, r.v[h][1] = x.y, r.v[h][2] = x.z, r.v[h][3] = x.w;
+            if (op.gate) {
+                const float4 gt = *reinterpret_cast<const float4*>(op.gate + off);
+                if (!(gt.x > 0.f)) r.v[h][0] = 0.f;
+                if (!(gt.y > 0.f)) r.v[h][1] = 0.f;
+                if (!(gt.z > 0.f)) r.v[h][2] = 0.f;
+                if (!(gt.w > 0.f)) r.v[h][3] = 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float x = 0.f;
+                if (in[u]) {
+                    x = op.ptr[off + u];
+                    if (op.gate && !(op.gate[off + u] > 0.f)) x = 0.f;
+                }
+                r.v[h][u] = x;
+            }
+        }
+    }
+}
+
+// Writes the registers into the k-major LDS tile s[BK][BM + PAD].
+__device__ __forceinline__ void store_tile(const OperandDev& op, const TileRegs& r, float (*s)[BM + PAD]) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int f = tid + h * kThreads;
+        if (op.k_contig) {
+            const int i = f >> 2, kk = (f & 3) << 2;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s[kk + u][i] = r.v[h][u];
+        } else {
+            const int kk = f >> 5, i = (f & 31) << 2;
+            *reinterpret_cast<float4*>(&s[kk][i]) = make_float4(r.v[h][0], r.v[h][1], r.v[h][2], r.v[h][3]);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
+    __shared__ __attribute__((aligned(16))) float sa[2][BK][BM + PAD];
+    __shared__ __attribute__((aligned(16))) float sb[2][BK][BN + PAD];
+
+    // Workgroups are dealt to the 8 XCDs round-robin. The tiles that share streamed data (the column tiles
+    // of one row tile; or, for a split reduction, all output tiles of one slab of the reduction range) are
+    // given to one XCD, so that the streamed operand is fetched into a single L2.
+    const int32_t xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+    const int32_t in = within % g.inner, out = (within / g.inner) * 8 + xcd;
+    if (out >= g.outer) return;        // whole workgroup leaves together: no barrier is skipped
+    int32_t tm, tn, z;
+    if (g.split_k > 1) {
+        z = out, tm = in / g.tiles_n, tn = in % g.tiles_n;
+    } else {
+        z = 0, tm = out, tn = in;
+    }
+    const int32_t m0 = tm * BM, n0 = tn * BN;
+
+    const int32_t tiles1 = (g.k + BK - 1) / BK;
+    const int32_t tiles2 = (g.k2 + BK - 1) / BK;
+    int32_t t_begin = 0, t_end = tiles1 + tiles2;
+    if (g.split_k > 1) {
+        t_begin = z * g.tiles_per_split;
+        t_end = min(t_end, t_begin + g.tiles_per_split);
+    }
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    TileRegs ra, rb;
+    auto fetch = [&](int32_t t) {
+        if (t < tiles1) {
+            load_tile(g.a, m0, g.m, t * BK, g.k, ra);
+            load_tile(g.b, n0, g.n, t * BK, g.k, rb);
+        } else {
+            load_tile(g.a2, m0, g.m, (t - tiles1) * BK, g.k2, ra);
+            load_tile(g.b2, n0, g.n, (t - tiles1) * BK, g.k2, rb);
+        }
+    };
+    auto stash = [&](int32_t t, int buf) {
+        store_tile(t < tiles1 ? g.a : g.a2, ra, sa[buf]);
+        store_tile(t < tiles1 ? g.b : g.b2, rb, sb[buf]);
+    };
+
+    if (t_begin < t_end) {
+        fetch(t_begin);
+        stash(t_begin, 0);
+    }
+    __syncthreads();
+    for (int32_t t = t_begin; t < t_end; ++t) {
+        const int buf = (t - t_begin) & 1;
+        if (t + 1 < t_end) fetch(t + 1);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+            const float a0 = sa[buf][kk + lk][wm + lrow];
+            const float a1 = sa[buf][kk + lk][wm + 32 + lrow];
+            const float b0 = sb[buf][kk + lk][wn + lrow];
+            const float b1 = sb[buf][kk + lk][wn + 32 + lrow];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (t + 1 < t_end) stash(t + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32)
+    float* cbase = g.c;
+    int64_t ldc = g.ldc;
+    const bool to_partial = g.split_k > 1;
+    if (to_partial) {
+        cbase = g.partial + int64_t(z) * g.m * g.n;
+        ldc = g.n;
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int32_t col = n0 + wn + j * 32 + lrow;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                if (row < g.m && col < g.n) {
+                    float* dst = cbase + int64_t(row) * ldc + col;
+                    float x = acc[i][j][v];
+                    if (!to_partial) {
+                        if (g.accumulate) x += *dst;
+                        if (g.relu) x = fmaxf(x, 0.f);
+                    }
+                    *dst = x;
+                }
+            }
+        }
+    }
+}
+
+// C (+)= sum over splits of partial[s], in split order.
+__global__ __launch_bounds__(kThreads) void gemm_reduce_kernel(const float* partial, int32_t splits, int64_t mn,
+                                                               int32_t n, float* c, int64_t ldc, int32_t accumulate,
+                                                               int32_t relu) {
+    const int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (i >= mn) return;
+    float x = 0.f;
+    for (int32_t s = 0; s < splits; ++s) x += partial[int64_t(s) * mn + i];
+    float* dst = c + (i / n) * ldc + (i % n);
+    if (accumulate) x += *dst;
+    if (relu) x = fmaxf(x, 0.f);
+    *dst = x;
+}
+
+OperandDev make_operand(const GemmOperand& o, bool stored_k_contig) {
+    OperandDev d;
+    d.ptr = o.ptr;
+    d.gate = o.gate;
+    d.ld = o.ld;
+    d.k_contig = stored_k_contig ? 1 : 0;
+    const bool al = (reinterpret_cast<uintptr_t>(o.ptr) & 15u) == 0 && (reinterpret_cast<uintptr_t>(o.gate) & 15u) == 0;
+    d.vec_ok = (al && o.ld % 4 == 0) ? 1 : 0;
+    return d;
+}
+
+}  // namespace
+
+hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream) {
+    if (ga.m == 0 || ga.n == 0) return hipSuccess;
+    GemmDev g;
+    g.m = ga.m, g.n = ga.n, g.k = ga.k, g.k2 = ga.k2;
+    // A is M x K: k-contiguous as stored unless transposed. B is K x N: k-contiguous only when transposed.
+    g.a = make_operand(ga.a, !ga.a.transposed);
+    g.b = make_operand(ga.b, ga.b.transposed);
+    g.a2 = make_operand(ga.a2, !ga.a2.transposed);
+    g.b2 = make_operand(ga.b2, ga.b2.transposed);
+    g.c = ga.c;
+    g.ldc = ga.ldc;
+    g.accumulate = ga.accumulate ? 1 : 0;
+    g.relu = ga.relu ? 1 : 0;
+    g.tiles_m = (ga.m + BM - 1) / BM;
+    g.tiles_n = (ga.n + BN - 1) / BN;
+    const int32_t k_tiles = (ga.k + BK - 1) / BK + (ga.k2 + BK - 1) / BK;
+    int32_t split = ga.split_k < 1 ? 1 : ga.split_k;
+    if (split > k_tiles) split = k_tiles < 1 ? 1 : k_tiles;
+    g.tiles_per_split = (k_tiles + split - 1) / split;
+    split = g.tiles_per_split > 0 ? (k_tiles + g.tiles_per_split - 1) / g.tiles_per_split : 1;
+    if (split < 1) split = 1;
+    g.split_k = split;
+    g.partial = ga.partial;
+    if (split > 1 && !ga.partial) return hipErrorInvalidValue;
+    if (split > 1) {
+        g.inner = g.tiles_m * g.tiles_n;
+        g.outer = split;
+    } else {
+        g.inner = g.tiles_n;
+        g.outer = g.tiles_m;
+    }
+    const int64_t blocks = int64_t((g.outer + 7) / 8 * 8) * g.inner;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(gemm_kernel, dim3(unsigned(blocks)), dim3(kThreads), 0, stream, g);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    if (split > 1) {
+        const int64_t mn = int64_t(ga.m) * ga.n;
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(unsigned((mn + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                           stream, ga.partial, split, mn, ga.n, ga.c, ga.ldc, g.accumulate, g.relu);
+        err = hipGetLastError();
+    }
+    return err;
+}

@@ -1,0 +1,597 @@
+// C ABI of libvarco: context, argument checking, per-step mask state and the sequencing of kernels for
+// one partition's layer forward / backward (Algorithm 1 of the paper, one layer of eq. (2)).
+#include <algorithm>
+#include <climits>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "varco_internal.h"
+
+namespace {
+
+constexpr int32_t kSpmmChunk = 256;   // longest run of CSR entries one wavefront takes
+
+struct LayerState {
+    uint32_t num = 1, den = 1;
+    int32_t k = 0;
+    int32_t n_units = 0;
+    std::vector<uint16_t> h_units, h_units_inv;   // host copies; uploaded on first device use
+    uint16_t* units = nullptr;       // device
+    uint16_t* units_inv = nullptr;   // device
+    bool ran_forward = false;        // in the current step
+};
+
+struct PartState {
+    bool registered = false;
+    varco_partition_desc d{};
+    SpmmPlan fwd, t_local, t_halo;
+    HaloDesc* halo_desc = nullptr;   // device [n_halo]
+    int32_t* boundary_gid = nullptr; // device [n_boundary]
+};
+
+std::mutex g_err_mutex;
+std::string g_global_error;
+
+}  // namespace
+
+struct varco_ctx {
+    int32_t n_layers = 0, n_parts = 0, conv = 0, dtype = 0;
+    uint64_t key = 0, step = 0;
+    std::vector<int32_t> widths, act;
+    std::vector<LayerState> layers;
+    std::vector<PartState> parts;
+    // device workspace shared by all calls on this context
+    float* ws_dm = nullptr;        size_t ws_dm_elems = 0;        // dM: n_local x width
+    float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
+    float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
+    varco_stats stats{};
+    mutable std::string error;
+};
+
+int32_t varco_fail(const varco_ctx* ctx, int32_t code, const char* msg) {
+    if (ctx) {
+        ctx->error = msg;
+    } else {
+        std::lock_guard<std::mutex> lock(g_err_mutex);
+        g_global_error = msg;
+    }
+    return code;
+}
+
+namespace {
+
+int32_t hip_fail(const varco_ctx* ctx, hipError_t e, const char* what) {
+    std::string m = std::string(what) + ": " + hipGetErrorString(e);
+    return varco_fail(ctx, VARCO_ERR_HIP, m.c_str());
+}
+
+#define VARCO_HIP(ctx, call)                                   \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
+    } while (0)
+
+uint64_t mix64(uint64_t x) {   // splitmix64 output function
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+MaskRule make_rule(const varco_ctx* ctx, int32_t layer) {
+    const LayerState& ls = ctx->layers[layer];
+    const uint64_t inner = mix64(ctx->step + 0x9E3779B97F4A7C15ull * uint64_t(layer + 1));
+    const uint64_t s = mix64(ctx->key ^ inner);
+    MaskRule r;
+    r.s0 = uint32_t(s & 0xFFFFFFFFull);
+    r.s1 = uint32_t(s >> 32);
+    r.width = uint32_t(ctx->widths[layer]);
+    r.k = uint32_t(ls.k);
+    r.n_units = uint32_t(ls.n_units);
+    r.width_magic = r.width == 1 ? 0xFFFFFFFFu : uint32_t((uint64_t(1) << 32) / r.width);
+    r.units = ls.units;
+    r.units_inv = ls.units_inv;
+    return r;
+}
+
+// A rule that keeps every element of `width`-wide rows (used for purely dense aggregations).
+MaskRule full_rule(int32_t width) {
+    MaskRule r{};
+    r.width = uint32_t(width);
+    r.k = uint32_t(width);
+    r.n_units = 1;
+    r.width_magic = width == 1 ? 0xFFFFFFFFu : uint32_t((uint64_t(1) << 32) / uint32_t(width));
+    return r;
+}
+
+int32_t keep_count(int32_t width, uint32_t num, uint32_t den) {
+    const uint64_t k = (uint64_t(width) * den + num - 1) / num;
+    return int32_t(std::max<uint64_t>(1, k));
+}
+
+void free_plan(SpmmPlan& p) {
+    if (p.items) (void)hipFree(p.items);
+    if (p.splits) (void)hipFree(p.splits);
+    p = SpmmPlan{};
+}
+
+void free_part(PartState& ps) {
+    free_plan(ps.fwd);
+    free_plan(ps.t_local);
+    free_plan(ps.t_halo);
+    if (ps.halo_desc) (void)hipFree(ps.halo_desc);
+    if (ps.boundary_gid) (void)hipFree(ps.boundary_gid);
+    ps = PartState{};
+}
+
+// Work list for rows [r0, r1) of a CSR given its host row pointers: long rows first (split into chunks
+// whose partial sums are reduced afterwards), then every other row, empty ones included.
+hipError_t build_plan(const std::vector<int32_t>& rowptr, int32_t r0, int32_t r1, SpmmPlan& plan) {
+    std::vector<SpmmItem> items;
+    std::vector<SpmmSplit> splits;
+    items.reserve(size_t(r1 - r0) + 64);
+    int32_t n_partials = 0;
+    for (int32_t r = r0; r < r1; ++r) {
+        const int32_t len = rowptr[r + 1] - rowptr[r];
+        if (len > kSpmmChunk) {
+            const int32_t pieces = (len + kSpmmChunk - 1) / kSpmmChunk;
+            splits.push_back({r, n_partials, pieces, 0});
+            for (int32_t c = 0; c < pieces; ++c) {
+                const int32_t e0 = rowptr[r] + c * kSpmmChunk;
+                items.push_back({r, e0, std::min(e0 + kSpmmChunk, rowptr[r + 1]), n_partials++});
+            }
+        }
+    }
+    for (int32_t r = r0; r < r1; ++r) {
+        const int32_t len = rowptr[r + 1] - rowptr[r];
+        if (len <= kSpmmChunk) items.push_back({r, rowptr[r], rowptr[r + 1], -1});
+    }
+    plan.n_items = int32_t(items.size());
+    plan.n_splits = int32_t(splits.size());
+    plan.n_partials = n_partials;
+    hipError_t e = hipSuccess;
+    if (!items.empty()) {
+        e = hipMalloc(reinterpret_cast<void**>(&plan.items), items.size() * sizeof(SpmmItem));
+        if (e != hipSuccess) return e;
+        e = hipMemcpy(plan.items, items.data(), items.size() * sizeof(SpmmItem), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+    }
+    if (!splits.empty()) {
+        e = hipMalloc(reinterpret_cast<void**>(&plan.splits), splits.size() * sizeof(SpmmSplit));
+        if (e != hipSuccess) return e;
+        e = hipMemcpy(plan.splits, splits.data(), splits.size() * sizeof(SpmmSplit), hipMemcpyHostToDevice);
+    }
+    return e;
+}
+
+hipError_t grow(float*& buf, size_t& have, size_t want) {
+    if (want <= have) return hipSuccess;
+    hipError_t e = hipDeviceSynchronize();   // nothing may still be using the old buffer
+    if (e != hipSuccess) return e;
+    if (buf) (void)hipFree(buf);
+    buf = nullptr;
+    have = 0;
+    e = hipMalloc(reinterpret_cast<void**>(&buf), want * sizeof(float));
+    if (e == hipSuccess) have = want;
+    return e;
+}
+
+int32_t gemm_split_for(int32_t m, int32_t n, int64_t k) {
+    const int64_t tiles = int64_t((m + 127) / 128) * ((n + 127) / 128);
+    const int64_t k_tiles = (k + 15) / 16;
+    int64_t split = (1024 + tiles - 1) / tiles;          // about four workgroups per compute unit in total
+    split = std::min<int64_t>(split, std::max<int64_t>(1, k_tiles / 8));
+    return int32_t(std::max<int64_t>(1, split));
+}
+
+// Uploads the multiplier tables of every layer on first use (varco_create itself touches no device).
+int32_t ensure_tables(varco_ctx* ctx) {
+    for (LayerState& ls : ctx->layers) {
+        if (ls.units) continue;
+        const size_t bytes = ls.h_units.size() * sizeof(uint16_t);
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ls.units), bytes));
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ls.units_inv), bytes));
+        VARCO_HIP(ctx, hipMemcpy(ls.units, ls.h_units.data(), bytes, hipMemcpyHostToDevice));
+        VARCO_HIP(ctx, hipMemcpy(ls.units_inv, ls.h_units_inv.data(), bytes, hipMemcpyHostToDevice));
+    }
+    return VARCO_OK;
+}
+
+int32_t check_layer(const varco_ctx* ctx, int32_t layer, const char* fn) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "null context");
+    if (layer < 0 || layer >= ctx->n_layers) {
+        std::string m = std::string(fn) + ": layer out of range";
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, m.c_str());
+    }
+    return VARCO_OK;
+}
+
+int32_t check_part(const varco_ctx* ctx, int32_t q, const char* fn) {
+    if (q < 0 || q >= ctx->n_parts) {
+        std::string m = std::string(fn) + ": partition out of range";
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, m.c_str());
+    }
+    if (!ctx->parts[q].registered) {
+        std::string m = std::string(fn) + ": partition is not registered";
+        return varco_fail(ctx, VARCO_ERR_STATE, m.c_str());
+    }
+    return VARCO_OK;
+}
+
+}  // namespace
+
+extern "C" const char* varco_last_error(const varco_ctx* ctx) {
+    if (ctx) return ctx->error.c_str();
+    std::lock_guard<std::mutex> lock(g_err_mutex);
+    return g_global_error.c_str();
+}
+
+extern "C" int32_t varco_create(const varco_config* cfg, varco_ctx** out) {
+    if (!out) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_create: out is null");
+    *out = nullptr;
+    if (!cfg || !cfg->widths || !cfg->act) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_create: null config field");
+    if (cfg->n_layers < 1 || cfg->n_layers > VARCO_MAX_LAYERS)
+        return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_create: n_layers outside 1..VARCO_MAX_LAYERS");
+    if (cfg->n_partitions < 1) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_create: n_partitions must be positive");
+    if (cfg->conv != VARCO_CONV_GCN && cfg->conv != VARCO_CONV_SAGE)
+        return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: unknown conv");
+    if (cfg->dtype != VARCO_F32) return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: only fp32 storage is implemented");
+    for (int32_t l = 0; l <= cfg->n_layers; ++l) {
+        const int32_t w = cfg->widths[l];
+        if (w < 1 || w > VARCO_MAX_WIDTH) return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_create: width outside 1..VARCO_MAX_WIDTH");
+        if (w % 4 != 0 && w > 512)
+            return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: widths above 512 must be multiples of 4");
+    }
+    for (int32_t l = 0; l < cfg->n_layers; ++l)
+        if (cfg->act[l] != VARCO_ACT_IDENTITY && cfg->act[l] != VARCO_ACT_RELU)
+            return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: unknown activation");
+
+    auto* ctx = new varco_ctx;
+    ctx->n_layers = cfg->n_layers;
+    ctx->n_parts = cfg->n_partitions;
+    ctx->conv = cfg->conv;
+    ctx->dtype = cfg->dtype;
+    ctx->key = cfg->mask_key;
+    ctx->widths.assign(cfg->widths, cfg->widths + cfg->n_layers + 1);
+    ctx->act.assign(cfg->act, cfg->act + cfg->n_layers);
+    ctx->layers.resize(cfg->n_layers);
+    ctx->parts.resize(cfg->n_partitions);
+    ctx->stats.bytes_per_elem = 4;
+    for (int32_t l = 0; l < ctx->n_layers; ++l) {
+        LayerState& ls = ctx->layers[l];
+        const int32_t w = ctx->widths[l];
+        ls.k = w;
+        // multipliers coprime with the width and their inverses (a * a_inv = 1 mod width)
+        std::vector<uint16_t> units, inv;
+        for (int32_t a = 1; a < std::max(w, 2); ++a)
+            if (std::gcd(a, w) == 1) units.push_back(uint16_t(a));
+        for (uint16_t a : units) {
+            int64_t t = 0, nt = 1, r = w, nr = a % w;     // extended Euclid
+            while (nr != 0) {
+                const int64_t qd = r / nr;
+                std::swap(t, nt), nt -= qd * t;
+                std::swap(r, nr), nr -= qd * r;
+            }
+            inv.push_back(uint16_t(((t % w) + w) % w));
+        }
+        ls.n_units = int32_t(units.size());
+        ls.h_units = units;
+        ls.h_units_inv = inv;
+    }
+    *out = ctx;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_destroy(varco_ctx* ctx) {
+    if (!ctx) return VARCO_OK;
+    (void)hipDeviceSynchronize();
+    for (LayerState& ls : ctx->layers) {
+        if (ls.units) (void)hipFree(ls.units);
+        if (ls.units_inv) (void)hipFree(ls.units_inv);
+    }
+    for (PartState& ps : ctx->parts) free_part(ps);
+    if (ctx->ws_dm) (void)hipFree(ctx->ws_dm);
+    if (ctx->ws_spmm) (void)hipFree(ctx->ws_spmm);
+    if (ctx->ws_gemm) (void)hipFree(ctx->ws_gemm);
+    delete ctx;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const varco_partition_desc* dev) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_register_partition: null context");
+    if (!dev) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null descriptor");
+    if (q < 0 || q >= ctx->n_parts) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: partition out of range");
+    if (dev->n_local < 0 || dev->n_halo < 0 || dev->n_boundary < 0 || dev->nnz < 0 || dev->z_row_offset < 0 ||
+        dev->n_boundary > dev->n_local)
+        return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: negative or inconsistent sizes");
+    if (dev->nnz >= (int64_t(1) << 31) || int64_t(dev->n_local) + dev->n_halo >= (int64_t(1) << 31))
+        return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: partition too large for 32-bit row pointers");
+    if (!dev->rowptr || !dev->t_rowptr || !dev->local_gid || !dev->halo_owner_ptr)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null index array");
+    if (dev->nnz > 0 && (!dev->colidx || !dev->vals || !dev->t_colidx || !dev->t_vals))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null entry array");
+    if (dev->n_halo > 0 && (!dev->halo_gid || !dev->halo_zrow || !dev->halo_src_row))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null halo array");
+    if (dev->n_boundary > 0 && !dev->boundary_rows)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null boundary array");
+
+    VARCO_HIP(ctx, hipDeviceSynchronize());
+    if (int32_t rc = ensure_tables(ctx)) return rc;
+    PartState& ps = ctx->parts[q];
+    free_part(ps);
+    ps.d = *dev;
+    const int32_t nl = dev->n_local, nh = dev->n_halo, nb = dev->n_boundary;
+
+    std::vector<int32_t> rowptr(size_t(nl) + 1), t_rowptr(size_t(nl) + nh + 1);
+    VARCO_HIP(ctx, hipMemcpy(rowptr.data(), dev->rowptr, rowptr.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    VARCO_HIP(ctx, hipMemcpy(t_rowptr.data(), dev->t_rowptr, t_rowptr.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+    auto monotone = [](const std::vector<int32_t>& p, int64_t nnz) {
+        if (p.front() != 0 || p.back() != nnz) return false;
+        for (size_t i = 1; i < p.size(); ++i)
+            if (p[i] < p[i - 1]) return false;
+        return true;
+    };
+    if (!monotone(rowptr, dev->nnz) || !monotone(t_rowptr, dev->nnz)) {
+        free_part(ps);
+        return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: row pointers do not match nnz");
+    }
+    VARCO_HIP(ctx, build_plan(rowptr, 0, nl, ps.fwd));
+    VARCO_HIP(ctx, build_plan(t_rowptr, 0, nl, ps.t_local));
+    VARCO_HIP(ctx, build_plan(t_rowptr, nl, nl + nh, ps.t_halo));
+
+    if (nh > 0) {
+        std::vector<int32_t> zrow(nh), gid(nh);
+        VARCO_HIP(ctx, hipMemcpy(zrow.data(), dev->halo_zrow, size_t(nh) * sizeof(int32_t), hipMemcpyDeviceToHost));
+        VARCO_HIP(ctx, hipMemcpy(gid.data(), dev->halo_gid, size_t(nh) * sizeof(int32_t), hipMemcpyDeviceToHost));
+        std::vector<HaloDesc> desc(nh);
+        for (int32_t s = 0; s < nh; ++s) {
+            if (zrow[s] < 0 || gid[s] < 0) {
+                free_part(ps);
+                return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: negative halo row or id");
+            }
+            desc[s] = {zrow[s], gid[s]};
+        }
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.halo_desc), size_t(nh) * sizeof(HaloDesc)));
+        VARCO_HIP(ctx, hipMemcpy(ps.halo_desc, desc.data(), size_t(nh) * sizeof(HaloDesc), hipMemcpyHostToDevice));
+    }
+    if (nb > 0) {
+        std::vector<int32_t> lgid(nl), brow(nb), bgid(nb);
+        VARCO_HIP(ctx, hipMemcpy(lgid.data(), dev->local_gid, size_t(nl) * sizeof(int32_t), hipMemcpyDeviceToHost));
+        VARCO_HIP(ctx, hipMemcpy(brow.data(), dev->boundary_rows, size_t(nb) * sizeof(int32_t), hipMemcpyDeviceToHost));
+        for (int32_t i = 0; i < nb; ++i) {
+            if (brow[i] < 0 || brow[i] >= nl) {
+                free_part(ps);
+                return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: boundary row outside the partition");
+            }
+            bgid[i] = lgid[brow[i]];
+        }
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.boundary_gid), size_t(nb) * sizeof(int32_t)));
+        VARCO_HIP(ctx, hipMemcpy(ps.boundary_gid, bgid.data(), size_t(nb) * sizeof(int32_t), hipMemcpyHostToDevice));
+    }
+
+    // workspace: dM and partial rows sized for the widest layer, split-K partials for the largest weight
+    const int32_t wmax = *std::max_element(ctx->widths.begin(), ctx->widths.end());
+    int64_t max_partials = std::max({ps.fwd.n_partials, ps.t_local.n_partials, ps.t_halo.n_partials});
+    int64_t gemm_elems = 0;
+    for (int32_t l = 0; l < ctx->n_layers; ++l) {
+        const int32_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
+        gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl)) * fi * fo);
+    }
+    VARCO_HIP(ctx, grow(ctx->ws_dm, ctx->ws_dm_elems, size_t(nl) * wmax));
+    VARCO_HIP(ctx, grow(ctx->ws_spmm, ctx->ws_spmm_elems, size_t(max_partials) * wmax));
+    VARCO_HIP(ctx, grow(ctx->ws_gemm, ctx->ws_gemm_elems, size_t(gemm_elems)));
+    ps.registered = true;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_begin_step(varco_ctx* ctx, uint64_t step) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_begin_step: null context");
+    ctx->step = step;
+    for (LayerState& ls : ctx->layers) ls.ran_forward = false;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, uint32_t den) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_set_ratio: null context");
+    if (layer < -1 || layer >= ctx->n_layers) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_ratio: layer out of range");
+    if (den == 0 || num < den) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_ratio: ratio must be a rational >= 1");
+    const int32_t l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->n_layers : layer + 1;
+    for (int32_t l = l0; l < l1; ++l)
+        if (ctx->layers[l].ran_forward)
+            return varco_fail(ctx, VARCO_ERR_STATE,
+                              "varco_set_ratio: the layer already ran forward in this step; call varco_begin_step first");
+    for (int32_t l = l0; l < l1; ++l) {
+        ctx->layers[l].num = num;
+        ctx->layers[l].den = den;
+        ctx->layers[l].k = keep_count(ctx->widths[l], num, den);
+    }
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_get_keep(const varco_ctx* ctx, int32_t layer, int32_t* k) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_get_keep")) return rc;
+    if (!k) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_get_keep: null output");
+    *k = ctx->layers[layer].k;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
+                                  int64_t n_rows, const void* x, int64_t ldx, void* z, varco_stream stream) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_compress")) return rc;
+    if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: negative row count");
+    if (n_rows == 0) return VARCO_OK;
+    if (!gids || !x || !z) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_compress: null pointer");
+    if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: ldx is smaller than the layer width");
+    if (int32_t rc = ensure_tables(ctx)) return rc;
+    ctx->layers[layer].ran_forward = true;   // the step's positions of this layer are now in use
+    const MaskRule rule = make_rule(ctx, layer);
+    VARCO_HIP(ctx, varco_launch_compress(rule, gids, rows, n_rows, static_cast<const float*>(x), ldx,
+                                         static_cast<float*>(z), static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
+                                    int64_t n_rows, const void* z, void* x, int64_t ldx, int32_t accumulate,
+                                    varco_stream stream) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_decompress")) return rc;
+    if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: negative row count");
+    if (accumulate != 0 && accumulate != 1) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: accumulate must be 0 or 1");
+    if (n_rows == 0) return VARCO_OK;
+    if (!gids || !x || !z) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: null pointer");
+    if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: ldx is smaller than the layer width");
+    if (int32_t rc = ensure_tables(ctx)) return rc;
+    ctx->layers[layer].ran_forward = true;
+    const MaskRule rule = make_rule(ctx, layer);
+    VARCO_HIP(ctx, varco_launch_decompress(rule, gids, rows, n_rows, static_cast<const float*>(z), static_cast<float*>(x),
+                                           ldx, accumulate, static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_local, const void* z_in,
+                                   const void* h1, const void* h0, void* x_out, void* z_out, void* m_saved,
+                                   varco_stream stream) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_layer_fwd")) return rc;
+    if (int32_t rc = check_part(ctx, q, "varco_layer_fwd")) return rc;
+    const PartState& ps = ctx->parts[q];
+    const varco_partition_desc& d = ps.d;
+    const bool sage = ctx->conv == VARCO_CONV_SAGE;
+    if (!h1 || (d.n_local > 0 && (!x_local || !x_out || !m_saved)))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: null pointer");
+    if (sage && !h0) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: h0 is required for the SAGE convolution");
+    if (!sage && h0) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: h0 must be null for the single-tap convolution");
+    if (d.n_halo > 0 && !z_in) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_in is null but the partition has halo nodes");
+    if (z_out && layer == ctx->n_layers - 1)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_out must be null on the last layer");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+    const MaskRule rule = make_rule(ctx, layer);
+    ctx->layers[layer].ran_forward = true;
+
+    // aggregate: local rows dense, halo rows straight from the owners' compressed buffers
+    VARCO_HIP(ctx, varco_launch_spmm(ps.fwd, d.colidx, d.vals, d.n_local, static_cast<const float*>(x_local), ps.halo_desc,
+                                     static_cast<const float*>(z_in), rule, static_cast<float*>(m_saved), 0, ctx->ws_spmm, st));
+    // transform + nonlinearity
+    GemmArgs g;
+    g.m = d.n_local, g.n = fo, g.k = fi;
+    g.a.ptr = static_cast<const float*>(m_saved), g.a.ld = fi;
+    g.b.ptr = static_cast<const float*>(h1), g.b.ld = fo;
+    if (sage) {
+        g.k2 = fi;
+        g.a2.ptr = static_cast<const float*>(x_local), g.a2.ld = fi;
+        g.b2.ptr = static_cast<const float*>(h0), g.b2.ld = fo;
+    }
+    g.c = static_cast<float*>(x_out), g.ldc = fo;
+    g.relu = ctx->act[layer] == VARCO_ACT_RELU;
+    VARCO_HIP(ctx, varco_launch_gemm(g, st));
+    // boundary rows of the output, compressed for the next layer's exchange
+    if (z_out && d.n_boundary > 0) {
+        ctx->layers[layer + 1].ran_forward = true;   // its positions are now in use
+        const MaskRule next = make_rule(ctx, layer + 1);
+        float* zdst = static_cast<float*>(z_out) + int64_t(d.z_row_offset) * next.k;
+        VARCO_HIP(ctx, varco_launch_compress(next, ps.boundary_gid, d.boundary_rows, d.n_boundary,
+                                             static_cast<const float*>(x_out), fo, zdst, st));
+    }
+    ctx->stats.fwd_elems[layer] += int64_t(d.n_halo) * rule.k;
+    ctx->stats.full_fwd_elems[layer] += int64_t(d.n_halo) * fi;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx_out, const void* x_out,
+                                   const void* x_local, const void* m_saved, const void* h1, const void* h0,
+                                   void* dh1, void* dh0, void* dx_local, void* dz_halo, varco_stream stream) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_layer_bwd")) return rc;
+    if (int32_t rc = check_part(ctx, q, "varco_layer_bwd")) return rc;
+    const PartState& ps = ctx->parts[q];
+    const varco_partition_desc& d = ps.d;
+    const bool sage = ctx->conv == VARCO_CONV_SAGE;
+    if (!h1 || !dh1 || (d.n_local > 0 && (!dx_out || !x_out || !x_local || !m_saved)))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: null pointer");
+    if (sage && (!h0 || !dh0)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: h0 and dh0 are required for the SAGE convolution");
+    if (!sage && (h0 || dh0)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: h0 and dh0 must be null for the single-tap convolution");
+    if (!dx_local && dz_halo) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo given without dx_local");
+    if (dx_local && d.n_halo > 0 && !dz_halo)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo is null but the partition has halo nodes");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+    const float* gate = ctx->act[layer] == VARCO_ACT_RELU ? static_cast<const float*>(x_out) : nullptr;
+    const int32_t nl = d.n_local;
+    if (nl == 0) return VARCO_OK;
+
+    // weight gradients: reductions over the partition's rows, split over workgroups
+    const int32_t split = gemm_split_for(fi, fo, nl);
+    if (size_t(split) * fi * fo > ctx->ws_gemm_elems) return varco_fail(ctx, VARCO_ERR_STATE, "varco_layer_bwd: workspace too small");
+    {
+        GemmArgs g;
+        g.m = fi, g.n = fo, g.k = nl;
+        g.a.ptr = static_cast<const float*>(m_saved), g.a.ld = fi, g.a.transposed = true;
+        g.b.ptr = static_cast<const float*>(dx_out), g.b.gate = gate, g.b.ld = fo;
+        g.c = static_cast<float*>(dh1), g.ldc = fo;
+        g.accumulate = true;
+        g.split_k = split, g.partial = ctx->ws_gemm;
+        VARCO_HIP(ctx, varco_launch_gemm(g, st));
+        if (sage) {
+            g.a.ptr = static_cast<const float*>(x_local);
+            g.c = static_cast<float*>(dh0);
+            VARCO_HIP(ctx, varco_launch_gemm(g, st));
+        }
+    }
+    if (!dx_local) return VARCO_OK;
+
+    // dM = dZ H1^T
+    {
+        GemmArgs g;
+        g.m = nl, g.n = fi, g.k = fo;
+        g.a.ptr = static_cast<const float*>(dx_out), g.a.gate = gate, g.a.ld = fo;
+        g.b.ptr = static_cast<const float*>(h1), g.b.ld = fo, g.b.transposed = true;
+        g.c = ctx->ws_dm, g.ldc = fi;
+        VARCO_HIP(ctx, varco_launch_gemm(g, st));
+    }
+    // transposed aggregation: local rows in full, halo rows only at their kept positions
+    const MaskRule rule = make_rule(ctx, layer);
+    const MaskRule dense_rule = full_rule(fi);
+    VARCO_HIP(ctx, varco_launch_spmm(ps.t_local, d.t_colidx, d.t_vals, INT_MAX, ctx->ws_dm, nullptr, nullptr, dense_rule,
+                                     static_cast<float*>(dx_local), 0, ctx->ws_spmm, st));
+    if (d.n_halo > 0) {
+        if (rule.k == rule.width) {
+            VARCO_HIP(ctx, varco_launch_spmm(ps.t_halo, d.t_colidx, d.t_vals, INT_MAX, ctx->ws_dm, nullptr, nullptr, dense_rule,
+                                             static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st));
+        } else {
+            VARCO_HIP(ctx, varco_launch_spmm_kept(ps.t_halo, d.t_colidx, d.t_vals, ctx->ws_dm, d.halo_gid, rule,
+                                                  static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st));
+        }
+        ctx->stats.bwd_elems[layer] += int64_t(d.n_halo) * rule.k;
+        ctx->stats.full_bwd_elems[layer] += int64_t(d.n_halo) * fi;
+    }
+    // self tap: dX_loc += dZ H0^T
+    if (sage) {
+        GemmArgs g;
+        g.m = nl, g.n = fi, g.k = fo;
+        g.a.ptr = static_cast<const float*>(dx_out), g.a.gate = gate, g.a.ld = fo;
+        g.b.ptr = static_cast<const float*>(h0), g.b.ld = fo, g.b.transposed = true;
+        g.c = static_cast<float*>(dx_local), g.ldc = fi;
+        g.accumulate = true;
+        VARCO_HIP(ctx, varco_launch_gemm(g, st));
+    }
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_get_stats(const varco_ctx* ctx, varco_stats* out) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_get_stats: null context");
+    if (!out) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_get_stats: null output");
+    *out = ctx->stats;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_reset_stats(varco_ctx* ctx) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_reset_stats: null context");
+    const int32_t b = ctx->stats.bytes_per_elem;
+    ctx->stats = varco_stats{};
+    ctx->stats.bytes_per_elem = b;
+    return VARCO_OK;
+}

@@ -1,0 +1,84 @@
+// Internal declarations shared by the translation units of libvarco (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "varco.h"
+
+// Records `msg` as the last error of ctx (or of the process when ctx is null) and returns `code`.
+int32_t varco_fail(const varco_ctx* ctx, int32_t code, const char* msg);
+
+// The kept positions of a node vector (Definition 1 / Appendix A of the paper, with this library's keyed
+// rule): pi_v(j) = (a_v * j + b_v) mod width, j < k, where b_v = floor(h1 * width / 2^32), a_v =
+// units[floor(h2 * n_units / 2^32)], h1 = mix(v ^ s0), h2 = mix(h1 ^ s1), and (s0, s1) are derived on the
+// host from (key, step, layer). k == width means the identity. Passed by value to kernels.
+struct MaskRule {
+    uint32_t s0, s1;
+    uint32_t width, k;
+    uint32_t n_units;
+    uint32_t width_magic;       // floor(2^32 / width), 0xFFFFFFFF for width 1
+    const uint16_t* units;      // device: ascending multipliers coprime with width
+    const uint16_t* units_inv;  // device: their inverses modulo width
+};
+
+// One unit of SpMM work: entries [e0, e1) of CSR row `row`; dst < 0 writes the output row directly, else
+// the partial sum goes to slot dst of the partial buffer (rows longer than the chunk length are split).
+struct SpmmItem {
+    int32_t row, e0, e1, dst;
+};
+// A split row and the contiguous range of partial slots that add up to it.
+struct SpmmSplit {
+    int32_t row, first, count, pad;
+};
+struct SpmmPlan {
+    int32_t n_items = 0, n_splits = 0, n_partials = 0;
+    SpmmItem* items = nullptr;    // device
+    SpmmSplit* splits = nullptr;  // device
+};
+
+struct HaloDesc {
+    int32_t zrow, gid;
+};
+
+hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                                 const float* x, int64_t ldx, float* z, hipStream_t stream);
+hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream);
+
+// out[row - row_base, :] = sum_e vals[e] * src(colidx[e]) for the rows of `plan`, width = rule.width.
+//   colidx[e] <  n_dense_cols : src = dense + colidx[e] * width          (full row)
+//   colidx[e] >= n_dense_cols : halo slot s = colidx[e] - n_dense_cols, the k kept elements
+//                               z[desc[s].zrow * k + j] land at pi_gid(j)  (full row when k == width)
+// partial: workspace of plan.n_partials * width floats.
+hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const float* vals, int32_t n_dense_cols,
+                             const float* dense, const HaloDesc* desc, const float* z, const MaskRule& rule,
+                             float* out, int32_t row_base, float* partial, hipStream_t stream);
+
+// out[row - row_base, j] = sum_e vals[e] * src[colidx[e] * width + pi_v(j)], j < k, v = gids[row - row_base]
+// (the halo rows of the transposed aggregation, produced directly in compressed form).
+hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, const float* vals, const float* src,
+                                  const int32_t* gids, const MaskRule& rule, float* out, int32_t row_base,
+                                  float* partial, hipStream_t stream);
+
+// C (+)= op(A) op(B) in fp32 on the matrix cores, row-major everywhere.
+struct GemmOperand {
+    const float* ptr = nullptr;   // matrix as stored
+    const float* gate = nullptr;  // optional, same shape: elements are used only where gate > 0 (ReLU mask)
+    int64_t ld = 0;
+    bool transposed = false;      // false: stored [rows=M or K][cols=K or N]; true: stored the other way round
+};
+struct GemmArgs {
+    int32_t m = 0, n = 0, k = 0;
+    GemmOperand a, b;             // first product
+    GemmOperand a2, b2;           // optional second product summed into the same C (k2 reduction length)
+    int32_t k2 = 0;
+    float* c = nullptr;
+    int64_t ldc = 0;
+    bool accumulate = false;      // C += instead of C =
+    bool relu = false;            // C = max(., 0)
+    int32_t split_k = 1;          // > 1: partial products into `partial` then reduced in a second kernel
+    float* partial = nullptr;     // split_k * m * n floats
+};
+hipError_t varco_launch_gemm(const GemmArgs& g, hipStream_t stream);

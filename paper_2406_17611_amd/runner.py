@@ -1,0 +1,154 @@
+"""Harness that holds all partitions of a graph in one GPU's memory and drives the C ABI "in turn":
+Algorithm 1's forward and backward for every layer and partition, with the inter-machine exchange
+replaced by on-device buffers (the compressed rows an owner writes are read in place by its consumers).
+
+Only sequencing and buffer bookkeeping live here; all arithmetic is in libvarco's kernels.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as vb
+
+
+class PartitionedNetwork:
+    def __init__(self, host_parts, widths, conv: str, mask_key: int, device="cuda", need_backward=True):
+        self.device = torch.device(device)
+        self.host_parts = host_parts
+        self.P = len(host_parts)
+        self.widths = list(widths)
+        self.L = len(widths) - 1
+        self.conv = conv
+        act = [vb.ACT_RELU] * (self.L - 1) + [vb.ACT_IDENTITY]
+        self.ctx = vb.Context(self.widths, act, vb.CONV_SAGE if conv == "sage" else vb.CONV_GCN, self.P, mask_key)
+        self.dev_parts = [self.ctx.register_partition(q, hp, self.device) for q, hp in enumerate(host_parts)]
+
+        self.n_local = [hp.n_local for hp in host_parts]
+        self.n_halo = [hp.n_halo for hp in host_parts]
+        self.row_off = np.concatenate(([0], np.cumsum(self.n_local))).astype(np.int64)
+        self.halo_off = np.concatenate(([0], np.cumsum(self.n_halo))).astype(np.int64)
+        self.n_total = int(self.row_off[-1])
+        self.b_total = int(sum(hp.n_boundary for hp in host_parts))
+        self.nnz_total = int(sum(hp.nnz for hp in host_parts))
+
+        # owner-side targets of the returned errors: arena row of every halo node
+        self.halo_arena_row = []
+        self.boundary_gid = []
+        for q, hp in enumerate(host_parts):
+            rows = np.empty(hp.n_halo, dtype=np.int64)
+            for o in range(self.P):
+                s0, s1 = hp.halo_owner_ptr[o], hp.halo_owner_ptr[o + 1]
+                rows[s0:s1] = self.row_off[o] + host_parts[o].boundary_rows[hp.halo_src_row[s0:s1]]
+            assert rows.max(initial=0) < 2 ** 31
+            self.halo_arena_row.append(torch.from_numpy(rows.astype(np.int32)).to(self.device))
+            self.boundary_gid.append(torch.from_numpy(hp.local_gid[hp.boundary_rows]).to(self.device))
+
+        f32 = dict(dtype=torch.float32, device=self.device)
+        self.x = [torch.empty((self.n_total, w), **f32) for w in self.widths]
+        self.m = [torch.empty((self.n_total, self.widths[l]), **f32) for l in range(self.L)]
+        self.h1 = [torch.empty((self.widths[l], self.widths[l + 1]), **f32) for l in range(self.L)]
+        self.h0 = [torch.empty_like(h) if conv == "sage" else None for h in self.h1]
+        self.z = [None] * self.L           # allocated per step (k changes with the ratio)
+        self.need_backward = need_backward
+        if need_backward:
+            self.dh1 = [torch.zeros_like(h) for h in self.h1]
+            self.dh0 = [torch.zeros_like(h) if conv == "sage" else None for h in self.h1]
+            self.dx = [None] + [torch.empty((self.n_total, self.widths[l]), **f32) for l in range(1, self.L + 1)]
+            self.dz_halo = [None] * self.L
+        self._zcap = [0] * self.L
+        self._dzcap = [0] * self.L
+
+    # ------------------------------------------------------------------ data placement
+    def rows(self, q):
+        return slice(int(self.row_off[q]), int(self.row_off[q + 1]))
+
+    def set_inputs(self, x0_global: np.ndarray):
+        """Scatter a global [n, F_0] feature matrix into the partition-ordered arena."""
+        order = np.concatenate([hp.local_gid for hp in self.host_parts]).astype(np.int64)
+        self.x[0].copy_(torch.from_numpy(np.ascontiguousarray(x0_global[order])).to(self.device))
+
+    def set_weights(self, h1_list, h0_list=None):
+        for l in range(self.L):
+            self.h1[l].copy_(torch.from_numpy(h1_list[l]).to(self.device))
+            if self.conv == "sage":
+                self.h0[l].copy_(torch.from_numpy(h0_list[l]).to(self.device))
+
+    def set_upstream(self, dx_global: np.ndarray):
+        order = np.concatenate([hp.local_gid for hp in self.host_parts]).astype(np.int64)
+        self.dx[self.L].copy_(torch.from_numpy(np.ascontiguousarray(dx_global[order])).to(self.device))
+
+    def to_global(self, arena: torch.Tensor) -> np.ndarray:
+        order = np.concatenate([hp.local_gid for hp in self.host_parts]).astype(np.int64)
+        out = np.empty(tuple(arena.shape), dtype=np.float32)
+        out[order] = arena.cpu().numpy()
+        return out
+
+    # ------------------------------------------------------------------ one step
+    def _ensure_buffers(self):
+        for l in range(self.L):
+            k = self.ctx.keep(l)
+            need = self.b_total * k
+            if self._zcap[l] < need:
+                self.z[l] = torch.empty(max(need, 1), dtype=torch.float32, device=self.device)
+                self._zcap[l] = need
+            if self.need_backward and l > 0:
+                need = int(self.halo_off[-1]) * k
+                if self._dzcap[l] < need:
+                    self.dz_halo[l] = torch.empty(max(need, 1), dtype=torch.float32, device=self.device)
+                    self._dzcap[l] = need
+
+    def forward(self, step: int, ratio=None, stream=None):
+        """Forward of all layers and partitions for training step `step`. `ratio` = (num, den) for every layer
+        or a list of per-layer pairs: Algorithm 1 updates the rate at the step boundary."""
+        ctx = self.ctx
+        ctx.begin_step(step)
+        if ratio is not None:
+            if isinstance(ratio[0], (tuple, list)):
+                for l, (num, den) in enumerate(ratio):
+                    ctx.set_ratio(l, num, den)
+            else:
+                ctx.set_ratio(-1, ratio[0], ratio[1])
+        self._ensure_buffers()
+        # layer 0's exchange: owners compress the boundary rows of the input features
+        k0 = ctx.keep(0)
+        for p, hp in enumerate(self.host_parts):
+            if hp.n_boundary:
+                zp = self.z[0][hp.z_row_offset * k0:]
+                ctx.compress(0, self.boundary_gid[p], self.dev_parts[p]["boundary_rows"], hp.n_boundary,
+                             self.x[0][self.rows(p)], self.widths[0], zp, stream)
+        for l in range(self.L):
+            last = l == self.L - 1
+            for q in range(self.P):
+                r = self.rows(q)
+                ctx.layer_fwd(l, q, self.x[l][r], self.z[l], self.h1[l], self.h0[l], self.x[l + 1][r],
+                              None if last else self.z[l + 1], self.m[l][r], stream)
+
+    def backward(self, stream=None):
+        ctx = self.ctx
+        for l in range(self.L - 1, -1, -1):
+            need = l > 0
+            k = ctx.keep(l)
+            for q in range(self.P):
+                r = self.rows(q)
+                dzh = None
+                if need and self.n_halo[q]:
+                    dzh = self.dz_halo[l][int(self.halo_off[q]) * k:]
+                ctx.layer_bwd(l, q, self.dx[l + 1][r], self.x[l + 1][r], self.x[l][r], self.m[l][r], self.h1[l],
+                              self.h0[l], self.dh1[l], self.dh0[l], self.dx[l][r] if need else None, dzh, stream)
+            if need:
+                # errors handed back: owners add them at the kept positions, consumers in ascending order
+                for q in range(self.P):
+                    if self.n_halo[q]:
+                        ctx.decompress(l, self.dev_parts[q]["halo_gid"], self.halo_arena_row[q], self.n_halo[q],
+                                       self.dz_halo[l][int(self.halo_off[q]) * k:], self.dx[l], self.widths[l], 1, stream)
+
+    def zero_grads(self):
+        for l in range(self.L):
+            self.dh1[l].zero_()
+            if self.dh0[l] is not None:
+                self.dh0[l].zero_()
+
+    def step(self, step: int, ratio=None, stream=None):
+        self.forward(step, ratio, stream)
+        self.backward(stream)

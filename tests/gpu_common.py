@@ -1,0 +1,57 @@
+"""Shared helpers of the GPU parity tests: the same seeded inputs go to the CPU oracle (oracle/) and to
+the HIP library (through its C ABI); nothing computed by one side is ever fed to the other."""
+import numpy as np
+import torch
+
+from oracle import partition as opart
+from paper_2406_17611_amd import binding as vb
+
+KEY = 0x240617611
+TOL = 1e-4   # norm-wise relative tolerance on fp32 activations and gradients
+
+
+def assert_close(got, ref, what, tol=TOL):
+    """||got - ref||_inf <= tol * ||ref||_inf  and  ||got - ref||_F <= tol * ||ref||_F."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    assert np.isfinite(got).all(), what
+    diff = got - ref
+    inf_ref, fro_ref = np.abs(ref).max(initial=0.0), np.linalg.norm(ref)
+    inf_err, fro_err = np.abs(diff).max(initial=0.0), np.linalg.norm(diff)
+    assert inf_err <= tol * inf_ref + 1e-30, f"{what}: max err {inf_err:.3e} vs {tol} * {inf_ref:.3e}"
+    assert fro_err <= tol * fro_ref + 1e-30, f"{what}: fro err {fro_err:.3e} vs {tol} * {fro_ref:.3e}"
+
+
+def both_partitions(g, part, n_parts):
+    host = vb.partition_build(g.n, g.rowptr, g.colidx, g.vals, part, n_parts)
+    orc = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, part, n_parts)
+    return host, orc
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def hub_graph(n, n_hubs, hub_deg, avg_deg, conv, seed):
+    """Random graph with a few very high-degree nodes, so that rows longer than the kernels' chunk
+    length (split rows) and many short rows occur together."""
+    from paper_2406_17611_amd import synth
+    rng = np.random.default_rng(seed)
+    m = int(n * avg_deg / 2)
+    u = rng.integers(0, n, size=m)
+    v = rng.integers(0, n, size=m)
+    hubs = rng.permutation(n)[:n_hubs]
+    hu = np.repeat(hubs, hub_deg)
+    hv = rng.integers(0, n, size=hu.shape[0])
+    u = np.concatenate([u, hu])
+    v = np.concatenate([v, hv])
+    keep = u != v
+    lo = np.minimum(u[keep], v[keep]).astype(np.int64)
+    hi = np.maximum(u[keep], v[keep]).astype(np.int64)
+    key = np.unique(lo * n + hi)
+    u, v = key // n, key % n
+    return synth.gcn_operator(n, u, v) if conv == "gcn" else synth.sage_mean_operator(n, u, v)

@@ -1,0 +1,104 @@
+"""GPU parity of the whole path (all layers, all partitions in turn, forward and backward, exchange
+hand-offs and owner-side accumulation) on the benchmark configurations the oracle finishes in seconds."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_common import KEY, assert_close, both_partitions
+from oracle import layer as olayer
+from oracle import mask as omask
+from paper_2406_17611_amd import synth
+from paper_2406_17611_amd.runner import PartitionedNetwork
+
+pytestmark = pytest.mark.gpu
+
+
+def _weights(widths, conv):
+    h1 = [synth.glorot(widths[l], widths[l + 1], synth.SEED_WEIGHT, 2 * l) for l in range(len(widths) - 1)]
+    h0 = [synth.glorot(widths[l], widths[l + 1], synth.SEED_WEIGHT, 2 * l + 1) for l in range(len(widths) - 1)] \
+        if conv == "sage" else None
+    return h1, h0
+
+
+def _f32(a):
+    return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4):
+    host, orc = both_partitions(g, part, n_parts)
+    L = len(widths) - 1
+    x0 = synth.features(g.n, widths[0], synth.SEED_FEAT)
+    dxl = synth.upstream_grad(g.n, widths[-1], synth.SEED_GRAD)
+    h1, h0 = _weights(widths, conv)
+    net = PartitionedNetwork(host, widths, conv, KEY)
+    net.set_inputs(x0)
+    net.set_weights(h1, h0)
+    net.set_upstream(dxl)
+    acts = [olayer.RELU] * (L - 1) + [olayer.IDENTITY]
+    weights = [(h1[l], h0[l] if h0 is not None else None) for l in range(L)]
+    for step, ratio in zip(steps, ratios):
+        net.zero_grads()
+        net.ctx.reset_stats()
+        net.step(step, ratio)
+        torch.cuda.synchronize()
+        keep = [omask.keep_count(widths[l], *ratio) for l in range(L)]
+        assert [net.ctx.keep(l) for l in range(L)] == keep
+        ref = olayer.network_step(orc, [x0[p.local_gid] for p in orc], weights, acts, keep, KEY, step,
+                                  [dxl[p.local_gid] for p in orc], round_store=_f32)
+        tag = f"step {step} ratio {ratio}"
+        for l in range(L):
+            assert_close(net.to_global(net.x[l + 1]), _gather(orc, ref["x"][l + 1], g.n), f"{tag} X_{l + 1}", tol)
+            assert_close(net.to_global(net.m[l]), _gather(orc, ref["m"][l], g.n), f"{tag} M_{l}", tol)
+            assert_close(net.dh1[l].cpu().numpy(), ref["dh"][l][0], f"{tag} dH1_{l}", tol)
+            if conv == "sage":
+                assert_close(net.dh0[l].cpu().numpy(), ref["dh"][l][1], f"{tag} dH0_{l}", tol)
+            k = keep[l]
+            z = net.z[l][:net.b_total * k].reshape(net.b_total, k).cpu().numpy()
+            if l == 0:
+                assert np.array_equal(z, ref["z"][0].astype(np.float32)), f"{tag} Z_0 must be bit-exact"
+            else:
+                assert_close(z, ref["z"][l], f"{tag} Z_{l}", tol)
+        for l in range(1, L):
+            assert_close(net.to_global(net.dx[l]), _gather(orc, ref["dx"][l], g.n), f"{tag} dX_{l}", tol)
+        st = net.ctx.stats()
+        assert st["fwd_elems"] == ref["fwd_elems"] and st["bwd_elems"] == ref["bwd_elems"], tag
+    return net
+
+
+def _gather(parts, per_part, n):
+    out = np.empty((n, per_part[0].shape[1]))
+    for p in parts:
+        out[p.local_gid] = per_part[p.q]
+    return out
+
+
+def test_tiny_config_full_step():
+    w = synth.make_workload("tiny")
+    _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, [(4, 1), (1, 1)], steps=[0, 1])
+
+
+def test_medium_config_all_ratios():
+    w = synth.make_workload("medium")
+    _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, list(w.ratios), steps=list(range(len(w.ratios))))
+
+
+def test_medium_bfs16_config_on_the_variable_schedule():
+    w = synth.make_workload("medium_bfs16")
+    steps = [0, 1, 50, 98, 99]
+    _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, [w.ratios[t] for t in steps], steps=steps)
+
+
+def test_sage_network_small():
+    g = synth.small_random_graph(3000, 10.0, "sage", seed=31)
+    part = synth.random_partition(g.n, 4, seed=32)
+    _compare_network(g, part, 4, "sage", (100, 256, 256, 47), [(8, 1), (2, 1)], steps=[5, 6])
+
+
+def test_two_runs_give_identical_bits():
+    w = synth.make_workload("tiny")
+    outs = []
+    for _ in range(2):
+        net = _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, [(4, 1)], steps=[7])
+        outs.append([t.cpu().numpy().copy() for t in net.x[1:] + net.dh1 + net.dx[1:]])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)

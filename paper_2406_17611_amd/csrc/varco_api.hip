@@ -312,7 +312,7 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
         return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: negative or inconsistent sizes");
     if (dev->nnz >= (int64_t(1) << 31) || int64_t(dev->n_local) + dev->n_halo >= (int64_t(1) << 31))
         return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: partition too large for 32-bit row pointers");
-    if (!dev->rowptr || !dev->t_rowptr || !dev->local_gid || !dev->halo_owner_ptr)
+    if (!dev->rowptr || !dev->t_rowptr || !dev->halo_owner_ptr || (dev->n_local > 0 && !dev->local_gid))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null index array");
     if (dev->nnz > 0 && (!dev->colidx || !dev->vals || !dev->t_colidx || !dev->t_vals))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null entry array");

@@ -39,25 +39,37 @@ def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4):
     for step, ratio in zip(steps, ratios):
         net.zero_grads()
         net.ctx.reset_stats()
-        net.step(step, ratio)
+        net.forward(step, ratio)
         torch.cuda.synchronize()
         keep = [omask.keep_count(widths[l], *ratio) for l in range(L)]
         assert [net.ctx.keep(l) for l in range(L)] == keep
         ref = olayer.network_step(orc, [x0[p.local_gid] for p in orc], weights, acts, keep, KEY, step,
                                   [dxl[p.local_gid] for p in orc], round_store=_f32)
         tag = f"step {step} ratio {ratio}"
+        # forward: free-running chain on both sides
         for l in range(L):
             assert_close(net.to_global(net.x[l + 1]), _gather(orc, ref["x"][l + 1], g.n), f"{tag} X_{l + 1}", tol)
             assert_close(net.to_global(net.m[l]), _gather(orc, ref["m"][l], g.n), f"{tag} M_{l}", tol)
-            assert_close(net.dh1[l].cpu().numpy(), ref["dh"][l][0], f"{tag} dH1_{l}", tol)
-            if conv == "sage":
-                assert_close(net.dh0[l].cpu().numpy(), ref["dh"][l][1], f"{tag} dH0_{l}", tol)
             k = keep[l]
             z = net.z[l][:net.b_total * k].reshape(net.b_total, k).cpu().numpy()
             if l == 0:
                 assert np.array_equal(z, ref["z"][0].astype(np.float32)), f"{tag} Z_0 must be bit-exact"
             else:
                 assert_close(z, ref["z"][l], f"{tag} Z_{l}", tol)
+        # backward: the ReLU gate [x_out > 0] is a discrete decision, so both sides must take it on the same
+        # stored activations. The oracle's stored (fp32) activations and aggregates become the saved tensors
+        # of the device path; the gradient chain itself (dX through all layers, returned errors, owner-side
+        # accumulation, weight-gradient sums) then runs free on the device.
+        for l in range(L + 1):
+            net.x[l].copy_(torch.from_numpy(np.vstack(ref["x"][l]).astype(np.float32)))
+        for l in range(L):
+            net.m[l].copy_(torch.from_numpy(np.vstack(ref["m"][l]).astype(np.float32)))
+        net.backward()
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert_close(net.dh1[l].cpu().numpy(), ref["dh"][l][0], f"{tag} dH1_{l}", tol)
+            if conv == "sage":
+                assert_close(net.dh0[l].cpu().numpy(), ref["dh"][l][1], f"{tag} dH0_{l}", tol)
         for l in range(1, L):
             assert_close(net.to_global(net.dx[l]), _gather(orc, ref["dx"][l], g.n), f"{tag} dX_{l}", tol)
         st = net.ctx.stats()

@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the VARCO layer hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over the workload: for every layer and every partition in turn,
+compress boundary rows, aggregate (local rows + compressed halo rows), transform, activate, then the
+backward of the same (weight gradients, dM, transposed aggregation, compressed error hand-back, owner-side
+accumulation). Inputs are seeded synthetic graphs shaped like the paper's datasets and are resident in HBM
+before the timed region starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large_sage|medium|tiny|medium_bfs16]
+
+Prints one JSON line: whole-job GEdges/s (directed CSR entries x layers per step / step time), the roofline
+figures of the dominant kernel measured live with HIP events, and the CPU oracle's rate on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
+HBM_CLASSES = ("compress", "decompress", "agg_fwd", "agg_bwd_local", "agg_bwd_halo", "reduce")
+MFMA_CLASSES = ("gemm_fwd", "gemm_wgrad", "gemm_dgrad")
+DEFAULT_RATIO = {"tiny": (4, 1), "medium": (8, 1), "medium_bfs16": (1584 - 15 * 50, 99), "large_sage": (8, 1)}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, ratio, budget_note=""):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: one partition, the middle
+    (hidden -> hidden) layer, forward + backward. Returns the dict reported under "cpu_baseline"."""
+    import numpy as np
+    from threadpoolctl import threadpool_info, threadpool_limits
+
+    from oracle import layer as olayer
+    from oracle import mask as omask
+    from oracle import partition as opart
+    from paper_2406_17611_amd import synth
+
+    g = w.graph
+    cores = min(os.cpu_count() or 1, 16)
+    layer = 1 if len(w.widths) > 2 else 0
+    fi, fo = w.widths[layer], w.widths[layer + 1]
+    k = omask.keep_count(fi, *ratio)
+    p = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, w.part, w.n_parts, only=[0])[0]
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((p.n_local, fi)).astype(np.float32)
+    z_all = rng.standard_normal((int(p.halo_zrow.max(initial=-1)) + 1, k)).astype(np.float32)
+    h1 = synth.glorot(fi, fo, synth.SEED_WEIGHT, 2 * layer)
+    h0 = synth.glorot(fi, fo, synth.SEED_WEIGHT, 2 * layer + 1) if w.conv == "sage" else None
+    dxo = rng.standard_normal((p.n_local, fo)).astype(np.float32)
+    with threadpool_limits(limits=cores):
+        t0 = time.perf_counter()
+        cols = omask.kept_columns(p.halo_gid, fi, k, synth.MASK_KEY, 0, layer)
+        xo, m = olayer.layer_forward(p, x, z_all, cols, h1, h0, olayer.RELU)
+        olayer.layer_backward(p, dxo, xo, x, m, cols, h1, h0, olayer.RELU, True)
+        dt = time.perf_counter() - t0
+    return {"value": p.nnz / dt / 1e9, "unit": "GEdges/s", "cores": cores, "kind": "oracle",
+            "sample": f"partition 0 of {w.n_parts}, layer {layer + 1} of {len(w.widths) - 1} ({fi}->{fo}, k={k}), "
+                      f"forward+backward, {p.nnz} directed entries, {dt:.1f} s; numpy/scipy fp64, BLAS threads "
+                      f"capped at {cores} (the sparse products run on one){budget_note}"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large_sage")
+    ap.add_argument("--ratio", default=None, help="num/den, default: the configuration's ratio")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-only", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the partitions of the paper's setting are held in "
+                 "one MI355X's memory and processed in turn); --gpus must be 1")
+
+    from paper_2406_17611_amd import synth
+    ratio = DEFAULT_RATIO.get(args.workload, (8, 1))
+    if args.ratio:
+        num, _, den = args.ratio.partition("/")
+        ratio = (int(num), int(den or 1))
+
+    t0 = time.time()
+    w = synth.make_workload(args.workload)
+    if w.dtype != "f32":
+        sys.exit("bench.py: only fp32 workloads are implemented")
+    g = w.graph
+    log(f"[bench] workload {w.name}: n={g.n} nnz={g.nnz} P={w.n_parts} conv={w.conv} widths={w.widths} "
+        f"ratio={ratio} (generated in {time.time() - t0:.1f}s)")
+    if args.cpu_baseline_only:
+        print(json.dumps(cpu_baseline(w, ratio)))
+        return
+
+    import numpy as np
+    import torch
+
+    from paper_2406_17611_amd import binding as vb
+    from paper_2406_17611_amd.runner import PartitionedNetwork
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t0 = time.time()
+    host = vb.partition_build(g.n, g.rowptr, g.colidx, g.vals, w.part, w.n_parts)
+    log(f"[bench] partitions built in {time.time() - t0:.1f}s: halo rows {sum(h.n_halo for h in host)}, "
+        f"boundary rows {sum(h.n_boundary for h in host)}")
+    t0 = time.time()
+    L = len(w.widths) - 1
+    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY)
+    net.set_inputs(synth.features(g.n, w.widths[0], synth.SEED_FEAT))
+    net.set_weights([synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l) for l in range(L)],
+                    [synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l + 1) for l in range(L)])
+    net.set_upstream(synth.upstream_grad(g.n, w.widths[-1], synth.SEED_GRAD))
+    torch.cuda.synchronize()
+    log(f"[bench] device buffers ready in {time.time() - t0:.1f}s, "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated by torch")
+
+    for s in range(args.warmup):
+        net.step(s, ratio)
+    torch.cuda.synchronize()
+    net.ctx.reset_stats()
+    net.ctx.profile_enable(True)
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        net.step(args.warmup + s, ratio)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = net.ctx.profile_read()
+    net.ctx.profile_enable(False)
+    stats = net.ctx.stats()
+    ms_per_step = dt * 1e3 / args.steps
+    edges_per_step = L * net.nnz_total
+    assert all(torch.isfinite(t).all().item() for t in net.dh1), "non-finite weight gradient"
+
+    kernels = {}
+    for name, p in prof.items():
+        if not p["launches"]:
+            continue
+        avg_ms = p["ms"] / p["launches"]
+        entry = {"launches_per_step": p["launches"] / args.steps, "ms_per_step": p["ms"] / args.steps,
+                 "avg_launch_ms": avg_ms}
+        if name in MFMA_CLASSES:
+            ach = p["flops"] / p["ms"] / 1e9
+            entry.update(bound="mfma", achieved=ach, peak=MFMA_FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                         frac=ach / MFMA_FP32_PEAK_TFLOPS)
+        else:
+            ach = p["bytes"] / p["ms"] / 1e6
+            entry.update(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
+        kernels[name] = entry
+    dominant = max((n for n in kernels if n != "reduce"), key=lambda n: kernels[n]["ms_per_step"])
+    d = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
+                "unit": d["unit"], "frac": d["frac"], "traffic": None, "avg_launch_ms": d["avg_launch_ms"]}
+
+    bpe = stats["bytes_per_elem"]
+    out = {
+        "metric": "GNN layer fwd+bwd GEdges/s at 1 GPU",
+        "value": edges_per_step / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GEdges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "nodes": g.n, "directed_entries": g.nnz, "partitions": w.n_parts,
+                   "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
+                   "keep": [net.ctx.keep(l) for l in range(L)], "layers": L,
+                   "edges_counted_per_step": edges_per_step},
+        "roofline": roofline,
+        "kernels": kernels,
+        "exchanged_bytes_per_step": {
+            "forward": sum(stats["fwd_elems"]) * bpe // args.steps,
+            "backward": sum(stats["bwd_elems"]) * bpe // args.steps,
+            "forward_at_ratio_1": sum(stats["full_fwd_elems"]) * bpe // args.steps,
+            "backward_at_ratio_1": sum(stats["full_bwd_elems"]) * bpe // args.steps},
+    }
+    if not args.no_cpu_baseline:
+        del net
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w, ratio)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

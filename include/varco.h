@@ -187,6 +187,37 @@ int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx
 int32_t varco_get_stats(const varco_ctx* ctx, varco_stats* out);
 int32_t varco_reset_stats(varco_ctx* ctx);
 
+/* ------------------------------------------------------------------------------------------------
+ * Per-kernel timing for roofline reports (not part of the method). While enabled, every kernel launch of
+ * the library is bracketed by a pair of HIP events on the launch stream. varco_profile_read synchronises
+ * those events and returns, per kernel class, the number of launches, the summed duration in ms and the
+ * summed algorithmic work of those launches: bytes the method itself must move (CSR entries and row
+ * pointers, each local row once, each halo row once in compressed form, each output row once) for the
+ * memory-bound classes, floating-point operations (2 m n k) for the matrix-core classes.
+ */
+enum {
+    VARCO_K_COMPRESS = 0,       /* encoder: boundary rows -> k kept elements */
+    VARCO_K_DECOMPRESS = 1,     /* decoder / owner-side accumulation of returned errors */
+    VARCO_K_AGG_FWD = 2,        /* M = S_q [X_loc ; compressed halo] */
+    VARCO_K_GEMM_FWD = 3,       /* act(M H1 + X H0) */
+    VARCO_K_GEMM_WGRAD = 4,     /* dH += M^T dZ, X^T dZ (split reduction, partial products) */
+    VARCO_K_GEMM_DGRAD = 5,     /* dM = dZ H1^T, dX += dZ H0^T */
+    VARCO_K_AGG_BWD_LOCAL = 6,  /* dX_loc = S_loc^T dM */
+    VARCO_K_AGG_BWD_HALO = 7,   /* dZ_halo = kept positions of S_halo^T dM */
+    VARCO_K_REDUCE = 8,         /* fixed-order sums of split rows / split reductions */
+    VARCO_K_COUNT = 9
+};
+typedef struct {
+    int64_t launches[VARCO_K_COUNT];
+    double ms[VARCO_K_COUNT];
+    double bytes[VARCO_K_COUNT];
+    double flops[VARCO_K_COUNT];
+} varco_profile;
+int32_t varco_profile_enable(varco_ctx* ctx, int32_t on);
+/* Synchronises the recorded events (blocks until the bracketed work has finished); reset != 0 clears the
+ * totals afterwards. */
+int32_t varco_profile_read(varco_ctx* ctx, varco_profile* out, int32_t reset);
+
 #ifdef __cplusplus
 }
 #endif

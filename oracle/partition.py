@@ -55,7 +55,8 @@ class Partition:
 
 
 def build_partitions(n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray,
-                     part: np.ndarray, n_parts: int) -> list[Partition]:
+                     part: np.ndarray, n_parts: int, only=None) -> list[Partition]:
+    """All partitions' structures, or just those listed in `only` (same values, less work)."""
     rowptr = np.asarray(rowptr, dtype=np.int64)
     colidx = np.asarray(colidx, dtype=np.int64)
     part = np.asarray(part, dtype=np.int64)
@@ -66,9 +67,25 @@ def build_partitions(n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.nd
         local_index[mine] = np.arange(mine.shape[0])
         locals_of.append(mine)
 
-    parts: list[Partition] = []
+    # boundary nodes: referenced by a row that another partition owns
+    row_owner = np.repeat(part, np.diff(rowptr))
     needed_by_others = np.zeros(n, dtype=bool)
-    for q in range(n_parts):
+    needed_by_others[colidx[row_owner != part[colidx]]] = True
+    del row_owner
+    boundary_index = np.full(n, -1, dtype=np.int64)    # position inside the owner's boundary list
+    boundary_rows, offsets = [], []
+    offset = 0
+    for p in range(n_parts):
+        mine = locals_of[p]
+        brow = np.nonzero(needed_by_others[mine])[0]
+        boundary_rows.append(brow.astype(np.int32))
+        boundary_index[mine[brow]] = np.arange(brow.shape[0])
+        offsets.append(offset)
+        offset += brow.shape[0]
+    offsets = np.asarray(offsets, dtype=np.int64)
+
+    parts: list[Partition] = []
+    for q in (range(n_parts) if only is None else only):
         mine = locals_of[q]
         n_local = mine.shape[0]
         lens = rowptr[mine + 1] - rowptr[mine]
@@ -86,7 +103,6 @@ def build_partitions(n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.nd
         halo = halo[order]
         n_halo = halo.shape[0]
         owner_ptr = np.searchsorted(part[halo], np.arange(n_parts + 1), side="left").astype(np.int64)
-        needed_by_others[halo] = True
 
         slot = np.empty(n, dtype=np.int64)              # scratch map gid -> halo slot (valid on halo only)
         slot[halo] = np.arange(n_halo)
@@ -101,32 +117,17 @@ def build_partitions(n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.nd
         t_counts = np.bincount(newcol, minlength=n_local + n_halo)
         t_rowptr = np.concatenate(([0], np.cumsum(t_counts))).astype(np.int64)
 
+        src = boundary_index[halo]
+        assert (src >= 0).all()
         parts.append(Partition(
             q=q, n_local=int(n_local), n_halo=int(n_halo),
             local_gid=mine.astype(np.int32), halo_gid=halo.astype(np.int32),
             halo_owner_ptr=owner_ptr.astype(np.int32),
             rowptr=my_rowptr.astype(np.int32), colidx=newcol.astype(np.int32), vals=val.astype(np.float32),
             t_rowptr=t_rowptr.astype(np.int32), t_colidx=row_of[tperm].astype(np.int32),
-            t_vals=val[tperm].astype(np.float32)))
-
-    # boundary lists and where each halo node sits in its owner's list
-    boundary_index = np.full(n, -1, dtype=np.int64)
-    offset = 0
-    offsets = []
-    for p in range(n_parts):
-        mine = locals_of[p]
-        brow = np.nonzero(needed_by_others[mine])[0]
-        parts[p].boundary_rows = brow.astype(np.int32)
-        boundary_index[mine[brow]] = np.arange(brow.shape[0])
-        parts[p].z_row_offset = offset
-        offsets.append(offset)
-        offset += brow.shape[0]
-    offsets = np.asarray(offsets, dtype=np.int64)
-    for pq in parts:
-        src = boundary_index[pq.halo_gid.astype(np.int64)]
-        assert (src >= 0).all()
-        pq.halo_src_row = src.astype(np.int32)
-        pq.halo_zrow = (src + offsets[part[pq.halo_gid.astype(np.int64)]]).astype(np.int32)
+            t_vals=val[tperm].astype(np.float32),
+            boundary_rows=boundary_rows[q], halo_src_row=src.astype(np.int32),
+            halo_zrow=(src + offsets[part[halo]]).astype(np.int32), z_row_offset=int(offsets[q])))
     return parts
 
 

@@ -25,8 +25,10 @@ EXPORTS = [
     "varco_create", "varco_destroy", "varco_register_partition", "varco_last_error",
     "varco_begin_step", "varco_set_ratio", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
-    "varco_get_stats", "varco_reset_stats",
+    "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
 ]
+KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
+                  "agg_bwd_halo", "reduce"]
 
 
 class Config(C.Structure):
@@ -49,6 +51,11 @@ class Stats(C.Structure):
     _fields_ = [("fwd_elems", C.c_int64 * MAX_LAYERS), ("bwd_elems", C.c_int64 * MAX_LAYERS),
                 ("full_fwd_elems", C.c_int64 * MAX_LAYERS), ("full_bwd_elems", C.c_int64 * MAX_LAYERS),
                 ("bytes_per_elem", C.c_int32)]
+
+
+class Profile(C.Structure):
+    _fields_ = [("launches", C.c_int64 * 9), ("ms", C.c_double * 9), ("bytes", C.c_double * 9),
+                ("flops", C.c_double * 9)]
 
 
 class VarcoError(RuntimeError):
@@ -85,6 +92,8 @@ def lib() -> C.CDLL:
         L.varco_layer_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.varco_get_stats.argtypes = [vp, C.POINTER(Stats)]
         L.varco_reset_stats.argtypes = [vp]
+        L.varco_profile_enable.argtypes = [vp, i32]
+        L.varco_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         for name in EXPORTS:
             if name not in ("varco_partition_free", "varco_last_error"):
                 getattr(L, name).restype = i32
@@ -254,3 +263,13 @@ class Context:
 
     def reset_stats(self):
         _check(lib().varco_reset_stats(self._h), self._h)
+
+    def profile_enable(self, on: bool):
+        _check(lib().varco_profile_enable(self._h, int(on)), self._h)
+
+    def profile_read(self, reset: bool = True) -> dict:
+        """Per kernel class: launches, total ms, algorithmic bytes and flops of the bracketed launches."""
+        p = Profile()
+        _check(lib().varco_profile_read(self._h, C.byref(p), int(reset)), self._h)
+        return {name: dict(launches=p.launches[i], ms=p.ms[i], bytes=p.bytes[i], flops=p.flops[i])
+                for i, name in enumerate(KERNEL_CLASSES)}

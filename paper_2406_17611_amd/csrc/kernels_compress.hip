@@ -96,17 +96,21 @@ unsigned grid_for(int64_t n_rows, int g_log2) {
 }  // namespace
 
 hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                 const float* x, int64_t ldx, float* z, hipStream_t stream) {
+                                 const float* x, int64_t ldx, float* z, hipStream_t stream, const LaunchTag& tag) {
     if (n_rows == 0) return hipSuccess;
     const int gl = group_log2(rule.k);
+    tag.begin(stream);
     hipLaunchKernelGGL(compress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows, n_rows,
                        x, ldx, z, gl);
+    tag.end(stream);
     return hipGetLastError();
 }
 
 hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream) {
+                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream,
+                                   const LaunchTag& tag) {
     if (n_rows == 0) return hipSuccess;
+    tag.begin(stream);
     if (accumulate) {
         const int gl = group_log2(rule.k);
         hipLaunchKernelGGL(decompress_add_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids,
@@ -116,5 +120,6 @@ hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, co
         hipLaunchKernelGGL(decompress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
                            n_rows, z, x, ldx, gl);
     }
+    tag.end(stream);
     return hipGetLastError();
 }

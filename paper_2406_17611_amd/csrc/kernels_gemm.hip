@@ -245,7 +245,7 @@ OperandDev make_operand(const GemmOperand& o, bool stored_k_contig) {
 
 }  // namespace
 
-hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream) {
+hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag) {
     if (ga.m == 0 || ga.n == 0) return hipSuccess;
     GemmDev g;
     g.m = ga.m, g.n = ga.n, g.k = ga.k, g.k2 = ga.k2;
@@ -278,13 +278,17 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream) {
     }
     const int64_t blocks = int64_t((g.outer + 7) / 8 * 8) * g.inner;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    tag.begin(stream);
     hipLaunchKernelGGL(gemm_kernel, dim3(unsigned(blocks)), dim3(kThreads), 0, stream, g);
+    tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (split > 1) {
         const int64_t mn = int64_t(ga.m) * ga.n;
+        tag.begin_as(VARCO_K_REDUCE, stream);
         hipLaunchKernelGGL(gemm_reduce_kernel, dim3(unsigned((mn + kThreads - 1) / kThreads)), dim3(kThreads), 0,
                            stream, ga.partial, split, mn, ga.n, ga.c, ga.ldc, g.accumulate, g.relu);
+        tag.end(stream);
         err = hipGetLastError();
     }
     return err;

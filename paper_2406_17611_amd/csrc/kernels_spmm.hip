@@ -269,7 +269,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const float* vals, int32_t n_dense_cols,
                              const float* dense, const HaloDesc* desc, const float* z, const MaskRule& rule,
-                             float* out, int32_t row_base, float* partial, hipStream_t stream) {
+                             float* out, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag) {
     if (plan.n_items == 0) return hipSuccess;
     const int32_t width = int32_t(rule.width);
     const bool full = rule.k == rule.width;
@@ -300,12 +300,16 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const 
     a.k_magic = rule.k > 1 ? uint32_t((uint64_t(1) << 32) / rule.k) + 1u : 0u;
     const dim3 grid((plan.n_items + kWaves - 1) / kWaves);
     const size_t lds_bytes = size_t(kWaves) * width * sizeof(float);
+    tag.begin(stream);
     hipError_t err = vec4 ? launch_spmm_vec<4>(nv, a, grid, lds_bytes, stream)
                           : launch_spmm_vec<1>(nv, a, grid, lds_bytes, stream);
+    tag.end(stream);
     if (err != hipSuccess) return err;
     if (plan.n_splits > 0) {
+        tag.begin_as(VARCO_K_REDUCE, stream);
         hipLaunchKernelGGL(spmm_fixup_kernel, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
                            partial, out, row_base, width);
+        tag.end(stream);
         err = hipGetLastError();
     }
     return err;
@@ -313,7 +317,7 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const 
 
 hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, const float* vals, const float* src,
                                   const int32_t* gids, const MaskRule& rule, float* out, int32_t row_base,
-                                  float* partial, hipStream_t stream) {
+                                  float* partial, hipStream_t stream, const LaunchTag& tag) {
     if (plan.n_items == 0) return hipSuccess;
     KeptArgs a;
     a.items = plan.items;
@@ -330,12 +334,16 @@ hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, c
     while ((1u << g_log2) < rule.k && g_log2 < 6) ++g_log2;
     a.g_log2 = g_log2;
     const dim3 grid((plan.n_items + kWaves - 1) / kWaves);
+    tag.begin(stream);
     hipLaunchKernelGGL(spmm_kept_kernel, grid, dim3(kBlock), 0, stream, a);
+    tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (plan.n_splits > 0) {
+        tag.begin_as(VARCO_K_REDUCE, stream);
         hipLaunchKernelGGL(spmm_fixup_kernel, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
                            partial, out, row_base, int32_t(rule.k));
+        tag.end(stream);
         err = hipGetLastError();
     }
     return err;

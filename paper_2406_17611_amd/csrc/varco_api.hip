@@ -31,6 +31,7 @@ struct PartState {
     SpmmPlan fwd, t_local, t_halo;
     HaloDesc* halo_desc = nullptr;   // device [n_halo]
     int32_t* boundary_gid = nullptr; // device [n_boundary]
+    int64_t nnz_t_local = 0;         // transposed entries whose row is a local node
 };
 
 std::mutex g_err_mutex;
@@ -49,7 +50,16 @@ struct varco_ctx {
     float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
     float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
     varco_stats stats{};
+    VarcoProfiler prof;
+    double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
+    int64_t prof_launches[VARCO_K_COUNT] = {};
     mutable std::string error;
+    LaunchTag tag(int cls, double bytes, double flops) {
+        LaunchTag t;
+        t.prof = prof.on ? &prof : nullptr;
+        t.cls = cls, t.bytes = bytes, t.flops = flops;
+        return t;
+    }
 };
 
 int32_t varco_fail(const varco_ctx* ctx, int32_t code, const char* msg) {
@@ -299,6 +309,11 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     if (ctx->ws_dm) (void)hipFree(ctx->ws_dm);
     if (ctx->ws_spmm) (void)hipFree(ctx->ws_spmm);
     if (ctx->ws_gemm) (void)hipFree(ctx->ws_gemm);
+    for (VarcoProfiler::Rec& r : ctx->prof.recs) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
     delete ctx;
     return VARCO_OK;
 }
@@ -341,6 +356,7 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
         free_part(ps);
         return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: row pointers do not match nnz");
     }
+    ps.nnz_t_local = t_rowptr[nl];
     VARCO_HIP(ctx, build_plan(rowptr, 0, nl, ps.fwd));
     VARCO_HIP(ctx, build_plan(t_rowptr, 0, nl, ps.t_local));
     VARCO_HIP(ctx, build_plan(t_rowptr, nl, nl + nh, ps.t_halo));
@@ -431,8 +447,10 @@ extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* 
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;   // the step's positions of this layer are now in use
     const MaskRule rule = make_rule(ctx, layer);
+    const double bytes = double(n_rows) * (rule.width + rule.k) * 4.0;
     VARCO_HIP(ctx, varco_launch_compress(rule, gids, rows, n_rows, static_cast<const float*>(x), ldx,
-                                         static_cast<float*>(z), static_cast<hipStream_t>(stream)));
+                                         static_cast<float*>(z), static_cast<hipStream_t>(stream),
+                                         ctx->tag(VARCO_K_COMPRESS, bytes, 0)));
     return VARCO_OK;
 }
 
@@ -448,8 +466,10 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;
     const MaskRule rule = make_rule(ctx, layer);
+    const double bytes = accumulate ? double(n_rows) * rule.k * 12.0 : double(n_rows) * (rule.width + rule.k) * 4.0;
     VARCO_HIP(ctx, varco_launch_decompress(rule, gids, rows, n_rows, static_cast<const float*>(z), static_cast<float*>(x),
-                                           ldx, accumulate, static_cast<hipStream_t>(stream)));
+                                           ldx, accumulate, static_cast<hipStream_t>(stream),
+                                           ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));
     return VARCO_OK;
 }
 
@@ -474,8 +494,11 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     ctx->layers[layer].ran_forward = true;
 
     // aggregate: local rows dense, halo rows straight from the owners' compressed buffers
+    const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * 4.0 +
+                             double(d.n_halo) * rule.k * 4.0;
     VARCO_HIP(ctx, varco_launch_spmm(ps.fwd, d.colidx, d.vals, d.n_local, static_cast<const float*>(x_local), ps.halo_desc,
-                                     static_cast<const float*>(z_in), rule, static_cast<float*>(m_saved), 0, ctx->ws_spmm, st));
+                                     static_cast<const float*>(z_in), rule, static_cast<float*>(m_saved), 0, ctx->ws_spmm, st,
+                                     ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0)));
     // transform + nonlinearity
     GemmArgs g;
     g.m = d.n_local, g.n = fo, g.k = fi;
@@ -488,14 +511,15 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     }
     g.c = static_cast<float*>(x_out), g.ldc = fo;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
-    VARCO_HIP(ctx, varco_launch_gemm(g, st));
+    VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
     if (z_out && d.n_boundary > 0) {
         ctx->layers[layer + 1].ran_forward = true;   // its positions are now in use
         const MaskRule next = make_rule(ctx, layer + 1);
         float* zdst = static_cast<float*>(z_out) + int64_t(d.z_row_offset) * next.k;
         VARCO_HIP(ctx, varco_launch_compress(next, ps.boundary_gid, d.boundary_rows, d.n_boundary,
-                                             static_cast<const float*>(x_out), fo, zdst, st));
+                                             static_cast<const float*>(x_out), fo, zdst, st,
+                                             ctx->tag(VARCO_K_COMPRESS, double(d.n_boundary) * (next.width + next.k) * 4.0, 0)));
     }
     ctx->stats.fwd_elems[layer] += int64_t(d.n_halo) * rule.k;
     ctx->stats.full_fwd_elems[layer] += int64_t(d.n_halo) * fi;
@@ -534,11 +558,12 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.c = static_cast<float*>(dh1), g.ldc = fo;
         g.accumulate = true;
         g.split_k = split, g.partial = ctx->ws_gemm;
-        VARCO_HIP(ctx, varco_launch_gemm(g, st));
+        const LaunchTag wtag = ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl));
+        VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
         if (sage) {
             g.a.ptr = static_cast<const float*>(x_local);
             g.c = static_cast<float*>(dh0);
-            VARCO_HIP(ctx, varco_launch_gemm(g, st));
+            VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
         }
     }
     if (!dx_local) return VARCO_OK;
@@ -550,20 +575,26 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.a.ptr = static_cast<const float*>(dx_out), g.a.gate = gate, g.a.ld = fo;
         g.b.ptr = static_cast<const float*>(h1), g.b.ld = fo, g.b.transposed = true;
         g.c = ctx->ws_dm, g.ldc = fi;
-        VARCO_HIP(ctx, varco_launch_gemm(g, st));
+        VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
     const MaskRule rule = make_rule(ctx, layer);
     const MaskRule dense_rule = full_rule(fi);
+    const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * 4.0;
+    const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + (double(d.n_halo) + 1.0) * 4.0 + double(nl) * fi * 4.0 +
+                            double(d.n_halo) * rule.k * 4.0;
     VARCO_HIP(ctx, varco_launch_spmm(ps.t_local, d.t_colidx, d.t_vals, INT_MAX, ctx->ws_dm, nullptr, nullptr, dense_rule,
-                                     static_cast<float*>(dx_local), 0, ctx->ws_spmm, st));
+                                     static_cast<float*>(dx_local), 0, ctx->ws_spmm, st,
+                                     ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
     if (d.n_halo > 0) {
         if (rule.k == rule.width) {
             VARCO_HIP(ctx, varco_launch_spmm(ps.t_halo, d.t_colidx, d.t_vals, INT_MAX, ctx->ws_dm, nullptr, nullptr, dense_rule,
-                                             static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st));
+                                             static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st,
+                                             ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             VARCO_HIP(ctx, varco_launch_spmm_kept(ps.t_halo, d.t_colidx, d.t_vals, ctx->ws_dm, d.halo_gid, rule,
-                                                  static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st));
+                                                  static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st,
+                                                  ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         }
         ctx->stats.bwd_elems[layer] += int64_t(d.n_halo) * rule.k;
         ctx->stats.full_bwd_elems[layer] += int64_t(d.n_halo) * fi;
@@ -576,7 +607,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = static_cast<const float*>(h0), g.b.ld = fo, g.b.transposed = true;
         g.c = static_cast<float*>(dx_local), g.ldc = fi;
         g.accumulate = true;
-        VARCO_HIP(ctx, varco_launch_gemm(g, st));
+        VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     return VARCO_OK;
 }
@@ -593,5 +624,36 @@ extern "C" int32_t varco_reset_stats(varco_ctx* ctx) {
     const int32_t b = ctx->stats.bytes_per_elem;
     ctx->stats = varco_stats{};
     ctx->stats.bytes_per_elem = b;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_profile_enable(varco_ctx* ctx, int32_t on) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_profile_enable: null context");
+    ctx->prof.on = on != 0;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_profile_read(varco_ctx* ctx, varco_profile* out, int32_t reset) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_profile_read: null context");
+    if (!out) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_profile_read: null output");
+    for (VarcoProfiler::Rec& r : ctx->prof.recs) {
+        VARCO_HIP(ctx, hipEventSynchronize(r.stop));
+        float ms = 0.f;
+        VARCO_HIP(ctx, hipEventElapsedTime(&ms, r.start, r.stop));
+        ctx->prof_ms[r.cls] += ms;
+        ctx->prof_bytes[r.cls] += r.bytes;
+        ctx->prof_flops[r.cls] += r.flops;
+        ctx->prof_launches[r.cls] += 1;
+        ctx->prof.pool.push_back(r.start);
+        ctx->prof.pool.push_back(r.stop);
+    }
+    ctx->prof.recs.clear();
+    for (int c = 0; c < VARCO_K_COUNT; ++c) {
+        out->launches[c] = ctx->prof_launches[c];
+        out->ms[c] = ctx->prof_ms[c];
+        out->bytes[c] = ctx->prof_bytes[c];
+        out->flops[c] = ctx->prof_flops[c];
+        if (reset) ctx->prof_launches[c] = 0, ctx->prof_ms[c] = ctx->prof_bytes[c] = ctx->prof_flops[c] = 0.0;
+    }
     return VARCO_OK;
 }

@@ -4,8 +4,50 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <vector>
 
 #include "varco.h"
+
+// Brackets kernel launches with HIP events on the launch stream (see varco_profile_enable).
+struct VarcoProfiler {
+    struct Rec {
+        int cls;
+        hipEvent_t start, stop;
+        double bytes, flops;
+    };
+    bool on = false;
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get() {
+        if (!pool.empty()) {
+            hipEvent_t e = pool.back();
+            pool.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+    void begin(int cls, hipStream_t st, double bytes, double flops) {
+        if (!on) return;
+        Rec r{cls, get(), get(), bytes, flops};
+        (void)hipEventRecord(r.start, st);
+        recs.push_back(r);
+    }
+    void end(hipStream_t st) {
+        if (!on) return;
+        (void)hipEventRecord(recs.back().stop, st);
+    }
+};
+// Work attributed to one launch, handed from the API layer to the launchers.
+struct LaunchTag {
+    VarcoProfiler* prof = nullptr;
+    int cls = 0;
+    double bytes = 0, flops = 0;
+    void begin(hipStream_t st) const { if (prof) prof->begin(cls, st, bytes, flops); }
+    void begin_as(int other, hipStream_t st) const { if (prof) prof->begin(other, st, 0, 0); }
+    void end(hipStream_t st) const { if (prof) prof->end(st); }
+};
 
 // Records `msg` as the last error of ctx (or of the process when ctx is null) and returns `code`.
 int32_t varco_fail(const varco_ctx* ctx, int32_t code, const char* msg);
@@ -43,9 +85,10 @@ struct HaloDesc {
 };
 
 hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                 const float* x, int64_t ldx, float* z, hipStream_t stream);
+                                 const float* x, int64_t ldx, float* z, hipStream_t stream, const LaunchTag& tag);
 hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream);
+                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream,
+                                   const LaunchTag& tag);
 
 // out[row - row_base, :] = sum_e vals[e] * src(colidx[e]) for the rows of `plan`, width = rule.width.
 //   colidx[e] <  n_dense_cols : src = dense + colidx[e] * width          (full row)
@@ -54,13 +97,13 @@ hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, co
 // partial: workspace of plan.n_partials * width floats.
 hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const float* vals, int32_t n_dense_cols,
                              const float* dense, const HaloDesc* desc, const float* z, const MaskRule& rule,
-                             float* out, int32_t row_base, float* partial, hipStream_t stream);
+                             float* out, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag);
 
 // out[row - row_base, j] = sum_e vals[e] * src[colidx[e] * width + pi_v(j)], j < k, v = gids[row - row_base]
 // (the halo rows of the transposed aggregation, produced directly in compressed form).
 hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, const float* vals, const float* src,
                                   const int32_t* gids, const MaskRule& rule, float* out, int32_t row_base,
-                                  float* partial, hipStream_t stream);
+                                  float* partial, hipStream_t stream, const LaunchTag& tag);
 
 // C (+)= op(A) op(B) in fp32 on the matrix cores, row-major everywhere.
 struct GemmOperand {
@@ -81,4 +124,4 @@ struct GemmArgs {
     int32_t split_k = 1;          // > 1: partial products into `partial` then reduced in a second kernel
     float* partial = nullptr;     // split_k * m * n floats
 };
-hipError_t varco_launch_gemm(const GemmArgs& g, hipStream_t stream);
+hipError_t varco_launch_gemm(const GemmArgs& g, hipStream_t stream, const LaunchTag& tag);

@@ -60,7 +60,7 @@ def sbm_edges(block_sizes, p_in: float, p_out: float, seed: int) -> tuple[int, n
         hit = np.nonzero(rng.random(n - 1 - i) < p)[0]
         us.append(np.full(hit.shape, i, dtype=np.int64))
         vs.append(hit.astype(np.int64) + i + 1)
-    return n, np.concatenate(us), np.concatenate(vs)
+    return n, np.concatenate(us), np.concatenate(vs)          # u < v, sorted by (u, v)
 
 
 def chung_lu_edges(n: int, n_edges: int, exponent: float, seed: int) -> tuple[np.ndarray, np.ndarray]:
@@ -69,7 +69,8 @@ def chung_lu_edges(n: int, n_edges: int, exponent: float, seed: int) -> tuple[np
     Expected-degree weights w_i ~ (i+1)^(-1/(exponent-1)), scaled to sum 2*n_edges and capped at
     sqrt(2*n_edges) (so that w_u*w_v/sum(w) <= 1). Endpoints are drawn independently in proportion to w,
     loops and repeats are dropped, and the surplus is thinned uniformly to the exact edge count. Node
-    ids are shuffled so that id order carries no degree information.
+    ids are shuffled so that id order carries no degree information. Returned pairs have u < v and are
+    sorted by (u, v).
     """
     rng = _rng(seed)
     alpha = 1.0 / (exponent - 1.0)
@@ -78,71 +79,78 @@ def chung_lu_edges(n: int, n_edges: int, exponent: float, seed: int) -> tuple[np
     for _ in range(8):
         w *= (2.0 * n_edges) / w.sum()
         np.minimum(w, cap, out=w)
-    cdf = np.cumsum(w)
-    cdf /= cdf[-1]
+    prob = w / w.sum()
     relabel = rng.permutation(n).astype(np.int64)
+
+    def endpoints(m: int) -> np.ndarray:
+        # m independent draws in proportion to w, returned in ascending order: draw how often each node
+        # is hit (one multinomial) instead of searching a cumulative table m times
+        return np.repeat(np.arange(n, dtype=np.int64), rng.multinomial(m, prob))
 
     have = np.empty(0, dtype=np.int64)
     want = n_edges
     over = 1.12
     while have.shape[0] < want:
         m = int((want - have.shape[0]) * over) + 1024
-        u = np.searchsorted(cdf, rng.random(m), side="right")
-        v = np.searchsorted(cdf, rng.random(m), side="right")
-        np.minimum(u, n - 1, out=u)
-        np.minimum(v, n - 1, out=v)
+        u = relabel[endpoints(m)]
+        v = relabel[endpoints(m)[rng.permutation(m)]]     # random pairing of the two endpoint multisets
         keep = u != v
         u, v = u[keep], v[keep]
-        lo = np.minimum(u, v).astype(np.int64)
-        hi = np.maximum(u, v).astype(np.int64)
-        have = np.union1d(have, lo * n + hi)  # sorted unique keys
+        key = np.minimum(u, v) * n + np.maximum(u, v)
+        del u, v
+        have = np.unique(key) if have.shape[0] == 0 else np.union1d(have, key)
         over *= 1.5
     if have.shape[0] > want:
         drop = rng.choice(have.shape[0], size=have.shape[0] - want, replace=False)
         mask = np.ones(have.shape[0], dtype=bool)
         mask[drop] = False
         have = have[mask]
-    u = relabel[have // n]
-    v = relabel[have % n]
-    return u, v
+    return have // n, have % n
 
 
 # --------------------------------------------------------------------------------------------------
 # shift operators
 # --------------------------------------------------------------------------------------------------
 
-def _symmetric_csr(n: int, u: np.ndarray, v: np.ndarray, self_loops: bool) -> sp.csr_matrix:
-    rows = [u, v]
-    cols = [v, u]
+def _symmetric_csr(n: int, u: np.ndarray, v: np.ndarray, self_loops: bool):
+    """Pattern of A (+ I) as (rowptr int64, colidx int32) with ascending columns, from distinct
+    undirected pairs u < v sorted by (u, v)."""
+    m = u.shape[0]
+    assert (u < v).all()
+    up_cnt = np.bincount(u, minlength=n).astype(np.int64)          # entries (u -> v): columns above the row
+    up_ptr = np.concatenate(([0], np.cumsum(up_cnt)))
+    # entries (v -> u): transpose of the upper triangle by a counting sort (columns ascend within a row)
+    lower = sp.csr_matrix((np.ones(m, dtype=np.int8), v.astype(np.int32), up_ptr), shape=(n, n)).tocsc()
+    lo_ptr = lower.indptr.astype(np.int64)
+    lo_cnt = np.diff(lo_ptr)
+    self_cnt = 1 if self_loops else 0
+    rowptr = np.concatenate(([0], np.cumsum(lo_cnt + self_cnt + up_cnt)))
+    colidx = np.empty(int(rowptr[-1]), dtype=np.int32)
+    dest = np.repeat(rowptr[:-1] - lo_ptr[:-1], lo_cnt) + np.arange(m, dtype=np.int64)
+    colidx[dest] = lower.indices
+    dest = np.repeat(rowptr[:-1] + lo_cnt + self_cnt - up_ptr[:-1], up_cnt) + np.arange(m, dtype=np.int64)
+    colidx[dest] = v
     if self_loops:
-        d = np.arange(n, dtype=np.int64)
-        rows.append(d)
-        cols.append(d)
-    r = np.concatenate(rows)
-    c = np.concatenate(cols)
-    a = sp.coo_matrix((np.ones(r.shape[0], dtype=np.float32), (r, c)), shape=(n, n)).tocsr()
-    a.sum_duplicates()
-    a.sort_indices()
-    return a
+        colidx[rowptr[:-1] + lo_cnt] = np.arange(n, dtype=np.int32)
+    return rowptr, colidx
 
 
 def gcn_operator(n: int, u: np.ndarray, v: np.ndarray) -> Graph:
     """S = D~^{-1/2} (A + I) D~^{-1/2}, degrees of the whole graph (self-loop included)."""
-    a = _symmetric_csr(n, u, v, self_loops=True)
-    deg = np.diff(a.indptr).astype(np.float64)
-    dinv = 1.0 / np.sqrt(deg)
-    row_of = np.repeat(np.arange(n, dtype=np.int64), np.diff(a.indptr))
-    vals = (dinv[row_of] * dinv[a.indices]).astype(np.float32)
-    return Graph(n, a.indptr.astype(np.int64), a.indices.astype(np.int32), vals, int(u.shape[0]), True)
+    rowptr, colidx = _symmetric_csr(n, u, v, self_loops=True)
+    deg = np.diff(rowptr)
+    dinv = 1.0 / np.sqrt(deg.astype(np.float64))
+    vals = (np.repeat(dinv, deg) * dinv[colidx]).astype(np.float32)
+    return Graph(n, rowptr, colidx, vals, int(u.shape[0]), True)
 
 
 def sage_mean_operator(n: int, u: np.ndarray, v: np.ndarray) -> Graph:
     """S = D^{-1} A (mean over neighbours, no self-loop; isolated nodes have an empty row)."""
-    a = _symmetric_csr(n, u, v, self_loops=False)
-    deg = np.diff(a.indptr).astype(np.float64)
-    row_of = np.repeat(np.arange(n, dtype=np.int64), np.diff(a.indptr))
-    vals = (1.0 / deg[row_of]).astype(np.float32)
-    return Graph(n, a.indptr.astype(np.int64), a.indices.astype(np.int32), vals, int(u.shape[0]), False)
+    rowptr, colidx = _symmetric_csr(n, u, v, self_loops=False)
+    deg = np.diff(rowptr)
+    with np.errstate(divide="ignore"):
+        vals = np.repeat(1.0 / deg.astype(np.float64), deg).astype(np.float32)
+    return Graph(n, rowptr, colidx, vals, int(u.shape[0]), False)
 
 
 # --------------------------------------------------------------------------------------------------

@@ -1,28 +1,40 @@
 // Graph-convolution aggregation M = S_q [X_loc ; X~_halo] (eq. (1)-(2) of the paper; Algorithm 1: local
 // rows uncompressed, remote rows in compressed form) and its transpose for the backward pass.
 //
-// HBM-bound streaming kernels, one wavefront (64 lanes) per work item = a run of at most kSpmmChunk CSR
-// entries of one row; rows longer than that are split and their partial sums reduced in a second pass,
-// so the power-law hubs do not serialise on one wavefront and no floating-point atomics reach memory.
+// HBM-bound gather kernels. One wavefront (64 lanes) takes one work item = a run of at most 256 CSR entries
+// of one row; longer rows are split and their partial sums reduced in a second pass, so power-law hubs
+// do not serialise on one wavefront and no floating-point atomics reach memory. The kernels are latency
+// bound unless many loads are in flight, so every gather loop first issues a block of independent loads
+// and only then consumes them.
 //
 //   dense source rows (local rows; halo rows when k == width): a power-of-two group of lanes covers one
 //     row with 16-byte loads, the groups of a wavefront take different edges and are summed at the end
 //     with cross-lane shuffles (wavefront-level segmented reduction);
-//   compressed halo rows (k < width): never decompressed to memory. The k stored elements of several
-//     edges are loaded side by side (lane = (edge, j)), their positions pi_v(j) are recomputed from the
-//     key, and they are accumulated into a per-wavefront row in LDS.
+//   compressed halo rows (k < width): never decompressed to memory. The stored elements of several edges
+//     are loaded side by side (lane = (edge, j)), their positions pi_v(j) are recomputed from the key,
+//     and they are accumulated into a per-wavefront row in LDS.
+//
+// The forward kernel reads a per-entry record {source row, node id} that the library derives once from
+// the caller's column indices, so that a halo entry needs no dependent index lookups before its data load.
+#include <algorithm>
+
 #include "mask_device.h"
 
 namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
+constexpr int kUnroll = 4;   // independent gathers issued back to back
 
 template <int VEC>
 struct Vec;
 template <>
 struct Vec<4> {
     using type = float4;
+};
+template <>
+struct Vec<2> {
+    using type = float2;
 };
 template <>
 struct Vec<1> {
@@ -49,43 +61,112 @@ __device__ __forceinline__ float4 shfl_xor_vec(const float4& v, int mask) {
 __device__ __forceinline__ float shfl_xor_vec(const float& v, int mask) { return __shfl_xor(v, mask); }
 __device__ __forceinline__ void zero_vec(float4& v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
 __device__ __forceinline__ void zero_vec(float& v) { v = 0.f; }
+__device__ __forceinline__ void zero_vec(float2& v) { v = make_float2(0.f, 0.f); }
+__device__ __forceinline__ float elem(const float2& v, int i) { return i == 0 ? v.x : v.y; }
+__device__ __forceinline__ float elem(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+__device__ __forceinline__ float elem(const float& v, int) { return v; }
 
 struct SpmmArgs {
     const SpmmItem* items;
     int32_t n_items;
-    const int32_t* colidx;
+    const VarcoEdge* edge;    // HALO kernels: one record per CSR entry
+    const int32_t* colidx;    // dense-only kernels: column = source row
     const float* vals;
-    int32_t n_dense_cols;
     const float* dense;
-    const HaloDesc* desc;
     const float* z;
     MaskRule rule;
     float* out;
     int32_t row_base;
     float* partial;
-    int32_t lpr_log2;   // lanes per dense row = 1 << lpr_log2
-    uint32_t k_magic;   // floor(2^32 / k) + 1 for k > 1
+    int32_t lpr_log2;         // lanes per dense row = 1 << lpr_log2
+    int32_t ev;               // stored elements of a compressed row per lane and load: 4, 2 or 1
+    int32_t ku;               // loads per compressed row = k / ev
+    int32_t lpe_log2;         // lanes that share one compressed row = 1 << lpe_log2 (>= min(ku, 64))
+    int32_t epi;              // compressed rows handled per instruction = private LDS rows per wavefront
 };
 
+// Scatter-accumulate the compressed rows of the wavefront's current batch: lanes [nd, nd + ns) hold one
+// halo entry each (row in z, weight, packed (a, b)). A group of `lpe` lanes takes one entry (lane = group
+// of EV stored elements), `epi` entries are handled per instruction, and each of those lane groups adds
+// into a private LDS row of its own: the positions of one entry are distinct, so plain read-add-write is
+// race-free and no LDS atomics (which run at a small fraction of the plain LDS rate) are needed.
+template <int EV>
+__device__ __forceinline__ void sparse_phase(const SpmmArgs& p, int lane, int nd, int ns, int32_t srow, float w,
+                                             uint32_t mab, float* lpriv) {
+    using V = typename Vec<EV>::type;
+    const int32_t k = int32_t(p.rule.k);
+    const uint32_t width = p.rule.width;
+    const int sub = lane >> p.lpe_log2;
+    const int jl = lane & ((1 << p.lpe_log2) - 1);
+    const bool lane_ok = sub < p.epi && jl < p.ku;
+    float* row = lpriv + sub * int32_t(width);
+    for (int j0 = 0; j0 < p.ku; j0 += 64) {          // more than one pass only when an entry needs > 64 lanes
+        const int ju = j0 + jl;
+        const bool j_ok = lane_ok && ju < p.ku;
+        const int j = ju * EV;
+        for (int r0 = 0; r0 < ns; r0 += p.epi * kUnroll) {
+            V v[kUnroll];
+            float wi[kUnroll];
+            uint32_t pos[kUnroll], a[kUnroll];
+            bool act[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const int es = r0 + u * p.epi + sub;
+                act[u] = j_ok && es < ns;
+                const int src_lane = act[u] ? nd + es : 0;
+                const int32_t r = __shfl(srow, src_lane);
+                wi[u] = __shfl(w, src_lane);
+                const uint32_t ab = __shfl(mab, src_lane);
+                a[u] = ab & 0xFFFFu;
+                pos[u] = varco_mod_width(a[u] * uint32_t(j) + (ab >> 16), width, p.rule.width_magic);
+                zero_vec(v[u]);
+                if (act[u]) v[u] = *reinterpret_cast<const V*>(p.z + int64_t(r) * k + j);
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (act[u]) {
+                    uint32_t q[EV];
+                    float cur[EV];
+                    q[0] = pos[u];
+#pragma unroll
+                    for (int i = 1; i < EV; ++i) {
+                        q[i] = q[i - 1] + a[u];
+                        if (q[i] >= width) q[i] -= width;
+                    }
+#pragma unroll
+                    for (int i = 0; i < EV; ++i) cur[i] = row[q[i]];          // distinct positions of one entry
+#pragma unroll
+                    for (int i = 0; i < EV; ++i) row[q[i]] = cur[i] + wi[u] * elem(v[u], i);
+                }
+            }
+        }
+    }
+}
+
 // VEC: floats per lane per load of a dense row (4 needs width % 4 == 0 and 16-byte aligned bases);
-// NV: such loads per lane per row, so that width <= VEC * NV * lanes-per-row.
-template <int VEC, int NV>
+// NV: such loads per lane per row, so that width <= VEC * NV * lanes-per-row;
+// HALO: entries may refer to compressed halo rows (forward aggregation) or all rows are dense.
+template <int VEC, int NV, bool HALO>
 __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
     using V = typename Vec<VEC>::type;
+    constexpr int U = NV >= 4 ? 1 : (NV == 2 ? 2 : kUnroll);
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int32_t width = int32_t(p.rule.width);
-    const int32_t k = int32_t(p.rule.k);
-    const bool full = k == width;
-    float* lacc = lds + wave * width;   // this wavefront's row of sparse contributions
+    const bool full = p.rule.k == p.rule.width;
+    const bool sparse = HALO && !full;
+    float* lpriv = lds + wave * p.epi * width;   // this wavefront's private rows of compressed-row sums
+    uint16_t* lunits = reinterpret_cast<uint16_t*>(lds + kWaves * p.epi * width);
 
+    if (sparse) {   // the multiplier table is looked up once per halo entry: keep it in LDS
+        for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
+        for (int c = lane; c < p.epi * width; c += 64) lpriv[c] = 0.f;
+        __syncthreads();
+    }
     const int32_t idx = blockIdx.x * kWaves + wave;
     if (idx >= p.n_items) return;       // no block-wide barrier below: wavefronts are independent
     const SpmmItem it = p.items[idx];
-
-    for (int c = lane; c < width; c += 64) lacc[c] = 0.f;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
 
     const int lpr = 1 << p.lpr_log2;
     const int t = lane & (lpr - 1);     // position inside the group
@@ -100,65 +181,63 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
     for (int32_t base = it.e0; base < it.e1; base += 64) {
         const int32_t e = base + lane;
         const bool valid = e < it.e1;
-        const int32_t c = valid ? p.colidx[e] : 0;
-        const float w = valid ? p.vals[e] : 0.f;
-        const bool is_halo = valid && c >= p.n_dense_cols;
-        int32_t srow = c;
-        uint32_t ma = 0, mb = 0;
-        if (is_halo) {
-            const HaloDesc d = p.desc[c - p.n_dense_cols];
-            srow = d.zrow;
-            if (!full) {
-                const MaskAffine m = varco_affine(p.rule, uint32_t(d.gid));
-                ma = m.a;
-                mb = m.b;
+        int32_t srow = 0;
+        bool is_halo = false;
+        uint32_t mab = 0;
+        if (HALO) {
+            VarcoEdge ed{0, -1};
+            if (valid) ed = p.edge[e];
+            srow = ed.src;
+            is_halo = ed.gid >= 0;
+            if (sparse && is_halo) {
+                const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ p.rule.s0);
+                const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
+                mab = uint32_t(lunits[__umulhi(h2, p.rule.n_units)]) | (__umulhi(h1, p.rule.width) << 16);
             }
+        } else {
+            srow = valid ? p.colidx[e] : 0;
         }
-        const uint64_t hmask = __ballot(is_halo);
+        const float w = valid ? p.vals[e] : 0.f;
+        const uint64_t hmask = HALO ? __ballot(is_halo) : 0ull;
         const int cnt = min(64, it.e1 - base);
-        const int ns = full ? 0 : __popcll(hmask);
-        const int nd = cnt - ns;        // columns ascend within a row, so dense edges sit in lanes [0, nd)
+        const int ns = sparse ? __popcll(hmask) : 0;
+        const int nd = cnt - ns;        // columns ascend within a row, so dense entries sit in lanes [0, nd)
 
-        // dense rows: group g takes edges g, g + ng, ...
-        for (int i0 = 0; i0 < nd; i0 += ng) {
-            const int i = i0 + g;
-            const int src_lane = i < nd ? i : 0;
-            const int32_t r = __shfl(srow, src_lane);
-            const float wi = __shfl(w, src_lane);
-            if (i < nd) {
-                const bool h = (hmask >> i) & 1;
+        // dense rows: group g takes entries g, g + ng, ...; U row loads are issued before they are used
+        for (int i0 = 0; i0 < nd; i0 += ng * U) {
+            V v[U][NV];
+            float wi[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * ng + g;
+                ok[u] = i < nd;
+                const int src_lane = ok[u] ? i : 0;
+                const int32_t r = __shfl(srow, src_lane);
+                wi[u] = __shfl(w, src_lane);
+                const bool h = HALO && ((hmask >> src_lane) & 1);
                 const float* src = (h ? p.z : p.dense) + int64_t(r) * width;
 #pragma unroll
                 for (int m = 0; m < NV; ++m) {
                     const int col = VEC * (t + lpr * m);
-                    if (col < width) {
-                        const V v = *reinterpret_cast<const V*>(src + col);
-                        fma_vec(acc[m], wi, v);
-                    }
+                    zero_vec(v[u][m]);
+                    if (ok[u] && col < width) v[u][m] = *reinterpret_cast<const V*>(src + col);
                 }
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int m = 0; m < NV; ++m) fma_vec(acc[m], ok[u] ? wi[u] : 0.f, v[u][m]);
         }
 
-        // compressed rows: lane = (edge, j), 64 stored elements per step whatever k is
         if (ns > 0) {
             any_sparse = true;
-            const int total = ns * k;
-            for (int t0 = 0; t0 < total; t0 += 64) {
-                const int tt = t0 + lane;
-                const bool act = tt < total;
-                const int es = k == 1 ? tt : int(__umulhi(uint32_t(tt), p.k_magic));
-                const int j = tt - es * k;
-                const int src_lane = act ? nd + es : 0;
-                const int32_t r = __shfl(srow, src_lane);
-                const float wi = __shfl(w, src_lane);
-                const uint32_t a = __shfl(ma, src_lane);
-                const uint32_t b = __shfl(mb, src_lane);
-                if (act) {
-                    const float v = p.z[int64_t(r) * k + j];
-                    const uint32_t pos = varco_mod_width(a * uint32_t(j) + b, p.rule.width, p.rule.width_magic);
-                    __hip_atomic_fetch_add(&lacc[pos], wi * v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                }
-            }
+            if (p.ev == 4)
+                sparse_phase<4>(p, lane, nd, ns, srow, w, mab, lpriv);
+            else if (p.ev == 2)
+                sparse_phase<2>(p, lane, nd, ns, srow, w, mab, lpriv);
+            else
+                sparse_phase<1>(p, lane, nd, ns, srow, w, mab, lpriv);
         }
     }
 
@@ -175,7 +254,8 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
             const int col = VEC * (t + lpr * m);
             if (col < width) {
                 V v = acc[m];
-                if (any_sparse) add_vec(v, *reinterpret_cast<const V*>(lacc + col));
+                if (any_sparse)
+                    for (int sub = 0; sub < p.epi; ++sub) add_vec(v, *reinterpret_cast<const V*>(lpriv + sub * width + col));
                 *reinterpret_cast<V*>(dst + col) = v;
             }
         }
@@ -207,57 +287,80 @@ struct KeptArgs {
     float* out;
     int32_t row_base;
     float* partial;
-    int32_t g_log2;   // lanes per edge = 1 << g_log2 >= min(k, 64)
+    int32_t g_log2;   // lanes per item = 1 << g_log2 >= min(k, 64)
 };
 
-// Transposed aggregation for halo rows, produced directly in compressed form: only the k kept columns
-// of each gathered row of `src` are read. Lane = (edge sub-group, j).
+// Transposed aggregation for halo rows, produced directly in compressed form: only the k kept columns of
+// each gathered row of `src` are read. A group of lanes (one per kept position) owns one work item, so a
+// wavefront serves 64 / group items at once; each lane walks its item's entries, kUnroll gathers at a time.
 __global__ __launch_bounds__(kBlock) void spmm_kept_kernel(KeptArgs p) {
+    extern __shared__ float lds[];
+    uint16_t* lunits = reinterpret_cast<uint16_t*>(lds);
+    for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
+    __syncthreads();
+
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int32_t idx = blockIdx.x * kWaves + wave;
-    if (idx >= p.n_items) return;
-    const SpmmItem it = p.items[idx];
-    const int32_t width = int32_t(p.rule.width);
-    const int32_t k = int32_t(p.rule.k);
     const int gsz = 1 << p.g_log2;
     const int jl = lane & (gsz - 1);
     const int sg = lane >> p.g_log2;
-    const int nsg = 64 >> p.g_log2;
-    const MaskAffine m = varco_affine(p.rule, uint32_t(p.gids[it.row - p.row_base]));
+    const int ipw = 64 >> p.g_log2;
+    const int32_t idx = (blockIdx.x * kWaves + wave) * ipw + sg;
+    if (idx >= p.n_items) return;       // lanes are independent below (no cross-lane operations)
+    const SpmmItem it = p.items[idx];
+    const int32_t width = int32_t(p.rule.width);
+    const int32_t k = int32_t(p.rule.k);
+    const uint32_t gid = uint32_t(p.gids[it.row - p.row_base]);
+    const uint32_t h1 = varco_mix32(gid ^ p.rule.s0);
+    const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
+    const uint32_t a = lunits[__umulhi(h2, p.rule.n_units)];
+    const uint32_t b = __umulhi(h1, p.rule.width);
     float* dst = it.dst < 0 ? p.out + int64_t(it.row - p.row_base) * k : p.partial + int64_t(it.dst) * k;
 
-    for (int jbase = 0; jbase < k; jbase += gsz) {
-        const int j = jbase + jl;
-        const bool jact = j < k;
-        const uint32_t pos = jact ? varco_position(p.rule, m, uint32_t(j)) : 0u;
+    for (int j = jl; j < k; j += gsz) {
+        const uint32_t pos = varco_mod_width(a * uint32_t(j) + b, p.rule.width, p.rule.width_magic);
+        const float* col = p.src + pos;
         float acc = 0.f;
-        for (int32_t base = it.e0; base < it.e1; base += 64) {
-            const int32_t e = base + lane;
-            const bool valid = e < it.e1;
-            const int32_t c = valid ? p.colidx[e] : 0;
-            const float w = valid ? p.vals[e] : 0.f;
-            const int cnt = min(64, it.e1 - base);
-            for (int i0 = 0; i0 < cnt; i0 += nsg) {
-                const int i = i0 + sg;
-                const int src_lane = i < cnt ? i : 0;
-                const int32_t r = __shfl(c, src_lane);
-                const float wi = __shfl(w, src_lane);
-                if (i < cnt && jact) acc += wi * p.src[int64_t(r) * width + pos];
+        for (int32_t e = it.e0; e < it.e1; e += kUnroll) {
+            float w[kUnroll], v[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const bool ok = e + u < it.e1;
+                const int32_t c = ok ? p.colidx[e + u] : 0;
+                w[u] = ok ? p.vals[e + u] : 0.f;
+                v[u] = ok ? col[int64_t(c) * width] : 0.f;
             }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) acc += w[u] * v[u];
         }
-        for (int off = gsz; off < 64; off <<= 1) acc += __shfl_xor(acc, off);
-        if (sg == 0 && jact) dst[j] = acc;
+        dst[j] = acc;
     }
 }
 
-template <int VEC>
+// Per-entry records of a partition's row block: local column -> {row, -1}; halo column -> {row of the
+// node in the concatenated compressed buffer, node id}.
+__global__ __launch_bounds__(kBlock) void build_edges_kernel(const int32_t* colidx, int64_t nnz, int32_t n_local,
+                                                             const int32_t* halo_zrow, const int32_t* halo_gid,
+                                                             VarcoEdge* edge) {
+    const int64_t e = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (e >= nnz) return;
+    const int32_t c = colidx[e];
+    VarcoEdge ed;
+    if (c < n_local) {
+        ed.src = c, ed.gid = -1;
+    } else {
+        ed.src = halo_zrow[c - n_local], ed.gid = halo_gid[c - n_local];
+    }
+    edge[e] = ed;
+}
+
+template <int VEC, bool HALO>
 hipError_t launch_spmm_vec(int nv, const SpmmArgs& a, dim3 grid, size_t lds_bytes, hipStream_t stream) {
     switch (nv) {
-        case 1: hipLaunchKernelGGL((spmm_kernel<VEC, 1>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 2: hipLaunchKernelGGL((spmm_kernel<VEC, 2>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 4: hipLaunchKernelGGL((spmm_kernel<VEC, 4>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 8: hipLaunchKernelGGL((spmm_kernel<VEC, 8>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 1: hipLaunchKernelGGL((spmm_kernel<VEC, 1, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 2: hipLaunchKernelGGL((spmm_kernel<VEC, 2, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 4: hipLaunchKernelGGL((spmm_kernel<VEC, 4, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 8: hipLaunchKernelGGL((spmm_kernel<VEC, 8, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -267,14 +370,23 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 }  // namespace
 
-hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const float* vals, int32_t n_dense_cols,
-                             const float* dense, const HaloDesc* desc, const float* z, const MaskRule& rule,
-                             float* out, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag) {
+hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
+                                    const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream) {
+    if (nnz == 0) return hipSuccess;
+    hipLaunchKernelGGL(build_edges_kernel, dim3(unsigned((nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, colidx,
+                       nnz, n_local, halo_zrow, halo_gid, edge);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx, const float* vals,
+                             const float* dense, const float* z, const MaskRule& rule, float* out, int32_t row_base,
+                             float* partial, hipStream_t stream, const LaunchTag& tag) {
     if (plan.n_items == 0) return hipSuccess;
     const int32_t width = int32_t(rule.width);
     const bool full = rule.k == rule.width;
+    const bool halo = edge != nullptr;
     const bool vec4 = width % 4 == 0 && aligned16(dense) && aligned16(out) && aligned16(partial) &&
-                      (!full || aligned16(z));
+                      (!(halo && full) || aligned16(z));
     const int vec = vec4 ? 4 : 1;
     const int per_row = (width + vec - 1) / vec;   // loads of VEC floats that cover a row
     int lpr_log2 = 0;
@@ -286,23 +398,46 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const 
     SpmmArgs a;
     a.items = plan.items;
     a.n_items = plan.n_items;
+    a.edge = edge;
     a.colidx = colidx;
     a.vals = vals;
-    a.n_dense_cols = n_dense_cols;
     a.dense = dense;
-    a.desc = desc;
     a.z = z;
     a.rule = rule;
     a.out = out;
     a.row_base = row_base;
     a.partial = partial;
     a.lpr_log2 = lpr_log2;
-    a.k_magic = rule.k > 1 ? uint32_t((uint64_t(1) << 32) / rule.k) + 1u : 0u;
+    // Compressed rows: `ev` stored elements per lane and load, lpe = pow2 >= k / ev lanes per row, epi = 64 / lpe
+    // rows per instruction, each with a private LDS row. Prefer wide loads, but keep the private rows of
+    // a wavefront within 4 KB so that LDS does not limit the number of resident wavefronts.
+    const int epi_cap = std::max(1, 1024 / width);
+    a.ev = 1;
+    for (int ev : {4, 2}) {
+        if (rule.k % ev != 0 || (reinterpret_cast<uintptr_t>(z) & (4 * ev - 1)) != 0) continue;
+        int lg = 0;
+        while ((1 << lg) < int(rule.k) / ev && lg < 6) ++lg;
+        if ((64 >> lg) <= epi_cap) {
+            a.ev = ev;
+            break;
+        }
+    }
+    a.ku = int32_t(rule.k) / a.ev;
+    a.lpe_log2 = 0;
+    while ((1 << a.lpe_log2) < a.ku && a.lpe_log2 < 6) ++a.lpe_log2;
+    a.epi = std::max(1, std::min(64 >> a.lpe_log2, epi_cap));
     const dim3 grid((plan.n_items + kWaves - 1) / kWaves);
-    const size_t lds_bytes = size_t(kWaves) * width * sizeof(float);
+    size_t lds_bytes = 0;
+    if (halo && !full)
+        lds_bytes = size_t(kWaves) * a.epi * width * sizeof(float) + size_t(rule.n_units) * sizeof(uint16_t);
     tag.begin(stream);
-    hipError_t err = vec4 ? launch_spmm_vec<4>(nv, a, grid, lds_bytes, stream)
-                          : launch_spmm_vec<1>(nv, a, grid, lds_bytes, stream);
+    hipError_t err;
+    if (halo)
+        err = vec4 ? launch_spmm_vec<4, true>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<1, true>(nv, a, grid, lds_bytes, stream);
+    else
+        err = vec4 ? launch_spmm_vec<4, false>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<1, false>(nv, a, grid, lds_bytes, stream);
     tag.end(stream);
     if (err != hipSuccess) return err;
     if (plan.n_splits > 0) {
@@ -333,9 +468,10 @@ hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, c
     int g_log2 = 0;
     while ((1u << g_log2) < rule.k && g_log2 < 6) ++g_log2;
     a.g_log2 = g_log2;
-    const dim3 grid((plan.n_items + kWaves - 1) / kWaves);
+    const int items_per_block = kWaves * (64 >> g_log2);
+    const dim3 grid((plan.n_items + items_per_block - 1) / items_per_block);
     tag.begin(stream);
-    hipLaunchKernelGGL(spmm_kept_kernel, grid, dim3(kBlock), 0, stream, a);
+    hipLaunchKernelGGL(spmm_kept_kernel, grid, dim3(kBlock), size_t(rule.n_units) * sizeof(uint16_t), stream, a);
     tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;

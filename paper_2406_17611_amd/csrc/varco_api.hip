@@ -29,7 +29,7 @@ struct PartState {
     bool registered = false;
     varco_partition_desc d{};
     SpmmPlan fwd, t_local, t_halo;
-    HaloDesc* halo_desc = nullptr;   // device [n_halo]
+    VarcoEdge* edges = nullptr;      // device [nnz]: per-entry {source row, node id}
     int32_t* boundary_gid = nullptr; // device [n_boundary]
     int64_t nnz_t_local = 0;         // transposed entries whose row is a local node
 };
@@ -135,7 +135,7 @@ void free_part(PartState& ps) {
     free_plan(ps.fwd);
     free_plan(ps.t_local);
     free_plan(ps.t_halo);
-    if (ps.halo_desc) (void)hipFree(ps.halo_desc);
+    if (ps.edges) (void)hipFree(ps.edges);
     if (ps.boundary_gid) (void)hipFree(ps.boundary_gid);
     ps = PartState{};
 }
@@ -361,20 +361,10 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     VARCO_HIP(ctx, build_plan(t_rowptr, 0, nl, ps.t_local));
     VARCO_HIP(ctx, build_plan(t_rowptr, nl, nl + nh, ps.t_halo));
 
-    if (nh > 0) {
-        std::vector<int32_t> zrow(nh), gid(nh);
-        VARCO_HIP(ctx, hipMemcpy(zrow.data(), dev->halo_zrow, size_t(nh) * sizeof(int32_t), hipMemcpyDeviceToHost));
-        VARCO_HIP(ctx, hipMemcpy(gid.data(), dev->halo_gid, size_t(nh) * sizeof(int32_t), hipMemcpyDeviceToHost));
-        std::vector<HaloDesc> desc(nh);
-        for (int32_t s = 0; s < nh; ++s) {
-            if (zrow[s] < 0 || gid[s] < 0) {
-                free_part(ps);
-                return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: negative halo row or id");
-            }
-            desc[s] = {zrow[s], gid[s]};
-        }
-        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.halo_desc), size_t(nh) * sizeof(HaloDesc)));
-        VARCO_HIP(ctx, hipMemcpy(ps.halo_desc, desc.data(), size_t(nh) * sizeof(HaloDesc), hipMemcpyHostToDevice));
+    if (dev->nnz > 0) {
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.edges), size_t(dev->nnz) * sizeof(VarcoEdge)));
+        VARCO_HIP(ctx, varco_launch_build_edges(dev->colidx, dev->nnz, nl, dev->halo_zrow, dev->halo_gid, ps.edges, nullptr));
+        VARCO_HIP(ctx, hipDeviceSynchronize());
     }
     if (nb > 0) {
         std::vector<int32_t> lgid(nl), brow(nb), bgid(nb);
@@ -496,7 +486,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     // aggregate: local rows dense, halo rows straight from the owners' compressed buffers
     const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * 4.0 +
                              double(d.n_halo) * rule.k * 4.0;
-    VARCO_HIP(ctx, varco_launch_spmm(ps.fwd, d.colidx, d.vals, d.n_local, static_cast<const float*>(x_local), ps.halo_desc,
+    VARCO_HIP(ctx, varco_launch_spmm(ps.fwd, ps.edges, nullptr, d.vals, static_cast<const float*>(x_local),
                                      static_cast<const float*>(z_in), rule, static_cast<float*>(m_saved), 0, ctx->ws_spmm, st,
                                      ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0)));
     // transform + nonlinearity
@@ -583,12 +573,12 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * 4.0;
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + (double(d.n_halo) + 1.0) * 4.0 + double(nl) * fi * 4.0 +
                             double(d.n_halo) * rule.k * 4.0;
-    VARCO_HIP(ctx, varco_launch_spmm(ps.t_local, d.t_colidx, d.t_vals, INT_MAX, ctx->ws_dm, nullptr, nullptr, dense_rule,
+    VARCO_HIP(ctx, varco_launch_spmm(ps.t_local, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
                                      static_cast<float*>(dx_local), 0, ctx->ws_spmm, st,
                                      ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
     if (d.n_halo > 0) {
         if (rule.k == rule.width) {
-            VARCO_HIP(ctx, varco_launch_spmm(ps.t_halo, d.t_colidx, d.t_vals, INT_MAX, ctx->ws_dm, nullptr, nullptr, dense_rule,
+            VARCO_HIP(ctx, varco_launch_spmm(ps.t_halo, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
                                              static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st,
                                              ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {

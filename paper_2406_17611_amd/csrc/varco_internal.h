@@ -80,8 +80,11 @@ struct SpmmPlan {
     SpmmSplit* splits = nullptr;  // device
 };
 
-struct HaloDesc {
-    int32_t zrow, gid;
+// Per-entry record of a partition's row block, derived by the library at registration: a local column
+// becomes {local row, -1}; a halo column becomes {row of that node in the concatenated compressed buffer,
+// node id} (the id keys the node's kept positions).
+struct VarcoEdge {
+    int32_t src, gid;
 };
 
 hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
@@ -90,14 +93,17 @@ hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, co
                                    const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream,
                                    const LaunchTag& tag);
 
-// out[row - row_base, :] = sum_e vals[e] * src(colidx[e]) for the rows of `plan`, width = rule.width.
-//   colidx[e] <  n_dense_cols : src = dense + colidx[e] * width          (full row)
-//   colidx[e] >= n_dense_cols : halo slot s = colidx[e] - n_dense_cols, the k kept elements
-//                               z[desc[s].zrow * k + j] land at pi_gid(j)  (full row when k == width)
+hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
+                                    const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream);
+
+// out[row - row_base, :] = sum_e vals[e] * source_row(e) for the rows of `plan`, width = rule.width.
+//   edge != null (forward): entry e reads dense + edge[e].src * width when edge[e].gid < 0, else the k kept
+//       elements z[edge[e].src * k + j], which land at pi_gid(j) (a full row of z when k == width);
+//   edge == null (transposed, all dense): entry e reads dense + colidx[e] * width.
 // partial: workspace of plan.n_partials * width floats.
-hipError_t varco_launch_spmm(const SpmmPlan& plan, const int32_t* colidx, const float* vals, int32_t n_dense_cols,
-                             const float* dense, const HaloDesc* desc, const float* z, const MaskRule& rule,
-                             float* out, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag);
+hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx, const float* vals,
+                             const float* dense, const float* z, const MaskRule& rule, float* out, int32_t row_base,
+                             float* partial, hipStream_t stream, const LaunchTag& tag);
 
 // out[row - row_base, j] = sum_e vals[e] * src[colidx[e] * width + pi_v(j)], j < k, v = gids[row - row_base]
 // (the halo rows of the transposed aggregation, produced directly in compressed form).

@@ -39,78 +39,82 @@ struct GemmDev {
     int32_t inner, outer;               // see the workgroup -> tile mapping in the kernel
 };
 
-// Registers holding this thread's share (2 x 4 floats) of one operand tile.
+// Registers holding this thread's share (2 x 4 floats) of one operand tile, and of its gate when the
+// operand is masked. Loads only fill these registers; nothing consumes them before the tile is written to
+// LDS, so the global-memory latency of tile t+1 hides behind the matrix instructions of tile t.
+template <bool GATE>
 struct TileRegs {
     float v[2][4];
+    float g[GATE ? 2 : 1][4];
+    uint32_t inside;   // bit h * 4 + u: element (h, u) lies inside the matrix
 };
 
-// Loads the thread's share of a (rows x BK) operand tile whose row index is `i0 + ...` (M or N side).
-// `extent` bounds the row index, `kmax` the reduction index.
+// Loads the thread's share of a (128 x BK) operand tile whose row index starts at i0 (M or N side).
+// KC: the reduction index is contiguous in memory. Nothing consumes the loaded registers before the tile
+// is written to LDS.
+//   VEC: a group of 4 floats is wholly inside or wholly outside the matrix (the host checks alignment and
+//        divisibility) and is fetched by one predicated 16-byte load;
+//   otherwise every element is loaded on its own, unconditionally (an out-of-range element reads element
+//        0 of the matrix instead and is zeroed at the LDS write), so that the loads stay straight-line code.
+template <bool KC, bool GATE, bool VEC>
 __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int32_t extent, int32_t k0, int32_t kmax,
-                                          TileRegs& r) {
+                                          TileRegs<GATE>& r) {
     const int tid = threadIdx.x;
+    r.inside = VEC ? 0xFFu : 0u;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int f = tid + h * kThreads;   // index of a group of 4 floats in the tile
-        int32_t i, kk;
-        int64_t off;
-        bool in4, in[4];
-        if (op.k_contig) {                  // 4 consecutive reduction indices of one row
-            i = i0 + (f >> 2);
-            kk = k0 + ((f & 3) << 2);
-            off = int64_t(i) * op.ld + kk;
-            in4 = i < extent && kk + 3 < kmax;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) in[u] = i < extent && kk + u < kmax;
-        } else {                            // 4 consecutive rows of one reduction index
-            kk = k0 + (f >> 5);
-            i = i0 + ((f & 31) << 2);
-            off = int64_t(kk) * op.ld + i;
-            in4 = kk < kmax && i + 3 < extent;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) in[u] = kk < kmax && i + u < extent;
-        }
-        if (in4 && op.vec_ok) {
-            const float4 x = *reinterpret_cast<const float4*>(op.ptr + off);
-            r.v[h][0] = x.x, r.v[h][1] = x.y, r.v[h][2] = x.z, r.v[h][3] = x.w;
-            if (op.gate) {
-                const float4 gt = *reinterpret_cast<const float4*>(op.gate + off);
-                if (!(gt.x > 0.f)) r.v[h][0] = 0.f;
-                if (!(gt.y > 0.f)) r.v[h][1] = 0.f;
-                if (!(gt.z > 0.f)) r.v[h][2] = 0.f;
-                if (!(gt.w > 0.f)) r.v[h][3] = 0.f;
+        const int32_t i = KC ? i0 + (f >> 2) : i0 + ((f & 31) << 2);
+        const int32_t kk = KC ? k0 + ((f & 3) << 2) : k0 + (f >> 5);
+        const int64_t off = KC ? int64_t(i) * op.ld + kk : int64_t(kk) * op.ld + i;
+        if (VEC) {
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f), gt = x;
+            if (i < extent && kk < kmax) {
+                x = *reinterpret_cast<const float4*>(op.ptr + off);
+                if (GATE) gt = *reinterpret_cast<const float4*>(op.gate + off);
             }
+            r.v[h][0] = x.x, r.v[h][1] = x.y, r.v[h][2] = x.z, r.v[h][3] = x.w;
+            if (GATE) r.g[h][0] = gt.x, r.g[h][1] = gt.y, r.g[h][2] = gt.z, r.g[h][3] = gt.w;
         } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                float x = 0.f;
-                if (in[u]) {
-                    x = op.ptr[off + u];
-                    if (op.gate && !(op.gate[off + u] > 0.f)) x = 0.f;
-                }
-                r.v[h][u] = x;
+                const bool in = KC ? (i < extent && kk + u < kmax) : (kk < kmax && i + u < extent);
+                const int64_t o = in ? off + u : 0;
+                r.v[h][u] = op.ptr[o];
+                if (GATE) r.g[h][u] = op.gate[o];
+                r.inside |= in ? (1u << (4 * h + u)) : 0u;
             }
         }
     }
 }
 
-// Writes the registers into the k-major LDS tile s[BK][BM + PAD].
-__device__ __forceinline__ void store_tile(const OperandDev& op, const TileRegs& r, float (*s)[BM + PAD]) {
+// Writes the registers into the k-major LDS tile s[BK][BM + PAD], applying bounds and the gate (ReLU mask).
+template <bool KC, bool GATE, bool VEC>
+__device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float (*s)[BM + PAD]) {
     const int tid = threadIdx.x;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int f = tid + h * kThreads;
-        if (op.k_contig) {
+        float x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool keep = (VEC || ((r.inside >> (4 * h + u)) & 1u)) && (!GATE || r.g[h][u] > 0.f);
+            x[u] = keep ? r.v[h][u] : 0.f;
+        }
+        if (KC) {
             const int i = f >> 2, kk = (f & 3) << 2;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) s[kk + u][i] = r.v[h][u];
+            for (int u = 0; u < 4; ++u) s[kk + u][i] = x[u];
         } else {
             const int kk = f >> 5, i = (f & 31) << 2;
-            *reinterpret_cast<float4*>(&s[kk][i]) = make_float4(r.v[h][0], r.v[h][1], r.v[h][2], r.v[h][3]);
+            *reinterpret_cast<float4*>(&s[kk][i]) = make_float4(x[0], x[1], x[2], x[3]);
         }
     }
 }
 
+// A_KC / B_KC: operand stored with the reduction index contiguous; A_GATE / B_GATE: operand is masked;
+// VEC: every operand may be fetched with 16-byte loads.
+template <bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool VEC>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
     __shared__ __attribute__((aligned(16))) float sa[2][BK][BM + PAD];
     __shared__ __attribute__((aligned(16))) float sb[2][BK][BN + PAD];
@@ -150,24 +154,25 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    TileRegs ra, rb;
+    TileRegs<A_GATE> ra;
+    TileRegs<B_GATE> rb;
     auto fetch = [&](int32_t t) {
         if (t < tiles1) {
-            load_tile(g.a, m0, g.m, t * BK, g.k, ra);
-            load_tile(g.b, n0, g.n, t * BK, g.k, rb);
+            load_tile<A_KC, A_GATE, VEC>(g.a, m0, g.m, t * BK, g.k, ra);
+            load_tile<B_KC, B_GATE, VEC>(g.b, n0, g.n, t * BK, g.k, rb);
         } else {
-            load_tile(g.a2, m0, g.m, (t - tiles1) * BK, g.k2, ra);
-            load_tile(g.b2, n0, g.n, (t - tiles1) * BK, g.k2, rb);
+            load_tile<A_KC, A_GATE, VEC>(g.a2, m0, g.m, (t - tiles1) * BK, g.k2, ra);
+            load_tile<B_KC, B_GATE, VEC>(g.b2, n0, g.n, (t - tiles1) * BK, g.k2, rb);
         }
     };
-    auto stash = [&](int32_t t, int buf) {
-        store_tile(t < tiles1 ? g.a : g.a2, ra, sa[buf]);
-        store_tile(t < tiles1 ? g.b : g.b2, rb, sb[buf]);
+    auto stash = [&](int buf) {
+        store_tile<A_KC, A_GATE, VEC>(ra, sa[buf]);
+        store_tile<B_KC, B_GATE, VEC>(rb, sb[buf]);
     };
 
     if (t_begin < t_end) {
         fetch(t_begin);
-        stash(t_begin, 0);
+        stash(0);
     }
     __syncthreads();
     for (int32_t t = t_begin; t < t_end; ++t) {
@@ -184,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
             acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
             acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
         }
-        if (t + 1 < t_end) stash(t + 1, buf ^ 1);
+        if (t + 1 < t_end) stash(buf ^ 1);
         __syncthreads();
     }
 
@@ -218,28 +223,47 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
     }
 }
 
-// C (+)= sum over splits of partial[s], in split order.
+// C (+)= sum over splits of partial[s]. 64 consecutive output elements per workgroup; the four wavefronts
+// sum interleaved quarters of the splits (several loads in flight each) and the quarters are added in a
+// fixed order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(kThreads) void gemm_reduce_kernel(const float* partial, int32_t splits, int64_t mn,
                                                                int32_t n, float* c, int64_t ldc, int32_t accumulate,
                                                                int32_t relu) {
-    const int64_t i = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    if (i >= mn) return;
+    __shared__ float part[4][64];
+    const int e = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+    const int64_t i = int64_t(blockIdx.x) * 64 + e;
     float x = 0.f;
-    for (int32_t s = 0; s < splits; ++s) x += partial[int64_t(s) * mn + i];
-    float* dst = c + (i / n) * ldc + (i % n);
-    if (accumulate) x += *dst;
-    if (relu) x = fmaxf(x, 0.f);
-    *dst = x;
+    if (i < mn) {
+        int32_t s = quarter;
+        for (; s + 12 < splits; s += 16) {
+            const float x0 = partial[int64_t(s) * mn + i], x1 = partial[int64_t(s + 4) * mn + i];
+            const float x2 = partial[int64_t(s + 8) * mn + i], x3 = partial[int64_t(s + 12) * mn + i];
+            x += x0, x += x1, x += x2, x += x3;
+        }
+        for (; s < splits; s += 4) x += partial[int64_t(s) * mn + i];
+    }
+    part[quarter][e] = x;
+    __syncthreads();
+    if (quarter == 0 && i < mn) {
+        x = ((part[0][e] + part[1][e]) + part[2][e]) + part[3][e];
+        float* dst = c + (i / n) * ldc + (i % n);
+        if (accumulate) x += *dst;
+        if (relu) x = fmaxf(x, 0.f);
+        *dst = x;
+    }
 }
 
-OperandDev make_operand(const GemmOperand& o, bool stored_k_contig) {
+// `rows` is the extent of the non-reduction index (M for A, N for B), `red` the reduction length.
+OperandDev make_operand(const GemmOperand& o, bool stored_k_contig, int32_t rows, int32_t red) {
     OperandDev d;
     d.ptr = o.ptr;
     d.gate = o.gate;
     d.ld = o.ld;
     d.k_contig = stored_k_contig ? 1 : 0;
     const bool al = (reinterpret_cast<uintptr_t>(o.ptr) & 15u) == 0 && (reinterpret_cast<uintptr_t>(o.gate) & 15u) == 0;
-    d.vec_ok = (al && o.ld % 4 == 0) ? 1 : 0;
+    // groups of 4 consecutive floats never straddle the matrix edge
+    const bool whole = stored_k_contig ? red % 4 == 0 : rows % 4 == 0;
+    d.vec_ok = (al && o.ld % 4 == 0 && whole) ? 1 : 0;
     return d;
 }
 
@@ -250,10 +274,10 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
     GemmDev g;
     g.m = ga.m, g.n = ga.n, g.k = ga.k, g.k2 = ga.k2;
     // A is M x K: k-contiguous as stored unless transposed. B is K x N: k-contiguous only when transposed.
-    g.a = make_operand(ga.a, !ga.a.transposed);
-    g.b = make_operand(ga.b, ga.b.transposed);
-    g.a2 = make_operand(ga.a2, !ga.a2.transposed);
-    g.b2 = make_operand(ga.b2, ga.b2.transposed);
+    g.a = make_operand(ga.a, !ga.a.transposed, ga.m, ga.k);
+    g.b = make_operand(ga.b, ga.b.transposed, ga.n, ga.k);
+    g.a2 = make_operand(ga.a2, !ga.a2.transposed, ga.m, ga.k2);
+    g.b2 = make_operand(ga.b2, ga.b2.transposed, ga.n, ga.k2);
     g.c = ga.c;
     g.ldc = ga.ldc;
     g.accumulate = ga.accumulate ? 1 : 0;
@@ -278,16 +302,34 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
     }
     const int64_t blocks = int64_t((g.outer + 7) / 8 * 8) * g.inner;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const bool a_kc = g.a.k_contig, b_kc = g.b.k_contig, a_gate = ga.a.gate != nullptr, b_gate = ga.b.gate != nullptr;
+    if ((ga.k2 > 0 && (g.a2.k_contig != g.a.k_contig || g.b2.k_contig != g.b.k_contig || ga.a2.gate || ga.b2.gate)))
+        return hipErrorInvalidValue;   // the chained product must share the first one's layout and is never masked
+    const dim3 grid{unsigned(blocks)}, block{kThreads};
+    const bool vec = g.a.vec_ok && g.b.vec_ok && (ga.k2 == 0 || (g.a2.vec_ok && g.b2.vec_ok));
+    void (*kernel)(GemmDev) = nullptr;
+    if (a_kc && !b_kc && !a_gate && !b_gate)        // act(M H)
+        kernel = vec ? gemm_kernel<true, false, false, false, true> : gemm_kernel<true, false, false, false, false>;
+    else if (a_kc && b_kc && a_gate && !b_gate)     // dZ H^T, masked
+        kernel = vec ? gemm_kernel<true, true, true, false, true> : gemm_kernel<true, true, true, false, false>;
+    else if (a_kc && b_kc && !a_gate && !b_gate)    // dZ H^T
+        kernel = vec ? gemm_kernel<true, true, false, false, true> : gemm_kernel<true, true, false, false, false>;
+    else if (!a_kc && !b_kc && !a_gate && b_gate)   // M^T dZ, masked
+        kernel = vec ? gemm_kernel<false, false, false, true, true> : gemm_kernel<false, false, false, true, false>;
+    else if (!a_kc && !b_kc && !a_gate && !b_gate)  // M^T dZ
+        kernel = vec ? gemm_kernel<false, false, false, false, true> : gemm_kernel<false, false, false, false, false>;
+    else
+        return hipErrorInvalidValue;
     tag.begin(stream);
-    hipLaunchKernelGGL(gemm_kernel, dim3(unsigned(blocks)), dim3(kThreads), 0, stream, g);
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, g);
     tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (split > 1) {
         const int64_t mn = int64_t(ga.m) * ga.n;
         tag.begin_as(VARCO_K_REDUCE, stream);
-        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(unsigned((mn + kThreads - 1) / kThreads)), dim3(kThreads), 0,
-                           stream, ga.partial, split, mn, ga.n, ga.c, ga.ldc, g.accumulate, g.relu);
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream, ga.partial,
+                           split, mn, ga.n, ga.c, ga.ldc, g.accumulate, g.relu);
         tag.end(stream);
         err = hipGetLastError();
     }

@@ -192,12 +192,15 @@ hipError_t grow(float*& buf, size_t& have, size_t want) {
     return e;
 }
 
+// Number of slabs the node dimension of a weight-gradient product is cut into: the workgroups of one launch
+// should fill the chip exactly once (three 256-thread workgroups of the GEMM kernel are resident per
+// compute unit, 256 compute units), so that no partly filled second round is left over.
 int32_t gemm_split_for(int32_t m, int32_t n, int64_t k) {
     const int64_t tiles = int64_t((m + 127) / 128) * ((n + 127) / 128);
     const int64_t k_tiles = (k + 15) / 16;
-    int64_t split = (1024 + tiles - 1) / tiles;          // about four workgroups per compute unit in total
+    int64_t split = std::max<int64_t>(1, (3 * 256) / tiles);
     split = std::min<int64_t>(split, std::max<int64_t>(1, k_tiles / 8));
-    return int32_t(std::max<int64_t>(1, split));
+    return int32_t(split);
 }
 
 // Uploads the multiplier tables of every layer on first use (varco_create itself touches no device).

@@ -184,6 +184,19 @@ int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx
                         const void* x_local, const void* m_saved, const void* h1, const void* h0, void* dh1,
                         void* dh0, void* dx_local, void* dz_halo, varco_stream stream);
 
+/* Owner side of the backward exchange for partition p, all consumers at once (Section III: "the gradients
+ * flow in the opposite direction"; Algorithm 1: errors are back-propagated across machines): for every
+ * boundary row b of p, v = its node id,
+ *   dx_local[boundary_rows[b], pi_v(j)] += sum_{e in [ret_ptr[b], ret_ptr[b+1])} returned[ret_src[e], j],  j < k_layer
+ * where `returned` holds rows of k_layer values (the consumers' dz_halo buffers, addressed as one array)
+ * and ret_src lists, consumer partitions in ascending order, the rows that belong to b. The sum over
+ * consumers is formed first, in that fixed order, then added to dx_local once. Equivalent to one
+ * varco_decompress(accumulate = 1) per consumer, with a fraction of the memory traffic.
+ * ret_ptr[n_boundary + 1], ret_src[ret_ptr[n_boundary]] device int32; dx_local n_local x width[layer]. */
+int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int32_t p, const int32_t* ret_ptr,
+                                  const int32_t* ret_src, const void* returned, void* dx_local,
+                                  varco_stream stream);
+
 int32_t varco_get_stats(const varco_ctx* ctx, varco_stats* out);
 int32_t varco_reset_stats(varco_ctx* ctx);
 

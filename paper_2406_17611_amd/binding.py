@@ -25,7 +25,7 @@ EXPORTS = [
     "varco_create", "varco_destroy", "varco_register_partition", "varco_last_error",
     "varco_begin_step", "varco_set_ratio", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
-    "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
+    "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
 ]
 KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
                   "agg_bwd_halo", "reduce"]
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         L.varco_decompress.argtypes = [vp, i32, vp, vp, i64, vp, vp, i64, i32, vp]
         L.varco_layer_fwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.varco_layer_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.varco_accumulate_returned.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
         L.varco_get_stats.argtypes = [vp, C.POINTER(Stats)]
         L.varco_reset_stats.argtypes = [vp]
         L.varco_profile_enable.argtypes = [vp, i32]
@@ -252,6 +253,10 @@ class Context:
         _check(lib().varco_layer_bwd(self._h, layer, q, _ptr(dx_out), _ptr(x_out), _ptr(x_local), _ptr(m_saved),
                                      _ptr(h1), _ptr(h0), _ptr(dh1), _ptr(dh0), _ptr(dx_local), _ptr(dz_halo),
                                      _stream(stream)), self._h)
+
+    def accumulate_returned(self, layer, p, ret_ptr, ret_src, returned, dx_local, stream=None):
+        _check(lib().varco_accumulate_returned(self._h, layer, p, _ptr(ret_ptr), _ptr(ret_src), _ptr(returned),
+                                               _ptr(dx_local), _stream(stream)), self._h)
 
     def stats(self) -> dict:
         s = Stats()

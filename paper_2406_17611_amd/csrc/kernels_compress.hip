@@ -78,6 +78,40 @@ __global__ __launch_bounds__(kBlock) void decompress_add_kernel(MaskRule rule, c
     }
 }
 
+// Owner-side sum over all consumers: a group of lanes (one per stored element) owns one boundary row, adds
+// up the rows returned for it (coalesced reads of k consecutive values each, four in flight), and touches
+// the wide gradient row once.
+__global__ __launch_bounds__(kBlock) void accumulate_returned_kernel(MaskRule rule, const int32_t* __restrict__ gids,
+                                                                     const int32_t* __restrict__ rows, int64_t n_rows,
+                                                                     const int32_t* __restrict__ ptr,
+                                                                     const int32_t* __restrict__ src,
+                                                                     const float* __restrict__ returned,
+                                                                     float* __restrict__ x, int64_t ldx, int g_log2) {
+    const uint32_t g = 1u << g_log2;
+    const uint32_t gl = threadIdx.x & (g - 1);
+    const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
+    const int64_t k = rule.k;
+    for (int64_t b = group_row(g_log2); b < n_rows; b += stride) {
+        const int32_t e0 = ptr[b], e1 = ptr[b + 1];
+        if (e0 == e1) continue;
+        float* xr = x + int64_t(rows[b]) * ldx;
+        MaskAffine m{1, 0, 1};
+        if (rule.k != rule.width) m = varco_affine(rule, uint32_t(gids[b]));
+        for (uint32_t j = gl; j < rule.k; j += g) {
+            float acc = 0.f;
+            int32_t e = e0;
+            for (; e + 3 < e1; e += 4) {
+                const float v0 = returned[int64_t(src[e]) * k + j], v1 = returned[int64_t(src[e + 1]) * k + j];
+                const float v2 = returned[int64_t(src[e + 2]) * k + j], v3 = returned[int64_t(src[e + 3]) * k + j];
+                acc += v0, acc += v1, acc += v2, acc += v3;
+            }
+            for (; e < e1; ++e) acc += returned[int64_t(src[e]) * k + j];
+            const uint32_t pos = rule.k == rule.width ? j : varco_position(rule, m, j);
+            xr[pos] += acc;
+        }
+    }
+}
+
 int group_log2(uint32_t elems) {
     int l = 0;
     while ((1u << l) < elems && l < 6) ++l;
@@ -120,6 +154,19 @@ hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, co
         hipLaunchKernelGGL(decompress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
                            n_rows, z, x, ldx, gl);
     }
+    tag.end(stream);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_accumulate_returned(const MaskRule& rule, const int32_t* gids, const int32_t* rows,
+                                            int64_t n_rows, const int32_t* ptr, const int32_t* src,
+                                            const float* returned, float* x, int64_t ldx, hipStream_t stream,
+                                            const LaunchTag& tag) {
+    if (n_rows == 0) return hipSuccess;
+    const int gl = group_log2(rule.k);
+    tag.begin(stream);
+    hipLaunchKernelGGL(accumulate_returned_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
+                       n_rows, ptr, src, returned, x, ldx, gl);
     tag.end(stream);
     return hipGetLastError();
 }

@@ -605,6 +605,26 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     return VARCO_OK;
 }
 
+extern "C" int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int32_t p, const int32_t* ret_ptr,
+                                             const int32_t* ret_src, const void* returned, void* dx_local,
+                                             varco_stream stream) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_accumulate_returned")) return rc;
+    if (int32_t rc = check_part(ctx, p, "varco_accumulate_returned")) return rc;
+    const PartState& ps = ctx->parts[p];
+    if (ps.d.n_boundary == 0) return VARCO_OK;
+    if (!ret_ptr || !ret_src || !returned || !dx_local)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_accumulate_returned: null pointer");
+    ctx->layers[layer].ran_forward = true;
+    const MaskRule rule = make_rule(ctx, layer);
+    // rows returned are not known on the host; attribute the owner-side read-modify-write of k values per row
+    const double bytes = double(ps.d.n_boundary) * rule.k * 12.0;
+    VARCO_HIP(ctx, varco_launch_accumulate_returned(rule, ps.boundary_gid, ps.d.boundary_rows, ps.d.n_boundary, ret_ptr,
+                                                    ret_src, static_cast<const float*>(returned),
+                                                    static_cast<float*>(dx_local), ctx->widths[layer],
+                                                    static_cast<hipStream_t>(stream), ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));
+    return VARCO_OK;
+}
+
 extern "C" int32_t varco_get_stats(const varco_ctx* ctx, varco_stats* out) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_get_stats: null context");
     if (!out) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_get_stats: null output");

@@ -93,6 +93,12 @@ hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, co
                                    const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream,
                                    const LaunchTag& tag);
 
+// x[rows[b], pi_v(j)] += sum_{e in [ptr[b], ptr[b+1])} returned[src[e] * k + j], v = gids[b].
+hipError_t varco_launch_accumulate_returned(const MaskRule& rule, const int32_t* gids, const int32_t* rows,
+                                            int64_t n_rows, const int32_t* ptr, const int32_t* src,
+                                            const float* returned, float* x, int64_t ldx, hipStream_t stream,
+                                            const LaunchTag& tag);
+
 hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
                                     const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream);
 

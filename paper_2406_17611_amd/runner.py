@@ -32,17 +32,23 @@ class PartitionedNetwork:
         self.b_total = int(sum(hp.n_boundary for hp in host_parts))
         self.nnz_total = int(sum(hp.nnz for hp in host_parts))
 
-        # owner-side targets of the returned errors: arena row of every halo node
-        self.halo_arena_row = []
-        self.boundary_gid = []
-        for q, hp in enumerate(host_parts):
-            rows = np.empty(hp.n_halo, dtype=np.int64)
-            for o in range(self.P):
-                s0, s1 = hp.halo_owner_ptr[o], hp.halo_owner_ptr[o + 1]
-                rows[s0:s1] = self.row_off[o] + host_parts[o].boundary_rows[hp.halo_src_row[s0:s1]]
-            assert rows.max(initial=0) < 2 ** 31
-            self.halo_arena_row.append(torch.from_numpy(rows.astype(np.int32)).to(self.device))
-            self.boundary_gid.append(torch.from_numpy(hp.local_gid[hp.boundary_rows]).to(self.device))
+        self.boundary_gid = [torch.from_numpy(hp.local_gid[hp.boundary_rows]).to(self.device) for hp in host_parts]
+
+        # the backward exchange seen from the owners: for each boundary row, where the rows returned for it sit
+        # in the concatenation of all consumers' dz_halo buffers (consumers in ascending order)
+        self.ret_ptr, self.ret_src = [], []
+        for p, hp in enumerate(host_parts):
+            owner_rows, arena_rows = [], []
+            for q, hq in enumerate(host_parts):
+                s0, s1 = hq.halo_owner_ptr[p], hq.halo_owner_ptr[p + 1]
+                owner_rows.append(hq.halo_src_row[s0:s1].astype(np.int64))
+                arena_rows.append(self.halo_off[q] + np.arange(s0, s1, dtype=np.int64))
+            owner_rows, arena_rows = np.concatenate(owner_rows), np.concatenate(arena_rows)
+            order = np.argsort(owner_rows, kind="stable")          # stable: consumers stay in ascending order
+            ptr = np.concatenate(([0], np.cumsum(np.bincount(owner_rows, minlength=hp.n_boundary))))
+            assert ptr[-1] < 2 ** 31 and arena_rows.max(initial=0) < 2 ** 31
+            self.ret_ptr.append(torch.from_numpy(ptr.astype(np.int32)).to(self.device))
+            self.ret_src.append(torch.from_numpy(arena_rows[order].astype(np.int32)).to(self.device))
 
         f32 = dict(dtype=torch.float32, device=self.device)
         self.x = [torch.empty((self.n_total, w), **f32) for w in self.widths]
@@ -137,11 +143,11 @@ class PartitionedNetwork:
                 ctx.layer_bwd(l, q, self.dx[l + 1][r], self.x[l + 1][r], self.x[l][r], self.m[l][r], self.h1[l],
                               self.h0[l], self.dh1[l], self.dh0[l], self.dx[l][r] if need else None, dzh, stream)
             if need:
-                # errors handed back: owners add them at the kept positions, consumers in ascending order
-                for q in range(self.P):
-                    if self.n_halo[q]:
-                        ctx.decompress(l, self.dev_parts[q]["halo_gid"], self.halo_arena_row[q], self.n_halo[q],
-                                       self.dz_halo[l][int(self.halo_off[q]) * k:], self.dx[l], self.widths[l], 1, stream)
+                # errors handed back: every owner adds what its consumers returned, at the kept positions
+                for p in range(self.P):
+                    if self.host_parts[p].n_boundary:
+                        ctx.accumulate_returned(l, p, self.ret_ptr[p], self.ret_src[p], self.dz_halo[l],
+                                                self.dx[l][self.rows(p)], stream)
 
     def zero_grads(self):
         for l in range(self.L):

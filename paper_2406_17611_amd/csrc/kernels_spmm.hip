@@ -55,6 +55,10 @@ __device__ __forceinline__ void add_vec(float4& a, const float4& b) {
     a.w += b.w;
 }
 __device__ __forceinline__ void add_vec(float& a, const float& b) { a += b; }
+__device__ __forceinline__ void add_vec(float2& a, const float2& b) {
+    a.x += b.x;
+    a.y += b.y;
+}
 __device__ __forceinline__ float4 shfl_xor_vec(const float4& v, int mask) {
     return make_float4(__shfl_xor(v.x, mask), __shfl_xor(v.y, mask), __shfl_xor(v.z, mask), __shfl_xor(v.w, mask));
 }
@@ -276,64 +280,193 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* spl
     }
 }
 
-struct KeptArgs {
-    const SpmmItem* items;
+// ---------------------------------------------------------------------------------------------------------
+// Transposed aggregation for halo rows, produced directly in compressed form:
+//     dz_halo[s, j] = sum over local rows i of S[i, halo s] * dM[i, pi_v(j)],  j < k,  v = node of slot s.
+// Gathering the k scattered columns of every dM row an entry refers to would pull whole cache lines for
+// 4 useful bytes each, once per entry. Instead the work is done in two streaming passes:
+//   1. row order: a wavefront stages dM[i, :] in LDS once, and for each halo entry of row i writes the k
+//      products w * dM[i, pi_v(j)] as one contiguous row of a product buffer, at the entry's position in
+//      the transposed order (prow, derived once at registration);
+//   2. transposed order: the products of one halo slot are now consecutive rows; they are summed in entry
+//      order (fixed order: reproducible bits) into dz_halo.
+// ---------------------------------------------------------------------------------------------------------
+struct ProductArgs {
+    const SpmmItem* items;      // work list of the forward row block
     int32_t n_items;
-    const int32_t* colidx;
+    const VarcoEdge* edge;
     const float* vals;
-    const float* src;
-    const int32_t* gids;
+    const int32_t* prow;        // per entry: row of the product buffer (halo entries only)
+    const float* dm;            // n_local x width
     MaskRule rule;
+    float* prod;                // (halo entries) x k
+    int32_t ev;                 // floats per lane and store: 4, 2 or 1
+    int32_t ku;                 // stores per entry = k / ev
+    int32_t lpe_log2;           // lanes per entry
+};
+
+template <int EV>
+__device__ __forceinline__ void product_phase(const ProductArgs& p, int lane, int first, int ns, int32_t pr, float w,
+                                              uint32_t mab, const float* lrow) {
+    using V = typename Vec<EV>::type;
+    const int64_t k = p.rule.k;
+    const uint32_t width = p.rule.width;
+    const int epi = 64 >> p.lpe_log2;
+    const int sub = lane >> p.lpe_log2;
+    const int jl = lane & ((1 << p.lpe_log2) - 1);
+    for (int j0 = 0; j0 < p.ku; j0 += 64) {
+        const int ju = j0 + jl;
+        const bool j_ok = ju < p.ku;
+        const int j = ju * EV;
+        for (int r0 = 0; r0 < ns; r0 += epi) {
+            const int es = r0 + sub;
+            const bool act = j_ok && es < ns;
+            const int src_lane = act ? first + es : 0;
+            const int32_t row = __shfl(pr, src_lane);
+            const float wi = __shfl(w, src_lane);
+            const uint32_t ab = __shfl(mab, src_lane);
+            if (act) {
+                const uint32_t a = ab & 0xFFFFu;
+                uint32_t q = varco_mod_width(a * uint32_t(j) + (ab >> 16), width, p.rule.width_magic);
+                float out[EV];
+#pragma unroll
+                for (int i = 0; i < EV; ++i) {
+                    out[i] = wi * lrow[q];
+                    q += a;
+                    if (q >= width) q -= width;
+                }
+                float* dst = p.prod + int64_t(row) * k + j;
+                if (EV == 4)
+                    *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
+                else if (EV == 2)
+                    *reinterpret_cast<float2*>(dst) = make_float2(out[0], out[EV - 1]);
+                else
+                    *dst = out[0];
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs p) {
+    extern __shared__ float lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int32_t width = int32_t(p.rule.width);
+    float* lrow = lds + wave * width;
+    uint16_t* lunits = reinterpret_cast<uint16_t*>(lds + kWaves * width);
+    for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
+    __syncthreads();
+    const int32_t idx = blockIdx.x * kWaves + wave;
+    if (idx >= p.n_items) return;       // no block-wide barrier below
+    const SpmmItem it = p.items[idx];
+
+    bool staged = false;
+    for (int32_t base = it.e0; base < it.e1; base += 64) {
+        const int32_t e = base + lane;
+        const bool valid = e < it.e1;
+        VarcoEdge ed{0, -1};
+        if (valid) ed = p.edge[e];
+        const bool is_halo = ed.gid >= 0;
+        const uint64_t hmask = __ballot(is_halo);
+        if (hmask == 0) continue;       // uniform: this batch holds local entries only
+        if (!staged) {                  // the row of dM is read once, by the first batch that needs it
+            const float* src = p.dm + int64_t(it.row) * width;
+            for (int c = lane; c < width; c += 64) lrow[c] = src[c];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            staged = true;
+        }
+        float w = 0.f;
+        int32_t pr = 0;
+        uint32_t mab = 0;
+        if (is_halo) {
+            w = p.vals[e];
+            pr = p.prow[e];
+            const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ p.rule.s0);
+            const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
+            mab = uint32_t(lunits[__umulhi(h2, p.rule.n_units)]) | (__umulhi(h1, p.rule.width) << 16);
+        }
+        const int cnt = min(64, it.e1 - base);
+        const int ns = __popcll(hmask);
+        const int first = cnt - ns;     // columns ascend within a row: halo entries sit in the last lanes
+        if (p.ev == 4)
+            product_phase<4>(p, lane, first, ns, pr, w, mab, lrow);
+        else if (p.ev == 2)
+            product_phase<2>(p, lane, first, ns, pr, w, mab, lrow);
+        else
+            product_phase<1>(p, lane, first, ns, pr, w, mab, lrow);
+    }
+}
+
+struct SegsumArgs {
+    const SpmmItem* items;      // work list of the transposed halo rows (entry ranges in transposed order)
+    int32_t n_items;
+    const float* prod;
+    int32_t prod_base;          // transposed position of the first halo entry (= product row 0)
+    int32_t k;
     float* out;
     int32_t row_base;
     float* partial;
-    int32_t g_log2;   // lanes per item = 1 << g_log2 >= min(k, 64)
+    int32_t ev, ku, lpe_log2;
 };
 
-// Transposed aggregation for halo rows, produced directly in compressed form: only the k kept columns of
-// each gathered row of `src` are read. A group of lanes (one per kept position) owns one work item, so a
-// wavefront serves 64 / group items at once; each lane walks its item's entries, kUnroll gathers at a time.
-__global__ __launch_bounds__(kBlock) void spmm_kept_kernel(KeptArgs p) {
-    extern __shared__ float lds[];
-    uint16_t* lunits = reinterpret_cast<uint16_t*>(lds);
-    for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
-    __syncthreads();
-
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int gsz = 1 << p.g_log2;
-    const int jl = lane & (gsz - 1);
-    const int sg = lane >> p.g_log2;
-    const int ipw = 64 >> p.g_log2;
-    const int32_t idx = (blockIdx.x * kWaves + wave) * ipw + sg;
-    if (idx >= p.n_items) return;       // lanes are independent below (no cross-lane operations)
-    const SpmmItem it = p.items[idx];
-    const int32_t width = int32_t(p.rule.width);
-    const int32_t k = int32_t(p.rule.k);
-    const uint32_t gid = uint32_t(p.gids[it.row - p.row_base]);
-    const uint32_t h1 = varco_mix32(gid ^ p.rule.s0);
-    const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
-    const uint32_t a = lunits[__umulhi(h2, p.rule.n_units)];
-    const uint32_t b = __umulhi(h1, p.rule.width);
-    float* dst = it.dst < 0 ? p.out + int64_t(it.row - p.row_base) * k : p.partial + int64_t(it.dst) * k;
-
-    for (int j = jl; j < k; j += gsz) {
-        const uint32_t pos = varco_mod_width(a * uint32_t(j) + b, p.rule.width, p.rule.width_magic);
-        const float* col = p.src + pos;
-        float acc = 0.f;
-        for (int32_t e = it.e0; e < it.e1; e += kUnroll) {
-            float w[kUnroll], v[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const bool ok = e + u < it.e1;
-                const int32_t c = ok ? p.colidx[e + u] : 0;
-                w[u] = ok ? p.vals[e + u] : 0.f;
-                v[u] = ok ? col[int64_t(c) * width] : 0.f;
-            }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) acc += w[u] * v[u];
+template <int EV>
+__device__ __forceinline__ void segsum_body(const SegsumArgs& p, const SpmmItem& it, int jl, int lpe) {
+    using V = typename Vec<EV>::type;
+    float* dst = it.dst < 0 ? p.out + int64_t(it.row - p.row_base) * p.k : p.partial + int64_t(it.dst) * p.k;
+    for (int ju = jl; ju < p.ku; ju += lpe) {
+        const float* src = p.prod + int64_t(it.e0 - p.prod_base) * p.k + ju * EV;
+        V acc;
+        zero_vec(acc);
+        int32_t n = it.e1 - it.e0;
+        for (; n >= 4; n -= 4) {
+            const V v0 = *reinterpret_cast<const V*>(src), v1 = *reinterpret_cast<const V*>(src + p.k);
+            const V v2 = *reinterpret_cast<const V*>(src + 2 * int64_t(p.k));
+            const V v3 = *reinterpret_cast<const V*>(src + 3 * int64_t(p.k));
+            add_vec(acc, v0), add_vec(acc, v1), add_vec(acc, v2), add_vec(acc, v3);
+            src += 4 * int64_t(p.k);
         }
-        dst[j] = acc;
+        for (; n > 0; --n) {
+            add_vec(acc, *reinterpret_cast<const V*>(src));
+            src += p.k;
+        }
+        *reinterpret_cast<V*>(dst + ju * EV) = acc;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void halo_segsum_kernel(SegsumArgs p) {
+    const int lpe = 1 << p.lpe_log2;
+    const int64_t gidx = (int64_t(blockIdx.x) * kBlock + threadIdx.x) >> p.lpe_log2;
+    if (gidx >= p.n_items) return;
+    const SpmmItem it = p.items[gidx];
+    const int jl = threadIdx.x & (lpe - 1);
+    if (p.ev == 4)
+        segsum_body<4>(p, it, jl, lpe);
+    else if (p.ev == 2)
+        segsum_body<2>(p, it, jl, lpe);
+    else
+        segsum_body<1>(p, it, jl, lpe);
+}
+
+// prow[e] of a halo entry e = (local row i, halo column c): its position among the halo entries in the
+// transposed order, found by searching i in the ascending row list of transposed row c. One thread per row.
+__global__ __launch_bounds__(kBlock) void build_prow_kernel(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
+                                                            const int32_t* t_rowptr, const int32_t* t_colidx,
+                                                            int32_t* prow) {
+    const int32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n_local) return;
+    const int32_t base = t_rowptr[n_local];
+    for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+        const int32_t c = colidx[e];
+        int32_t pos = -1;
+        if (c >= n_local) {
+            int32_t lo = t_rowptr[c], hi = t_rowptr[c + 1] - 1;
+            while (lo < hi) {
+                const int32_t mid = (lo + hi) >> 1;
+                if (t_colidx[mid] < i) lo = mid + 1; else hi = mid;
+            }
+            pos = lo - base;
+        }
+        prow[e] = pos;
     }
 }
 
@@ -450,35 +583,69 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const 
     return err;
 }
 
-hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, const float* vals, const float* src,
-                                  const int32_t* gids, const MaskRule& rule, float* out, int32_t row_base,
-                                  float* partial, hipStream_t stream, const LaunchTag& tag) {
-    if (plan.n_items == 0) return hipSuccess;
-    KeptArgs a;
-    a.items = plan.items;
-    a.n_items = plan.n_items;
-    a.colidx = colidx;
+hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
+                                   const int32_t* t_rowptr, const int32_t* t_colidx, int32_t* prow, hipStream_t stream) {
+    if (n_local == 0) return hipSuccess;
+    hipLaunchKernelGGL(build_prow_kernel, dim3(unsigned((n_local + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, rowptr,
+                       colidx, n_local, t_rowptr, t_colidx, prow);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
+                                  const float* vals, const int32_t* prow, int32_t prod_base, const float* dm,
+                                  const MaskRule& rule, float* prod, float* out, int32_t row_base, float* partial,
+                                  hipStream_t stream, const LaunchTag& tag) {
+    if (t_halo_plan.n_items == 0 || fwd_plan.n_items == 0) return hipSuccess;
+    const int32_t width = int32_t(rule.width);
+    int ev = 1;
+    for (int c : {4, 2})
+        if (rule.k % c == 0 && (reinterpret_cast<uintptr_t>(prod) & (4 * c - 1)) == 0 &&
+            (reinterpret_cast<uintptr_t>(out) & (4 * c - 1)) == 0 && (reinterpret_cast<uintptr_t>(partial) & (4 * c - 1)) == 0) {
+            ev = c;
+            break;
+        }
+    const int ku = int(rule.k) / ev;
+    int lpe_log2 = 0;
+    while ((1 << lpe_log2) < ku && lpe_log2 < 6) ++lpe_log2;
+
+    ProductArgs a;
+    a.items = fwd_plan.items;
+    a.n_items = fwd_plan.n_items;
+    a.edge = edge;
     a.vals = vals;
-    a.src = src;
-    a.gids = gids;
+    a.prow = prow;
+    a.dm = dm;
     a.rule = rule;
-    a.out = out;
-    a.row_base = row_base;
-    a.partial = partial;
-    int g_log2 = 0;
-    while ((1u << g_log2) < rule.k && g_log2 < 6) ++g_log2;
-    a.g_log2 = g_log2;
-    const int items_per_block = kWaves * (64 >> g_log2);
-    const dim3 grid((plan.n_items + items_per_block - 1) / items_per_block);
+    a.prod = prod;
+    a.ev = ev, a.ku = ku, a.lpe_log2 = lpe_log2;
+    const size_t lds_bytes = size_t(kWaves) * width * sizeof(float) + size_t(rule.n_units) * sizeof(uint16_t);
     tag.begin(stream);
-    hipLaunchKernelGGL(spmm_kept_kernel, grid, dim3(kBlock), size_t(rule.n_units) * sizeof(uint16_t), stream, a);
-    tag.end(stream);
+    hipLaunchKernelGGL(halo_products_kernel, dim3((fwd_plan.n_items + kWaves - 1) / kWaves), dim3(kBlock), lds_bytes,
+                       stream, a);
     hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        tag.end(stream);
+        return err;
+    }
+    SegsumArgs b;
+    b.items = t_halo_plan.items;
+    b.n_items = t_halo_plan.n_items;
+    b.prod = prod;
+    b.prod_base = prod_base;
+    b.k = int32_t(rule.k);
+    b.out = out;
+    b.row_base = row_base;
+    b.partial = partial;
+    b.ev = ev, b.ku = ku, b.lpe_log2 = lpe_log2;
+    const int64_t threads = int64_t(t_halo_plan.n_items) << lpe_log2;
+    hipLaunchKernelGGL(halo_segsum_kernel, dim3(unsigned((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, b);
+    tag.end(stream);
+    err = hipGetLastError();
     if (err != hipSuccess) return err;
-    if (plan.n_splits > 0) {
+    if (t_halo_plan.n_splits > 0) {
         tag.begin_as(VARCO_K_REDUCE, stream);
-        hipLaunchKernelGGL(spmm_fixup_kernel, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
-                           partial, out, row_base, int32_t(rule.k));
+        hipLaunchKernelGGL(spmm_fixup_kernel, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
+                           t_halo_plan.n_splits, partial, out, row_base, int32_t(rule.k));
         tag.end(stream);
         err = hipGetLastError();
     }

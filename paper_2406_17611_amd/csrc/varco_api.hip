@@ -30,6 +30,7 @@ struct PartState {
     varco_partition_desc d{};
     SpmmPlan fwd, t_local, t_halo;
     VarcoEdge* edges = nullptr;      // device [nnz]: per-entry {source row, node id}
+    int32_t* prow = nullptr;         // device [nnz]: per-entry row of the halo-gradient product buffer
     int32_t* boundary_gid = nullptr; // device [n_boundary]
     int64_t nnz_t_local = 0;         // transposed entries whose row is a local node
 };
@@ -49,6 +50,7 @@ struct varco_ctx {
     float* ws_dm = nullptr;        size_t ws_dm_elems = 0;        // dM: n_local x width
     float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
     float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
+    float* ws_prod = nullptr;      size_t ws_prod_elems = 0;      // halo-gradient products: (halo entries) x k
     varco_stats stats{};
     VarcoProfiler prof;
     double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
@@ -136,6 +138,7 @@ void free_part(PartState& ps) {
     free_plan(ps.t_local);
     free_plan(ps.t_halo);
     if (ps.edges) (void)hipFree(ps.edges);
+    if (ps.prow) (void)hipFree(ps.prow);
     if (ps.boundary_gid) (void)hipFree(ps.boundary_gid);
     ps = PartState{};
 }
@@ -312,6 +315,7 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     if (ctx->ws_dm) (void)hipFree(ctx->ws_dm);
     if (ctx->ws_spmm) (void)hipFree(ctx->ws_spmm);
     if (ctx->ws_gemm) (void)hipFree(ctx->ws_gemm);
+    if (ctx->ws_prod) (void)hipFree(ctx->ws_prod);
     for (VarcoProfiler::Rec& r : ctx->prof.recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -367,6 +371,8 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     if (dev->nnz > 0) {
         VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.edges), size_t(dev->nnz) * sizeof(VarcoEdge)));
         VARCO_HIP(ctx, varco_launch_build_edges(dev->colidx, dev->nnz, nl, dev->halo_zrow, dev->halo_gid, ps.edges, nullptr));
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.prow), size_t(dev->nnz) * sizeof(int32_t)));
+        VARCO_HIP(ctx, varco_launch_build_prow(dev->rowptr, dev->colidx, nl, dev->t_rowptr, dev->t_colidx, ps.prow, nullptr));
         VARCO_HIP(ctx, hipDeviceSynchronize());
     }
     if (nb > 0) {
@@ -585,9 +591,12 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
                                              static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st,
                                              ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
-            VARCO_HIP(ctx, varco_launch_spmm_kept(ps.t_halo, d.t_colidx, d.t_vals, ctx->ws_dm, d.halo_gid, rule,
-                                                  static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st,
-                                                  ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
+            // product buffer: grown on demand (the first call at a larger k synchronises the device)
+            const size_t need = size_t(d.nnz - ps.nnz_t_local) * rule.k;
+            if (need > ctx->ws_prod_elems) VARCO_HIP(ctx, grow(ctx->ws_prod, ctx->ws_prod_elems, need + need / 4));
+            VARCO_HIP(ctx, varco_launch_halo_grad(ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
+                                                  ctx->ws_dm, rule, ctx->ws_prod, static_cast<float*>(dz_halo), nl,
+                                                  ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         }
         ctx->stats.bwd_elems[layer] += int64_t(d.n_halo) * rule.k;
         ctx->stats.full_bwd_elems[layer] += int64_t(d.n_halo) * fi;

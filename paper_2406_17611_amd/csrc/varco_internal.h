@@ -111,11 +111,17 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const 
                              const float* dense, const float* z, const MaskRule& rule, float* out, int32_t row_base,
                              float* partial, hipStream_t stream, const LaunchTag& tag);
 
-// out[row - row_base, j] = sum_e vals[e] * src[colidx[e] * width + pi_v(j)], j < k, v = gids[row - row_base]
-// (the halo rows of the transposed aggregation, produced directly in compressed form).
-hipError_t varco_launch_spmm_kept(const SpmmPlan& plan, const int32_t* colidx, const float* vals, const float* src,
-                                  const int32_t* gids, const MaskRule& rule, float* out, int32_t row_base,
-                                  float* partial, hipStream_t stream, const LaunchTag& tag);
+// prow[e] = position of forward entry e among the halo entries of the transposed order (-1 for local entries).
+hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
+                                   const int32_t* t_rowptr, const int32_t* t_colidx, int32_t* prow, hipStream_t stream);
+
+// out[s, j] = sum over local rows i of S[i, halo s] * dm[i, pi_v(j)], j < k (the halo rows of the transposed
+// aggregation, produced directly in compressed form) in two streaming passes through the product buffer
+// `prod` ((halo entries) x k floats). prod_base = transposed position of the first halo entry.
+hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
+                                  const float* vals, const int32_t* prow, int32_t prod_base, const float* dm,
+                                  const MaskRule& rule, float* prod, float* out, int32_t row_base, float* partial,
+                                  hipStream_t stream, const LaunchTag& tag);
 
 // C (+)= op(A) op(B) in fp32 on the matrix cores, row-major everywhere.
 struct GemmOperand {

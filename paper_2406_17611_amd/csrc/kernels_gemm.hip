@@ -3,8 +3,8 @@
 //
 // One 256-thread workgroup (4 wavefronts, 2 x 2) computes a 128 x 128 tile of C; each wavefront owns a
 // 64 x 64 sub-tile as 2 x 2 MFMA blocks of 32 x 32 (64 accumulator registers per lane). Operand tiles of
-// 16 reduction steps are staged through LDS in k-major order (so that an MFMA operand is one conflict-free
-// 32-float row read) and double-buffered against the global loads of the next tile. The ReLU mask of the
+// 16 reduction steps are staged through LDS (layout per operand: see store_tile) and double-buffered
+// against the global loads of the next tile. The ReLU mask of the
 // backward pass is applied while an operand is loaded ("gate"), the activation in the epilogue. A second
 // (A2, B2) product can be chained into the same accumulators (the two taps of a SAGE layer). Reductions
 // over the node dimension (weight gradients) are split over workgroups into a partial buffer and summed
@@ -88,9 +88,20 @@ __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int3
     }
 }
 
-// Writes the registers into the k-major LDS tile s[BK][BM + PAD], applying bounds and the gate (ReLU mask).
+// LDS layout of an operand tile (128 rows x BK reduction steps), chosen so that the global -> LDS copy is a
+// 16-byte store whichever way the operand lies in memory:
+//   KC  (reduction index contiguous in memory): row-major, s[row * kRowStride + k]; a lane then fetches the
+//        8 reduction steps it feeds to the matrix cores with two 16-byte reads;
+//   !KC (row index contiguous in memory): k-major, s[k * kColStride + row]; fragments are scalar reads.
+// Matrix-core step t of a tile multiplies reduction indices t (lanes 0-31) and 8 + t (lanes 32-63); any
+// pairing is valid as long as both operands use the same one.
+constexpr int kRowStride = BK + 4;    // 20 floats: 16-byte aligned rows, conflict-free 16-byte reads
+constexpr int kColStride = BM + PAD;  // 132 floats
+constexpr int kTileFloats = BM * kRowStride > BK * kColStride ? BM * kRowStride : BK * kColStride;
+
+// Writes the registers into the LDS tile, applying bounds and the gate (ReLU mask).
 template <bool KC, bool GATE, bool VEC>
-__device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float (*s)[BM + PAD]) {
+__device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float* s) {
     const int tid = threadIdx.x;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -101,14 +112,23 @@ __device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float (*s)[B
             const bool keep = (VEC || ((r.inside >> (4 * h + u)) & 1u)) && (!GATE || r.g[h][u] > 0.f);
             x[u] = keep ? r.v[h][u] : 0.f;
         }
-        if (KC) {
-            const int i = f >> 2, kk = (f & 3) << 2;
+        const int off = KC ? (f >> 2) * kRowStride + ((f & 3) << 2) : (f >> 5) * kColStride + ((f & 31) << 2);
+        *reinterpret_cast<float4*>(s + off) = make_float4(x[0], x[1], x[2], x[3]);
+    }
+}
+
+// The 8 values a lane feeds to the matrix cores for tile row `row` during one tile: reduction indices
+// lk * 8 .. lk * 8 + 7.
+template <bool KC>
+__device__ __forceinline__ void load_fragment(const float* s, int row, int lk, float (&out)[8]) {
+    if (KC) {
+        const float4 lo = *reinterpret_cast<const float4*>(s + row * kRowStride + lk * 8);
+        const float4 hi = *reinterpret_cast<const float4*>(s + row * kRowStride + lk * 8 + 4);
+        out[0] = lo.x, out[1] = lo.y, out[2] = lo.z, out[3] = lo.w;
+        out[4] = hi.x, out[5] = hi.y, out[6] = hi.z, out[7] = hi.w;
+    } else {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) s[kk + u][i] = x[u];
-        } else {
-            const int kk = f >> 5, i = (f & 31) << 2;
-            *reinterpret_cast<float4*>(&s[kk][i]) = make_float4(x[0], x[1], x[2], x[3]);
-        }
+        for (int t = 0; t < 8; ++t) out[t] = s[(lk * 8 + t) * kColStride + row];
     }
 }
 
@@ -116,8 +136,8 @@ __device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float (*s)[B
 // VEC: every operand may be fetched with 16-byte loads.
 template <bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool VEC>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
-    __shared__ __attribute__((aligned(16))) float sa[2][BK][BM + PAD];
-    __shared__ __attribute__((aligned(16))) float sb[2][BK][BN + PAD];
+    __shared__ __attribute__((aligned(16))) float sa[2][kTileFloats];
+    __shared__ __attribute__((aligned(16))) float sb[2][kTileFloats];
 
     // Workgroups are dealt to the 8 XCDs round-robin. The tiles that share streamed data (the column tiles
     // of one row tile; or, for a split reduction, all output tiles of one slab of the reduction range) are
@@ -156,14 +176,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
 
     TileRegs<A_GATE> ra;
     TileRegs<B_GATE> rb;
+    // Tile t of the chained reduction: tiles [0, tiles1) come from the first product, the rest from the second.
+    // The operands are picked with selects, not branches: a branch around the loads would make the compiler
+    // wait for every load in flight where the two paths meet.
     auto fetch = [&](int32_t t) {
-        if (t < tiles1) {
-            load_tile<A_KC, A_GATE, VEC>(g.a, m0, g.m, t * BK, g.k, ra);
-            load_tile<B_KC, B_GATE, VEC>(g.b, n0, g.n, t * BK, g.k, rb);
-        } else {
-            load_tile<A_KC, A_GATE, VEC>(g.a2, m0, g.m, (t - tiles1) * BK, g.k2, ra);
-            load_tile<B_KC, B_GATE, VEC>(g.b2, n0, g.n, (t - tiles1) * BK, g.k2, rb);
-        }
+        const bool first = t < tiles1;
+        OperandDev oa = g.a, ob = g.b;
+        oa.ptr = first ? g.a.ptr : g.a2.ptr, oa.gate = first ? g.a.gate : g.a2.gate, oa.ld = first ? g.a.ld : g.a2.ld;
+        ob.ptr = first ? g.b.ptr : g.b2.ptr, ob.gate = first ? g.b.gate : g.b2.gate, ob.ld = first ? g.b.ld : g.b2.ld;
+        const int32_t k0 = (first ? t : t - tiles1) * BK, kmax = first ? g.k : g.k2;
+        load_tile<A_KC, A_GATE, VEC>(oa, m0, g.m, k0, kmax, ra);
+        load_tile<B_KC, B_GATE, VEC>(ob, n0, g.n, k0, kmax, rb);
     };
     auto stash = [&](int buf) {
         store_tile<A_KC, A_GATE, VEC>(ra, sa[buf]);
@@ -178,16 +201,17 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
     for (int32_t t = t_begin; t < t_end; ++t) {
         const int buf = (t - t_begin) & 1;
         if (t + 1 < t_end) fetch(t + 1);
+        float fa[2][8], fb[2][8];
+        load_fragment<A_KC>(sa[buf], wm + lrow, lk, fa[0]);
+        load_fragment<A_KC>(sa[buf], wm + 32 + lrow, lk, fa[1]);
+        load_fragment<B_KC>(sb[buf], wn + lrow, lk, fb[0]);
+        load_fragment<B_KC>(sb[buf], wn + 32 + lrow, lk, fb[1]);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            const float a0 = sa[buf][kk + lk][wm + lrow];
-            const float a1 = sa[buf][kk + lk][wm + 32 + lrow];
-            const float b0 = sb[buf][kk + lk][wn + lrow];
-            const float b1 = sb[buf][kk + lk][wn + 32 + lrow];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        for (int s8 = 0; s8 < 8; ++s8) {
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0][s8], fb[0][s8], acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0][s8], fb[1][s8], acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1][s8], fb[0][s8], acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1][s8], fb[1][s8], acc[1][1], 0, 0, 0);
         }
         if (t + 1 < t_end) stash(buf ^ 1);
         __syncthreads();

@@ -24,13 +24,25 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
-HBM_CLASSES = ("compress", "decompress", "agg_fwd", "agg_bwd_local", "agg_bwd_halo", "reduce")
+HBM_CLASSES = ("compress", "decompress", "agg_fwd", "agg_bwd_local", "agg_bwd_halo", "agg_bwd_halo_sum", "reduce")
 MFMA_CLASSES = ("gemm_fwd", "gemm_wgrad", "gemm_dgrad")
 DEFAULT_RATIO = {"tiny": (4, 1), "medium": (8, 1), "medium_bfs16": (1584 - 15 * 50, 99), "large_sage": (8, 1)}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def measured_traffic(workload, kernel_class):
+    """HBM bytes per launch of a kernel class from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the same counter reads for the library's plain copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            rec = json.load(f)[workload][kernel_class]
+        return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(w, ratio, budget_note=""):
@@ -121,6 +133,13 @@ def main():
     log(f"[bench] device buffers ready in {time.time() - t0:.1f}s, "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB allocated by torch")
 
+    # one plain copy of known size (256 MiB), outside the timed region: the reference that hardware byte
+    # counters of a profiled run are scaled by
+    cal_src = torch.ones(64 * 2**20, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    vb.calibration_copy(cal_dst, cal_src)
+    del cal_src, cal_dst
+
     for s in range(args.warmup):
         net.step(s, ratio)
     torch.cuda.synchronize()
@@ -156,7 +175,8 @@ def main():
     dominant = max((n for n in kernels if n != "reduce"), key=lambda n: kernels[n]["ms_per_step"])
     d = kernels[dominant]
     roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
-                "unit": d["unit"], "frac": d["frac"], "traffic": None, "avg_launch_ms": d["avg_launch_ms"]}
+                "unit": d["unit"], "frac": d["frac"], "traffic": measured_traffic(w.name, dominant),
+                "avg_launch_ms": d["avg_launch_ms"]}
 
     bpe = stats["bytes_per_elem"]
     out = {

@@ -216,9 +216,10 @@ enum {
     VARCO_K_GEMM_WGRAD = 4,     /* dH += M^T dZ, X^T dZ (split reduction, partial products) */
     VARCO_K_GEMM_DGRAD = 5,     /* dM = dZ H1^T, dX += dZ H0^T */
     VARCO_K_AGG_BWD_LOCAL = 6,  /* dX_loc = S_loc^T dM */
-    VARCO_K_AGG_BWD_HALO = 7,   /* dZ_halo = kept positions of S_halo^T dM */
+    VARCO_K_AGG_BWD_HALO = 7,   /* dZ_halo = kept positions of S_halo^T dM (first pass: products in row order) */
     VARCO_K_REDUCE = 8,         /* fixed-order sums of split rows / split reductions */
-    VARCO_K_COUNT = 9
+    VARCO_K_AGG_BWD_HALO_SUM = 9, /* second pass of dZ_halo: sums of each halo row's products */
+    VARCO_K_COUNT = 10
 };
 typedef struct {
     int64_t launches[VARCO_K_COUNT];
@@ -226,6 +227,9 @@ typedef struct {
     double bytes[VARCO_K_COUNT];
     double flops[VARCO_K_COUNT];
 } varco_profile;
+/* A plain device-to-device copy of `bytes` bytes (multiple of 16, 16-byte aligned pointers) by a kernel
+ * of this library: the known-size reference against which hardware byte counters are scaled. */
+int32_t varco_calibration_copy(void* dst, const void* src, int64_t bytes, varco_stream stream);
 int32_t varco_profile_enable(varco_ctx* ctx, int32_t on);
 /* Synchronises the recorded events (blocks until the bracketed work has finished); reset != 0 clears the
  * totals afterwards. */

@@ -26,9 +26,10 @@ EXPORTS = [
     "varco_begin_step", "varco_set_ratio", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
+    "varco_calibration_copy",
 ]
 KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
-                  "agg_bwd_halo", "reduce"]
+                  "agg_bwd_halo", "reduce", "agg_bwd_halo_sum"]
 
 
 class Config(C.Structure):
@@ -54,8 +55,8 @@ class Stats(C.Structure):
 
 
 class Profile(C.Structure):
-    _fields_ = [("launches", C.c_int64 * 9), ("ms", C.c_double * 9), ("bytes", C.c_double * 9),
-                ("flops", C.c_double * 9)]
+    _fields_ = [("launches", C.c_int64 * 10), ("ms", C.c_double * 10), ("bytes", C.c_double * 10),
+                ("flops", C.c_double * 10)]
 
 
 class VarcoError(RuntimeError):
@@ -93,6 +94,7 @@ def lib() -> C.CDLL:
         L.varco_accumulate_returned.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
         L.varco_get_stats.argtypes = [vp, C.POINTER(Stats)]
         L.varco_reset_stats.argtypes = [vp]
+        L.varco_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.varco_profile_enable.argtypes = [vp, i32]
         L.varco_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         for name in EXPORTS:
@@ -122,6 +124,11 @@ def _stream(stream):
         import torch
         return torch.cuda.current_stream().cuda_stream
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else stream
+
+
+def calibration_copy(dst, src, stream=None):
+    """Copies the bytes of tensor `src` into `dst` with the library's plain copy kernel."""
+    _check(lib().varco_calibration_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------------

@@ -112,6 +112,12 @@ __global__ __launch_bounds__(kBlock) void accumulate_returned_kernel(MaskRule ru
     }
 }
 
+__global__ __launch_bounds__(kBlock) void calibration_copy_kernel(const float4* __restrict__ src,
+                                                                  float4* __restrict__ dst, int64_t n) {
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
 int group_log2(uint32_t elems) {
     int l = 0;
     while ((1u << l) < elems && l < 6) ++l;
@@ -168,5 +174,12 @@ hipError_t varco_launch_accumulate_returned(const MaskRule& rule, const int32_t*
     hipLaunchKernelGGL(accumulate_returned_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
                        n_rows, ptr, src, returned, x, ldx, gl);
     tag.end(stream);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream) {
+    if (bytes == 0) return hipSuccess;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(256 * 32), dim3(kBlock), 0, stream, static_cast<const float4*>(src),
+                       static_cast<float4*>(dst), bytes / 16);
     return hipGetLastError();
 }

@@ -594,7 +594,7 @@ hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx,
 hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
                                   const float* vals, const int32_t* prow, int32_t prod_base, const float* dm,
                                   const MaskRule& rule, float* prod, float* out, int32_t row_base, float* partial,
-                                  hipStream_t stream, const LaunchTag& tag) {
+                                  hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag) {
     if (t_halo_plan.n_items == 0 || fwd_plan.n_items == 0) return hipSuccess;
     const int32_t width = int32_t(rule.width);
     int ev = 1;
@@ -622,11 +622,9 @@ hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_ha
     tag.begin(stream);
     hipLaunchKernelGGL(halo_products_kernel, dim3((fwd_plan.n_items + kWaves - 1) / kWaves), dim3(kBlock), lds_bytes,
                        stream, a);
+    tag.end(stream);
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess) {
-        tag.end(stream);
-        return err;
-    }
+    if (err != hipSuccess) return err;
     SegsumArgs b;
     b.items = t_halo_plan.items;
     b.n_items = t_halo_plan.n_items;
@@ -638,8 +636,9 @@ hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_ha
     b.partial = partial;
     b.ev = ev, b.ku = ku, b.lpe_log2 = lpe_log2;
     const int64_t threads = int64_t(t_halo_plan.n_items) << lpe_log2;
+    sum_tag.begin(stream);
     hipLaunchKernelGGL(halo_segsum_kernel, dim3(unsigned((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, b);
-    tag.end(stream);
+    sum_tag.end(stream);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (t_halo_plan.n_splits > 0) {

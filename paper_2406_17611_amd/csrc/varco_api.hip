@@ -580,8 +580,8 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const MaskRule rule = make_rule(ctx, layer);
     const MaskRule dense_rule = full_rule(fi);
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * 4.0;
-    const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + (double(d.n_halo) + 1.0) * 4.0 + double(nl) * fi * 4.0 +
-                            double(d.n_halo) * rule.k * 4.0;
+    const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * 4.0;
+    const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * 4.0 + th_out_bytes;
     VARCO_HIP(ctx, varco_launch_spmm(ps.t_local, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
                                      static_cast<float*>(dx_local), 0, ctx->ws_spmm, st,
                                      ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
@@ -596,7 +596,8 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
             if (need > ctx->ws_prod_elems) VARCO_HIP(ctx, grow(ctx->ws_prod, ctx->ws_prod_elems, need + need / 4));
             VARCO_HIP(ctx, varco_launch_halo_grad(ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
                                                   ctx->ws_dm, rule, ctx->ws_prod, static_cast<float*>(dz_halo), nl,
-                                                  ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
+                                                  ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
+                                                  ctx->tag(VARCO_K_AGG_BWD_HALO_SUM, th_out_bytes, 0)));
         }
         ctx->stats.bwd_elems[layer] += int64_t(d.n_halo) * rule.k;
         ctx->stats.full_bwd_elems[layer] += int64_t(d.n_halo) * fi;
@@ -646,6 +647,16 @@ extern "C" int32_t varco_reset_stats(varco_ctx* ctx) {
     const int32_t b = ctx->stats.bytes_per_elem;
     ctx->stats = varco_stats{};
     ctx->stats.bytes_per_elem = b;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_calibration_copy(void* dst, const void* src, int64_t bytes, varco_stream stream) {
+    if (bytes < 0 || bytes % 16 != 0) return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_calibration_copy: bytes must be a non-negative multiple of 16");
+    if (bytes == 0) return VARCO_OK;
+    if (!dst || !src || (reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16 != 0)
+        return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_calibration_copy: null or misaligned pointer");
+    VARCO_HIP(static_cast<const varco_ctx*>(nullptr),
+              varco_launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
     return VARCO_OK;
 }
 

@@ -99,6 +99,8 @@ hipError_t varco_launch_accumulate_returned(const MaskRule& rule, const int32_t*
                                             const float* returned, float* x, int64_t ldx, hipStream_t stream,
                                             const LaunchTag& tag);
 
+hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
+
 hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
                                     const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream);
 
@@ -121,7 +123,7 @@ hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx,
 hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
                                   const float* vals, const int32_t* prow, int32_t prod_base, const float* dm,
                                   const MaskRule& rule, float* prod, float* out, int32_t row_base, float* partial,
-                                  hipStream_t stream, const LaunchTag& tag);
+                                  hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag);
 
 // C (+)= op(A) op(B) in fp32 on the matrix cores, row-major everywhere.
 struct GemmOperand {

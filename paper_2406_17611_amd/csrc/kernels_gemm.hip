@@ -1,20 +1,22 @@
 // Dense feature transform of eq. (2) and its gradients on the CDNA matrix cores, in true fp32
 // (v_mfma_f32_32x32x2_f32): X_out = act(M H1 + X H0), dM = dZ H1^T, dH += M^T dZ.
 //
-// One 256-thread workgroup (4 wavefronts, 2 x 2) computes a 128 x 128 tile of C; each wavefront owns a
-// 64 x 64 sub-tile as 2 x 2 MFMA blocks of 32 x 32 (64 accumulator registers per lane). Operand tiles of
-// 16 reduction steps are staged through LDS (layout per operand: see store_tile) and double-buffered
-// against the global loads of the next tile. The ReLU mask of the
-// backward pass is applied while an operand is loaded ("gate"), the activation in the epilogue. A second
-// (A2, B2) product can be chained into the same accumulators (the two taps of a SAGE layer). Reductions
-// over the node dimension (weight gradients) are split over workgroups into a partial buffer and summed
-// by a second kernel in a fixed order.
+// One 256-thread workgroup (4 wavefronts) computes a tile of C; each wavefront owns a 64 x 64 sub-tile as
+// 2 x 2 MFMA blocks of 32 x 32 (64 accumulator registers per lane). The wavefronts are laid out 2 x 2
+// (128 x 128 tile) or, for outputs at most 64 columns wide (the class logits), 4 x 1 (256 x 64 tile), so that
+// a narrow output does not waste most of a 128-wide tile. Operand tiles of 16 reduction steps are staged
+// through LDS (layout per operand: see store_tile) and double-buffered against the global loads of the next
+// tile. The ReLU mask of the backward pass is applied when an operand tile is written to LDS ("gate"), the
+// activation in the epilogue. A second (A2, B2) product can be chained into the same accumulators (the two
+// taps of a SAGE layer). Reductions over the node dimension (weight gradients) are split over workgroups
+// into a partial buffer and summed by a second kernel in a fixed order.
+#include <type_traits>
+
 #include "varco_internal.h"
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 16;
-constexpr int PAD = 4;
+constexpr int BK = 16;
 constexpr int kThreads = 256;
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -23,8 +25,6 @@ struct OperandDev {
     const float* ptr;
     const float* gate;
     int64_t ld;
-    int32_t k_contig;   // 1: element (i, kk) at ptr[i * ld + kk]; 0: at ptr[kk * ld + i]
-    int32_t vec_ok;     // 16-byte loads are legal (aligned base, ld % 4 == 0)
 };
 
 struct GemmDev {
@@ -39,33 +39,36 @@ struct GemmDev {
     int32_t inner, outer;               // see the workgroup -> tile mapping in the kernel
 };
 
-// Registers holding this thread's share (2 x 4 floats) of one operand tile, and of its gate when the
-// operand is masked. Loads only fill these registers; nothing consumes them before the tile is written to
-// LDS, so the global-memory latency of tile t+1 hides behind the matrix instructions of tile t.
-template <bool GATE>
+// Registers holding this thread's share (ROWS / 64 groups of 4 floats) of one ROWS x BK operand tile, and
+// of its gate when the operand is masked. Loads only fill these registers; nothing consumes them before the
+// tile is written to LDS, so the global-memory latency of tile t+1 hides behind the matrix instructions
+// of tile t.
+template <int ROWS, bool GATE>
 struct TileRegs {
-    float v[2][4];
-    float g[GATE ? 2 : 1][4];
-    uint32_t inside;   // bit h * 4 + u: element (h, u) lies inside the matrix
+    static constexpr int H = ROWS / 64;
+    float v[H][4];
+    float g[GATE ? H : 1][4];
+    uint32_t inside;   // bit h * 4 + u: element (h, u) lies inside the matrix (scalar path only)
 };
 
-// Loads the thread's share of a (128 x BK) operand tile whose row index starts at i0 (M or N side).
-// KC: the reduction index is contiguous in memory. Nothing consumes the loaded registers before the tile
-// is written to LDS.
+// Loads the thread's share of a (ROWS x BK) operand tile whose row index starts at i0 (M or N side).
+// KC: the reduction index is contiguous in memory.
 //   VEC: a group of 4 floats is wholly inside or wholly outside the matrix (the host checks alignment and
 //        divisibility) and is fetched by one predicated 16-byte load;
 //   otherwise every element is loaded on its own, unconditionally (an out-of-range element reads element
 //        0 of the matrix instead and is zeroed at the LDS write), so that the loads stay straight-line code.
-template <bool KC, bool GATE, bool VEC>
+template <int ROWS, bool KC, bool GATE, bool VEC>
 __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int32_t extent, int32_t k0, int32_t kmax,
-                                          TileRegs<GATE>& r) {
+                                          TileRegs<ROWS, GATE>& r) {
+    constexpr int H = ROWS / 64;
+    constexpr int Q = ROWS / 4;   // groups of 4 rows per reduction index (layout with rows contiguous)
     const int tid = threadIdx.x;
-    r.inside = VEC ? 0xFFu : 0u;
+    r.inside = 0u;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < H; ++h) {
         const int f = tid + h * kThreads;   // index of a group of 4 floats in the tile
-        const int32_t i = KC ? i0 + (f >> 2) : i0 + ((f & 31) << 2);
-        const int32_t kk = KC ? k0 + ((f & 3) << 2) : k0 + (f >> 5);
+        const int32_t i = KC ? i0 + (f >> 2) : i0 + ((f % Q) << 2);
+        const int32_t kk = KC ? k0 + ((f & 3) << 2) : k0 + f / Q;
         const int64_t off = KC ? int64_t(i) * op.ld + kk : int64_t(kk) * op.ld + i;
         if (VEC) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f), gt = x;
@@ -88,23 +91,27 @@ __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int3
     }
 }
 
-// LDS layout of an operand tile (128 rows x BK reduction steps), chosen so that the global -> LDS copy is a
+// LDS layout of an operand tile (ROWS rows x BK reduction steps), chosen so that the global -> LDS copy is a
 // 16-byte store whichever way the operand lies in memory:
 //   KC  (reduction index contiguous in memory): row-major, s[row * kRowStride + k]; a lane then fetches the
 //        8 reduction steps it feeds to the matrix cores with two 16-byte reads;
-//   !KC (row index contiguous in memory): k-major, s[k * kColStride + row]; fragments are scalar reads.
+//   !KC (row index contiguous in memory): k-major, s[k * (ROWS + 4) + row]; fragments are scalar reads.
 // Matrix-core step t of a tile multiplies reduction indices t (lanes 0-31) and 8 + t (lanes 32-63); any
 // pairing is valid as long as both operands use the same one.
 constexpr int kRowStride = BK + 4;    // 20 floats: 16-byte aligned rows, conflict-free 16-byte reads
-constexpr int kColStride = BM + PAD;  // 132 floats
-constexpr int kTileFloats = BM * kRowStride > BK * kColStride ? BM * kRowStride : BK * kColStride;
+template <int ROWS>
+constexpr int tile_floats() {
+    return ROWS * kRowStride > BK * (ROWS + 4) ? ROWS * kRowStride : BK * (ROWS + 4);
+}
 
 // Writes the registers into the LDS tile, applying bounds and the gate (ReLU mask).
-template <bool KC, bool GATE, bool VEC>
-__device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float* s) {
+template <int ROWS, bool KC, bool GATE, bool VEC>
+__device__ __forceinline__ void store_tile(const TileRegs<ROWS, GATE>& r, float* s) {
+    constexpr int H = ROWS / 64;
+    constexpr int Q = ROWS / 4;
     const int tid = threadIdx.x;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < H; ++h) {
         const int f = tid + h * kThreads;
         float x[4];
 #pragma unroll
@@ -112,14 +119,14 @@ __device__ __forceinline__ void store_tile(const TileRegs<GATE>& r, float* s) {
             const bool keep = (VEC || ((r.inside >> (4 * h + u)) & 1u)) && (!GATE || r.g[h][u] > 0.f);
             x[u] = keep ? r.v[h][u] : 0.f;
         }
-        const int off = KC ? (f >> 2) * kRowStride + ((f & 3) << 2) : (f >> 5) * kColStride + ((f & 31) << 2);
+        const int off = KC ? (f >> 2) * kRowStride + ((f & 3) << 2) : (f / Q) * (ROWS + 4) + ((f % Q) << 2);
         *reinterpret_cast<float4*>(s + off) = make_float4(x[0], x[1], x[2], x[3]);
     }
 }
 
 // The 8 values a lane feeds to the matrix cores for tile row `row` during one tile: reduction indices
 // lk * 8 .. lk * 8 + 7.
-template <bool KC>
+template <int ROWS, bool KC>
 __device__ __forceinline__ void load_fragment(const float* s, int row, int lk, float (&out)[8]) {
     if (KC) {
         const float4 lo = *reinterpret_cast<const float4*>(s + row * kRowStride + lk * 8);
@@ -128,16 +135,18 @@ __device__ __forceinline__ void load_fragment(const float* s, int row, int lk, f
         out[4] = hi.x, out[5] = hi.y, out[6] = hi.z, out[7] = hi.w;
     } else {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) out[t] = s[(lk * 8 + t) * kColStride + row];
+        for (int t = 0; t < 8; ++t) out[t] = s[(lk * 8 + t) * (ROWS + 4) + row];
     }
 }
 
-// A_KC / B_KC: operand stored with the reduction index contiguous; A_GATE / B_GATE: operand is masked;
-// VEC: every operand may be fetched with 16-byte loads.
-template <bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool VEC>
+// WM x WN: layout of the four wavefronts over the tile (2 x 2 or 4 x 1); A_KC / B_KC: operand stored with
+// the reduction index contiguous; A_GATE / B_GATE: operand is masked; A_VEC / B_VEC: operand may be
+// fetched with 16-byte loads.
+template <int WM, int WN, bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool A_VEC, bool B_VEC>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
-    __shared__ __attribute__((aligned(16))) float sa[2][kTileFloats];
-    __shared__ __attribute__((aligned(16))) float sb[2][kTileFloats];
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    __shared__ __attribute__((aligned(16))) float sa[2][tile_floats<BM>()];
+    __shared__ __attribute__((aligned(16))) float sb[2][tile_floats<BN>()];
 
     // Workgroups are dealt to the 8 XCDs round-robin. The tiles that share streamed data (the column tiles
     // of one row tile; or, for a split reduction, all output tiles of one slab of the reduction range) are
@@ -163,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = (wave / WN) * 64, wn = (wave % WN) * 64;
     const int lrow = lane & 31, lk = lane >> 5;
 
     floatx16 acc[2][2];
@@ -174,23 +183,23 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    TileRegs<A_GATE> ra;
-    TileRegs<B_GATE> rb;
+    TileRegs<BM, A_GATE> ra;
+    TileRegs<BN, B_GATE> rb;
     // Tile t of the chained reduction: tiles [0, tiles1) come from the first product, the rest from the second.
     // The operands are picked with selects, not branches: a branch around the loads would make the compiler
     // wait for every load in flight where the two paths meet.
     auto fetch = [&](int32_t t) {
         const bool first = t < tiles1;
-        OperandDev oa = g.a, ob = g.b;
+        OperandDev oa, ob;
         oa.ptr = first ? g.a.ptr : g.a2.ptr, oa.gate = first ? g.a.gate : g.a2.gate, oa.ld = first ? g.a.ld : g.a2.ld;
         ob.ptr = first ? g.b.ptr : g.b2.ptr, ob.gate = first ? g.b.gate : g.b2.gate, ob.ld = first ? g.b.ld : g.b2.ld;
         const int32_t k0 = (first ? t : t - tiles1) * BK, kmax = first ? g.k : g.k2;
-        load_tile<A_KC, A_GATE, VEC>(oa, m0, g.m, k0, kmax, ra);
-        load_tile<B_KC, B_GATE, VEC>(ob, n0, g.n, k0, kmax, rb);
+        load_tile<BM, A_KC, A_GATE, A_VEC>(oa, m0, g.m, k0, kmax, ra);
+        load_tile<BN, B_KC, B_GATE, B_VEC>(ob, n0, g.n, k0, kmax, rb);
     };
     auto stash = [&](int buf) {
-        store_tile<A_KC, A_GATE, VEC>(ra, sa[buf]);
-        store_tile<B_KC, B_GATE, VEC>(rb, sb[buf]);
+        store_tile<BM, A_KC, A_GATE, A_VEC>(ra, sa[buf]);
+        store_tile<BN, B_KC, B_GATE, B_VEC>(rb, sb[buf]);
     };
 
     if (t_begin < t_end) {
@@ -202,10 +211,10 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
         const int buf = (t - t_begin) & 1;
         if (t + 1 < t_end) fetch(t + 1);
         float fa[2][8], fb[2][8];
-        load_fragment<A_KC>(sa[buf], wm + lrow, lk, fa[0]);
-        load_fragment<A_KC>(sa[buf], wm + 32 + lrow, lk, fa[1]);
-        load_fragment<B_KC>(sb[buf], wn + lrow, lk, fb[0]);
-        load_fragment<B_KC>(sb[buf], wn + 32 + lrow, lk, fb[1]);
+        load_fragment<BM, A_KC>(sa[buf], wm + lrow, lk, fa[0]);
+        load_fragment<BM, A_KC>(sa[buf], wm + 32 + lrow, lk, fa[1]);
+        load_fragment<BN, B_KC>(sb[buf], wn + lrow, lk, fb[0]);
+        load_fragment<BN, B_KC>(sb[buf], wn + 32 + lrow, lk, fb[1]);
 #pragma unroll
         for (int s8 = 0; s8 < 8; ++s8) {
             acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0][s8], fb[0][s8], acc[0][0], 0, 0, 0);
@@ -277,37 +286,63 @@ __global__ __launch_bounds__(kThreads) void gemm_reduce_kernel(const float* part
     }
 }
 
-// `rows` is the extent of the non-reduction index (M for A, N for B), `red` the reduction length.
-OperandDev make_operand(const GemmOperand& o, bool stored_k_contig, int32_t rows, int32_t red) {
-    OperandDev d;
-    d.ptr = o.ptr;
-    d.gate = o.gate;
-    d.ld = o.ld;
-    d.k_contig = stored_k_contig ? 1 : 0;
+// 16-byte loads are legal for an operand when its base (and gate) are aligned, its leading dimension is a
+// multiple of 4 and groups of 4 consecutive floats never straddle the matrix edge. `rows` is the extent of
+// the non-reduction index (M for A, N for B), `red` the reduction length.
+bool vector_ok(const GemmOperand& o, bool k_contig, int32_t rows, int32_t red) {
+    if (!o.ptr) return true;
     const bool al = (reinterpret_cast<uintptr_t>(o.ptr) & 15u) == 0 && (reinterpret_cast<uintptr_t>(o.gate) & 15u) == 0;
-    // groups of 4 consecutive floats never straddle the matrix edge
-    const bool whole = stored_k_contig ? red % 4 == 0 : rows % 4 == 0;
-    d.vec_ok = (al && o.ld % 4 == 0 && whole) ? 1 : 0;
-    return d;
+    const bool whole = k_contig ? red % 4 == 0 : rows % 4 == 0;
+    return al && o.ld % 4 == 0 && whole;
+}
+
+template <class F>
+void with_flag(bool b, F&& f) {
+    if (b)
+        f(std::true_type{});
+    else
+        f(std::false_type{});
+}
+
+template <bool A_KC, bool B_KC, bool A_GATE, bool B_GATE>
+void launch_layout(bool narrow, bool a_vec, bool b_vec, dim3 grid, hipStream_t stream, const GemmDev& g) {
+    with_flag(narrow, [&](auto nr) {
+        with_flag(a_vec, [&](auto av) {
+            with_flag(b_vec, [&](auto bv) {
+                constexpr int WM = decltype(nr)::value ? 4 : 2, WN = decltype(nr)::value ? 1 : 2;
+                hipLaunchKernelGGL((gemm_kernel<WM, WN, A_KC, B_KC, A_GATE, B_GATE, decltype(av)::value, decltype(bv)::value>),
+                                   grid, dim3(kThreads), 0, stream, g);
+            });
+        });
+    });
 }
 
 }  // namespace
 
 hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag) {
     if (ga.m == 0 || ga.n == 0) return hipSuccess;
+    // A is M x K: k-contiguous as stored unless transposed. B is K x N: k-contiguous only when transposed.
+    const bool a_kc = !ga.a.transposed, b_kc = ga.b.transposed;
+    const bool a_gate = ga.a.gate != nullptr, b_gate = ga.b.gate != nullptr;
+    if (ga.k2 > 0 && (ga.a2.transposed != ga.a.transposed || ga.b2.transposed != ga.b.transposed || ga.a2.gate || ga.b2.gate))
+        return hipErrorInvalidValue;   // the chained product must share the first one's layout and is never masked
+    const bool a_vec = vector_ok(ga.a, a_kc, ga.m, ga.k) && (ga.k2 == 0 || vector_ok(ga.a2, a_kc, ga.m, ga.k2));
+    const bool b_vec = vector_ok(ga.b, b_kc, ga.n, ga.k) && (ga.k2 == 0 || vector_ok(ga.b2, b_kc, ga.n, ga.k2));
+    const bool narrow = ga.n <= 64;
+    const int bm = narrow ? 256 : 128, bn = narrow ? 64 : 128;
+
     GemmDev g;
     g.m = ga.m, g.n = ga.n, g.k = ga.k, g.k2 = ga.k2;
-    // A is M x K: k-contiguous as stored unless transposed. B is K x N: k-contiguous only when transposed.
-    g.a = make_operand(ga.a, !ga.a.transposed, ga.m, ga.k);
-    g.b = make_operand(ga.b, ga.b.transposed, ga.n, ga.k);
-    g.a2 = make_operand(ga.a2, !ga.a2.transposed, ga.m, ga.k2);
-    g.b2 = make_operand(ga.b2, ga.b2.transposed, ga.n, ga.k2);
+    g.a = {ga.a.ptr, ga.a.gate, ga.a.ld};
+    g.b = {ga.b.ptr, ga.b.gate, ga.b.ld};
+    g.a2 = {ga.a2.ptr, ga.a2.gate, ga.a2.ld};
+    g.b2 = {ga.b2.ptr, ga.b2.gate, ga.b2.ld};
     g.c = ga.c;
     g.ldc = ga.ldc;
     g.accumulate = ga.accumulate ? 1 : 0;
     g.relu = ga.relu ? 1 : 0;
-    g.tiles_m = (ga.m + BM - 1) / BM;
-    g.tiles_n = (ga.n + BN - 1) / BN;
+    g.tiles_m = (ga.m + bm - 1) / bm;
+    g.tiles_n = (ga.n + bn - 1) / bn;
     const int32_t k_tiles = (ga.k + BK - 1) / BK + (ga.k2 + BK - 1) / BK;
     int32_t split = ga.split_k < 1 ? 1 : ga.split_k;
     if (split > k_tiles) split = k_tiles < 1 ? 1 : k_tiles;
@@ -326,26 +361,21 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
     }
     const int64_t blocks = int64_t((g.outer + 7) / 8 * 8) * g.inner;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
-    const bool a_kc = g.a.k_contig, b_kc = g.b.k_contig, a_gate = ga.a.gate != nullptr, b_gate = ga.b.gate != nullptr;
-    if ((ga.k2 > 0 && (g.a2.k_contig != g.a.k_contig || g.b2.k_contig != g.b.k_contig || ga.a2.gate || ga.b2.gate)))
-        return hipErrorInvalidValue;   // the chained product must share the first one's layout and is never masked
-    const dim3 grid{unsigned(blocks)}, block{kThreads};
-    const bool vec = g.a.vec_ok && g.b.vec_ok && (ga.k2 == 0 || (g.a2.vec_ok && g.b2.vec_ok));
-    void (*kernel)(GemmDev) = nullptr;
-    if (a_kc && !b_kc && !a_gate && !b_gate)        // act(M H)
-        kernel = vec ? gemm_kernel<true, false, false, false, true> : gemm_kernel<true, false, false, false, false>;
-    else if (a_kc && b_kc && a_gate && !b_gate)     // dZ H^T, masked
-        kernel = vec ? gemm_kernel<true, true, true, false, true> : gemm_kernel<true, true, true, false, false>;
-    else if (a_kc && b_kc && !a_gate && !b_gate)    // dZ H^T
-        kernel = vec ? gemm_kernel<true, true, false, false, true> : gemm_kernel<true, true, false, false, false>;
-    else if (!a_kc && !b_kc && !a_gate && b_gate)   // M^T dZ, masked
-        kernel = vec ? gemm_kernel<false, false, false, true, true> : gemm_kernel<false, false, false, true, false>;
-    else if (!a_kc && !b_kc && !a_gate && !b_gate)  // M^T dZ
-        kernel = vec ? gemm_kernel<false, false, false, false, true> : gemm_kernel<false, false, false, false, false>;
-    else
-        return hipErrorInvalidValue;
+    const dim3 grid{unsigned(blocks)};
+
+    const bool known = (a_kc && !b_kc && !a_gate && !b_gate) || (a_kc && b_kc && !b_gate) || (!a_kc && !b_kc && !a_gate);
+    if (!known) return hipErrorInvalidValue;
     tag.begin(stream);
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, g);
+    if (a_kc && !b_kc)                                   // act(M H)
+        launch_layout<true, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+    else if (a_kc && b_kc && a_gate)                     // dZ H^T, masked
+        launch_layout<true, true, true, false>(narrow, a_vec, b_vec, grid, stream, g);
+    else if (a_kc && b_kc)                               // dZ H^T
+        launch_layout<true, true, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+    else if (b_gate)                                     // M^T dZ, masked
+        launch_layout<false, false, false, true>(narrow, a_vec, b_vec, grid, stream, g);
+    else                                                 // M^T dZ
+        launch_layout<false, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
     tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;

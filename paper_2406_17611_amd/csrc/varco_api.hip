@@ -199,7 +199,8 @@ hipError_t grow(float*& buf, size_t& have, size_t want) {
 // should fill the chip exactly once (three 256-thread workgroups of the GEMM kernel are resident per
 // compute unit, 256 compute units), so that no partly filled second round is left over.
 int32_t gemm_split_for(int32_t m, int32_t n, int64_t k) {
-    const int64_t tiles = int64_t((m + 127) / 128) * ((n + 127) / 128);
+    const int64_t bm = n <= 64 ? 256 : 128, bn = n <= 64 ? 64 : 128;   // tile shapes of the GEMM kernel
+    const int64_t tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
     const int64_t k_tiles = (k + 15) / 16;
     int64_t split = std::max<int64_t>(1, (3 * 256) / tiles);
     split = std::min<int64_t>(split, std::max<int64_t>(1, k_tiles / 8));

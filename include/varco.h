@@ -52,7 +52,7 @@ enum {
 
 enum { VARCO_CONV_GCN = 0 /* single tap S */, VARCO_CONV_SAGE = 1 /* taps I (H0) and S (H1) */ };
 enum { VARCO_ACT_IDENTITY = 0, VARCO_ACT_RELU = 1 };
-enum { VARCO_F32 = 0 };
+enum { VARCO_F32 = 0, VARCO_BF16 = 1 /* activations and gradients stored as bf16, arithmetic in fp32 */ };
 
 #define VARCO_MAX_LAYERS 16
 #define VARCO_MAX_WIDTH 2048
@@ -62,7 +62,7 @@ typedef struct {
     int32_t n_layers;       /* L, 1..VARCO_MAX_LAYERS */
     int32_t n_partitions;   /* Q of Section III */
     int32_t conv;           /* VARCO_CONV_* */
-    int32_t dtype;          /* VARCO_F32 */
+    int32_t dtype;          /* VARCO_F32 or VARCO_BF16: storage type of x, z, m_saved, dx, dz_halo; weights are fp32 */
     uint64_t mask_key;      /* the key shared a priori between encoder and decoder (Appendix A) */
     const int32_t* widths;  /* L+1 widths F_0..F_L, each 1..VARCO_MAX_WIDTH */
     const int32_t* act;     /* L activation codes VARCO_ACT_* */

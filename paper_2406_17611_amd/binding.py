@@ -18,6 +18,7 @@ OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP = range(6)
 CONV_GCN, CONV_SAGE = 0, 1
 ACT_IDENTITY, ACT_RELU = 0, 1
 F32 = 0
+BF16 = 1
 MAX_LAYERS = 16
 
 EXPORTS = [

@@ -2,6 +2,7 @@
 // each node vector; decode by writing them in place and zero elsewhere (no rescale). Pure data movement:
 // HBM-bound, no index bytes are stored or read. A power-of-two group of lanes serves one row, so that
 // narrow messages (k of 4..32) still fill the 64-wide wavefront with several rows.
+#include "elem.h"
 #include "mask_device.h"
 
 namespace {
@@ -12,17 +13,18 @@ __device__ __forceinline__ int64_t group_row(int g_log2) {
     return (int64_t(blockIdx.x) * kBlock + threadIdx.x) >> g_log2;
 }
 
+template <typename T>
 __global__ __launch_bounds__(kBlock) void compress_kernel(MaskRule rule, const int32_t* __restrict__ gids,
                                                           const int32_t* __restrict__ rows, int64_t n_rows,
-                                                          const float* __restrict__ x, int64_t ldx,
-                                                          float* __restrict__ z, int g_log2) {
+                                                          const T* __restrict__ x, int64_t ldx,
+                                                          T* __restrict__ z, int g_log2) {
     const uint32_t g = 1u << g_log2;
     const uint32_t gl = threadIdx.x & (g - 1);
     const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
     for (int64_t row = group_row(g_log2); row < n_rows; row += stride) {
         const int64_t src = rows ? int64_t(rows[row]) : row;
-        const float* xr = x + src * ldx;
-        float* zr = z + row * int64_t(rule.k);
+        const T* xr = x + src * ldx;
+        T* zr = z + row * int64_t(rule.k);
         if (rule.k == rule.width) {
             for (uint32_t j = gl; j < rule.k; j += g) zr[j] = xr[j];
         } else {
@@ -33,24 +35,25 @@ __global__ __launch_bounds__(kBlock) void compress_kernel(MaskRule rule, const i
 }
 
 // Full rows are written in one coalesced pass: column c holds z[j] when its inverse position j is kept.
+template <typename T>
 __global__ __launch_bounds__(kBlock) void decompress_kernel(MaskRule rule, const int32_t* __restrict__ gids,
                                                             const int32_t* __restrict__ rows, int64_t n_rows,
-                                                            const float* __restrict__ z, float* __restrict__ x,
+                                                            const T* __restrict__ z, T* __restrict__ x,
                                                             int64_t ldx, int g_log2) {
     const uint32_t g = 1u << g_log2;
     const uint32_t gl = threadIdx.x & (g - 1);
     const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
     for (int64_t row = group_row(g_log2); row < n_rows; row += stride) {
         const int64_t dst = rows ? int64_t(rows[row]) : row;
-        float* xr = x + dst * ldx;
-        const float* zr = z + row * int64_t(rule.k);
+        T* xr = x + dst * ldx;
+        const T* zr = z + row * int64_t(rule.k);
         if (rule.k == rule.width) {
             for (uint32_t c = gl; c < rule.width; c += g) xr[c] = zr[c];
         } else {
             const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
             for (uint32_t c = gl; c < rule.width; c += g) {
                 const uint32_t j = varco_inverse_position(rule, m, c);
-                xr[c] = j < rule.k ? zr[j] : 0.0f;
+                xr[c] = j < rule.k ? zr[j] : T{};
             }
         }
     }
@@ -58,22 +61,23 @@ __global__ __launch_bounds__(kBlock) void decompress_kernel(MaskRule rule, const
 
 // Owner-side sum of returned errors: rows are distinct within a call and positions are distinct within a
 // row, so plain read-modify-write is race-free and the result does not depend on scheduling.
+template <typename T>
 __global__ __launch_bounds__(kBlock) void decompress_add_kernel(MaskRule rule, const int32_t* __restrict__ gids,
                                                                 const int32_t* __restrict__ rows, int64_t n_rows,
-                                                                const float* __restrict__ z, float* __restrict__ x,
+                                                                const T* __restrict__ z, T* __restrict__ x,
                                                                 int64_t ldx, int g_log2) {
     const uint32_t g = 1u << g_log2;
     const uint32_t gl = threadIdx.x & (g - 1);
     const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
     for (int64_t row = group_row(g_log2); row < n_rows; row += stride) {
         const int64_t dst = rows ? int64_t(rows[row]) : row;
-        float* xr = x + dst * ldx;
-        const float* zr = z + row * int64_t(rule.k);
-        if (rule.k == rule.width) {
-            for (uint32_t j = gl; j < rule.k; j += g) xr[j] += zr[j];
-        } else {
-            const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
-            for (uint32_t j = gl; j < rule.k; j += g) xr[varco_position(rule, m, j)] += zr[j];
+        T* xr = x + dst * ldx;
+        const T* zr = z + row * int64_t(rule.k);
+        MaskAffine m{1, 0, 1};
+        if (rule.k != rule.width) m = varco_affine(rule, uint32_t(gids[row]));
+        for (uint32_t j = gl; j < rule.k; j += g) {
+            T* dstp = xr + (rule.k == rule.width ? j : varco_position(rule, m, j));
+            Elem<T>::store(dstp, Elem<T>::load(dstp) + Elem<T>::load(zr + j));
         }
     }
 }
@@ -81,12 +85,13 @@ __global__ __launch_bounds__(kBlock) void decompress_add_kernel(MaskRule rule, c
 // Owner-side sum over all consumers: a group of lanes (one per stored element) owns one boundary row, adds
 // up the rows returned for it (coalesced reads of k consecutive values each, four in flight), and touches
 // the wide gradient row once.
+template <typename T>
 __global__ __launch_bounds__(kBlock) void accumulate_returned_kernel(MaskRule rule, const int32_t* __restrict__ gids,
                                                                      const int32_t* __restrict__ rows, int64_t n_rows,
                                                                      const int32_t* __restrict__ ptr,
                                                                      const int32_t* __restrict__ src,
-                                                                     const float* __restrict__ returned,
-                                                                     float* __restrict__ x, int64_t ldx, int g_log2) {
+                                                                     const T* __restrict__ returned,
+                                                                     T* __restrict__ x, int64_t ldx, int g_log2) {
     const uint32_t g = 1u << g_log2;
     const uint32_t gl = threadIdx.x & (g - 1);
     const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
@@ -94,20 +99,22 @@ __global__ __launch_bounds__(kBlock) void accumulate_returned_kernel(MaskRule ru
     for (int64_t b = group_row(g_log2); b < n_rows; b += stride) {
         const int32_t e0 = ptr[b], e1 = ptr[b + 1];
         if (e0 == e1) continue;
-        float* xr = x + int64_t(rows[b]) * ldx;
+        T* xr = x + int64_t(rows[b]) * ldx;
         MaskAffine m{1, 0, 1};
         if (rule.k != rule.width) m = varco_affine(rule, uint32_t(gids[b]));
         for (uint32_t j = gl; j < rule.k; j += g) {
             float acc = 0.f;
             int32_t e = e0;
             for (; e + 3 < e1; e += 4) {
-                const float v0 = returned[int64_t(src[e]) * k + j], v1 = returned[int64_t(src[e + 1]) * k + j];
-                const float v2 = returned[int64_t(src[e + 2]) * k + j], v3 = returned[int64_t(src[e + 3]) * k + j];
+                const float v0 = Elem<T>::load(returned + int64_t(src[e]) * k + j);
+                const float v1 = Elem<T>::load(returned + int64_t(src[e + 1]) * k + j);
+                const float v2 = Elem<T>::load(returned + int64_t(src[e + 2]) * k + j);
+                const float v3 = Elem<T>::load(returned + int64_t(src[e + 3]) * k + j);
                 acc += v0, acc += v1, acc += v2, acc += v3;
             }
-            for (; e < e1; ++e) acc += returned[int64_t(src[e]) * k + j];
+            for (; e < e1; ++e) acc += Elem<T>::load(returned + int64_t(src[e]) * k + j);
             const uint32_t pos = rule.k == rule.width ? j : varco_position(rule, m, j);
-            xr[pos] += acc;
+            Elem<T>::store(xr + pos, Elem<T>::load(xr + pos) + acc);
         }
     }
 }
@@ -133,48 +140,74 @@ unsigned grid_for(int64_t n_rows, int g_log2) {
     return unsigned(blocks);
 }
 
-}  // namespace
-
-hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                 const float* x, int64_t ldx, float* z, hipStream_t stream, const LaunchTag& tag) {
-    if (n_rows == 0) return hipSuccess;
+template <typename T>
+hipError_t launch_compress_t(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows, const void* x,
+                             int64_t ldx, void* z, hipStream_t stream) {
     const int gl = group_log2(rule.k);
-    tag.begin(stream);
-    hipLaunchKernelGGL(compress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows, n_rows,
-                       x, ldx, z, gl);
-    tag.end(stream);
+    hipLaunchKernelGGL(compress_kernel<T>, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows, n_rows,
+                       static_cast<const T*>(x), ldx, static_cast<T*>(z), gl);
     return hipGetLastError();
 }
 
-hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream,
-                                   const LaunchTag& tag) {
-    if (n_rows == 0) return hipSuccess;
-    tag.begin(stream);
+template <typename T>
+hipError_t launch_decompress_t(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                               const void* z, void* x, int64_t ldx, int accumulate, hipStream_t stream) {
     if (accumulate) {
         const int gl = group_log2(rule.k);
-        hipLaunchKernelGGL(decompress_add_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids,
-                           rows, n_rows, z, x, ldx, gl);
+        hipLaunchKernelGGL(decompress_add_kernel<T>, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids,
+                           rows, n_rows, static_cast<const T*>(z), static_cast<T*>(x), ldx, gl);
     } else {
         const int gl = group_log2(rule.width);
-        hipLaunchKernelGGL(decompress_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
-                           n_rows, z, x, ldx, gl);
+        hipLaunchKernelGGL(decompress_kernel<T>, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
+                           n_rows, static_cast<const T*>(z), static_cast<T*>(x), ldx, gl);
     }
-    tag.end(stream);
     return hipGetLastError();
 }
 
-hipError_t varco_launch_accumulate_returned(const MaskRule& rule, const int32_t* gids, const int32_t* rows,
-                                            int64_t n_rows, const int32_t* ptr, const int32_t* src,
-                                            const float* returned, float* x, int64_t ldx, hipStream_t stream,
-                                            const LaunchTag& tag) {
-    if (n_rows == 0) return hipSuccess;
+template <typename T>
+hipError_t launch_accumulate_t(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                               const int32_t* ptr, const int32_t* src, const void* returned, void* x, int64_t ldx,
+                               hipStream_t stream) {
     const int gl = group_log2(rule.k);
-    tag.begin(stream);
-    hipLaunchKernelGGL(accumulate_returned_kernel, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows,
-                       n_rows, ptr, src, returned, x, ldx, gl);
-    tag.end(stream);
+    hipLaunchKernelGGL(accumulate_returned_kernel<T>, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids,
+                       rows, n_rows, ptr, src, static_cast<const T*>(returned), static_cast<T*>(x), ldx, gl);
     return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t varco_launch_compress(int dtype, const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                                 const void* x, int64_t ldx, void* z, hipStream_t stream, const LaunchTag& tag) {
+    if (n_rows == 0) return hipSuccess;
+    tag.begin(stream);
+    const hipError_t e = dtype == VARCO_BF16 ? launch_compress_t<bf16_t>(rule, gids, rows, n_rows, x, ldx, z, stream)
+                                             : launch_compress_t<float>(rule, gids, rows, n_rows, x, ldx, z, stream);
+    tag.end(stream);
+    return e;
+}
+
+hipError_t varco_launch_decompress(int dtype, const MaskRule& rule, const int32_t* gids, const int32_t* rows,
+                                   int64_t n_rows, const void* z, void* x, int64_t ldx, int accumulate,
+                                   hipStream_t stream, const LaunchTag& tag) {
+    if (n_rows == 0) return hipSuccess;
+    tag.begin(stream);
+    const hipError_t e = dtype == VARCO_BF16
+                             ? launch_decompress_t<bf16_t>(rule, gids, rows, n_rows, z, x, ldx, accumulate, stream)
+                             : launch_decompress_t<float>(rule, gids, rows, n_rows, z, x, ldx, accumulate, stream);
+    tag.end(stream);
+    return e;
+}
+
+hipError_t varco_launch_accumulate_returned(int dtype, const MaskRule& rule, const int32_t* gids, const int32_t* rows,
+                                            int64_t n_rows, const int32_t* ptr, const int32_t* src, const void* returned,
+                                            void* x, int64_t ldx, hipStream_t stream, const LaunchTag& tag) {
+    if (n_rows == 0) return hipSuccess;
+    tag.begin(stream);
+    const hipError_t e = dtype == VARCO_BF16
+                             ? launch_accumulate_t<bf16_t>(rule, gids, rows, n_rows, ptr, src, returned, x, ldx, stream)
+                             : launch_accumulate_t<float>(rule, gids, rows, n_rows, ptr, src, returned, x, ldx, stream);
+    tag.end(stream);
+    return e;
 }
 
 hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream) {

@@ -1,5 +1,6 @@
 // Dense feature transform of eq. (2) and its gradients on the CDNA matrix cores, in true fp32
-// (v_mfma_f32_32x32x2_f32): X_out = act(M H1 + X H0), dM = dZ H1^T, dH += M^T dZ.
+// (v_mfma_f32_32x32x2_f32): X_out = act(M H1 + X H0), dM = dZ H1^T, dH += M^T dZ. Operands and results
+// stored as bf16 are widened when a tile is fetched and rounded (to nearest even) in the epilogue.
 //
 // One 256-thread workgroup (4 wavefronts) computes a tile of C; each wavefront owns a 64 x 64 sub-tile as
 // 2 x 2 MFMA blocks of 32 x 32 (64 accumulator registers per lane). The wavefronts are laid out 2 x 2
@@ -12,6 +13,7 @@
 // into a partial buffer and summed by a second kernel in a fixed order.
 #include <type_traits>
 
+#include "elem.h"
 #include "varco_internal.h"
 
 namespace {
@@ -22,15 +24,15 @@ constexpr int kThreads = 256;
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct OperandDev {
-    const float* ptr;
-    const float* gate;
+    const void* ptr;     // elements of the kernel's operand type (TA or TB)
+    const void* gate;
     int64_t ld;
 };
 
 struct GemmDev {
     int32_t m, n, k, k2;
     OperandDev a, b, a2, b2;
-    float* c;
+    void* c;             // elements of type TC
     int64_t ldc;
     int32_t accumulate, relu;
     int32_t split_k, tiles_per_split;   // reduction tiles (of BK) handled by one split
@@ -53,16 +55,18 @@ struct TileRegs {
 
 // Loads the thread's share of a (ROWS x BK) operand tile whose row index starts at i0 (M or N side).
 // KC: the reduction index is contiguous in memory.
-//   VEC: a group of 4 floats is wholly inside or wholly outside the matrix (the host checks alignment and
-//        divisibility) and is fetched by one predicated 16-byte load;
+//   VEC: a group of 4 elements is wholly inside or wholly outside the matrix (the host checks alignment and
+//        divisibility) and is fetched by one predicated load of 4 elements;
 //   otherwise every element is loaded on its own, unconditionally (an out-of-range element reads element
 //        0 of the matrix instead and is zeroed at the LDS write), so that the loads stay straight-line code.
-template <int ROWS, bool KC, bool GATE, bool VEC>
+template <typename T, int ROWS, bool KC, bool GATE, bool VEC>
 __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int32_t extent, int32_t k0, int32_t kmax,
                                           TileRegs<ROWS, GATE>& r) {
     constexpr int H = ROWS / 64;
     constexpr int Q = ROWS / 4;   // groups of 4 rows per reduction index (layout with rows contiguous)
     const int tid = threadIdx.x;
+    const T* ptr = static_cast<const T*>(op.ptr);
+    const T* gate = static_cast<const T*>(op.gate);
     r.inside = 0u;
 #pragma unroll
     for (int h = 0; h < H; ++h) {
@@ -73,8 +77,8 @@ __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int3
         if (VEC) {
             float4 x = make_float4(0.f, 0.f, 0.f, 0.f), gt = x;
             if (i < extent && kk < kmax) {
-                x = *reinterpret_cast<const float4*>(op.ptr + off);
-                if (GATE) gt = *reinterpret_cast<const float4*>(op.gate + off);
+                x = load_vec<T, 4>(ptr + off);
+                if (GATE) gt = load_vec<T, 4>(gate + off);
             }
             r.v[h][0] = x.x, r.v[h][1] = x.y, r.v[h][2] = x.z, r.v[h][3] = x.w;
             if (GATE) r.g[h][0] = gt.x, r.g[h][1] = gt.y, r.g[h][2] = gt.z, r.g[h][3] = gt.w;
@@ -83,8 +87,8 @@ __device__ __forceinline__ void load_tile(const OperandDev& op, int32_t i0, int3
             for (int u = 0; u < 4; ++u) {
                 const bool in = KC ? (i < extent && kk + u < kmax) : (kk < kmax && i + u < extent);
                 const int64_t o = in ? off + u : 0;
-                r.v[h][u] = op.ptr[o];
-                if (GATE) r.g[h][u] = op.gate[o];
+                r.v[h][u] = Elem<T>::load(ptr + o);
+                if (GATE) r.g[h][u] = Elem<T>::load(gate + o);
                 r.inside |= in ? (1u << (4 * h + u)) : 0u;
             }
         }
@@ -139,10 +143,11 @@ __device__ __forceinline__ void load_fragment(const float* s, int row, int lk, f
     }
 }
 
-// WM x WN: layout of the four wavefronts over the tile (2 x 2 or 4 x 1); A_KC / B_KC: operand stored with
-// the reduction index contiguous; A_GATE / B_GATE: operand is masked; A_VEC / B_VEC: operand may be
-// fetched with 16-byte loads.
-template <int WM, int WN, bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool A_VEC, bool B_VEC>
+// TA / TB / TC: storage types of the operands and of the result; WM x WN: layout of the four wavefronts
+// over the tile (2 x 2 or 4 x 1); A_KC / B_KC: operand stored with the reduction index contiguous;
+// A_GATE / B_GATE: operand is masked; A_VEC / B_VEC: operand may be fetched four elements at a time.
+template <typename TA, typename TB, typename TC, int WM, int WN, bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool A_VEC,
+          bool B_VEC>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     __shared__ __attribute__((aligned(16))) float sa[2][tile_floats<BM>()];
@@ -194,8 +199,8 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
         oa.ptr = first ? g.a.ptr : g.a2.ptr, oa.gate = first ? g.a.gate : g.a2.gate, oa.ld = first ? g.a.ld : g.a2.ld;
         ob.ptr = first ? g.b.ptr : g.b2.ptr, ob.gate = first ? g.b.gate : g.b2.gate, ob.ld = first ? g.b.ld : g.b2.ld;
         const int32_t k0 = (first ? t : t - tiles1) * BK, kmax = first ? g.k : g.k2;
-        load_tile<BM, A_KC, A_GATE, A_VEC>(oa, m0, g.m, k0, kmax, ra);
-        load_tile<BN, B_KC, B_GATE, B_VEC>(ob, n0, g.n, k0, kmax, rb);
+        load_tile<TA, BM, A_KC, A_GATE, A_VEC>(oa, m0, g.m, k0, kmax, ra);
+        load_tile<TB, BN, B_KC, B_GATE, B_VEC>(ob, n0, g.n, k0, kmax, rb);
     };
     auto stash = [&](int buf) {
         store_tile<BM, A_KC, A_GATE, A_VEC>(ra, sa[buf]);
@@ -227,13 +232,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
     }
 
     // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32)
-    float* cbase = g.c;
-    int64_t ldc = g.ldc;
     const bool to_partial = g.split_k > 1;
-    if (to_partial) {
-        cbase = g.partial + int64_t(z) * g.m * g.n;
-        ldc = g.n;
-    }
+    TC* cout = static_cast<TC*>(g.c);
+    float* pout = g.partial + int64_t(z) * g.m * g.n;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -243,13 +244,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
             for (int v = 0; v < 16; ++v) {
                 const int32_t row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
                 if (row < g.m && col < g.n) {
-                    float* dst = cbase + int64_t(row) * ldc + col;
                     float x = acc[i][j][v];
-                    if (!to_partial) {
-                        if (g.accumulate) x += *dst;
+                    if (to_partial) {
+                        pout[int64_t(row) * g.n + col] = x;
+                    } else {
+                        TC* dst = cout + int64_t(row) * g.ldc + col;
+                        if (g.accumulate) x += Elem<TC>::load(dst);
                         if (g.relu) x = fmaxf(x, 0.f);
+                        Elem<TC>::store(dst, x);
                     }
-                    *dst = x;
                 }
             }
         }
@@ -259,8 +262,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
 // C (+)= sum over splits of partial[s]. 64 consecutive output elements per workgroup; the four wavefronts
 // sum interleaved quarters of the splits (several loads in flight each) and the quarters are added in a
 // fixed order, so the result does not depend on scheduling.
+template <typename TC>
 __global__ __launch_bounds__(kThreads) void gemm_reduce_kernel(const float* partial, int32_t splits, int64_t mn,
-                                                               int32_t n, float* c, int64_t ldc, int32_t accumulate,
+                                                               int32_t n, TC* c, int64_t ldc, int32_t accumulate,
                                                                int32_t relu) {
     __shared__ float part[4][64];
     const int e = threadIdx.x & 63, quarter = threadIdx.x >> 6;
@@ -279,19 +283,20 @@ __global__ __launch_bounds__(kThreads) void gemm_reduce_kernel(const float* part
     __syncthreads();
     if (quarter == 0 && i < mn) {
         x = ((part[0][e] + part[1][e]) + part[2][e]) + part[3][e];
-        float* dst = c + (i / n) * ldc + (i % n);
-        if (accumulate) x += *dst;
+        TC* dst = c + (i / n) * ldc + (i % n);
+        if (accumulate) x += Elem<TC>::load(dst);
         if (relu) x = fmaxf(x, 0.f);
-        *dst = x;
+        Elem<TC>::store(dst, x);
     }
 }
 
-// 16-byte loads are legal for an operand when its base (and gate) are aligned, its leading dimension is a
-// multiple of 4 and groups of 4 consecutive floats never straddle the matrix edge. `rows` is the extent of
-// the non-reduction index (M for A, N for B), `red` the reduction length.
+// Loads of 4 elements are legal for an operand when its base (and gate) are aligned to them, its leading
+// dimension is a multiple of 4 and groups of 4 consecutive elements never straddle the matrix edge. `rows`
+// is the extent of the non-reduction index (M for A, N for B), `red` the reduction length.
 bool vector_ok(const GemmOperand& o, bool k_contig, int32_t rows, int32_t red) {
     if (!o.ptr) return true;
-    const bool al = (reinterpret_cast<uintptr_t>(o.ptr) & 15u) == 0 && (reinterpret_cast<uintptr_t>(o.gate) & 15u) == 0;
+    const uintptr_t mask = (o.dtype == VARCO_BF16 ? 8u : 16u) - 1u;
+    const bool al = (reinterpret_cast<uintptr_t>(o.ptr) & mask) == 0 && (reinterpret_cast<uintptr_t>(o.gate) & mask) == 0;
     const bool whole = k_contig ? red % 4 == 0 : rows % 4 == 0;
     return al && o.ld % 4 == 0 && whole;
 }
@@ -304,13 +309,14 @@ void with_flag(bool b, F&& f) {
         f(std::false_type{});
 }
 
-template <bool A_KC, bool B_KC, bool A_GATE, bool B_GATE>
+template <typename TA, typename TB, typename TC, bool A_KC, bool B_KC, bool A_GATE, bool B_GATE>
 void launch_layout(bool narrow, bool a_vec, bool b_vec, dim3 grid, hipStream_t stream, const GemmDev& g) {
     with_flag(narrow, [&](auto nr) {
         with_flag(a_vec, [&](auto av) {
             with_flag(b_vec, [&](auto bv) {
                 constexpr int WM = decltype(nr)::value ? 4 : 2, WN = decltype(nr)::value ? 1 : 2;
-                hipLaunchKernelGGL((gemm_kernel<WM, WN, A_KC, B_KC, A_GATE, B_GATE, decltype(av)::value, decltype(bv)::value>),
+                hipLaunchKernelGGL((gemm_kernel<TA, TB, TC, WM, WN, A_KC, B_KC, A_GATE, B_GATE, decltype(av)::value,
+                                                decltype(bv)::value>),
                                    grid, dim3(kThreads), 0, stream, g);
             });
         });
@@ -365,25 +371,51 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
 
     const bool known = (a_kc && !b_kc && !a_gate && !b_gate) || (a_kc && b_kc && !b_gate) || (!a_kc && !b_kc && !a_gate);
     if (!known) return hipErrorInvalidValue;
+    // storage types: all fp32; or bf16 activations with fp32 weights: (A, B, C) = (bf16, f32, bf16) for the
+    // transform and the input gradient, (bf16, bf16, f32) for the weight gradient
+    const int ta = ga.a.dtype, tb = ga.b.dtype, tc = ga.c_dtype;
+    if (ga.k2 > 0 && (ga.a2.dtype != ta || ga.b2.dtype != tb)) return hipErrorInvalidValue;
+    const bool all_f32 = ta == VARCO_F32 && tb == VARCO_F32 && tc == VARCO_F32;
+    const bool act_out = ta == VARCO_BF16 && tb == VARCO_F32 && tc == VARCO_BF16 && a_kc;
+    const bool weight_out = ta == VARCO_BF16 && tb == VARCO_BF16 && tc == VARCO_F32 && !a_kc;
+    if (!all_f32 && !act_out && !weight_out) return hipErrorInvalidValue;
     tag.begin(stream);
-    if (a_kc && !b_kc)                                   // act(M H)
-        launch_layout<true, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
-    else if (a_kc && b_kc && a_gate)                     // dZ H^T, masked
-        launch_layout<true, true, true, false>(narrow, a_vec, b_vec, grid, stream, g);
-    else if (a_kc && b_kc)                               // dZ H^T
-        launch_layout<true, true, false, false>(narrow, a_vec, b_vec, grid, stream, g);
-    else if (b_gate)                                     // M^T dZ, masked
-        launch_layout<false, false, false, true>(narrow, a_vec, b_vec, grid, stream, g);
-    else                                                 // M^T dZ
-        launch_layout<false, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+    if (all_f32) {
+        if (a_kc && !b_kc)                                   // act(M H)
+            launch_layout<float, float, float, true, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+        else if (a_kc && b_kc && a_gate)                     // dZ H^T, masked
+            launch_layout<float, float, float, true, true, true, false>(narrow, a_vec, b_vec, grid, stream, g);
+        else if (a_kc && b_kc)                               // dZ H^T
+            launch_layout<float, float, float, true, true, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+        else if (b_gate)                                     // M^T dZ, masked
+            launch_layout<float, float, float, false, false, false, true>(narrow, a_vec, b_vec, grid, stream, g);
+        else                                                 // M^T dZ
+            launch_layout<float, float, float, false, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+    } else if (act_out) {
+        if (!b_kc)
+            launch_layout<bf16_t, float, bf16_t, true, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+        else if (a_gate)
+            launch_layout<bf16_t, float, bf16_t, true, true, true, false>(narrow, a_vec, b_vec, grid, stream, g);
+        else
+            launch_layout<bf16_t, float, bf16_t, true, true, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+    } else {
+        if (b_gate)
+            launch_layout<bf16_t, bf16_t, float, false, false, false, true>(narrow, a_vec, b_vec, grid, stream, g);
+        else
+            launch_layout<bf16_t, bf16_t, float, false, false, false, false>(narrow, a_vec, b_vec, grid, stream, g);
+    }
     tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (split > 1) {
         const int64_t mn = int64_t(ga.m) * ga.n;
         tag.begin_as(VARCO_K_REDUCE, stream);
-        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream, ga.partial,
-                           split, mn, ga.n, ga.c, ga.ldc, g.accumulate, g.relu);
+        if (tc == VARCO_BF16)
+            hipLaunchKernelGGL(gemm_reduce_kernel<bf16_t>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream,
+                               ga.partial, split, mn, ga.n, static_cast<bf16_t*>(ga.c), ga.ldc, g.accumulate, g.relu);
+        else
+            hipLaunchKernelGGL(gemm_reduce_kernel<float>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream,
+                               ga.partial, split, mn, ga.n, static_cast<float*>(ga.c), ga.ldc, g.accumulate, g.relu);
         tag.end(stream);
         err = hipGetLastError();
     }

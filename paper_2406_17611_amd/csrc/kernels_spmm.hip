@@ -18,6 +18,7 @@
 // the caller's column indices, so that a halo entry needs no dependent index lookups before its data load.
 #include <algorithm>
 
+#include "elem.h"
 #include "mask_device.h"
 
 namespace {
@@ -27,19 +28,7 @@ constexpr int kWaves = kBlock / 64;
 constexpr int kUnroll = 4;   // independent gathers issued back to back
 
 template <int VEC>
-struct Vec;
-template <>
-struct Vec<4> {
-    using type = float4;
-};
-template <>
-struct Vec<2> {
-    using type = float2;
-};
-template <>
-struct Vec<1> {
-    using type = float;
-};
+using Vec = FloatVec<VEC>;
 
 __device__ __forceinline__ void fma_vec(float4& acc, float w, const float4& v) {
     acc.x += w * v.x;
@@ -70,18 +59,19 @@ __device__ __forceinline__ float elem(const float2& v, int i) { return i == 0 ? 
 __device__ __forceinline__ float elem(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 __device__ __forceinline__ float elem(const float& v, int) { return v; }
 
+template <typename T>
 struct SpmmArgs {
     const SpmmItem* items;
     int32_t n_items;
     const VarcoEdge* edge;    // HALO kernels: one record per CSR entry
     const int32_t* colidx;    // dense-only kernels: column = source row
     const float* vals;
-    const float* dense;
-    const float* z;
+    const T* dense;
+    const T* z;
     MaskRule rule;
-    float* out;
+    T* out;
     int32_t row_base;
-    float* partial;
+    float* partial;           // partial sums of split rows stay in fp32
     int32_t lpr_log2;         // lanes per dense row = 1 << lpr_log2
     int32_t ev;               // stored elements of a compressed row per lane and load: 4, 2 or 1
     int32_t ku;               // loads per compressed row = k / ev
@@ -94,8 +84,8 @@ struct SpmmArgs {
 // of EV stored elements), `epi` entries are handled per instruction, and each of those lane groups adds
 // into a private LDS row of its own: the positions of one entry are distinct, so plain read-add-write is
 // race-free and no LDS atomics (which run at a small fraction of the plain LDS rate) are needed.
-template <int EV>
-__device__ __forceinline__ void sparse_phase(const SpmmArgs& p, int lane, int nd, int ns, int32_t srow, float w,
+template <typename T, int EV>
+__device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int nd, int ns, int32_t srow, float w,
                                              uint32_t mab, float* lpriv) {
     using V = typename Vec<EV>::type;
     const int32_t k = int32_t(p.rule.k);
@@ -124,7 +114,7 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs& p, int lane, int nd
                 a[u] = ab & 0xFFFFu;
                 pos[u] = varco_mod_width(a[u] * uint32_t(j) + (ab >> 16), width, p.rule.width_magic);
                 zero_vec(v[u]);
-                if (act[u]) v[u] = *reinterpret_cast<const V*>(p.z + int64_t(r) * k + j);
+                if (act[u]) v[u] = load_vec<T, EV>(p.z + int64_t(r) * k + j);
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -147,11 +137,12 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs& p, int lane, int nd
     }
 }
 
-// VEC: floats per lane per load of a dense row (4 needs width % 4 == 0 and 16-byte aligned bases);
+// T: storage type of the dense rows, the compressed rows and the output (sums are kept in fp32);
+// VEC: elements per lane per load of a dense row (4 needs width % 4 == 0 and bases aligned to 4 elements);
 // NV: such loads per lane per row, so that width <= VEC * NV * lanes-per-row;
 // HALO: entries may refer to compressed halo rows (forward aggregation) or all rows are dense.
-template <int VEC, int NV, bool HALO>
-__global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
+template <typename T, int VEC, int NV, bool HALO>
+__global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
     using V = typename Vec<VEC>::type;
     constexpr int U = NV >= 4 ? 1 : (NV == 2 ? 2 : kUnroll);
     extern __shared__ float lds[];
@@ -220,12 +211,12 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
                 const int32_t r = __shfl(srow, src_lane);
                 wi[u] = __shfl(w, src_lane);
                 const bool h = HALO && ((hmask >> src_lane) & 1);
-                const float* src = (h ? p.z : p.dense) + int64_t(r) * width;
+                const T* src = (h ? p.z : p.dense) + int64_t(r) * width;
 #pragma unroll
                 for (int m = 0; m < NV; ++m) {
                     const int col = VEC * (t + lpr * m);
                     zero_vec(v[u][m]);
-                    if (ok[u] && col < width) v[u][m] = *reinterpret_cast<const V*>(src + col);
+                    if (ok[u] && col < width) v[u][m] = load_vec<T, VEC>(src + col);
                 }
             }
 #pragma unroll
@@ -237,11 +228,11 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
         if (ns > 0) {
             any_sparse = true;
             if (p.ev == 4)
-                sparse_phase<4>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 4>(p, lane, nd, ns, srow, w, mab, lpriv);
             else if (p.ev == 2)
-                sparse_phase<2>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 2>(p, lane, nd, ns, srow, w, mab, lpriv);
             else
-                sparse_phase<1>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 1>(p, lane, nd, ns, srow, w, mab, lpriv);
         }
     }
 
@@ -252,7 +243,6 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     if (g == 0) {
-        float* dst = it.dst < 0 ? p.out + int64_t(it.row - p.row_base) * width : p.partial + int64_t(it.dst) * width;
 #pragma unroll
         for (int m = 0; m < NV; ++m) {
             const int col = VEC * (t + lpr * m);
@@ -260,15 +250,19 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs p) {
                 V v = acc[m];
                 if (any_sparse)
                     for (int sub = 0; sub < p.epi; ++sub) add_vec(v, *reinterpret_cast<const V*>(lpriv + sub * width + col));
-                *reinterpret_cast<V*>(dst + col) = v;
+                if (it.dst < 0)
+                    store_vec<T, VEC>(p.out + int64_t(it.row - p.row_base) * width + col, v);
+                else
+                    *reinterpret_cast<V*>(p.partial + int64_t(it.dst) * width + col) = v;
             }
         }
     }
 }
 
 // out[row] = sum of the partial rows of a split row, in slot order (fixed order: reproducible bits).
+template <typename T>
 __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* splits, int32_t n_splits,
-                                                            const float* partial, float* out, int32_t row_base,
+                                                            const float* partial, T* out, int32_t row_base,
                                                             int32_t width) {
     const int32_t s = blockIdx.x;
     if (s >= n_splits) return;
@@ -276,7 +270,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* spl
     for (int c = threadIdx.x; c < width; c += kBlock) {
         float acc = 0.f;
         for (int i = 0; i < sp.count; ++i) acc += partial[int64_t(sp.first + i) * width + c];
-        out[int64_t(sp.row - row_base) * width + c] = acc;
+        Elem<T>::store(out + int64_t(sp.row - row_base) * width + c, acc);
     }
 }
 
@@ -291,22 +285,23 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* spl
 //   2. transposed order: the products of one halo slot are now consecutive rows; they are summed in entry
 //      order (fixed order: reproducible bits) into dz_halo.
 // ---------------------------------------------------------------------------------------------------------
+template <typename T>
 struct ProductArgs {
     const SpmmItem* items;      // work list of the forward row block
     int32_t n_items;
     const VarcoEdge* edge;
     const float* vals;
     const int32_t* prow;        // per entry: row of the product buffer (halo entries only)
-    const float* dm;            // n_local x width
+    const T* dm;                // n_local x width
     MaskRule rule;
-    float* prod;                // (halo entries) x k
+    float* prod;                // (halo entries) x k, fp32
     int32_t ev;                 // floats per lane and store: 4, 2 or 1
     int32_t ku;                 // stores per entry = k / ev
     int32_t lpe_log2;           // lanes per entry
 };
 
-template <int EV>
-__device__ __forceinline__ void product_phase(const ProductArgs& p, int lane, int first, int ns, int32_t pr, float w,
+template <typename T, int EV>
+__device__ __forceinline__ void product_phase(const ProductArgs<T>& p, int lane, int first, int ns, int32_t pr, float w,
                                               uint32_t mab, const float* lrow) {
     using V = typename Vec<EV>::type;
     const int64_t k = p.rule.k;
@@ -347,7 +342,8 @@ __device__ __forceinline__ void product_phase(const ProductArgs& p, int lane, in
     }
 }
 
-__global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs p) {
+template <typename T>
+__global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs<T> p) {
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -370,8 +366,8 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs p) {
         const uint64_t hmask = __ballot(is_halo);
         if (hmask == 0) continue;       // uniform: this batch holds local entries only
         if (!staged) {                  // the row of dM is read once, by the first batch that needs it
-            const float* src = p.dm + int64_t(it.row) * width;
-            for (int c = lane; c < width; c += 64) lrow[c] = src[c];
+            const T* src = p.dm + int64_t(it.row) * width;
+            for (int c = lane; c < width; c += 64) lrow[c] = Elem<T>::load(src + c);
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             staged = true;
         }
@@ -389,30 +385,30 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs p) {
         const int ns = __popcll(hmask);
         const int first = cnt - ns;     // columns ascend within a row: halo entries sit in the last lanes
         if (p.ev == 4)
-            product_phase<4>(p, lane, first, ns, pr, w, mab, lrow);
+            product_phase<T, 4>(p, lane, first, ns, pr, w, mab, lrow);
         else if (p.ev == 2)
-            product_phase<2>(p, lane, first, ns, pr, w, mab, lrow);
+            product_phase<T, 2>(p, lane, first, ns, pr, w, mab, lrow);
         else
-            product_phase<1>(p, lane, first, ns, pr, w, mab, lrow);
+            product_phase<T, 1>(p, lane, first, ns, pr, w, mab, lrow);
     }
 }
 
+template <typename T>
 struct SegsumArgs {
     const SpmmItem* items;      // work list of the transposed halo rows (entry ranges in transposed order)
     int32_t n_items;
     const float* prod;
     int32_t prod_base;          // transposed position of the first halo entry (= product row 0)
     int32_t k;
-    float* out;
+    T* out;
     int32_t row_base;
     float* partial;
     int32_t ev, ku, lpe_log2;
 };
 
-template <int EV>
-__device__ __forceinline__ void segsum_body(const SegsumArgs& p, const SpmmItem& it, int jl, int lpe) {
+template <typename T, int EV>
+__device__ __forceinline__ void segsum_body(const SegsumArgs<T>& p, const SpmmItem& it, int jl, int lpe) {
     using V = typename Vec<EV>::type;
-    float* dst = it.dst < 0 ? p.out + int64_t(it.row - p.row_base) * p.k : p.partial + int64_t(it.dst) * p.k;
     for (int ju = jl; ju < p.ku; ju += lpe) {
         const float* src = p.prod + int64_t(it.e0 - p.prod_base) * p.k + ju * EV;
         V acc;
@@ -429,22 +425,26 @@ __device__ __forceinline__ void segsum_body(const SegsumArgs& p, const SpmmItem&
             add_vec(acc, *reinterpret_cast<const V*>(src));
             src += p.k;
         }
-        *reinterpret_cast<V*>(dst + ju * EV) = acc;
+        if (it.dst < 0)
+            store_vec<T, EV>(p.out + int64_t(it.row - p.row_base) * p.k + ju * EV, acc);
+        else
+            *reinterpret_cast<V*>(p.partial + int64_t(it.dst) * p.k + ju * EV) = acc;
     }
 }
 
-__global__ __launch_bounds__(kBlock) void halo_segsum_kernel(SegsumArgs p) {
+template <typename T>
+__global__ __launch_bounds__(kBlock) void halo_segsum_kernel(SegsumArgs<T> p) {
     const int lpe = 1 << p.lpe_log2;
     const int64_t gidx = (int64_t(blockIdx.x) * kBlock + threadIdx.x) >> p.lpe_log2;
     if (gidx >= p.n_items) return;
     const SpmmItem it = p.items[gidx];
     const int jl = threadIdx.x & (lpe - 1);
     if (p.ev == 4)
-        segsum_body<4>(p, it, jl, lpe);
+        segsum_body<T, 4>(p, it, jl, lpe);
     else if (p.ev == 2)
-        segsum_body<2>(p, it, jl, lpe);
+        segsum_body<T, 2>(p, it, jl, lpe);
     else
-        segsum_body<1>(p, it, jl, lpe);
+        segsum_body<T, 1>(p, it, jl, lpe);
 }
 
 // prow[e] of a halo entry e = (local row i, halo column c): its position among the halo entries in the
@@ -487,48 +487,41 @@ __global__ __launch_bounds__(kBlock) void build_edges_kernel(const int32_t* coli
     edge[e] = ed;
 }
 
-template <int VEC, bool HALO>
-hipError_t launch_spmm_vec(int nv, const SpmmArgs& a, dim3 grid, size_t lds_bytes, hipStream_t stream) {
+template <typename T, int VEC, bool HALO>
+hipError_t launch_spmm_vec(int nv, const SpmmArgs<T>& a, dim3 grid, size_t lds_bytes, hipStream_t stream) {
     switch (nv) {
-        case 1: hipLaunchKernelGGL((spmm_kernel<VEC, 1, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 2: hipLaunchKernelGGL((spmm_kernel<VEC, 2, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 4: hipLaunchKernelGGL((spmm_kernel<VEC, 4, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 8: hipLaunchKernelGGL((spmm_kernel<VEC, 8, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 1: hipLaunchKernelGGL((spmm_kernel<T, VEC, 1, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 2: hipLaunchKernelGGL((spmm_kernel<T, VEC, 2, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 4: hipLaunchKernelGGL((spmm_kernel<T, VEC, 4, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 8: hipLaunchKernelGGL((spmm_kernel<T, VEC, 8, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned_to(const void* p, size_t bytes) { return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; }
 
-}  // namespace
-
-hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
-                                    const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream) {
-    if (nnz == 0) return hipSuccess;
-    hipLaunchKernelGGL(build_edges_kernel, dim3(unsigned((nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, colidx,
-                       nnz, n_local, halo_zrow, halo_gid, edge);
-    return hipGetLastError();
-}
-
-hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx, const float* vals,
-                             const float* dense, const float* z, const MaskRule& rule, float* out, int32_t row_base,
-                             float* partial, hipStream_t stream, const LaunchTag& tag) {
-    if (plan.n_items == 0) return hipSuccess;
+template <typename T>
+hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx, const float* vals, const void* dense_v,
+                  const void* z_v, const MaskRule& rule, void* out_v, int32_t row_base, float* partial,
+                  hipStream_t stream, const LaunchTag& tag) {
+    const T* dense = static_cast<const T*>(dense_v);
+    const T* z = static_cast<const T*>(z_v);
+    T* out = static_cast<T*>(out_v);
     const int32_t width = int32_t(rule.width);
     const bool full = rule.k == rule.width;
     const bool halo = edge != nullptr;
-    const bool vec4 = width % 4 == 0 && aligned16(dense) && aligned16(out) && aligned16(partial) &&
-                      (!(halo && full) || aligned16(z));
+    const bool vec4 = width % 4 == 0 && aligned_to(dense, 4 * sizeof(T)) && aligned_to(out, 4 * sizeof(T)) &&
+                      aligned_to(partial, 16) && (!(halo && full) || aligned_to(z, 4 * sizeof(T)));
     const int vec = vec4 ? 4 : 1;
-    const int per_row = (width + vec - 1) / vec;   // loads of VEC floats that cover a row
+    const int per_row = (width + vec - 1) / vec;   // loads of VEC elements that cover a row
     int lpr_log2 = 0;
     while ((1 << lpr_log2) < per_row && lpr_log2 < 6) ++lpr_log2;
     int nv = 1;
     while (nv * (1 << lpr_log2) < per_row) nv <<= 1;
     if (nv > 8) return hipErrorInvalidValue;
 
-    SpmmArgs a;
+    SpmmArgs<T> a;
     a.items = plan.items;
     a.n_items = plan.n_items;
     a.edge = edge;
@@ -547,7 +540,7 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const 
     const int epi_cap = std::max(1, 1024 / width);
     a.ev = 1;
     for (int ev : {4, 2}) {
-        if (rule.k % ev != 0 || (reinterpret_cast<uintptr_t>(z) & (4 * ev - 1)) != 0) continue;
+        if (rule.k % ev != 0 || !aligned_to(z, ev * sizeof(T))) continue;
         int lg = 0;
         while ((1 << lg) < int(rule.k) / ev && lg < 6) ++lg;
         if ((64 >> lg) <= epi_cap) {
@@ -566,16 +559,16 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const 
     tag.begin(stream);
     hipError_t err;
     if (halo)
-        err = vec4 ? launch_spmm_vec<4, true>(nv, a, grid, lds_bytes, stream)
-                   : launch_spmm_vec<1, true>(nv, a, grid, lds_bytes, stream);
+        err = vec4 ? launch_spmm_vec<T, 4, true>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<T, 1, true>(nv, a, grid, lds_bytes, stream);
     else
-        err = vec4 ? launch_spmm_vec<4, false>(nv, a, grid, lds_bytes, stream)
-                   : launch_spmm_vec<1, false>(nv, a, grid, lds_bytes, stream);
+        err = vec4 ? launch_spmm_vec<T, 4, false>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<T, 1, false>(nv, a, grid, lds_bytes, stream);
     tag.end(stream);
     if (err != hipSuccess) return err;
     if (plan.n_splits > 0) {
         tag.begin_as(VARCO_K_REDUCE, stream);
-        hipLaunchKernelGGL(spmm_fixup_kernel, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
+        hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
                            partial, out, row_base, width);
         tag.end(stream);
         err = hipGetLastError();
@@ -583,24 +576,16 @@ hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const 
     return err;
 }
 
-hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
-                                   const int32_t* t_rowptr, const int32_t* t_colidx, int32_t* prow, hipStream_t stream) {
-    if (n_local == 0) return hipSuccess;
-    hipLaunchKernelGGL(build_prow_kernel, dim3(unsigned((n_local + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, rowptr,
-                       colidx, n_local, t_rowptr, t_colidx, prow);
-    return hipGetLastError();
-}
-
-hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
-                                  const float* vals, const int32_t* prow, int32_t prod_base, const float* dm,
-                                  const MaskRule& rule, float* prod, float* out, int32_t row_base, float* partial,
-                                  hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag) {
-    if (t_halo_plan.n_items == 0 || fwd_plan.n_items == 0) return hipSuccess;
+template <typename T>
+hipError_t halo_grad_t(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge, const float* vals,
+                       const int32_t* prow, int32_t prod_base, const void* dm, const MaskRule& rule, float* prod,
+                       void* out_v, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag,
+                       const LaunchTag& sum_tag) {
+    T* out = static_cast<T*>(out_v);
     const int32_t width = int32_t(rule.width);
     int ev = 1;
     for (int c : {4, 2})
-        if (rule.k % c == 0 && (reinterpret_cast<uintptr_t>(prod) & (4 * c - 1)) == 0 &&
-            (reinterpret_cast<uintptr_t>(out) & (4 * c - 1)) == 0 && (reinterpret_cast<uintptr_t>(partial) & (4 * c - 1)) == 0) {
+        if (rule.k % c == 0 && aligned_to(prod, 4 * c) && aligned_to(out, c * sizeof(T)) && aligned_to(partial, 4 * c)) {
             ev = c;
             break;
         }
@@ -608,24 +593,24 @@ hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_ha
     int lpe_log2 = 0;
     while ((1 << lpe_log2) < ku && lpe_log2 < 6) ++lpe_log2;
 
-    ProductArgs a;
+    ProductArgs<T> a;
     a.items = fwd_plan.items;
     a.n_items = fwd_plan.n_items;
     a.edge = edge;
     a.vals = vals;
     a.prow = prow;
-    a.dm = dm;
+    a.dm = static_cast<const T*>(dm);
     a.rule = rule;
     a.prod = prod;
     a.ev = ev, a.ku = ku, a.lpe_log2 = lpe_log2;
     const size_t lds_bytes = size_t(kWaves) * width * sizeof(float) + size_t(rule.n_units) * sizeof(uint16_t);
     tag.begin(stream);
-    hipLaunchKernelGGL(halo_products_kernel, dim3((fwd_plan.n_items + kWaves - 1) / kWaves), dim3(kBlock), lds_bytes,
+    hipLaunchKernelGGL(halo_products_kernel<T>, dim3((fwd_plan.n_items + kWaves - 1) / kWaves), dim3(kBlock), lds_bytes,
                        stream, a);
     tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    SegsumArgs b;
+    SegsumArgs<T> b;
     b.items = t_halo_plan.items;
     b.n_items = t_halo_plan.n_items;
     b.prod = prod;
@@ -637,16 +622,54 @@ hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_ha
     b.ev = ev, b.ku = ku, b.lpe_log2 = lpe_log2;
     const int64_t threads = int64_t(t_halo_plan.n_items) << lpe_log2;
     sum_tag.begin(stream);
-    hipLaunchKernelGGL(halo_segsum_kernel, dim3(unsigned((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, b);
+    hipLaunchKernelGGL(halo_segsum_kernel<T>, dim3(unsigned((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, b);
     sum_tag.end(stream);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (t_halo_plan.n_splits > 0) {
         tag.begin_as(VARCO_K_REDUCE, stream);
-        hipLaunchKernelGGL(spmm_fixup_kernel, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
+        hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
                            t_halo_plan.n_splits, partial, out, row_base, int32_t(rule.k));
         tag.end(stream);
         err = hipGetLastError();
     }
     return err;
+}
+
+}  // namespace
+
+hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
+                                    const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream) {
+    if (nnz == 0) return hipSuccess;
+    hipLaunchKernelGGL(build_edges_kernel, dim3(unsigned((nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, colidx,
+                       nnz, n_local, halo_zrow, halo_gid, edge);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_spmm(int dtype, const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx,
+                             const float* vals, const void* dense, const void* z, const MaskRule& rule, void* out,
+                             int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag) {
+    if (plan.n_items == 0) return hipSuccess;
+    return dtype == VARCO_BF16
+               ? spmm_t<bf16_t>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag)
+               : spmm_t<float>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag);
+}
+
+hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
+                                   const int32_t* t_rowptr, const int32_t* t_colidx, int32_t* prow, hipStream_t stream) {
+    if (n_local == 0) return hipSuccess;
+    hipLaunchKernelGGL(build_prow_kernel, dim3(unsigned((n_local + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, rowptr,
+                       colidx, n_local, t_rowptr, t_colidx, prow);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_halo_grad(int dtype, const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
+                                  const float* vals, const int32_t* prow, int32_t prod_base, const void* dm,
+                                  const MaskRule& rule, float* prod, void* out, int32_t row_base, float* partial,
+                                  hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag) {
+    if (t_halo_plan.n_items == 0 || fwd_plan.n_items == 0) return hipSuccess;
+    return dtype == VARCO_BF16 ? halo_grad_t<bf16_t>(fwd_plan, t_halo_plan, edge, vals, prow, prod_base, dm, rule, prod, out,
+                                                     row_base, partial, stream, tag, sum_tag)
+                               : halo_grad_t<float>(fwd_plan, t_halo_plan, edge, vals, prow, prod_base, dm, rule, prod, out,
+                                                    row_base, partial, stream, tag, sum_tag);
 }

@@ -47,7 +47,7 @@ struct varco_ctx {
     std::vector<LayerState> layers;
     std::vector<PartState> parts;
     // device workspace shared by all calls on this context
-    float* ws_dm = nullptr;        size_t ws_dm_elems = 0;        // dM: n_local x width
+    float* ws_dm = nullptr;        size_t ws_dm_elems = 0;        // dM: n_local x width (elements of the storage type)
     float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
     float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
     float* ws_prod = nullptr;      size_t ws_prod_elems = 0;      // halo-gradient products: (halo entries) x k
@@ -56,6 +56,7 @@ struct varco_ctx {
     double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
     int64_t prof_launches[VARCO_K_COUNT] = {};
     mutable std::string error;
+    double elem_bytes() const { return dtype == VARCO_BF16 ? 2.0 : 4.0; }
     LaunchTag tag(int cls, double bytes, double flops) {
         LaunchTag t;
         t.prof = prof.on ? &prof : nullptr;
@@ -258,7 +259,8 @@ extern "C" int32_t varco_create(const varco_config* cfg, varco_ctx** out) {
     if (cfg->n_partitions < 1) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_create: n_partitions must be positive");
     if (cfg->conv != VARCO_CONV_GCN && cfg->conv != VARCO_CONV_SAGE)
         return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: unknown conv");
-    if (cfg->dtype != VARCO_F32) return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: only fp32 storage is implemented");
+    if (cfg->dtype != VARCO_F32 && cfg->dtype != VARCO_BF16)
+        return varco_fail(nullptr, VARCO_ERR_UNSUPPORTED, "varco_create: dtype must be VARCO_F32 or VARCO_BF16");
     for (int32_t l = 0; l <= cfg->n_layers; ++l) {
         const int32_t w = cfg->widths[l];
         if (w < 1 || w > VARCO_MAX_WIDTH) return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_create: width outside 1..VARCO_MAX_WIDTH");
@@ -279,7 +281,7 @@ extern "C" int32_t varco_create(const varco_config* cfg, varco_ctx** out) {
     ctx->act.assign(cfg->act, cfg->act + cfg->n_layers);
     ctx->layers.resize(cfg->n_layers);
     ctx->parts.resize(cfg->n_partitions);
-    ctx->stats.bytes_per_elem = 4;
+    ctx->stats.bytes_per_elem = cfg->dtype == VARCO_BF16 ? 2 : 4;
     for (int32_t l = 0; l < ctx->n_layers; ++l) {
         LayerState& ls = ctx->layers[l];
         const int32_t w = ctx->widths[l];
@@ -447,9 +449,8 @@ extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* 
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;   // the step's positions of this layer are now in use
     const MaskRule rule = make_rule(ctx, layer);
-    const double bytes = double(n_rows) * (rule.width + rule.k) * 4.0;
-    VARCO_HIP(ctx, varco_launch_compress(rule, gids, rows, n_rows, static_cast<const float*>(x), ldx,
-                                         static_cast<float*>(z), static_cast<hipStream_t>(stream),
+    const double bytes = double(n_rows) * (rule.width + rule.k) * ctx->elem_bytes();
+    VARCO_HIP(ctx, varco_launch_compress(ctx->dtype, rule, gids, rows, n_rows, x, ldx, z, static_cast<hipStream_t>(stream),
                                          ctx->tag(VARCO_K_COMPRESS, bytes, 0)));
     return VARCO_OK;
 }
@@ -466,10 +467,9 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;
     const MaskRule rule = make_rule(ctx, layer);
-    const double bytes = accumulate ? double(n_rows) * rule.k * 12.0 : double(n_rows) * (rule.width + rule.k) * 4.0;
-    VARCO_HIP(ctx, varco_launch_decompress(rule, gids, rows, n_rows, static_cast<const float*>(z), static_cast<float*>(x),
-                                           ldx, accumulate, static_cast<hipStream_t>(stream),
-                                           ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));
+    const double bytes = (accumulate ? double(n_rows) * rule.k * 3.0 : double(n_rows) * (rule.width + rule.k)) * ctx->elem_bytes();
+    VARCO_HIP(ctx, varco_launch_decompress(ctx->dtype, rule, gids, rows, n_rows, z, x, ldx, accumulate,
+                                           static_cast<hipStream_t>(stream), ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));
     return VARCO_OK;
 }
 
@@ -494,32 +494,32 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     ctx->layers[layer].ran_forward = true;
 
     // aggregate: local rows dense, halo rows straight from the owners' compressed buffers
-    const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * 4.0 +
-                             double(d.n_halo) * rule.k * 4.0;
-    VARCO_HIP(ctx, varco_launch_spmm(ps.fwd, ps.edges, nullptr, d.vals, static_cast<const float*>(x_local),
-                                     static_cast<const float*>(z_in), rule, static_cast<float*>(m_saved), 0, ctx->ws_spmm, st,
+    const int dt = ctx->dtype;
+    const double es = ctx->elem_bytes();
+    const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
+                             double(d.n_halo) * rule.k * es;
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, ps.edges, nullptr, d.vals, x_local, z_in, rule, m_saved, 0, ctx->ws_spmm, st,
                                      ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0)));
     // transform + nonlinearity
     GemmArgs g;
     g.m = d.n_local, g.n = fo, g.k = fi;
-    g.a.ptr = static_cast<const float*>(m_saved), g.a.ld = fi;
-    g.b.ptr = static_cast<const float*>(h1), g.b.ld = fo;
+    g.a.ptr = m_saved, g.a.ld = fi, g.a.dtype = dt;
+    g.b.ptr = h1, g.b.ld = fo;
     if (sage) {
         g.k2 = fi;
-        g.a2.ptr = static_cast<const float*>(x_local), g.a2.ld = fi;
-        g.b2.ptr = static_cast<const float*>(h0), g.b2.ld = fo;
+        g.a2.ptr = x_local, g.a2.ld = fi, g.a2.dtype = dt;
+        g.b2.ptr = h0, g.b2.ld = fo;
     }
-    g.c = static_cast<float*>(x_out), g.ldc = fo;
+    g.c = x_out, g.ldc = fo, g.c_dtype = dt;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
     if (z_out && d.n_boundary > 0) {
         ctx->layers[layer + 1].ran_forward = true;   // its positions are now in use
         const MaskRule next = make_rule(ctx, layer + 1);
-        float* zdst = static_cast<float*>(z_out) + int64_t(d.z_row_offset) * next.k;
-        VARCO_HIP(ctx, varco_launch_compress(next, ps.boundary_gid, d.boundary_rows, d.n_boundary,
-                                             static_cast<const float*>(x_out), fo, zdst, st,
-                                             ctx->tag(VARCO_K_COMPRESS, double(d.n_boundary) * (next.width + next.k) * 4.0, 0)));
+        char* zdst = static_cast<char*>(z_out) + int64_t(d.z_row_offset) * next.k * int64_t(es);
+        VARCO_HIP(ctx, varco_launch_compress(dt, next, ps.boundary_gid, d.boundary_rows, d.n_boundary, x_out, fo, zdst, st,
+                                             ctx->tag(VARCO_K_COMPRESS, double(d.n_boundary) * (next.width + next.k) * es, 0)));
     }
     ctx->stats.fwd_elems[layer] += int64_t(d.n_halo) * rule.k;
     ctx->stats.full_fwd_elems[layer] += int64_t(d.n_halo) * fi;
@@ -543,8 +543,10 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo is null but the partition has halo nodes");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
-    const float* gate = ctx->act[layer] == VARCO_ACT_RELU ? static_cast<const float*>(x_out) : nullptr;
+    const void* gate = ctx->act[layer] == VARCO_ACT_RELU ? x_out : nullptr;
     const int32_t nl = d.n_local;
+    const int dt = ctx->dtype;
+    const double es = ctx->elem_bytes();
     if (nl == 0) return VARCO_OK;
 
     // weight gradients: reductions over the partition's rows, split over workgroups
@@ -553,16 +555,16 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     {
         GemmArgs g;
         g.m = fi, g.n = fo, g.k = nl;
-        g.a.ptr = static_cast<const float*>(m_saved), g.a.ld = fi, g.a.transposed = true;
-        g.b.ptr = static_cast<const float*>(dx_out), g.b.gate = gate, g.b.ld = fo;
-        g.c = static_cast<float*>(dh1), g.ldc = fo;
+        g.a.ptr = m_saved, g.a.ld = fi, g.a.transposed = true, g.a.dtype = dt;
+        g.b.ptr = dx_out, g.b.gate = gate, g.b.ld = fo, g.b.dtype = dt;
+        g.c = dh1, g.ldc = fo;
         g.accumulate = true;
         g.split_k = split, g.partial = ctx->ws_gemm;
         const LaunchTag wtag = ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
         if (sage) {
-            g.a.ptr = static_cast<const float*>(x_local);
-            g.c = static_cast<float*>(dh0);
+            g.a.ptr = x_local;
+            g.c = dh0;
             VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
         }
     }
@@ -572,32 +574,30 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     {
         GemmArgs g;
         g.m = nl, g.n = fi, g.k = fo;
-        g.a.ptr = static_cast<const float*>(dx_out), g.a.gate = gate, g.a.ld = fo;
-        g.b.ptr = static_cast<const float*>(h1), g.b.ld = fo, g.b.transposed = true;
-        g.c = ctx->ws_dm, g.ldc = fi;
+        g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
+        g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
+        g.c = ctx->ws_dm, g.ldc = fi, g.c_dtype = dt;
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
     const MaskRule rule = make_rule(ctx, layer);
     const MaskRule dense_rule = full_rule(fi);
-    const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * 4.0;
-    const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * 4.0;
-    const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * 4.0 + th_out_bytes;
-    VARCO_HIP(ctx, varco_launch_spmm(ps.t_local, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
-                                     static_cast<float*>(dx_local), 0, ctx->ws_spmm, st,
-                                     ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
+    const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
+    const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
+    const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule, dx_local,
+                                     0, ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
     if (d.n_halo > 0) {
         if (rule.k == rule.width) {
-            VARCO_HIP(ctx, varco_launch_spmm(ps.t_halo, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
-                                             static_cast<float*>(dz_halo), nl, ctx->ws_spmm, st,
-                                             ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
+            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
+                                             dz_halo, nl, ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             // product buffer: grown on demand (the first call at a larger k synchronises the device)
             const size_t need = size_t(d.nnz - ps.nnz_t_local) * rule.k;
             if (need > ctx->ws_prod_elems) VARCO_HIP(ctx, grow(ctx->ws_prod, ctx->ws_prod_elems, need + need / 4));
-            VARCO_HIP(ctx, varco_launch_halo_grad(ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
-                                                  ctx->ws_dm, rule, ctx->ws_prod, static_cast<float*>(dz_halo), nl,
-                                                  ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
+            VARCO_HIP(ctx, varco_launch_halo_grad(dt, ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
+                                                  ctx->ws_dm, rule, ctx->ws_prod, dz_halo, nl, ctx->ws_spmm, st,
+                                                  ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
                                                   ctx->tag(VARCO_K_AGG_BWD_HALO_SUM, th_out_bytes, 0)));
         }
         ctx->stats.bwd_elems[layer] += int64_t(d.n_halo) * rule.k;
@@ -607,9 +607,9 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     if (sage) {
         GemmArgs g;
         g.m = nl, g.n = fi, g.k = fo;
-        g.a.ptr = static_cast<const float*>(dx_out), g.a.gate = gate, g.a.ld = fo;
-        g.b.ptr = static_cast<const float*>(h0), g.b.ld = fo, g.b.transposed = true;
-        g.c = static_cast<float*>(dx_local), g.ldc = fi;
+        g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
+        g.b.ptr = h0, g.b.ld = fo, g.b.transposed = true;
+        g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
         g.accumulate = true;
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
@@ -628,10 +628,9 @@ extern "C" int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int3
     ctx->layers[layer].ran_forward = true;
     const MaskRule rule = make_rule(ctx, layer);
     // rows returned are not known on the host; attribute the owner-side read-modify-write of k values per row
-    const double bytes = double(ps.d.n_boundary) * rule.k * 12.0;
-    VARCO_HIP(ctx, varco_launch_accumulate_returned(rule, ps.boundary_gid, ps.d.boundary_rows, ps.d.n_boundary, ret_ptr,
-                                                    ret_src, static_cast<const float*>(returned),
-                                                    static_cast<float*>(dx_local), ctx->widths[layer],
+    const double bytes = double(ps.d.n_boundary) * rule.k * 3.0 * ctx->elem_bytes();
+    VARCO_HIP(ctx, varco_launch_accumulate_returned(ctx->dtype, rule, ps.boundary_gid, ps.d.boundary_rows, ps.d.n_boundary,
+                                                    ret_ptr, ret_src, returned, dx_local, ctx->widths[layer],
                                                     static_cast<hipStream_t>(stream), ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));
     return VARCO_OK;
 }

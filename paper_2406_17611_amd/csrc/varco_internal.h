@@ -87,17 +87,18 @@ struct VarcoEdge {
     int32_t src, gid;
 };
 
-hipError_t varco_launch_compress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                 const float* x, int64_t ldx, float* z, hipStream_t stream, const LaunchTag& tag);
-hipError_t varco_launch_decompress(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
-                                   const float* z, float* x, int64_t ldx, int accumulate, hipStream_t stream,
-                                   const LaunchTag& tag);
+// `dtype` (VARCO_F32 / VARCO_BF16) is the storage type of every activation, message and gradient buffer
+// passed as void*; sums are formed in fp32 and rounded to nearest even on store.
+hipError_t varco_launch_compress(int dtype, const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
+                                 const void* x, int64_t ldx, void* z, hipStream_t stream, const LaunchTag& tag);
+hipError_t varco_launch_decompress(int dtype, const MaskRule& rule, const int32_t* gids, const int32_t* rows,
+                                   int64_t n_rows, const void* z, void* x, int64_t ldx, int accumulate,
+                                   hipStream_t stream, const LaunchTag& tag);
 
 // x[rows[b], pi_v(j)] += sum_{e in [ptr[b], ptr[b+1])} returned[src[e] * k + j], v = gids[b].
-hipError_t varco_launch_accumulate_returned(const MaskRule& rule, const int32_t* gids, const int32_t* rows,
-                                            int64_t n_rows, const int32_t* ptr, const int32_t* src,
-                                            const float* returned, float* x, int64_t ldx, hipStream_t stream,
-                                            const LaunchTag& tag);
+hipError_t varco_launch_accumulate_returned(int dtype, const MaskRule& rule, const int32_t* gids, const int32_t* rows,
+                                            int64_t n_rows, const int32_t* ptr, const int32_t* src, const void* returned,
+                                            void* x, int64_t ldx, hipStream_t stream, const LaunchTag& tag);
 
 hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 
@@ -108,10 +109,10 @@ hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t 
 //   edge != null (forward): entry e reads dense + edge[e].src * width when edge[e].gid < 0, else the k kept
 //       elements z[edge[e].src * k + j], which land at pi_gid(j) (a full row of z when k == width);
 //   edge == null (transposed, all dense): entry e reads dense + colidx[e] * width.
-// partial: workspace of plan.n_partials * width floats.
-hipError_t varco_launch_spmm(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx, const float* vals,
-                             const float* dense, const float* z, const MaskRule& rule, float* out, int32_t row_base,
-                             float* partial, hipStream_t stream, const LaunchTag& tag);
+// partial: workspace of plan.n_partials * width floats (fp32 for either storage type).
+hipError_t varco_launch_spmm(int dtype, const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx,
+                             const float* vals, const void* dense, const void* z, const MaskRule& rule, void* out,
+                             int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag);
 
 // prow[e] = position of forward entry e among the halo entries of the transposed order (-1 for local entries).
 hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
@@ -120,15 +121,16 @@ hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx,
 // out[s, j] = sum over local rows i of S[i, halo s] * dm[i, pi_v(j)], j < k (the halo rows of the transposed
 // aggregation, produced directly in compressed form) in two streaming passes through the product buffer
 // `prod` ((halo entries) x k floats). prod_base = transposed position of the first halo entry.
-hipError_t varco_launch_halo_grad(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
-                                  const float* vals, const int32_t* prow, int32_t prod_base, const float* dm,
-                                  const MaskRule& rule, float* prod, float* out, int32_t row_base, float* partial,
+hipError_t varco_launch_halo_grad(int dtype, const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
+                                  const float* vals, const int32_t* prow, int32_t prod_base, const void* dm,
+                                  const MaskRule& rule, float* prod, void* out, int32_t row_base, float* partial,
                                   hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag);
 
 // C (+)= op(A) op(B) in fp32 on the matrix cores, row-major everywhere.
 struct GemmOperand {
-    const float* ptr = nullptr;   // matrix as stored
-    const float* gate = nullptr;  // optional, same shape: elements are used only where gate > 0 (ReLU mask)
+    const void* ptr = nullptr;    // matrix as stored
+    const void* gate = nullptr;   // optional, same shape and type: elements are used only where gate > 0 (ReLU mask)
+    int dtype = VARCO_F32;        // storage type of ptr and gate
     int64_t ld = 0;
     bool transposed = false;      // false: stored [rows=M or K][cols=K or N]; true: stored the other way round
 };
@@ -137,7 +139,8 @@ struct GemmArgs {
     GemmOperand a, b;             // first product
     GemmOperand a2, b2;           // optional second product summed into the same C (k2 reduction length)
     int32_t k2 = 0;
-    float* c = nullptr;
+    void* c = nullptr;
+    int c_dtype = VARCO_F32;
     int64_t ldc = 0;
     bool accumulate = false;      // C += instead of C =
     bool relu = false;            // C = max(., 0)

@@ -13,7 +13,12 @@ from . import binding as vb
 
 
 class PartitionedNetwork:
-    def __init__(self, host_parts, widths, conv: str, mask_key: int, device="cuda", need_backward=True):
+    def __init__(self, host_parts, widths, conv: str, mask_key: int, device="cuda", need_backward=True, dtype="f32"):
+        """dtype: storage of activations, messages and their gradients ("f32" or "bf16"); weights and weight
+        gradients are always fp32."""
+        assert dtype in ("f32", "bf16")
+        self.dtype = dtype
+        self.act_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.device = torch.device(device)
         self.host_parts = host_parts
         self.P = len(host_parts)
@@ -21,7 +26,8 @@ class PartitionedNetwork:
         self.L = len(widths) - 1
         self.conv = conv
         act = [vb.ACT_RELU] * (self.L - 1) + [vb.ACT_IDENTITY]
-        self.ctx = vb.Context(self.widths, act, vb.CONV_SAGE if conv == "sage" else vb.CONV_GCN, self.P, mask_key)
+        self.ctx = vb.Context(self.widths, act, vb.CONV_SAGE if conv == "sage" else vb.CONV_GCN, self.P, mask_key,
+                              vb.BF16 if dtype == "bf16" else vb.F32)
         self.dev_parts = [self.ctx.register_partition(q, hp, self.device) for q, hp in enumerate(host_parts)]
 
         self.n_local = [hp.n_local for hp in host_parts]
@@ -51,8 +57,9 @@ class PartitionedNetwork:
             self.ret_src.append(torch.from_numpy(arena_rows[order].astype(np.int32)).to(self.device))
 
         f32 = dict(dtype=torch.float32, device=self.device)
-        self.x = [torch.empty((self.n_total, w), **f32) for w in self.widths]
-        self.m = [torch.empty((self.n_total, self.widths[l]), **f32) for l in range(self.L)]
+        act = dict(dtype=self.act_dtype, device=self.device)
+        self.x = [torch.empty((self.n_total, w), **act) for w in self.widths]
+        self.m = [torch.empty((self.n_total, self.widths[l]), **act) for l in range(self.L)]
         self.h1 = [torch.empty((self.widths[l], self.widths[l + 1]), **f32) for l in range(self.L)]
         self.h0 = [torch.empty_like(h) if conv == "sage" else None for h in self.h1]
         self.z = [None] * self.L           # allocated per step (k changes with the ratio)
@@ -60,7 +67,7 @@ class PartitionedNetwork:
         if need_backward:
             self.dh1 = [torch.zeros_like(h) for h in self.h1]
             self.dh0 = [torch.zeros_like(h) if conv == "sage" else None for h in self.h1]
-            self.dx = [None] + [torch.empty((self.n_total, self.widths[l]), **f32) for l in range(1, self.L + 1)]
+            self.dx = [None] + [torch.empty((self.n_total, self.widths[l]), **act) for l in range(1, self.L + 1)]
             self.dz_halo = [None] * self.L
         self._zcap = [0] * self.L
         self._dzcap = [0] * self.L
@@ -87,7 +94,7 @@ class PartitionedNetwork:
     def to_global(self, arena: torch.Tensor) -> np.ndarray:
         order = np.concatenate([hp.local_gid for hp in self.host_parts]).astype(np.int64)
         out = np.empty(tuple(arena.shape), dtype=np.float32)
-        out[order] = arena.cpu().numpy()
+        out[order] = arena.float().cpu().numpy()
         return out
 
     # ------------------------------------------------------------------ one step
@@ -96,12 +103,12 @@ class PartitionedNetwork:
             k = self.ctx.keep(l)
             need = self.b_total * k
             if self._zcap[l] < need:
-                self.z[l] = torch.empty(max(need, 1), dtype=torch.float32, device=self.device)
+                self.z[l] = torch.empty(max(need, 1), dtype=self.act_dtype, device=self.device)
                 self._zcap[l] = need
             if self.need_backward and l > 0:
                 need = int(self.halo_off[-1]) * k
                 if self._dzcap[l] < need:
-                    self.dz_halo[l] = torch.empty(max(need, 1), dtype=torch.float32, device=self.device)
+                    self.dz_halo[l] = torch.empty(max(need, 1), dtype=self.act_dtype, device=self.device)
                     self._dzcap[l] = need
 
     def forward(self, step: int, ratio=None, stream=None):

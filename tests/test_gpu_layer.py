@@ -4,21 +4,32 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_common import KEY, assert_close, both_partitions, dev, hub_graph
+from gpu_common import KEY, TOL, assert_close, both_partitions, dev, hub_graph
 from oracle import layer as olayer
 from oracle import mask as omask
+from oracle.rounding import round_bf16
 from paper_2406_17611_amd import binding as vb
 from paper_2406_17611_amd import synth
 
 pytestmark = pytest.mark.gpu
 
 
-def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1):
+BF16_TOL = 2.0 ** -7   # norm-wise bound with bf16 storage (aggregate, output and dM are each rounded once)
+
+
+def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32"):
+    """dtype "bf16": every activation / message / gradient tensor handed to the library is bf16 (the inputs
+    are bf16 values, so both sides start from identical numbers); weights and weight gradients stay fp32."""
     host, orc = both_partitions(g, part, n_parts)
     rng = np.random.default_rng(seed)
     sage = conv == "sage"
     widths = [8, fi, fo]
-    ctx = vb.Context(widths, [vb.ACT_RELU, act], vb.CONV_SAGE if sage else vb.CONV_GCN, n_parts, KEY)
+    bf16 = dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    tol = BF16_TOL if bf16 else TOL
+    stored = (lambda a: round_bf16(a).astype(np.float32)) if bf16 else (lambda a: np.asarray(a, dtype=np.float32))
+    ctx = vb.Context(widths, [vb.ACT_RELU, act], vb.CONV_SAGE if sage else vb.CONV_GCN, n_parts, KEY,
+                     vb.BF16 if bf16 else vb.F32)
     for q, hp in enumerate(host):
         ctx.register_partition(q, hp)
     ctx.begin_step(step)
@@ -26,22 +37,22 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
     k = ctx.keep(layer)
     assert k == omask.keep_count(fi, *ratio)
 
-    x = rng.standard_normal((g.n, fi)).astype(np.float32)
+    x = stored(rng.standard_normal((g.n, fi)))
     h1 = (rng.standard_normal((fi, fo)) * 0.3).astype(np.float32)
     h0 = (rng.standard_normal((fi, fo)) * 0.3).astype(np.float32) if sage else None
-    dxo = (rng.standard_normal((g.n, fo)) / g.n).astype(np.float32)
+    dxo = stored(rng.standard_normal((g.n, fo)) / g.n)
     b_total = sum(p.n_boundary for p in orc)
 
     # owners' compressed boundary rows: oracle version, and the library's own through varco_compress
     z_ref = np.vstack([olayer.compress(x[p.local_gid], p.boundary_rows,
                                        omask.kept_columns(p.local_gid[p.boundary_rows], fi, k, KEY, step, layer))
                        for p in orc]) if b_total else np.zeros((0, k))
-    z_dev = torch.empty((max(b_total, 1), k), dtype=torch.float32, device="cuda")
+    z_dev = torch.empty((max(b_total, 1), k), dtype=tdt, device="cuda")
     for q, p in enumerate(orc):
         if p.n_boundary:
             ctx.compress(layer, dev(p.local_gid[p.boundary_rows]), dev(p.boundary_rows), p.n_boundary,
-                         dev(x[p.local_gid]), fi, z_dev[p.z_row_offset:])
-    assert np.array_equal(z_dev.cpu().numpy()[:b_total], z_ref.astype(np.float32))
+                         dev(x[p.local_gid], tdt), fi, z_dev[p.z_row_offset:])
+    assert np.array_equal(z_dev.float().cpu().numpy()[:b_total], z_ref.astype(np.float32))
 
     h1d, h0d = dev(h1), (dev(h0) if sage else None)
     dh1_dev = torch.zeros((fi, fo), dtype=torch.float32, device="cuda")
@@ -54,29 +65,30 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
         cols = omask.kept_columns(p.halo_gid, fi, k, KEY, step, layer)
         xl = x[p.local_gid]
         xo_ref, m_ref = olayer.layer_forward(p, xl, z_ref, cols, h1, h0, o_act)
-        xld = dev(xl)
-        xo = torch.full((p.n_local, fo), float("nan"), dtype=torch.float32, device="cuda")
-        ms = torch.full((p.n_local, fi), float("nan"), dtype=torch.float32, device="cuda")
+        xld = dev(xl, tdt)
+        xo = torch.full((p.n_local, fo), float("nan"), dtype=tdt, device="cuda")
+        ms = torch.full((p.n_local, fi), float("nan"), dtype=tdt, device="cuda")
         ctx.layer_fwd(layer, q, xld, z_dev, h1d, h0d, xo, None, ms)
-        assert_close(ms.cpu().numpy(), m_ref, f"M q={q}")
-        assert_close(xo.cpu().numpy(), xo_ref, f"X_out q={q}")
+        assert_close(ms.float().cpu().numpy(), m_ref, f"M q={q}", tol)
+        assert_close(xo.float().cpu().numpy(), xo_ref, f"X_out q={q}", tol)
 
         # backward on synthetic upstream gradient, with the oracle's own x_out / m as saved tensors
-        xo32 = xo_ref.astype(np.float32)
-        m32 = m_ref.astype(np.float32)
+        xo32 = stored(xo_ref)
+        m32 = stored(m_ref)
         d = dxo[p.local_gid]
         r1, r0, rdx, rdz = olayer.layer_backward(p, d, xo32, xl, m32, cols, h1, h0, o_act, True)
         dh1_ref += r1
         if sage:
             dh0_ref += r0
-        dxl = torch.full((p.n_local, fi), float("nan"), dtype=torch.float32, device="cuda")
-        dzh = torch.full((max(p.n_halo, 1), k), float("nan"), dtype=torch.float32, device="cuda")
-        ctx.layer_bwd(layer, q, dev(d), dev(xo32), xld, dev(m32), h1d, h0d, dh1_dev, dh0_dev, dxl,
+        dxl = torch.full((p.n_local, fi), float("nan"), dtype=tdt, device="cuda")
+        dzh = torch.full((max(p.n_halo, 1), k), float("nan"), dtype=tdt, device="cuda")
+        ctx.layer_bwd(layer, q, dev(d, tdt), dev(xo32, tdt), xld, dev(m32, tdt), h1d, h0d, dh1_dev, dh0_dev, dxl,
                       dzh if p.n_halo else None)
-        assert_close(dxl.cpu().numpy(), rdx, f"dX_local q={q}")
+        assert_close(dxl.float().cpu().numpy(), rdx, f"dX_local q={q}", tol)
         if p.n_halo:
-            assert_close(dzh.cpu().numpy(), rdz, f"dZ_halo q={q}")
+            assert_close(dzh.float().cpu().numpy(), rdz, f"dZ_halo q={q}", tol)
         halo_rows += p.n_halo
+    # weight gradients: fp32 sums of products of stored values, no storage rounding on either side
     assert_close(dh1_dev.cpu().numpy(), dh1_ref, "dH1 summed over partitions")
     if sage:
         assert_close(dh0_dev.cpu().numpy(), dh0_ref, "dH0 summed over partitions")
@@ -103,6 +115,22 @@ def test_layer_parity_with_split_rows_and_identity_activation(conv, ratio):
     assert np.diff(g.rowptr).max() > 1000
     part = synth.random_partition(g.n, 2, seed=6)
     _run_layer_case(g, part, 2, conv, 64, 48, ratio, vb.ACT_IDENTITY, seed=77)
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("fi,fo,ratio", [(100, 512, (1, 1)), (100, 512, (4, 1)), (100, 512, (32, 1)), (512, 512, (4, 1)),
+                                         (512, 47, (32, 1)), (512, 47, (1, 1)), (37, 19, (3, 1)), (16, 32, (4, 1))])
+def test_layer_parity_bf16_storage(conv, fi, fo, ratio):
+    g = synth.small_random_graph(1500, 9.0, conv, seed=fi + fo)
+    part = synth.random_partition(g.n, 3, seed=5)
+    _run_layer_case(g, part, 3, conv, fi, fo, ratio, vb.ACT_RELU, seed=fi * 3 + fo, dtype="bf16")
+
+
+@pytest.mark.parametrize("ratio", [(1, 1), (8, 1)])
+def test_layer_parity_bf16_storage_with_split_rows(ratio):
+    g = hub_graph(6000, 4, 1500, 6.0, "gcn", seed=9)
+    part = synth.random_partition(g.n, 2, seed=6)
+    _run_layer_case(g, part, 2, "gcn", 64, 48, ratio, vb.ACT_IDENTITY, seed=77, dtype="bf16")
 
 
 def test_layer_parity_single_partition_has_no_exchange():

@@ -7,10 +7,13 @@ import torch
 from gpu_common import KEY, assert_close, both_partitions
 from oracle import layer as olayer
 from oracle import mask as omask
+from oracle.rounding import round_bf16
 from paper_2406_17611_amd import synth
 from paper_2406_17611_amd.runner import PartitionedNetwork
 
 pytestmark = pytest.mark.gpu
+
+BF16_TOL = 2.0 ** -7   # norm-wise bound of the bf16-storage configuration (a few roundings of 2^-9 each)
 
 
 def _weights(widths, conv):
@@ -24,13 +27,19 @@ def _f32(a):
     return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
 
 
-def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4):
+def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4, dtype="f32"):
+    """dtype "bf16": inputs are bf16 values, the oracle rounds to bf16 where the device stores bf16
+    (activations, aggregates, messages, gradients) and `tol` is the bound of that configuration."""
     host, orc = both_partitions(g, part, n_parts)
     L = len(widths) - 1
     x0 = synth.features(g.n, widths[0], synth.SEED_FEAT)
     dxl = synth.upstream_grad(g.n, widths[-1], synth.SEED_GRAD)
+    stored = _f32
+    if dtype == "bf16":
+        stored = round_bf16
+        x0, dxl = round_bf16(x0).astype(np.float32), round_bf16(dxl).astype(np.float32)
     h1, h0 = _weights(widths, conv)
-    net = PartitionedNetwork(host, widths, conv, KEY)
+    net = PartitionedNetwork(host, widths, conv, KEY, dtype=dtype)
     net.set_inputs(x0)
     net.set_weights(h1, h0)
     net.set_upstream(dxl)
@@ -44,14 +53,14 @@ def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4):
         keep = [omask.keep_count(widths[l], *ratio) for l in range(L)]
         assert [net.ctx.keep(l) for l in range(L)] == keep
         ref = olayer.network_step(orc, [x0[p.local_gid] for p in orc], weights, acts, keep, KEY, step,
-                                  [dxl[p.local_gid] for p in orc], round_store=_f32)
+                                  [dxl[p.local_gid] for p in orc], round_store=stored)
         tag = f"step {step} ratio {ratio}"
         # forward: free-running chain on both sides
         for l in range(L):
             assert_close(net.to_global(net.x[l + 1]), _gather(orc, ref["x"][l + 1], g.n), f"{tag} X_{l + 1}", tol)
             assert_close(net.to_global(net.m[l]), _gather(orc, ref["m"][l], g.n), f"{tag} M_{l}", tol)
             k = keep[l]
-            z = net.z[l][:net.b_total * k].reshape(net.b_total, k).cpu().numpy()
+            z = net.z[l][:net.b_total * k].reshape(net.b_total, k).float().cpu().numpy()
             if l == 0:
                 assert np.array_equal(z, ref["z"][0].astype(np.float32)), f"{tag} Z_0 must be bit-exact"
             else:
@@ -104,6 +113,22 @@ def test_sage_network_small():
     g = synth.small_random_graph(3000, 10.0, "sage", seed=31)
     part = synth.random_partition(g.n, 4, seed=32)
     _compare_network(g, part, 4, "sage", (100, 256, 256, 47), [(8, 1), (2, 1)], steps=[5, 6])
+
+
+def test_tiny_config_full_step_bf16_storage():
+    w = synth.make_workload("tiny")
+    _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, [(4, 1), (1, 1)], steps=[0, 1], tol=BF16_TOL,
+                     dtype="bf16")
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+def test_network_small_bf16_storage(conv):
+    # the widths of the bf16 configuration (100 -> 512 -> 512 -> 47) at its three ratios, on a graph the
+    # oracle finishes in seconds, with 4 partitions
+    g = synth.small_random_graph(3000, 10.0, conv, seed=51)
+    part = synth.random_partition(g.n, 4, seed=52)
+    _compare_network(g, part, 4, conv, (100, 512, 512, 47), [(1, 1), (4, 1), (32, 1)], steps=[2, 3, 4], tol=BF16_TOL,
+                     dtype="bf16")
 
 
 def test_two_runs_give_identical_bits():

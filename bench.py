@@ -7,7 +7,8 @@ backward of the same (weight gradients, dM, transposed aggregation, compressed e
 accumulation). Inputs are seeded synthetic graphs shaped like the paper's datasets and are resident in HBM
 before the timed region starts.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large_sage|medium|tiny|medium_bfs16]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--workload large_sage|large_gcn_bf16|medium|medium_bfs16|tiny] [--ratio NUM/DEN]
 
 Prints one JSON line: whole-job GEdges/s (directed CSR entries x layers per step / step time), the roofline
 figures of the dominant kernel measured live with HIP events, and the CPU oracle's rate on a bounded sample.
@@ -26,7 +27,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix rate
 HBM_CLASSES = ("compress", "decompress", "agg_fwd", "agg_bwd_local", "agg_bwd_halo", "agg_bwd_halo_sum", "reduce")
 MFMA_CLASSES = ("gemm_fwd", "gemm_wgrad", "gemm_dgrad")
-DEFAULT_RATIO = {"tiny": (4, 1), "medium": (8, 1), "medium_bfs16": (1584 - 15 * 50, 99), "large_sage": (8, 1)}
+DEFAULT_RATIO = {"tiny": (4, 1), "medium": (8, 1), "medium_bfs16": (1584 - 15 * 50, 99), "large_sage": (8, 1),
+                 "large_gcn_bf16": (4, 1)}
 
 
 def log(*a):
@@ -65,6 +67,9 @@ def cpu_baseline(w, ratio, budget_note=""):
     rng = np.random.default_rng(1)
     x = rng.standard_normal((p.n_local, fi)).astype(np.float32)
     z_all = rng.standard_normal((int(p.halo_zrow.max(initial=-1)) + 1, k)).astype(np.float32)
+    if w.dtype == "bf16":   # the oracle of the bf16 configuration: fp64 arithmetic on bf16-valued inputs
+        from oracle.rounding import round_bf16
+        x, z_all = round_bf16(x), round_bf16(z_all)
     h1 = synth.glorot(fi, fo, synth.SEED_WEIGHT, 2 * layer)
     h0 = synth.glorot(fi, fo, synth.SEED_WEIGHT, 2 * layer + 1) if w.conv == "sage" else None
     dxo = rng.standard_normal((p.n_local, fo)).astype(np.float32)
@@ -102,8 +107,6 @@ def main():
 
     t0 = time.time()
     w = synth.make_workload(args.workload)
-    if w.dtype != "f32":
-        sys.exit("bench.py: only fp32 workloads are implemented")
     g = w.graph
     log(f"[bench] workload {w.name}: n={g.n} nnz={g.nnz} P={w.n_parts} conv={w.conv} widths={w.widths} "
         f"ratio={ratio} (generated in {time.time() - t0:.1f}s)")
@@ -124,7 +127,7 @@ def main():
         f"boundary rows {sum(h.n_boundary for h in host)}")
     t0 = time.time()
     L = len(w.widths) - 1
-    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY)
+    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY, dtype=w.dtype)
     net.set_inputs(synth.features(g.n, w.widths[0], synth.SEED_FEAT))
     net.set_weights([synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l) for l in range(L)],
                     [synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l + 1) for l in range(L)])
@@ -184,7 +187,9 @@ def main():
         "value": edges_per_step / (ms_per_step * 1e-3) / 1e9,
         "unit": "GEdges/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "f32 arithmetic on bf16-stored activations and gradients",
+        "data": "synthetic",
         "config": {"workload": w.name, "nodes": g.n, "directed_entries": g.nnz, "partitions": w.n_parts,
                    "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
                    "keep": [net.ctx.keep(l) for l in range(L)], "layers": L,

@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import dataclasses
 import math
+import os
 
 import numpy as np
 import scipy.sparse as sp
@@ -209,8 +210,33 @@ def bfs_contiguous_partition(g: Graph, n_parts: int) -> np.ndarray:
 # dense inputs
 # --------------------------------------------------------------------------------------------------
 
+_NORMAL_CHUNK_ROWS = 1 << 16
+
+
+def _normal_rows(n: int, width: int, seed: int, salt: int) -> np.ndarray:
+    """[n, width] i.i.d. N(0, 1) in fp32. Rows are drawn in fixed chunks, chunk c from the Philox stream keyed
+    (seed, salt + c), so the values do not depend on how many threads fill the chunks."""
+    out = np.empty((n, width), dtype=np.float32)
+    starts = range(0, n, _NORMAL_CHUNK_ROWS)
+
+    def fill(c_r0):
+        c, r0 = c_r0
+        r1 = min(n, r0 + _NORMAL_CHUNK_ROWS)
+        _rng(seed, salt + c).standard_normal(out=out[r0:r1], dtype=np.float32)
+
+    jobs = list(enumerate(starts))
+    if len(jobs) <= 1:
+        for j in jobs:
+            fill(j)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+            list(pool.map(fill, jobs))
+    return out
+
+
 def features(n: int, width: int, seed: int) -> np.ndarray:
-    return _rng(seed).standard_normal((n, width), dtype=np.float32)
+    return _normal_rows(n, width, seed, 0)
 
 
 def glorot(fan_in: int, fan_out: int, seed: int, stream: int = 0) -> np.ndarray:
@@ -219,7 +245,9 @@ def glorot(fan_in: int, fan_out: int, seed: int, stream: int = 0) -> np.ndarray:
 
 
 def upstream_grad(n: int, width: int, seed: int) -> np.ndarray:
-    return (_rng(seed).standard_normal((n, width), dtype=np.float32) / np.float32(n)).astype(np.float32)
+    out = _normal_rows(n, width, seed, 1 << 20)
+    out /= np.float32(n)
+    return out
 
 
 # --------------------------------------------------------------------------------------------------

@@ -12,12 +12,8 @@ struct bf16_t {
 
 __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float(uint32_t(b) << 16); }
 
-__device__ __forceinline__ uint16_t float_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);                                           // round to nearest even
-    return uint16_t(u >> 16);
-}
+// Round to nearest even (the hardware conversion of gfx950); NaN stays NaN.
+__device__ __forceinline__ uint16_t float_to_bf16(float f) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f)); }
 
 template <typename T>
 struct Elem;

@@ -325,8 +325,32 @@ void launch_layout(bool narrow, bool a_vec, bool b_vec, dim3 grid, hipStream_t s
 
 }  // namespace
 
+namespace {
+
+hipError_t launch_reduce(const GemmArgs& ga, int32_t split, hipStream_t stream, const LaunchTag& tag) {
+    const int64_t mn = int64_t(ga.m) * ga.n;
+    const int32_t acc = ga.accumulate ? 1 : 0, relu = ga.relu ? 1 : 0;
+    tag.begin_as(VARCO_K_REDUCE, stream);
+    if (ga.c_dtype == VARCO_BF16)
+        hipLaunchKernelGGL(gemm_reduce_kernel<bf16_t>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream, ga.partial,
+                           split, mn, ga.n, static_cast<bf16_t*>(ga.c), ga.ldc, acc, relu);
+    else
+        hipLaunchKernelGGL(gemm_reduce_kernel<float>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream, ga.partial,
+                           split, mn, ga.n, static_cast<float*>(ga.c), ga.ldc, acc, relu);
+    tag.end(stream);
+    return hipGetLastError();
+}
+
+}  // namespace
+
 hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag) {
     if (ga.m == 0 || ga.n == 0) return hipSuccess;
+    if (varco_gemm_bf16_usable(ga)) {
+        int32_t split = 1;
+        const hipError_t e = varco_launch_gemm_bf16(ga, stream, tag, &split);
+        if (e != hipSuccess || split <= 1) return e;
+        return launch_reduce(ga, split, stream, tag);
+    }
     // A is M x K: k-contiguous as stored unless transposed. B is K x N: k-contiguous only when transposed.
     const bool a_kc = !ga.a.transposed, b_kc = ga.b.transposed;
     const bool a_gate = ga.a.gate != nullptr, b_gate = ga.b.gate != nullptr;
@@ -407,17 +431,6 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
     tag.end(stream);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
-    if (split > 1) {
-        const int64_t mn = int64_t(ga.m) * ga.n;
-        tag.begin_as(VARCO_K_REDUCE, stream);
-        if (tc == VARCO_BF16)
-            hipLaunchKernelGGL(gemm_reduce_kernel<bf16_t>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream,
-                               ga.partial, split, mn, ga.n, static_cast<bf16_t*>(ga.c), ga.ldc, g.accumulate, g.relu);
-        else
-            hipLaunchKernelGGL(gemm_reduce_kernel<float>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream,
-                               ga.partial, split, mn, ga.n, static_cast<float*>(ga.c), ga.ldc, g.accumulate, g.relu);
-        tag.end(stream);
-        err = hipGetLastError();
-    }
+    if (split > 1) err = launch_reduce(ga, split, stream, tag);
     return err;
 }

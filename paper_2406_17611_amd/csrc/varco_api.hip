@@ -51,6 +51,7 @@ struct varco_ctx {
     float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
     float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
     float* ws_prod = nullptr;      size_t ws_prod_elems = 0;      // halo-gradient products: (halo entries) x k
+    float* ws_w = nullptr;         size_t ws_w_elems = 0;         // bf16 copies of the two weights of a layer call
     varco_stats stats{};
     VarcoProfiler prof;
     double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
@@ -199,14 +200,17 @@ hipError_t grow(float*& buf, size_t& have, size_t want) {
 // Number of slabs the node dimension of a weight-gradient product is cut into: the workgroups of one launch
 // should fill the chip exactly once (three 256-thread workgroups of the GEMM kernel are resident per
 // compute unit, 256 compute units), so that no partly filled second round is left over.
-int32_t gemm_split_for(int32_t m, int32_t n, int64_t k) {
-    const int64_t bm = n <= 64 ? 256 : 128, bn = n <= 64 ? 64 : 128;   // tile shapes of the GEMM kernel
+// (The bf16 kernel has 256-row tiles, 32 reduction steps per tile and two resident workgroups per unit.)
+int32_t gemm_split_for(int32_t m, int32_t n, int64_t k, bool bf16_kernel) {
+    const int64_t bm = bf16_kernel || n <= 64 ? 256 : 128, bn = n <= 64 ? 64 : 128;   // tile shapes of the GEMM kernels
     const int64_t tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
-    const int64_t k_tiles = (k + 15) / 16;
-    int64_t split = std::max<int64_t>(1, (3 * 256) / tiles);
+    const int64_t k_tiles = bf16_kernel ? (k + 31) / 32 : (k + 15) / 16;
+    int64_t split = std::max<int64_t>(1, ((bf16_kernel ? 2 : 3) * 256) / tiles);
     split = std::min<int64_t>(split, std::max<int64_t>(1, k_tiles / 8));
     return int32_t(split);
 }
+
+int32_t pad8(int32_t x) { return (x + 7) / 8 * 8; }
 
 // Uploads the multiplier tables of every layer on first use (varco_create itself touches no device).
 int32_t ensure_tables(varco_ctx* ctx) {
@@ -219,6 +223,17 @@ int32_t ensure_tables(varco_ctx* ctx) {
         VARCO_HIP(ctx, hipMemcpy(ls.units_inv, ls.h_units_inv.data(), bytes, hipMemcpyHostToDevice));
     }
     return VARCO_OK;
+}
+
+// bf16 copy of a weight matrix in workspace slot 0 or 1, rows = the product's output index, pitch padded to 8.
+hipError_t prep_weight(varco_ctx* ctx, const void* h, int32_t fi, int32_t fo, bool transpose, int slot, hipStream_t st,
+                       const void** out, int64_t* pitch) {
+    const int32_t rows = transpose ? fo : fi, cols = transpose ? fi : fo;
+    const int32_t p = pad8(cols);
+    char* dst = reinterpret_cast<char*>(ctx->ws_w) + size_t(slot) * ctx->ws_w_elems * 2;
+    *out = dst;
+    *pitch = p;
+    return varco_launch_prep_weight(static_cast<const float*>(h), fo, rows, cols, p, transpose, dst, st);
 }
 
 int32_t check_layer(const varco_ctx* ctx, int32_t layer, const char* fn) {
@@ -319,6 +334,7 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     if (ctx->ws_spmm) (void)hipFree(ctx->ws_spmm);
     if (ctx->ws_gemm) (void)hipFree(ctx->ws_gemm);
     if (ctx->ws_prod) (void)hipFree(ctx->ws_prod);
+    if (ctx->ws_w) (void)hipFree(ctx->ws_w);
     for (VarcoProfiler::Rec& r : ctx->prof.recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -399,7 +415,17 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     int64_t gemm_elems = 0;
     for (int32_t l = 0; l < ctx->n_layers; ++l) {
         const int32_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
-        gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl)) * fi * fo);
+        gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl, false)) * fi * fo);
+        if (ctx->dtype == VARCO_BF16)
+            gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl, true)) * fi * fo);
+    }
+    if (ctx->dtype == VARCO_BF16) {   // two slots of bf16 weights, either orientation, rows padded to 8 elements
+        int64_t slot = 0;
+        for (int32_t l = 0; l < ctx->n_layers; ++l) {
+            const int64_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
+            slot = std::max({slot, fo * pad8(int32_t(fi)), fi * pad8(int32_t(fo))});
+        }
+        VARCO_HIP(ctx, grow(ctx->ws_w, ctx->ws_w_elems, size_t(slot)));   // 2 slots x 2 bytes = 4 bytes per element
     }
     VARCO_HIP(ctx, grow(ctx->ws_dm, ctx->ws_dm_elems, size_t(nl) * wmax));
     VARCO_HIP(ctx, grow(ctx->ws_spmm, ctx->ws_spmm_elems, size_t(max_partials) * wmax));
@@ -512,6 +538,10 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     }
     g.c = x_out, g.ldc = fo, g.c_dtype = dt;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
+    if (dt == VARCO_BF16 && d.n_local > 0) {   // weights as bf16, [output column][reduction index]
+        VARCO_HIP(ctx, prep_weight(ctx, h1, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
+        if (sage) VARCO_HIP(ctx, prep_weight(ctx, h0, fi, fo, true, 1, st, &g.b2_prep, &g.b2_prep_ld));
+    }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
     if (z_out && d.n_boundary > 0) {
@@ -550,8 +580,6 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     if (nl == 0) return VARCO_OK;
 
     // weight gradients: reductions over the partition's rows, split over workgroups
-    const int32_t split = gemm_split_for(fi, fo, nl);
-    if (size_t(split) * fi * fo > ctx->ws_gemm_elems) return varco_fail(ctx, VARCO_ERR_STATE, "varco_layer_bwd: workspace too small");
     {
         GemmArgs g;
         g.m = fi, g.n = fo, g.k = nl;
@@ -559,12 +587,13 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = dx_out, g.b.gate = gate, g.b.ld = fo, g.b.dtype = dt;
         g.c = dh1, g.ldc = fo;
         g.accumulate = true;
-        g.split_k = split, g.partial = ctx->ws_gemm;
+        g.partial = ctx->ws_gemm;
         const LaunchTag wtag = ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl));
-        VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
-        if (sage) {
-            g.a.ptr = x_local;
-            g.c = dh0;
+        for (int tap = 0; tap < (sage ? 2 : 1); ++tap) {
+            if (tap == 1) g.a.ptr = x_local, g.c = dh0;
+            g.split_k = gemm_split_for(fi, fo, nl, varco_gemm_bf16_usable(g));
+            if (size_t(g.split_k) * fi * fo > ctx->ws_gemm_elems)
+                return varco_fail(ctx, VARCO_ERR_STATE, "varco_layer_bwd: workspace too small");
             VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
         }
     }
@@ -577,6 +606,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
         g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
         g.c = ctx->ws_dm, g.ldc = fi, g.c_dtype = dt;
+        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx, h1, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
@@ -611,6 +641,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = h0, g.b.ld = fo, g.b.transposed = true;
         g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
         g.accumulate = true;
+        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx, h0, fi, fo, false, 1, st, &g.b_prep, &g.b_prep_ld));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     return VARCO_OK;

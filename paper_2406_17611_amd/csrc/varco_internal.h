@@ -139,6 +139,11 @@ struct GemmArgs {
     GemmOperand a, b;             // first product
     GemmOperand a2, b2;           // optional second product summed into the same C (k2 reduction length)
     int32_t k2 = 0;
+    // optional bf16 copies of B / B2 laid out [n][pitch] (reduction index contiguous, zero-padded to the pitch),
+    // made by varco_launch_prep_weight: with them, bf16 activations go through the bf16 matrix-core kernel
+    const void* b_prep = nullptr;
+    const void* b2_prep = nullptr;
+    int64_t b_prep_ld = 0, b2_prep_ld = 0;
     void* c = nullptr;
     int c_dtype = VARCO_F32;
     int64_t ldc = 0;
@@ -148,3 +153,12 @@ struct GemmArgs {
     float* partial = nullptr;     // split_k * m * n floats
 };
 hipError_t varco_launch_gemm(const GemmArgs& g, hipStream_t stream, const LaunchTag& tag);
+
+// bf16 matrix-core path (bf16 operands, fp32 accumulation). `usable` says whether the shapes, types and
+// alignments of `g` fit it; the launcher runs the product kernel only and reports the number of reduction
+// slabs it wrote to g.partial (1: the result is already in C).
+bool varco_gemm_bf16_usable(const GemmArgs& g);
+hipError_t varco_launch_gemm_bf16(const GemmArgs& g, hipStream_t stream, const LaunchTag& tag, int32_t* split_used);
+// out[r][c] (bf16, row pitch `pitch` >= cols, zero beyond cols) = transpose ? h[c][r] : h[r][c] for r < rows.
+hipError_t varco_launch_prep_weight(const float* h, int64_t ld, int32_t rows, int32_t cols, int32_t pitch, bool transpose,
+                                    void* out, hipStream_t stream);

@@ -14,7 +14,7 @@ from paper_2406_17611_amd import synth
 pytestmark = pytest.mark.gpu
 
 
-BF16_TOL = 2.0 ** -7   # norm-wise bound with bf16 storage (aggregate, output and dM are each rounded once)
+BF16_TOL = 2.0 ** -7   # norm-wise bound with bf16 storage: at most four roundings of 2^-9 (weight copy, dM, two stores)
 
 
 def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32"):

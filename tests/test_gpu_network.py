@@ -13,7 +13,11 @@ from paper_2406_17611_amd.runner import PartitionedNetwork
 
 pytestmark = pytest.mark.gpu
 
-BF16_TOL = 2.0 ** -7   # norm-wise bound of the bf16-storage configuration (a few roundings of 2^-9 each)
+# Norm-wise bound of the chained bf16 configuration. Every bf16 rounding is within 2^-9 relative, and up to six of
+# them lie between the (bf16-exact) inputs and a gradient dX_l: the bf16 copy of the weights fed to the matrix
+# cores, the stored dM, the compressed rows handed back, and three stores of dX_l (transposed aggregation, self
+# tap, owner-side sum); the oracle rounds at the stores only. 6 * 2^-9 < 2^-6.
+BF16_TOL = 2.0 ** -6
 
 
 def _weights(widths, conv):

@@ -9,6 +9,10 @@ namespace {
 
 constexpr int kBlock = 256;
 
+__device__ __forceinline__ float vec_elem(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+__device__ __forceinline__ float vec_elem(const float2& v, int i) { return i == 0 ? v.x : v.y; }
+__device__ __forceinline__ float vec_elem(const float& v, int) { return v; }
+
 __device__ __forceinline__ int64_t group_row(int g_log2) {
     return (int64_t(blockIdx.x) * kBlock + threadIdx.x) >> g_log2;
 }
@@ -82,39 +86,51 @@ __global__ __launch_bounds__(kBlock) void decompress_add_kernel(MaskRule rule, c
     }
 }
 
-// Owner-side sum over all consumers: a group of lanes (one per stored element) owns one boundary row, adds
-// up the rows returned for it (coalesced reads of k consecutive values each, four in flight), and touches
-// the wide gradient row once.
-template <typename T>
+// Owner-side sum over all consumers: a group of lanes (one per EV stored elements) owns one boundary row,
+// adds up the rows returned for it (coalesced reads of k consecutive values each, four in flight), and
+// touches the wide gradient row once.
+template <typename T, int EV>
 __global__ __launch_bounds__(kBlock) void accumulate_returned_kernel(MaskRule rule, const int32_t* __restrict__ gids,
                                                                      const int32_t* __restrict__ rows, int64_t n_rows,
                                                                      const int32_t* __restrict__ ptr,
                                                                      const int32_t* __restrict__ src,
                                                                      const T* __restrict__ returned,
                                                                      T* __restrict__ x, int64_t ldx, int g_log2) {
+    using V = typename FloatVec<EV>::type;
     const uint32_t g = 1u << g_log2;
     const uint32_t gl = threadIdx.x & (g - 1);
     const int64_t stride = (int64_t(gridDim.x) * kBlock) >> g_log2;
     const int64_t k = rule.k;
+    const uint32_t ku = rule.k / EV;
     for (int64_t b = group_row(g_log2); b < n_rows; b += stride) {
         const int32_t e0 = ptr[b], e1 = ptr[b + 1];
         if (e0 == e1) continue;
         T* xr = x + int64_t(rows[b]) * ldx;
         MaskAffine m{1, 0, 1};
         if (rule.k != rule.width) m = varco_affine(rule, uint32_t(gids[b]));
-        for (uint32_t j = gl; j < rule.k; j += g) {
-            float acc = 0.f;
-            int32_t e = e0;
-            for (; e + 3 < e1; e += 4) {
-                const float v0 = Elem<T>::load(returned + int64_t(src[e]) * k + j);
-                const float v1 = Elem<T>::load(returned + int64_t(src[e + 1]) * k + j);
-                const float v2 = Elem<T>::load(returned + int64_t(src[e + 2]) * k + j);
-                const float v3 = Elem<T>::load(returned + int64_t(src[e + 3]) * k + j);
-                acc += v0, acc += v1, acc += v2, acc += v3;
+        for (uint32_t ju = gl; ju < ku; ju += g) {
+            const uint32_t j = ju * EV;
+            float acc[EV];
+#pragma unroll
+            for (int i = 0; i < EV; ++i) acc[i] = 0.f;
+            for (int32_t e = e0; e < e1; e += 4) {          // rows past the end re-read row e0 and are dropped
+                V v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) v[u] = load_vec<T, EV>(returned + int64_t(src[e + u < e1 ? e + u : e0]) * k + j);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (e + u < e1) {
+#pragma unroll
+                        for (int i = 0; i < EV; ++i) acc[i] += vec_elem(v[u], i);
+                    }
             }
-            for (; e < e1; ++e) acc += Elem<T>::load(returned + int64_t(src[e]) * k + j);
-            const uint32_t pos = rule.k == rule.width ? j : varco_position(rule, m, j);
-            Elem<T>::store(xr + pos, Elem<T>::load(xr + pos) + acc);
+            uint32_t pos = rule.k == rule.width ? j : varco_position(rule, m, j);
+#pragma unroll
+            for (int i = 0; i < EV; ++i) {
+                Elem<T>::store(xr + pos, Elem<T>::load(xr + pos) + acc[i]);
+                pos += rule.k == rule.width ? 1u : m.a;
+                if (pos >= rule.width) pos -= rule.width;
+            }
         }
     }
 }
@@ -168,9 +184,27 @@ template <typename T>
 hipError_t launch_accumulate_t(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows,
                                const int32_t* ptr, const int32_t* src, const void* returned, void* x, int64_t ldx,
                                hipStream_t stream) {
-    const int gl = group_log2(rule.k);
-    hipLaunchKernelGGL(accumulate_returned_kernel<T>, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids,
-                       rows, n_rows, ptr, src, static_cast<const T*>(returned), static_cast<T*>(x), ldx, gl);
+    // wide loads only while at least 32 lanes still share a row: fewer lanes per row means more rows per
+    // wavefront, whose differing numbers of returned rows then serialise
+    int ev = 1;
+    for (int c : {4, 2})
+        if (rule.k % c == 0 && rule.k / c >= 32 && (reinterpret_cast<uintptr_t>(returned) & (c * sizeof(T) - 1)) == 0) {
+            ev = c;
+            break;
+        }
+    const int gl = group_log2(rule.k / ev);
+    const dim3 grid(grid_for(n_rows, gl)), block(kBlock);
+    const T* ret = static_cast<const T*>(returned);
+    T* xt = static_cast<T*>(x);
+    if (ev == 4)
+        hipLaunchKernelGGL((accumulate_returned_kernel<T, 4>), grid, block, 0, stream, rule, gids, rows, n_rows, ptr, src, ret,
+                           xt, ldx, gl);
+    else if (ev == 2)
+        hipLaunchKernelGGL((accumulate_returned_kernel<T, 2>), grid, block, 0, stream, rule, gids, rows, n_rows, ptr, src, ret,
+                           xt, ldx, gl);
+    else
+        hipLaunchKernelGGL((accumulate_returned_kernel<T, 1>), grid, block, 0, stream, rule, gids, rows, n_rows, ptr, src, ret,
+                           xt, ldx, gl);
     return hipGetLastError();
 }
 

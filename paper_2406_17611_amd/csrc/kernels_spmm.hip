@@ -280,8 +280,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* spl
 // Gathering the k scattered columns of every dM row an entry refers to would pull whole cache lines for
 // 4 useful bytes each, once per entry. Instead the work is done in two streaming passes:
 //   1. row order: a wavefront stages dM[i, :] in LDS once, and for each halo entry of row i writes the k
-//      products w * dM[i, pi_v(j)] as one contiguous row of a product buffer, at the entry's position in
-//      the transposed order (prow, derived once at registration);
+//      products w * dM[i, pi_v(j)] as one contiguous row of a product buffer (elements of the storage type),
+//      at the entry's position in the transposed order (prow, derived once at registration);
 //   2. transposed order: the products of one halo slot are now consecutive rows; they are summed in entry
 //      order (fixed order: reproducible bits) into dz_halo.
 // ---------------------------------------------------------------------------------------------------------
@@ -294,7 +294,7 @@ struct ProductArgs {
     const int32_t* prow;        // per entry: row of the product buffer (halo entries only)
     const T* dm;                // n_local x width
     MaskRule rule;
-    float* prod;                // (halo entries) x k, fp32
+    T* prod;                    // (halo entries) x k, in the storage type
     int32_t ev;                 // floats per lane and store: 4, 2 or 1
     int32_t ku;                 // stores per entry = k / ev
     int32_t lpe_log2;           // lanes per entry
@@ -330,13 +330,13 @@ __device__ __forceinline__ void product_phase(const ProductArgs<T>& p, int lane,
                     q += a;
                     if (q >= width) q -= width;
                 }
-                float* dst = p.prod + int64_t(row) * k + j;
-                if (EV == 4)
-                    *reinterpret_cast<float4*>(dst) = make_float4(out[0], out[1], out[2], out[3]);
-                else if (EV == 2)
-                    *reinterpret_cast<float2*>(dst) = make_float2(out[0], out[EV - 1]);
+                T* dst = p.prod + int64_t(row) * k + j;
+                if constexpr (EV == 4)
+                    store_vec<T, 4>(dst, make_float4(out[0], out[1], out[2], out[3]));
+                else if constexpr (EV == 2)
+                    store_vec<T, 2>(dst, make_float2(out[0], out[1]));
                 else
-                    *dst = out[0];
+                    store_vec<T, 1>(dst, out[0]);
             }
         }
     }
@@ -355,28 +355,30 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs<T> p)
     const int32_t idx = blockIdx.x * kWaves + wave;
     if (idx >= p.n_items) return;       // no block-wide barrier below
     const SpmmItem it = p.items[idx];
+    if (it.e0 >= it.e1) return;
 
-    bool staged = false;
-    for (int32_t base = it.e0; base < it.e1; base += 64) {
+    // The records of a batch (entry, weight, product row) are loaded together and for every entry, halo or
+    // not, so that one memory round trip serves all three; the first batch's loads are in flight while the
+    // row of dM is staged in LDS.
+    VarcoEdge ed{0, -1};
+    float w = 0.f;
+    int32_t pr = 0;
+    auto load_batch = [&](int32_t base) {
         const int32_t e = base + lane;
-        const bool valid = e < it.e1;
-        VarcoEdge ed{0, -1};
-        if (valid) ed = p.edge[e];
+        ed = VarcoEdge{0, -1}, w = 0.f, pr = 0;
+        if (e < it.e1) ed = p.edge[e], w = p.vals[e], pr = p.prow[e];
+    };
+    load_batch(it.e0);
+    {
+        const T* src = p.dm + int64_t(it.row) * width;
+        for (int c = lane; c < width; c += 64) lrow[c] = Elem<T>::load(src + c);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+    for (int32_t base = it.e0; base < it.e1; base += 64) {
         const bool is_halo = ed.gid >= 0;
         const uint64_t hmask = __ballot(is_halo);
-        if (hmask == 0) continue;       // uniform: this batch holds local entries only
-        if (!staged) {                  // the row of dM is read once, by the first batch that needs it
-            const T* src = p.dm + int64_t(it.row) * width;
-            for (int c = lane; c < width; c += 64) lrow[c] = Elem<T>::load(src + c);
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            staged = true;
-        }
-        float w = 0.f;
-        int32_t pr = 0;
         uint32_t mab = 0;
         if (is_halo) {
-            w = p.vals[e];
-            pr = p.prow[e];
             const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ p.rule.s0);
             const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
             mab = uint32_t(lunits[__umulhi(h2, p.rule.n_units)]) | (__umulhi(h1, p.rule.width) << 16);
@@ -384,12 +386,17 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs<T> p)
         const int cnt = min(64, it.e1 - base);
         const int ns = __popcll(hmask);
         const int first = cnt - ns;     // columns ascend within a row: halo entries sit in the last lanes
-        if (p.ev == 4)
-            product_phase<T, 4>(p, lane, first, ns, pr, w, mab, lrow);
-        else if (p.ev == 2)
-            product_phase<T, 2>(p, lane, first, ns, pr, w, mab, lrow);
-        else
-            product_phase<T, 1>(p, lane, first, ns, pr, w, mab, lrow);
+        const float wb = w;
+        const int32_t prb = pr;
+        if (base + 64 < it.e1) load_batch(base + 64);
+        if (ns > 0) {
+            if (p.ev == 4)
+                product_phase<T, 4>(p, lane, first, ns, prb, wb, mab, lrow);
+            else if (p.ev == 2)
+                product_phase<T, 2>(p, lane, first, ns, prb, wb, mab, lrow);
+            else
+                product_phase<T, 1>(p, lane, first, ns, prb, wb, mab, lrow);
+        }
     }
 }
 
@@ -397,7 +404,7 @@ template <typename T>
 struct SegsumArgs {
     const SpmmItem* items;      // work list of the transposed halo rows (entry ranges in transposed order)
     int32_t n_items;
-    const float* prod;
+    const T* prod;
     int32_t prod_base;          // transposed position of the first halo entry (= product row 0)
     int32_t k;
     T* out;
@@ -410,19 +417,19 @@ template <typename T, int EV>
 __device__ __forceinline__ void segsum_body(const SegsumArgs<T>& p, const SpmmItem& it, int jl, int lpe) {
     using V = typename Vec<EV>::type;
     for (int ju = jl; ju < p.ku; ju += lpe) {
-        const float* src = p.prod + int64_t(it.e0 - p.prod_base) * p.k + ju * EV;
+        const T* src = p.prod + int64_t(it.e0 - p.prod_base) * p.k + ju * EV;
         V acc;
         zero_vec(acc);
         int32_t n = it.e1 - it.e0;
         for (; n >= 4; n -= 4) {
-            const V v0 = *reinterpret_cast<const V*>(src), v1 = *reinterpret_cast<const V*>(src + p.k);
-            const V v2 = *reinterpret_cast<const V*>(src + 2 * int64_t(p.k));
-            const V v3 = *reinterpret_cast<const V*>(src + 3 * int64_t(p.k));
+            const V v0 = load_vec<T, EV>(src), v1 = load_vec<T, EV>(src + p.k);
+            const V v2 = load_vec<T, EV>(src + 2 * int64_t(p.k));
+            const V v3 = load_vec<T, EV>(src + 3 * int64_t(p.k));
             add_vec(acc, v0), add_vec(acc, v1), add_vec(acc, v2), add_vec(acc, v3);
             src += 4 * int64_t(p.k);
         }
         for (; n > 0; --n) {
-            add_vec(acc, *reinterpret_cast<const V*>(src));
+            add_vec(acc, load_vec<T, EV>(src));
             src += p.k;
         }
         if (it.dst < 0)
@@ -578,14 +585,15 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
 
 template <typename T>
 hipError_t halo_grad_t(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge, const float* vals,
-                       const int32_t* prow, int32_t prod_base, const void* dm, const MaskRule& rule, float* prod,
+                       const int32_t* prow, int32_t prod_base, const void* dm, const MaskRule& rule, void* prod_v,
                        void* out_v, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag,
                        const LaunchTag& sum_tag) {
     T* out = static_cast<T*>(out_v);
+    T* prod = static_cast<T*>(prod_v);
     const int32_t width = int32_t(rule.width);
     int ev = 1;
     for (int c : {4, 2})
-        if (rule.k % c == 0 && aligned_to(prod, 4 * c) && aligned_to(out, c * sizeof(T)) && aligned_to(partial, 4 * c)) {
+        if (rule.k % c == 0 && aligned_to(prod, c * sizeof(T)) && aligned_to(out, c * sizeof(T)) && aligned_to(partial, 4 * c)) {
             ev = c;
             break;
         }
@@ -665,7 +673,7 @@ hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx,
 
 hipError_t varco_launch_halo_grad(int dtype, const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
                                   const float* vals, const int32_t* prow, int32_t prod_base, const void* dm,
-                                  const MaskRule& rule, float* prod, void* out, int32_t row_base, float* partial,
+                                  const MaskRule& rule, void* prod, void* out, int32_t row_base, float* partial,
                                   hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag) {
     if (t_halo_plan.n_items == 0 || fwd_plan.n_items == 0) return hipSuccess;
     return dtype == VARCO_BF16 ? halo_grad_t<bf16_t>(fwd_plan, t_halo_plan, edge, vals, prow, prod_base, dm, rule, prod, out,

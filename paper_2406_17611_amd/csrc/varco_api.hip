@@ -50,7 +50,7 @@ struct varco_ctx {
     float* ws_dm = nullptr;        size_t ws_dm_elems = 0;        // dM: n_local x width (elements of the storage type)
     float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
     float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
-    float* ws_prod = nullptr;      size_t ws_prod_elems = 0;      // halo-gradient products: (halo entries) x k
+    float* ws_prod = nullptr;      size_t ws_prod_elems = 0;      // halo-gradient products: (halo entries) x k elements
     float* ws_w = nullptr;         size_t ws_w_elems = 0;         // bf16 copies of the two weights of a layer call
     varco_stats stats{};
     VarcoProfiler prof;
@@ -623,7 +623,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
                                              dz_halo, nl, ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             // product buffer: grown on demand (the first call at a larger k synchronises the device)
-            const size_t need = size_t(d.nnz - ps.nnz_t_local) * rule.k;
+            const size_t need = (size_t(d.nnz - ps.nnz_t_local) * rule.k * size_t(es) + 3) / 4;   // in floats
             if (need > ctx->ws_prod_elems) VARCO_HIP(ctx, grow(ctx->ws_prod, ctx->ws_prod_elems, need + need / 4));
             VARCO_HIP(ctx, varco_launch_halo_grad(dt, ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
                                                   ctx->ws_dm, rule, ctx->ws_prod, dz_halo, nl, ctx->ws_spmm, st,

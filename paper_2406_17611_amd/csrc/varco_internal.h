@@ -120,10 +120,10 @@ hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx,
 
 // out[s, j] = sum over local rows i of S[i, halo s] * dm[i, pi_v(j)], j < k (the halo rows of the transposed
 // aggregation, produced directly in compressed form) in two streaming passes through the product buffer
-// `prod` ((halo entries) x k floats). prod_base = transposed position of the first halo entry.
+// `prod` ((halo entries) x k elements of the storage type). prod_base = transposed position of the first halo entry.
 hipError_t varco_launch_halo_grad(int dtype, const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge,
                                   const float* vals, const int32_t* prow, int32_t prod_base, const void* dm,
-                                  const MaskRule& rule, float* prod, void* out, int32_t row_base, float* partial,
+                                  const MaskRule& rule, void* prod, void* out, int32_t row_base, float* partial,
                                   hipStream_t stream, const LaunchTag& tag, const LaunchTag& sum_tag);
 
 // C (+)= op(A) op(B) in fp32 on the matrix cores, row-major everywhere.

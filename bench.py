@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large_sage")
     ap.add_argument("--ratio", default=None, help="num/den, default: the configuration's ratio")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="HIP streams the partitions of a layer are dealt to (kernels of different partitions overlap)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-only", action="store_true")
     args = ap.parse_args()
@@ -128,7 +130,7 @@ def main():
         f"boundary rows {sum(h.n_boundary for h in host)}")
     t0 = time.time()
     L = len(w.widths) - 1
-    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY, dtype=w.dtype)
+    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY, dtype=w.dtype, n_streams=args.streams)
     net.set_inputs(synth.features(g.n, w.widths[0], synth.SEED_FEAT))
     net.set_weights([synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l) for l in range(L)],
                     [synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l + 1) for l in range(L)])
@@ -193,7 +195,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "nodes": g.n, "directed_entries": g.nnz, "partitions": w.n_parts,
                    "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
-                   "keep": [net.ctx.keep(l) for l in range(L)], "layers": L,
+                   "keep": [net.ctx.keep(l) for l in range(L)], "layers": L, "streams": args.streams,
                    "edges_counted_per_step": edges_per_step},
         "roofline": roofline,
         "kernels": kernels,

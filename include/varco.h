@@ -23,8 +23,11 @@
  *   - Matrices are row-major and dense (leading dimension = width) unless a leading dimension is given.
  *   - Node ids, row ids and counts are int32 (graphs below 2^31 nodes / entries per partition); element
  *     offsets are 64-bit inside the library.
- *   - A context is not thread-safe. Calls on one context must be issued on one stream at a time, because
- *     they share the context's workspace.
+ *   - A context is not thread-safe (one host thread issues its calls). Layer calls may be issued on up
+ *     to 4 different streams, whose work then may overlap on the device: the library keeps one workspace
+ *     set per stream (created on the stream's first call, which may synchronise the device). The caller
+ *     orders dependent work across streams (events), and gives calls that may overlap different output
+ *     buffers; dh1 / dh0 in particular are read-modify-written (see varco_sum_gradients).
  *   - Layers are numbered 0..L-1; layer l maps width[l] -> width[l+1]. k_l is the number of elements of a
  *     width[l] vector that is communicated at the current ratio of layer l.
  */
@@ -227,6 +230,11 @@ typedef struct {
     double bytes[VARCO_K_COUNT];
     double flops[VARCO_K_COUNT];
 } varco_profile;
+/* dst[i] += src[i] for n fp32 values (device pointers). Algorithm 1: the weight gradients computed on the
+ * partitions are summed before the update; a caller that lets overlapping layer calls accumulate into one
+ * gradient buffer per stream folds those buffers with this call. */
+int32_t varco_sum_gradients(void* dst, const void* src, int64_t n, varco_stream stream);
+
 /* A plain device-to-device copy of `bytes` bytes (multiple of 16, 16-byte aligned pointers) by a kernel
  * of this library: the known-size reference against which hardware byte counters are scaled. */
 int32_t varco_calibration_copy(void* dst, const void* src, int64_t bytes, varco_stream stream);

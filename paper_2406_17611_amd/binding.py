@@ -27,7 +27,7 @@ EXPORTS = [
     "varco_begin_step", "varco_set_ratio", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
-    "varco_calibration_copy",
+    "varco_calibration_copy", "varco_sum_gradients",
 ]
 KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
                   "agg_bwd_halo", "reduce", "agg_bwd_halo_sum"]
@@ -96,6 +96,7 @@ def lib() -> C.CDLL:
         L.varco_get_stats.argtypes = [vp, C.POINTER(Stats)]
         L.varco_reset_stats.argtypes = [vp]
         L.varco_calibration_copy.argtypes = [vp, vp, i64, vp]
+        L.varco_sum_gradients.argtypes = [vp, vp, i64, vp]
         L.varco_profile_enable.argtypes = [vp, i32]
         L.varco_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         for name in EXPORTS:
@@ -130,6 +131,12 @@ def _stream(stream):
 def calibration_copy(dst, src, stream=None):
     """Copies the bytes of tensor `src` into `dst` with the library's plain copy kernel."""
     _check(lib().varco_calibration_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
+
+
+def sum_gradients(dst, src, stream=None):
+    """dst += src (fp32 device tensors of equal size)."""
+    assert dst.numel() == src.numel() and dst.dtype == src.dtype
+    _check(lib().varco_sum_gradients(_ptr(dst), _ptr(src), dst.numel(), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------------------

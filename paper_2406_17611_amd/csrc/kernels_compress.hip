@@ -141,6 +141,12 @@ __global__ __launch_bounds__(kBlock) void calibration_copy_kernel(const float4* 
     for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) dst[i] = src[i];
 }
 
+__global__ __launch_bounds__(kBlock) void sum_gradients_kernel(float* __restrict__ dst, const float* __restrict__ src,
+                                                               int64_t n) {
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) dst[i] += src[i];
+}
+
 int group_log2(uint32_t elems) {
     int l = 0;
     while ((1u << l) < elems && l < 6) ++l;
@@ -248,5 +254,13 @@ hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t byt
     if (bytes == 0) return hipSuccess;
     hipLaunchKernelGGL(calibration_copy_kernel, dim3(256 * 32), dim3(kBlock), 0, stream, static_cast<const float4*>(src),
                        static_cast<float4*>(dst), bytes / 16);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_sum_gradients(float* dst, const float* src, int64_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    const int64_t want = (n + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(sum_gradients_kernel, dim3(unsigned(want < 256 * 16 ? want : 256 * 16)), dim3(kBlock), 0, stream, dst,
+                       src, n);
     return hipGetLastError();
 }

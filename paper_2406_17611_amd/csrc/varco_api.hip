@@ -35,6 +35,20 @@ struct PartState {
     int64_t nnz_t_local = 0;         // transposed entries whose row is a local node
 };
 
+// Device scratch of the layer calls. Calls issued on different streams may run concurrently, so every
+// stream that calls into a context gets a set of its own (up to kMaxStreams), sized from what the
+// registered partitions need.
+struct Workspace {
+    hipStream_t stream = nullptr;
+    bool used = false;
+    float* dm = nullptr;        size_t dm_elems = 0;        // dM: n_local x width (elements of the storage type)
+    float* spmm = nullptr;      size_t spmm_elems = 0;      // partial rows of split CSR rows
+    float* gemm = nullptr;      size_t gemm_elems = 0;      // split-K partial products
+    float* prod = nullptr;      size_t prod_elems = 0;      // halo-gradient products: (halo entries) x k elements
+    float* w = nullptr;         size_t w_elems = 0;         // bf16 copies of the two weights of a layer call
+};
+constexpr int kMaxStreams = 4;
+
 std::mutex g_err_mutex;
 std::string g_global_error;
 
@@ -46,12 +60,8 @@ struct varco_ctx {
     std::vector<int32_t> widths, act;
     std::vector<LayerState> layers;
     std::vector<PartState> parts;
-    // device workspace shared by all calls on this context
-    float* ws_dm = nullptr;        size_t ws_dm_elems = 0;        // dM: n_local x width (elements of the storage type)
-    float* ws_spmm = nullptr;      size_t ws_spmm_elems = 0;      // partial rows of split CSR rows
-    float* ws_gemm = nullptr;      size_t ws_gemm_elems = 0;      // split-K partial products
-    float* ws_prod = nullptr;      size_t ws_prod_elems = 0;      // halo-gradient products: (halo entries) x k elements
-    float* ws_w = nullptr;         size_t ws_w_elems = 0;         // bf16 copies of the two weights of a layer call
+    Workspace ws[kMaxStreams];
+    size_t need_dm = 0, need_spmm = 0, need_gemm = 0, need_w = 0;   // what the registered partitions ask for
     varco_stats stats{};
     VarcoProfiler prof;
     double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
@@ -226,14 +236,37 @@ int32_t ensure_tables(varco_ctx* ctx) {
 }
 
 // bf16 copy of a weight matrix in workspace slot 0 or 1, rows = the product's output index, pitch padded to 8.
-hipError_t prep_weight(varco_ctx* ctx, const void* h, int32_t fi, int32_t fo, bool transpose, int slot, hipStream_t st,
+hipError_t prep_weight(Workspace& ws, const void* h, int32_t fi, int32_t fo, bool transpose, int slot, hipStream_t st,
                        const void** out, int64_t* pitch) {
     const int32_t rows = transpose ? fo : fi, cols = transpose ? fi : fo;
     const int32_t p = pad8(cols);
-    char* dst = reinterpret_cast<char*>(ctx->ws_w) + size_t(slot) * ctx->ws_w_elems * 2;
+    char* dst = reinterpret_cast<char*>(ws.w) + size_t(slot) * ws.w_elems * 2;
     *out = dst;
     *pitch = p;
     return varco_launch_prep_weight(static_cast<const float*>(h), fo, rows, cols, p, transpose, dst, st);
+}
+
+// The workspace set of `st`, created on the stream's first call and brought up to the registered sizes.
+int32_t workspace_for(varco_ctx* ctx, hipStream_t st, Workspace** out) {
+    Workspace* ws = nullptr;
+    for (Workspace& w : ctx->ws)
+        if (w.used && w.stream == st) ws = &w;
+    if (!ws) {
+        for (Workspace& w : ctx->ws)
+            if (!w.used) {
+                ws = &w;
+                break;
+            }
+        if (!ws) return varco_fail(ctx, VARCO_ERR_STATE, "layer calls were issued on more streams than the context supports (4)");
+        ws->used = true;
+        ws->stream = st;
+    }
+    VARCO_HIP(ctx, grow(ws->dm, ws->dm_elems, ctx->need_dm));
+    VARCO_HIP(ctx, grow(ws->spmm, ws->spmm_elems, ctx->need_spmm));
+    VARCO_HIP(ctx, grow(ws->gemm, ws->gemm_elems, ctx->need_gemm));
+    VARCO_HIP(ctx, grow(ws->w, ws->w_elems, ctx->need_w));
+    *out = ws;
+    return VARCO_OK;
 }
 
 int32_t check_layer(const varco_ctx* ctx, int32_t layer, const char* fn) {
@@ -330,11 +363,9 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
         if (ls.units_inv) (void)hipFree(ls.units_inv);
     }
     for (PartState& ps : ctx->parts) free_part(ps);
-    if (ctx->ws_dm) (void)hipFree(ctx->ws_dm);
-    if (ctx->ws_spmm) (void)hipFree(ctx->ws_spmm);
-    if (ctx->ws_gemm) (void)hipFree(ctx->ws_gemm);
-    if (ctx->ws_prod) (void)hipFree(ctx->ws_prod);
-    if (ctx->ws_w) (void)hipFree(ctx->ws_w);
+    for (Workspace& w : ctx->ws)
+        for (float* p : {w.dm, w.spmm, w.gemm, w.prod, w.w})
+            if (p) (void)hipFree(p);
     for (VarcoProfiler::Rec& r : ctx->prof.recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -425,11 +456,11 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
             const int64_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
             slot = std::max({slot, fo * pad8(int32_t(fi)), fi * pad8(int32_t(fo))});
         }
-        VARCO_HIP(ctx, grow(ctx->ws_w, ctx->ws_w_elems, size_t(slot)));   // 2 slots x 2 bytes = 4 bytes per element
+        ctx->need_w = std::max(ctx->need_w, size_t(slot));   // in floats: 2 slots x 2 bytes = 4 bytes per element
     }
-    VARCO_HIP(ctx, grow(ctx->ws_dm, ctx->ws_dm_elems, size_t(nl) * wmax));
-    VARCO_HIP(ctx, grow(ctx->ws_spmm, ctx->ws_spmm_elems, size_t(max_partials) * wmax));
-    VARCO_HIP(ctx, grow(ctx->ws_gemm, ctx->ws_gemm_elems, size_t(gemm_elems)));
+    ctx->need_dm = std::max(ctx->need_dm, size_t(nl) * wmax);
+    ctx->need_spmm = std::max(ctx->need_spmm, size_t(max_partials) * wmax);
+    ctx->need_gemm = std::max(ctx->need_gemm, size_t(gemm_elems));
     ps.registered = true;
     return VARCO_OK;
 }
@@ -515,6 +546,9 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     if (z_out && layer == ctx->n_layers - 1)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_out must be null on the last layer");
     hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* wsp = nullptr;
+    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    Workspace& ws = *wsp;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const MaskRule rule = make_rule(ctx, layer);
     ctx->layers[layer].ran_forward = true;
@@ -524,7 +558,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double es = ctx->elem_bytes();
     const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
                              double(d.n_halo) * rule.k * es;
-    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, ps.edges, nullptr, d.vals, x_local, z_in, rule, m_saved, 0, ctx->ws_spmm, st,
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, ps.edges, nullptr, d.vals, x_local, z_in, rule, m_saved, 0, ws.spmm, st,
                                      ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0)));
     // transform + nonlinearity
     GemmArgs g;
@@ -539,8 +573,8 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     g.c = x_out, g.ldc = fo, g.c_dtype = dt;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
     if (dt == VARCO_BF16 && d.n_local > 0) {   // weights as bf16, [output column][reduction index]
-        VARCO_HIP(ctx, prep_weight(ctx, h1, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
-        if (sage) VARCO_HIP(ctx, prep_weight(ctx, h0, fi, fo, true, 1, st, &g.b2_prep, &g.b2_prep_ld));
+        VARCO_HIP(ctx, prep_weight(ws, h1, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
+        if (sage) VARCO_HIP(ctx, prep_weight(ws, h0, fi, fo, true, 1, st, &g.b2_prep, &g.b2_prep_ld));
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
@@ -578,6 +612,9 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const int dt = ctx->dtype;
     const double es = ctx->elem_bytes();
     if (nl == 0) return VARCO_OK;
+    Workspace* wsp = nullptr;
+    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    Workspace& ws = *wsp;
 
     // weight gradients: reductions over the partition's rows, split over workgroups
     {
@@ -587,12 +624,12 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = dx_out, g.b.gate = gate, g.b.ld = fo, g.b.dtype = dt;
         g.c = dh1, g.ldc = fo;
         g.accumulate = true;
-        g.partial = ctx->ws_gemm;
+        g.partial = ws.gemm;
         const LaunchTag wtag = ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl));
         for (int tap = 0; tap < (sage ? 2 : 1); ++tap) {
             if (tap == 1) g.a.ptr = x_local, g.c = dh0;
             g.split_k = gemm_split_for(fi, fo, nl, varco_gemm_bf16_usable(g));
-            if (size_t(g.split_k) * fi * fo > ctx->ws_gemm_elems)
+            if (size_t(g.split_k) * fi * fo > ws.gemm_elems)
                 return varco_fail(ctx, VARCO_ERR_STATE, "varco_layer_bwd: workspace too small");
             VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
         }
@@ -605,8 +642,8 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.m = nl, g.n = fi, g.k = fo;
         g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
         g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
-        g.c = ctx->ws_dm, g.ldc = fi, g.c_dtype = dt;
-        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx, h1, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
+        g.c = ws.dm, g.ldc = fi, g.c_dtype = dt;
+        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ws, h1, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
@@ -615,18 +652,18 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
     const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
-    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule, dx_local,
-                                     0, ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, dense_rule, dx_local,
+                                     0, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
     if (d.n_halo > 0) {
         if (rule.k == rule.width) {
-            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ctx->ws_dm, nullptr, dense_rule,
-                                             dz_halo, nl, ctx->ws_spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
+            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, dense_rule,
+                                             dz_halo, nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             // product buffer: grown on demand (the first call at a larger k synchronises the device)
             const size_t need = (size_t(d.nnz - ps.nnz_t_local) * rule.k * size_t(es) + 3) / 4;   // in floats
-            if (need > ctx->ws_prod_elems) VARCO_HIP(ctx, grow(ctx->ws_prod, ctx->ws_prod_elems, need + need / 4));
+            if (need > ws.prod_elems) VARCO_HIP(ctx, grow(ws.prod, ws.prod_elems, need + need / 4));
             VARCO_HIP(ctx, varco_launch_halo_grad(dt, ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
-                                                  ctx->ws_dm, rule, ctx->ws_prod, dz_halo, nl, ctx->ws_spmm, st,
+                                                  ws.dm, rule, ws.prod, dz_halo, nl, ws.spmm, st,
                                                   ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
                                                   ctx->tag(VARCO_K_AGG_BWD_HALO_SUM, th_out_bytes, 0)));
         }
@@ -641,7 +678,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = h0, g.b.ld = fo, g.b.transposed = true;
         g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
         g.accumulate = true;
-        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx, h0, fi, fo, false, 1, st, &g.b_prep, &g.b_prep_ld));
+        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ws, h0, fi, fo, false, 1, st, &g.b_prep, &g.b_prep_ld));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     return VARCO_OK;
@@ -678,6 +715,16 @@ extern "C" int32_t varco_reset_stats(varco_ctx* ctx) {
     const int32_t b = ctx->stats.bytes_per_elem;
     ctx->stats = varco_stats{};
     ctx->stats.bytes_per_elem = b;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_sum_gradients(void* dst, const void* src, int64_t n, varco_stream stream) {
+    if (n < 0) return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_sum_gradients: negative count");
+    if (n == 0) return VARCO_OK;
+    if (!dst || !src) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_sum_gradients: null pointer");
+    VARCO_HIP(static_cast<const varco_ctx*>(nullptr),
+              varco_launch_sum_gradients(static_cast<float*>(dst), static_cast<const float*>(src), n,
+                                         static_cast<hipStream_t>(stream)));
     return VARCO_OK;
 }
 

@@ -101,6 +101,7 @@ hipError_t varco_launch_accumulate_returned(int dtype, const MaskRule& rule, con
                                             void* x, int64_t ldx, hipStream_t stream, const LaunchTag& tag);
 
 hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
+hipError_t varco_launch_sum_gradients(float* dst, const float* src, int64_t n, hipStream_t stream);
 
 hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
                                     const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream);

@@ -13,10 +13,15 @@ from . import binding as vb
 
 
 class PartitionedNetwork:
-    def __init__(self, host_parts, widths, conv: str, mask_key: int, device="cuda", need_backward=True, dtype="f32"):
+    def __init__(self, host_parts, widths, conv: str, mask_key: int, device="cuda", need_backward=True, dtype="f32",
+                 n_streams=1):
         """dtype: storage of activations, messages and their gradients ("f32" or "bf16"); weights and weight
-        gradients are always fp32."""
+        gradients are always fp32. n_streams > 1: the partitions of a layer are dealt to that many HIP
+        streams, so that the matrix-core-bound kernels of one partition overlap the memory-bound kernels of
+        another; streams are joined wherever a step needs all partitions (layer boundaries, owner-side sums)."""
         assert dtype in ("f32", "bf16")
+        assert 1 <= n_streams <= 4
+        self.n_streams = n_streams
         self.dtype = dtype
         self.act_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.device = torch.device(device)
@@ -67,10 +72,39 @@ class PartitionedNetwork:
         if need_backward:
             self.dh1 = [torch.zeros_like(h) for h in self.h1]
             self.dh0 = [torch.zeros_like(h) if conv == "sage" else None for h in self.h1]
+            # one more set of weight-gradient accumulators per extra stream (overlapping calls must not
+            # read-modify-write the same buffer); folded into dh1 / dh0 at the end of backward()
+            self._dh1_extra = [[torch.zeros_like(h) for h in self.h1] for _ in range(n_streams - 1)]
+            self._dh0_extra = [[torch.zeros_like(h) if conv == "sage" else None for h in self.h1]
+                               for _ in range(n_streams - 1)]
             self.dx = [None] + [torch.empty((self.n_total, self.widths[l]), **act) for l in range(1, self.L + 1)]
             self.dz_halo = [None] * self.L
         self._zcap = [0] * self.L
         self._dzcap = [0] * self.L
+        self._streams = None
+
+    # ------------------------------------------------------------------ streams
+    def _stream_set(self, stream):
+        """The streams a step is issued on: the caller's (or torch's current) stream first, then the extra ones."""
+        if self.n_streams == 1:
+            return [stream]
+        if self._streams is None:
+            self._streams = [torch.cuda.Stream(device=self.device) for _ in range(self.n_streams - 1)]
+        return [stream if stream is not None else torch.cuda.current_stream(self.device)] + self._streams
+
+    @staticmethod
+    def _join(streams):
+        """Every stream waits for everything issued so far on all of them."""
+        if len(streams) == 1:
+            return
+        events = []
+        for st in streams:
+            e = torch.cuda.Event()
+            e.record(st)
+            events.append(e)
+        for st in streams:
+            for e in events:
+                st.wait_event(e)
 
     # ------------------------------------------------------------------ data placement
     def rows(self, q):
@@ -123,38 +157,61 @@ class PartitionedNetwork:
             else:
                 ctx.set_ratio(-1, ratio[0], ratio[1])
         self._ensure_buffers()
+        streams = self._stream_set(stream)
+        ns = len(streams)
+        self._join(streams)
         # layer 0's exchange: owners compress the boundary rows of the input features
         k0 = ctx.keep(0)
         for p, hp in enumerate(self.host_parts):
             if hp.n_boundary:
                 zp = self.z[0][hp.z_row_offset * k0:]
                 ctx.compress(0, self.boundary_gid[p], self.dev_parts[p]["boundary_rows"], hp.n_boundary,
-                             self.x[0][self.rows(p)], self.widths[0], zp, stream)
+                             self.x[0][self.rows(p)], self.widths[0], zp, streams[p % ns])
         for l in range(self.L):
             last = l == self.L - 1
+            self._join(streams)         # every owner's compressed rows of this layer's input are complete
             for q in range(self.P):
                 r = self.rows(q)
                 ctx.layer_fwd(l, q, self.x[l][r], self.z[l], self.h1[l], self.h0[l], self.x[l + 1][r],
-                              None if last else self.z[l + 1], self.m[l][r], stream)
+                              None if last else self.z[l + 1], self.m[l][r], streams[q % ns])
+        self._join(streams)
 
     def backward(self, stream=None):
         ctx = self.ctx
+        streams = self._stream_set(stream)
+        ns = len(streams)
+        self._join(streams)
         for l in range(self.L - 1, -1, -1):
             need = l > 0
             k = ctx.keep(l)
             for q in range(self.P):
                 r = self.rows(q)
+                si = q % ns
                 dzh = None
                 if need and self.n_halo[q]:
                     dzh = self.dz_halo[l][int(self.halo_off[q]) * k:]
+                dh1 = self.dh1[l] if si == 0 else self._dh1_extra[si - 1][l]
+                dh0 = self.dh0[l] if si == 0 else self._dh0_extra[si - 1][l]
                 ctx.layer_bwd(l, q, self.dx[l + 1][r], self.x[l + 1][r], self.x[l][r], self.m[l][r], self.h1[l],
-                              self.h0[l], self.dh1[l], self.dh0[l], self.dx[l][r] if need else None, dzh, stream)
+                              self.h0[l], dh1, dh0, self.dx[l][r] if need else None, dzh, streams[si])
+            self._join(streams)         # all consumers' returned rows and all local gradients of the layer exist
             if need:
                 # errors handed back: every owner adds what its consumers returned, at the kept positions
                 for p in range(self.P):
                     if self.host_parts[p].n_boundary:
                         ctx.accumulate_returned(l, p, self.ret_ptr[p], self.ret_src[p], self.dz_halo[l],
-                                                self.dx[l][self.rows(p)], stream)
+                                                self.dx[l][self.rows(p)], streams[p % ns])
+                self._join(streams)
+        # the partitions' weight gradients are summed (Algorithm 1): fold the per-stream accumulators
+        if ns > 1:
+            with torch.cuda.stream(streams[0]):
+                for extra1, extra0 in zip(self._dh1_extra, self._dh0_extra):
+                    for l in range(self.L):
+                        vb.sum_gradients(self.dh1[l], extra1[l], streams[0])
+                        extra1[l].zero_()
+                        if self.dh0[l] is not None:
+                            vb.sum_gradients(self.dh0[l], extra0[l], streams[0])
+                            extra0[l].zero_()
 
     def zero_grads(self):
         for l in range(self.L):

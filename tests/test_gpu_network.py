@@ -31,7 +31,7 @@ def _f32(a):
     return np.asarray(a, dtype=np.float64).astype(np.float32).astype(np.float64)
 
 
-def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4, dtype="f32"):
+def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4, dtype="f32", n_streams=1):
     """dtype "bf16": inputs are bf16 values, the oracle rounds to bf16 where the device stores bf16
     (activations, aggregates, messages, gradients) and `tol` is the bound of that configuration."""
     host, orc = both_partitions(g, part, n_parts)
@@ -43,7 +43,7 @@ def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4, dt
         stored = round_bf16
         x0, dxl = round_bf16(x0).astype(np.float32), round_bf16(dxl).astype(np.float32)
     h1, h0 = _weights(widths, conv)
-    net = PartitionedNetwork(host, widths, conv, KEY, dtype=dtype)
+    net = PartitionedNetwork(host, widths, conv, KEY, dtype=dtype, n_streams=n_streams)
     net.set_inputs(x0)
     net.set_weights(h1, h0)
     net.set_upstream(dxl)
@@ -117,6 +117,17 @@ def test_sage_network_small():
     g = synth.small_random_graph(3000, 10.0, "sage", seed=31)
     part = synth.random_partition(g.n, 4, seed=32)
     _compare_network(g, part, 4, "sage", (100, 256, 256, 47), [(8, 1), (2, 1)], steps=[5, 6])
+
+
+@pytest.mark.parametrize("n_streams", [2, 3])
+def test_partitions_dealt_to_several_streams(n_streams):
+    # overlapping layer calls on different streams (per-stream workspaces, joins at layer boundaries and before
+    # the owner-side sums, per-stream weight-gradient accumulators folded at the end) give the oracle's results
+    g = synth.small_random_graph(3000, 10.0, "sage", seed=31)
+    part = synth.random_partition(g.n, 5, seed=32)
+    _compare_network(g, part, 5, "sage", (100, 256, 256, 47), [(8, 1), (1, 1)], steps=[5, 6], n_streams=n_streams)
+    w = synth.make_workload("medium")
+    _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, [(8, 1)], steps=[3], n_streams=n_streams)
 
 
 def test_tiny_config_full_step_bf16_storage():

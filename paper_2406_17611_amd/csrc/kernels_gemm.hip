@@ -148,7 +148,7 @@ __device__ __forceinline__ void load_fragment(const float* s, int row, int lk, f
 // A_GATE / B_GATE: operand is masked; A_VEC / B_VEC: operand may be fetched four elements at a time.
 template <typename TA, typename TB, typename TC, int WM, int WN, bool A_KC, bool B_KC, bool A_GATE, bool B_GATE, bool A_VEC,
           bool B_VEC>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(GemmDev g) {
+__global__ __launch_bounds__(kThreads, 4) void gemm_kernel(GemmDev g) {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     __shared__ __attribute__((aligned(16))) float sa[2][tile_floats<BM>()];
     __shared__ __attribute__((aligned(16))) float sb[2][tile_floats<BN>()];

@@ -6,6 +6,7 @@ import torch
 from gpu_common import KEY, dev
 from oracle import layer as olayer
 from oracle import mask as omask
+from oracle.rounding import round_bf16
 from paper_2406_17611_amd import binding as vb
 
 pytestmark = pytest.mark.gpu
@@ -54,6 +55,42 @@ def test_compress_decompress_bit_exact(width, ratio):
     for i in range(n_rows):
         want_acc[rows[i], cols[i]] += want_z[i]
     assert np.array_equal(acc.cpu().numpy(), want_acc)
+    ctx.close()
+
+
+@pytest.mark.parametrize("width,ratio", [(16, (4, 1)), (100, (4, 1)), (512, (4, 1)), (512, (32, 1)), (512, (1, 1)),
+                                          (37, (3, 2)), (2048, (3, 1))])
+def test_compress_decompress_bit_exact_bf16_storage(width, ratio):
+    """bf16 storage: the encoder and decoder copy 2-byte elements; the owner-side add is one fp32 add of two bf16
+    values rounded to bf16 once, which the oracle's rounding reproduces exactly."""
+    rng = np.random.default_rng(width * 11 + ratio[0])
+    n_src, n_rows, ldx = 4000, 2501, width + 2
+    x = round_bf16(rng.standard_normal((n_src, ldx))).astype(np.float32)
+    rows = rng.permutation(n_src)[:n_rows].astype(np.int32)
+    gids = rng.integers(0, 2_449_029, size=n_rows).astype(np.int32)
+    step, layer = 9, 1
+    ctx = vb.Context([8, width, 8], [1, 0], vb.CONV_GCN, 1, KEY, vb.BF16)
+    ctx.begin_step(step)
+    ctx.set_ratio(layer, *ratio)
+    k = ctx.keep(layer)
+    cols = omask.kept_columns(gids, width, k, KEY, step, layer)
+    bf = torch.bfloat16
+    xd, rd, gd = dev(x, bf), dev(rows), dev(gids)
+    z = torch.full((n_rows, k), float("nan"), dtype=bf, device="cuda")
+    ctx.compress(layer, gd, rd, n_rows, xd, ldx, z)
+    want_z = olayer.compress(x, rows, cols).astype(np.float32)
+    assert np.array_equal(z.float().cpu().numpy(), want_z)
+    out = torch.full((n_src, ldx), 7.0, dtype=bf, device="cuda")
+    ctx.decompress(layer, gd, rd, n_rows, z, out, ldx, 0)
+    want = np.full((n_src, ldx), 7.0, dtype=np.float32)
+    want[rows, :width] = olayer.decompress(want_z.astype(np.float64), cols, width).astype(np.float32)
+    assert np.array_equal(out.float().cpu().numpy(), want)
+    acc = dev(x.copy(), bf)
+    ctx.decompress(layer, gd, rd, n_rows, z, acc, ldx, 1)
+    want_acc = x.astype(np.float64)
+    for i in range(n_rows):
+        want_acc[rows[i], cols[i]] += want_z[i]
+    assert np.array_equal(acc.float().cpu().numpy(), round_bf16(want_acc).astype(np.float32))
     ctx.close()
 
 

@@ -133,6 +133,14 @@ def test_layer_parity_bf16_storage_with_split_rows(ratio):
     _run_layer_case(g, part, 2, "gcn", 64, 48, ratio, vb.ACT_IDENTITY, seed=77, dtype="bf16")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("fi,fo", [(2048, 64), (64, 2048)])
+def test_layer_parity_at_the_maximum_width(fi, fo, dtype):
+    g = synth.small_random_graph(700, 8.0, "sage", seed=fi // 64)
+    part = synth.random_partition(g.n, 2, seed=3)
+    _run_layer_case(g, part, 2, "sage", fi, fo, (8, 1), vb.ACT_RELU, seed=fi + 1, dtype=dtype)
+
+
 def test_layer_parity_single_partition_has_no_exchange():
     g = synth.small_random_graph(900, 8.0, "gcn", seed=2)
     part = np.zeros(g.n, dtype=np.int32)

@@ -139,7 +139,7 @@ const char* varco_last_error(const varco_ctx* ctx);
  * step. Also closes the previous step (ratios may change again). */
 int32_t varco_begin_step(varco_ctx* ctx, uint64_t step);
 
-/* Section IV / Algorithm 1 ("update compression rate"): ratio r = num/den >= 1 of layer `layer`'s input
+/* Section IV / Algorithm 1 (the step that updates the compression rate): ratio r = num/den >= 1 of layer `layer`'s input
  * (-1 = every layer). k = max(1, ceil(width*den/num)); r = 1 keeps everything (lossless). STATE error if
  * the layer's positions are already in use in the current step (by compress, decompress or a forward
  * call; its backward must see the same positions). */
@@ -160,8 +160,8 @@ int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t* gids, con
                          int64_t n_rows, const void* z, void* x, int64_t ldx, int32_t accumulate,
                          varco_stream stream);
 
-/* Forward of layer `layer` on partition q (Algorithm 1, "compute forward pass by using non-compressed
- * activations for local nodes and compressed activations for non-local nodes"):
+/* Forward of layer `layer` on partition q (Algorithm 1's forward pass: local nodes contribute their
+ * activations as they are, nodes of other partitions their compressed ones):
  *   m      = S_q [x_local ; decompress(z_in[halo_zrow])]      n_local x width[layer]
  *   x_out  = act( m h1 (+ x_local h0) )                       n_local x width[layer+1]
  *   z_out rows [z_row_offset, +n_boundary) = compress(x_out[boundary_rows]) at layer+1's k   (optional)
@@ -174,8 +174,8 @@ int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_
                         const void* h1, const void* h0, void* x_out, void* z_out, void* m_saved,
                         varco_stream stream);
 
-/* Backward of layer `layer` on partition q ("back-propagating errors across machines and through the
- * differentiable compression routine"):
+/* Backward of layer `layer` on partition q (Algorithm 1's backward pass: the gradient of the forward above,
+ * taken through the compression, with the errors of remote nodes handed back to their owners):
  *   dz = dx_out * [x_out > 0] (ReLU) or dx_out;  dh1 += m_saved^T dz;  dh0 += x_local^T dz
  *   if dx_local != NULL:  dm = dz h1^T;  [dx_local ; dx_halo] = S_q^T dm;  dx_local += dz h0^T;
  *                         dz_halo[s, j] = dx_halo[s, pi_v(j)], j < k_layer, v = halo_gid[s]
@@ -187,8 +187,8 @@ int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx
                         const void* x_local, const void* m_saved, const void* h1, const void* h0, void* dh1,
                         void* dh0, void* dx_local, void* dz_halo, varco_stream stream);
 
-/* Owner side of the backward exchange for partition p, all consumers at once (Section III: "the gradients
- * flow in the opposite direction"; Algorithm 1: errors are back-propagated across machines): for every
+/* Owner side of the backward exchange for partition p, all consumers at once (Section III: in the backward
+ * pass the exchange runs from consumers to owners; Algorithm 1: errors cross machines): for every
  * boundary row b of p, v = its node id,
  *   dx_local[boundary_rows[b], pi_v(j)] += sum_{e in [ret_ptr[b], ret_ptr[b+1])} returned[ret_src[e], j],  j < k_layer
  * where `returned` holds rows of k_layer values (the consumers' dz_halo buffers, addressed as one array)

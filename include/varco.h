@@ -140,7 +140,10 @@ const char* varco_last_error(const varco_ctx* ctx);
 int32_t varco_begin_step(varco_ctx* ctx, uint64_t step);
 
 /* Section IV / Algorithm 1 (the step that updates the compression rate): ratio r = num/den >= 1 of layer `layer`'s input
- * (-1 = every layer). k = max(1, ceil(width*den/num)); r = 1 keeps everything (lossless). STATE error if
+ * (-1 = every layer). k = max(1, ceil(width*den/num)); r = 1 keeps everything (lossless). den = 0 (num >= 1)
+ * is the unbounded ratio, k = 0: nothing of that layer's input is exchanged, forward or backward (the
+ * no-communication setting Section V compares against; on every layer: each partition works on its own
+ * subgraph). With k = 0 the compressed buffers of that layer are not touched and may be NULL. STATE error if
  * the layer's positions are already in use in the current step (by compress, decompress or a forward
  * call; its backward must see the same positions). */
 int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, uint32_t den);

@@ -75,7 +75,15 @@ def affine_params(gids: np.ndarray, width: int, s0: int, s1: int) -> tuple[np.nd
 
 
 def keep_count(width: int, num: int, den: int) -> int:
-    """k = max(1, ceil(width * den / num)) for the ratio num/den >= 1."""
+    """k = max(1, ceil(width * den / num)) for the ratio num/den >= 1.
+
+    den == 0 (num > 0) stands for an unbounded ratio: nothing is communicated, k = 0. This is the
+    "no communication" setting the experiments of Section V compare against, per layer: with k = 0 on every
+    layer each partition trains on its own subgraph; with k = 0 only on the layers after the first, the
+    input features of adjacent nodes are still exchanged but no intermediate activations.
+    """
+    if den == 0 and num > 0:
+        return 0
     if num < den or den < 1:
         raise ValueError("compression ratio must be >= 1")
     return max(1, -((-width * den) // num))

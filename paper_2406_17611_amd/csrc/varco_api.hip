@@ -135,6 +135,7 @@ MaskRule full_rule(int32_t width) {
 }
 
 int32_t keep_count(int32_t width, uint32_t num, uint32_t den) {
+    if (den == 0) return 0;   // unbounded ratio: nothing is communicated
     const uint64_t k = (uint64_t(width) * den + num - 1) / num;
     return int32_t(std::max<uint64_t>(1, k));
 }
@@ -475,7 +476,8 @@ extern "C" int32_t varco_begin_step(varco_ctx* ctx, uint64_t step) {
 extern "C" int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, uint32_t den) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_set_ratio: null context");
     if (layer < -1 || layer >= ctx->n_layers) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_ratio: layer out of range");
-    if (den == 0 || num < den) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_ratio: ratio must be a rational >= 1");
+    if (num == 0 || (den != 0 && num < den))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_ratio: ratio must be a rational >= 1 (den = 0: no communication)");
     const int32_t l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? ctx->n_layers : layer + 1;
     for (int32_t l = l0; l < l1; ++l)
         if (ctx->layers[l].ran_forward)
@@ -500,7 +502,7 @@ extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* 
                                   int64_t n_rows, const void* x, int64_t ldx, void* z, varco_stream stream) {
     if (int32_t rc = check_layer(ctx, layer, "varco_compress")) return rc;
     if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: negative row count");
-    if (n_rows == 0) return VARCO_OK;
+    if (n_rows == 0 || ctx->layers[layer].k == 0) return VARCO_OK;   // k = 0: nothing is sent
     if (!gids || !x || !z) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_compress: null pointer");
     if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: ldx is smaller than the layer width");
     if (int32_t rc = ensure_tables(ctx)) return rc;
@@ -518,8 +520,9 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
     if (int32_t rc = check_layer(ctx, layer, "varco_decompress")) return rc;
     if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: negative row count");
     if (accumulate != 0 && accumulate != 1) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: accumulate must be 0 or 1");
-    if (n_rows == 0) return VARCO_OK;
-    if (!gids || !x || !z) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: null pointer");
+    if (n_rows == 0 || (accumulate && ctx->layers[layer].k == 0)) return VARCO_OK;
+    if (!gids || !x || (!z && ctx->layers[layer].k > 0))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: null pointer");
     if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: ldx is smaller than the layer width");
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;
@@ -542,7 +545,8 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: null pointer");
     if (sage && !h0) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: h0 is required for the SAGE convolution");
     if (!sage && h0) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: h0 must be null for the single-tap convolution");
-    if (d.n_halo > 0 && !z_in) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_in is null but the partition has halo nodes");
+    if (d.n_halo > 0 && !z_in && ctx->layers[layer].k > 0)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_in is null but the partition has halo nodes");
     if (z_out && layer == ctx->n_layers - 1)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_out must be null on the last layer");
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -578,7 +582,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
-    if (z_out && d.n_boundary > 0) {
+    if (z_out && d.n_boundary > 0 && ctx->layers[layer + 1].k > 0) {
         ctx->layers[layer + 1].ran_forward = true;   // its positions are now in use
         const MaskRule next = make_rule(ctx, layer + 1);
         char* zdst = static_cast<char*>(z_out) + int64_t(d.z_row_offset) * next.k * int64_t(es);
@@ -603,7 +607,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     if (sage && (!h0 || !dh0)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: h0 and dh0 are required for the SAGE convolution");
     if (!sage && (h0 || dh0)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: h0 and dh0 must be null for the single-tap convolution");
     if (!dx_local && dz_halo) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo given without dx_local");
-    if (dx_local && d.n_halo > 0 && !dz_halo)
+    if (dx_local && d.n_halo > 0 && !dz_halo && ctx->layers[layer].k > 0)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo is null but the partition has halo nodes");
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
@@ -654,7 +658,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
     VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, dense_rule, dx_local,
                                      0, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
-    if (d.n_halo > 0) {
+    if (d.n_halo > 0 && rule.k > 0) {   // k = 0: nothing is handed back
         if (rule.k == rule.width) {
             VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, dense_rule,
                                              dz_halo, nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
@@ -690,7 +694,7 @@ extern "C" int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int3
     if (int32_t rc = check_layer(ctx, layer, "varco_accumulate_returned")) return rc;
     if (int32_t rc = check_part(ctx, p, "varco_accumulate_returned")) return rc;
     const PartState& ps = ctx->parts[p];
-    if (ps.d.n_boundary == 0) return VARCO_OK;
+    if (ps.d.n_boundary == 0 || ctx->layers[layer].k == 0) return VARCO_OK;
     if (!ret_ptr || !ret_src || !returned || !dx_local)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_accumulate_returned: null pointer");
     ctx->layers[layer].ran_forward = true;

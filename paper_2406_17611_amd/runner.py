@@ -136,12 +136,12 @@ class PartitionedNetwork:
         for l in range(self.L):
             k = self.ctx.keep(l)
             need = self.b_total * k
-            if self._zcap[l] < need:
+            if self.z[l] is None or self._zcap[l] < need:
                 self.z[l] = torch.empty(max(need, 1), dtype=self.act_dtype, device=self.device)
                 self._zcap[l] = need
             if self.need_backward and l > 0:
                 need = int(self.halo_off[-1]) * k
-                if self._dzcap[l] < need:
+                if self.dz_halo[l] is None or self._dzcap[l] < need:
                     self.dz_halo[l] = torch.empty(max(need, 1), dtype=self.act_dtype, device=self.device)
                     self._dzcap[l] = need
 

@@ -94,6 +94,24 @@ def test_compress_decompress_bit_exact_bf16_storage(width, ratio):
     ctx.close()
 
 
+def test_unbounded_ratio_sends_nothing_and_decodes_to_zero():
+    ctx = vb.Context([8, 64, 8], [1, 0], vb.CONV_GCN, 1, KEY)
+    ctx.begin_step(0)
+    ctx.set_ratio(1, 1, 0)
+    assert ctx.keep(1) == 0
+    rows = dev(np.array([3, 0, 7], dtype=np.int32))
+    gids = dev(np.array([11, 12, 13], dtype=np.int32))
+    x = torch.full((9, 64), 5.0, device="cuda")
+    ctx.compress(1, gids, rows, 3, x, 64, None)          # nothing to write: the buffer may be NULL
+    ctx.decompress(1, gids, rows, 3, None, x, 64, 0)     # decoder: the listed rows become zero
+    want = np.full((9, 64), 5.0, dtype=np.float32)
+    want[[3, 0, 7]] = 0.0
+    assert np.array_equal(x.cpu().numpy(), want)
+    ctx.decompress(1, gids, rows, 3, None, x, 64, 1)     # nothing returned, nothing added
+    assert np.array_equal(x.cpu().numpy(), want)
+    ctx.close()
+
+
 def test_mask_changes_with_step_and_layer_like_the_oracle():
     width, k_ratio = 128, (8, 1)
     rng = np.random.default_rng(0)

@@ -54,7 +54,8 @@ def _compare_network(g, part, n_parts, conv, widths, ratios, steps, tol=1e-4, dt
         net.ctx.reset_stats()
         net.forward(step, ratio)
         torch.cuda.synchronize()
-        keep = [omask.keep_count(widths[l], *ratio) for l in range(L)]
+        per_layer = ratio if isinstance(ratio[0], (tuple, list)) else [ratio] * L
+        keep = [omask.keep_count(widths[l], *per_layer[l]) for l in range(L)]
         assert [net.ctx.keep(l) for l in range(L)] == keep
         ref = olayer.network_step(orc, [x0[p.local_gid] for p in orc], weights, acts, keep, KEY, step,
                                   [dxl[p.local_gid] for p in orc], round_store=stored)
@@ -128,6 +129,19 @@ def test_partitions_dealt_to_several_streams(n_streams):
     _compare_network(g, part, 5, "sage", (100, 256, 256, 47), [(8, 1), (1, 1)], steps=[5, 6], n_streams=n_streams)
     w = synth.make_workload("medium")
     _compare_network(w.graph, w.part, w.n_parts, w.conv, w.widths, [(8, 1)], steps=[3], n_streams=n_streams)
+
+
+@pytest.mark.parametrize("conv,dtype", [("gcn", "f32"), ("sage", "f32"), ("gcn", "bf16")])
+def test_no_communication_and_no_intermediate_communication(conv, dtype):
+    # unbounded ratio (k = 0) on every layer, then only on the layers after the first (input features of adjacent
+    # nodes still exchanged, at ratio 2): remote nodes contribute nothing there, forward or backward
+    g = synth.small_random_graph(2500, 9.0, conv, seed=61)
+    part = synth.random_partition(g.n, 3, seed=62)
+    tol = BF16_TOL if dtype == "bf16" else 1e-4
+    net = _compare_network(g, part, 3, conv, (64, 128, 128, 10), [(1, 0), [(2, 1), (1, 0), (1, 0)]], steps=[1, 2],
+                           tol=tol, dtype=dtype)
+    st = net.ctx.stats()
+    assert st["fwd_elems"][1:] == [0, 0] and st["bwd_elems"] == [0, 0, 0] and st["fwd_elems"][0] > 0
 
 
 def test_tiny_config_full_step_bf16_storage():

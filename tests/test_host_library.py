@@ -124,10 +124,12 @@ def test_ratio_to_keep_count_matches_oracle_and_rejects_expansion():
             assert ctx.keep(l) == omask.keep_count(widths[l], num, den)
     ctx.set_ratio(1, 4, 1)
     assert ctx.keep(1) == 64 and ctx.keep(0) == omask.keep_count(100, 114, 99)
-    for num, den in ((1, 2), (0, 1), (5, 0)):
+    for num, den in ((1, 2), (0, 1), (0, 0)):
         with pytest.raises(vb.VarcoError) as e:
             ctx.set_ratio(-1, num, den)
         assert e.value.code == vb.ERR_INVALID_ARG
+    ctx.set_ratio(2, 1, 0)                                           # unbounded ratio: no communication
+    assert ctx.keep(2) == 0 == omask.keep_count(128, 1, 0) and ctx.keep(1) == 64
     with pytest.raises(vb.VarcoError) as e:
         ctx.set_ratio(3, 2, 1)
     assert e.value.code == vb.ERR_INVALID_ARG

@@ -128,6 +128,43 @@ def test_any_ratio_equals_global_mask_formula(conv, n_parts, ratio):
     assert not _close(_gather(parts, res["x"][-1], g.n), _gather(parts, full["x"][-1], g.n), 1e-3)
 
 
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("keep_first", [False, True])
+def test_no_communication_equals_the_layer_without_cross_edges(conv, keep_first):
+    """k = 0: remote nodes contribute nothing, forward or backward (the operator loses its cross entries but
+    keeps its values: no renormalisation). With the first layer still exchanging, only that layer sees them."""
+    widths = (12, 20, 20, 5)
+    g, part, parts, x, weights, r = _setup(conv, 130, 3, widths, seed=81)
+    assert omask.keep_count(20, 1, 0) == 0
+    keep = [widths[0] if keep_first else 0, 0, 0]
+    res, _ = _run_oracle(g, parts, x, weights, r, keep, step=2)
+    assert res["fwd_elems"][1:] == [0, 0] and res["bwd_elems"] == [0, 0, 0]
+    assert (res["fwd_elems"][0] > 0) == keep_first
+    # brute force on dense matrices, nothing shared with the oracle's structures
+    s = dref.dense_operator(g)
+    s_in, _ = dref.split_operator(s, part)
+    xs, ms = [x], []
+    for l, (h1, h0) in enumerate(weights):
+        op = s if (l == 0 and keep_first) else s_in
+        m = op @ xs[l]
+        zpre = m @ h1 + (xs[l] @ h0 if h0 is not None else 0.0)
+        xs.append(np.maximum(zpre, 0.0) if l < 2 else zpre)
+        ms.append(m)
+    dx = r
+    for l in (2, 1, 0):
+        h1, h0 = weights[l]
+        dz = dx * (xs[l + 1] > 0) if l < 2 else dx
+        assert _close(res["dh"][l][0], ms[l].T @ dz)
+        if h0 is not None:
+            assert _close(res["dh"][l][1], xs[l].T @ dz)
+        if l == 0:
+            break
+        dx = s_in.T @ (dz @ h1.T) + (dz @ h0.T if h0 is not None else 0.0)
+        assert _close(_gather(parts, res["dx"][l], g.n), dx)
+    for l in range(3):
+        assert _close(_gather(parts, res["x"][l + 1], g.n), xs[l + 1])
+
+
 def test_exchanged_element_counts():
     widths = (16, 24, 24, 7)
     g, part, parts, x, weights, r = _setup("gcn", 140, 4, widths, seed=50)

@@ -103,24 +103,17 @@ def layer_backward(p: Partition, dx_out: np.ndarray, x_out: np.ndarray, x_local:
 # the loss and the parameter update)
 # ---------------------------------------------------------------------------------------------------
 
-def network_step(parts: list[Partition], x0: list[np.ndarray], weights: list[tuple], acts: list[int],
-                 keep: list[int], key: int, step: int, dx_last: list[np.ndarray],
-                 round_store=None):
-    """Forward then backward over all partitions.
+# (network_step = network_forward + network_backward)
 
-    x0[q]: partition q's input rows. weights[l] = (H1, H0 or None). keep[l] = k of layer l's input.
-    dx_last[q]: upstream gradient of the last layer's output. `round_store`, when given, is applied to
-    every tensor at the point where the device path stores it (e.g. rounding to fp32 or bf16).
-
-    Returns a dict with per-layer activations, saved aggregates, weight gradients, input gradients and the
-    number of compressed elements handed off forward and backward per layer.
-    """
+def network_forward(parts: list[Partition], x0: list[np.ndarray], weights: list[tuple], acts: list[int],
+                    keep: list[int], key: int, step: int, round_store=None):
+    """Forward over all layers and partitions. Returns the state network_backward needs: per-layer
+    activations `x`, saved aggregates `m`, compressed buffers `z` and the forward hand-off counts."""
     rnd = (lambda a: a) if round_store is None else round_store
     n_layers = len(weights)
-    n_parts = len(parts)
     xs = [[np.asarray(x, dtype=np.float64) for x in x0]]
     ms, zs = [], []
-    fwd_elems, bwd_elems = [], []
+    fwd_elems = []
     for l in range(n_layers):
         width = xs[l][0].shape[1]
         k = keep[l]
@@ -139,7 +132,18 @@ def network_step(parts: list[Partition], x0: list[np.ndarray], weights: list[tup
         xs.append(out)
         ms.append(agg)
         fwd_elems.append(sum(p.n_halo for p in parts) * k)
+    return dict(x=xs, m=ms, z=zs, fwd_elems=fwd_elems)
 
+
+def network_backward(parts: list[Partition], fwd: dict, weights: list[tuple], acts: list[int], keep: list[int],
+                     key: int, step: int, dx_last: list[np.ndarray], round_store=None):
+    """Backward over all layers and partitions from the upstream gradient of the last layer's output.
+    Returns weight gradients (summed over partitions), input gradients per layer and hand-off counts."""
+    rnd = (lambda a: a) if round_store is None else round_store
+    xs, ms = fwd["x"], fwd["m"]
+    n_layers = len(weights)
+    n_parts = len(parts)
+    bwd_elems = []
     dh = [[None, None] for _ in range(n_layers)]
     dx = list(dx_last)
     dxs = {n_layers: dx}
@@ -174,5 +178,22 @@ def network_step(parts: list[Partition], x0: list[np.ndarray], weights: list[tup
         dx = new_dx
         dxs[l] = dx
         bwd_elems.append(sum(p.n_halo for p in parts) * k)
-    bwd_elems = bwd_elems[::-1]
-    return dict(x=xs, m=ms, z=zs, dh=dh, dx=dxs, fwd_elems=fwd_elems, bwd_elems=bwd_elems)
+    return dict(dh=dh, dx=dxs, bwd_elems=bwd_elems[::-1])
+
+
+def network_step(parts: list[Partition], x0: list[np.ndarray], weights: list[tuple], acts: list[int],
+                 keep: list[int], key: int, step: int, dx_last: list[np.ndarray],
+                 round_store=None):
+    """Forward then backward over all partitions.
+
+    x0[q]: partition q's input rows. weights[l] = (H1, H0 or None). keep[l] = k of layer l's input.
+    dx_last[q]: upstream gradient of the last layer's output. `round_store`, when given, is applied to
+    every tensor at the point where the device path stores it (e.g. rounding to fp32 or bf16).
+
+    Returns a dict with per-layer activations, saved aggregates, weight gradients, input gradients and the
+    number of compressed elements handed off forward and backward per layer.
+    """
+    fwd = network_forward(parts, x0, weights, acts, keep, key, step, round_store)
+    bwd = network_backward(parts, fwd, weights, acts, keep, key, step, dx_last, round_store)
+    return dict(x=fwd["x"], m=fwd["m"], z=fwd["z"], dh=bwd["dh"], dx=bwd["dx"], fwd_elems=fwd["fwd_elems"],
+                bwd_elems=bwd["bwd_elems"])

@@ -130,3 +130,18 @@ def linear_ratio(c_max: int, c_min: int, slope: int, n_steps: int, step: int) ->
 def fixed_increment_ratio(r0: int, increment: int, c_min: int, step: int) -> tuple[int, int]:
     """r_{k+1} = r_k + R with R < 0 so that the ratio decreases; clamped at c_min."""
     return max(r0 + increment * step, c_min), 1
+
+
+def exponential_ratio(base: int, c_max: int, c_min: int, n_steps: int, step: int) -> tuple[int, int]:
+    """Exponential schedule of Appendix "Scheduler": the communicated fraction is base^-(K - k + 1), i.e. the
+    ratio is base^(K - k + 1), clamped to [c_min, c_max]. Read with an integer base >= 2 so that the ratio
+    is an exact integer (a fractional base would need a rounding rule the paper does not give)."""
+    if base < 2:
+        raise ValueError("base must be an integer >= 2")
+    exponent = max(n_steps - step + 1, 0)
+    value = 1
+    for _ in range(exponent):
+        value *= base
+        if value >= c_max:
+            return c_max, 1
+    return max(value, c_min), 1

@@ -279,6 +279,39 @@ def linear_schedule_config3(t: int) -> tuple[int, int]:
     return 1584 - 15 * t, 99
 
 
+@dataclasses.dataclass
+class LabelledGraph:
+    """A node-classification task on a synthetic graph: class labels, features that carry a weak class signal
+    under unit noise (so that averaging over neighbours, i.e. communication, helps), and a train / test split."""
+    graph: Graph
+    part: np.ndarray
+    n_parts: int
+    conv: str
+    widths: tuple
+    features: np.ndarray       # [n, F_0] fp32
+    labels: np.ndarray         # [n] int32 class ids
+    train: np.ndarray          # [n] bool: node is used for training (the rest is held out)
+
+
+def labelled_sbm(n_blocks: int = 4, block_size: int = 500, p_in: float = 0.02, p_out: float = 0.002, width: int = 16,
+                 hidden: int = 32, signal: float = 0.35, n_parts: int = 4, conv: str = "sage",
+                 seed: int = SEED_GRAPH + 100) -> LabelledGraph:
+    """Stochastic block model whose blocks are the classes. Node features = signal * (a fixed random sign vector of
+    the node's class) + N(0, 1) noise; nodes are dealt to `n_parts` equal random partitions (so most neighbours of
+    a node live on other partitions); every second node (by a random permutation) is a training node."""
+    sizes = (block_size,) * n_blocks
+    n, u, v = sbm_edges(sizes, p_in, p_out, seed)
+    g = sage_mean_operator(n, u, v) if conv == "sage" else gcn_operator(n, u, v)
+    labels = np.repeat(np.arange(n_blocks, dtype=np.int32), block_size)
+    rng = _rng(seed, 1)
+    means = rng.integers(0, 2, size=(n_blocks, width)).astype(np.float32) * 2.0 - 1.0
+    feats = (signal * means[labels] + _normal_rows(n, width, seed, 2)).astype(np.float32)
+    train = np.zeros(n, dtype=bool)
+    train[rng.permutation(n)[: n // 2]] = True
+    return LabelledGraph(g, random_partition(n, n_parts, seed + 1), n_parts, conv, (width, hidden, n_blocks), feats,
+                         labels, train)
+
+
 def make_workload(name: str) -> Workload:
     if name == "tiny":
         sizes = (1000, 1000)

@@ -238,6 +238,41 @@ typedef struct {
  * gradient buffer per stream folds those buffers with this call. */
 int32_t varco_sum_gradients(void* dst, const void* src, int64_t n, varco_stream stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * The rest of Algorithm 1's iteration around the layer calls: loss, gradient step, rate schedule.
+ */
+
+/* Section II, the empirical risk with the cross-entropy as the loss, on the rows of one partition:
+ *   loss_i = logsumexp(logits[i, :]) - logits[i, labels[i]]
+ *   dlogits[i, :] = scale * (softmax(logits[i, :]) - onehot(labels[i]))
+ * for rows with labels[i] in [0, n_classes); a row with labels[i] < 0 is not a training node: loss 0,
+ * gradient 0. scale is 1 / (number of training nodes of the whole graph), so that the weight gradients
+ * summed over partitions are those of the risk. Written: row_loss[n_rows] (fp32, unscaled), row_correct[n_rows]
+ * (int32, 1 when the largest logit, lowest index on ties, is the label); when totals != NULL also
+ * totals[0] += scale * sum(row_loss), totals[1] += sum(row_correct), summed in a fixed order (fp32[2]).
+ * logits (leading dimension ld) and dlogits (ldd) have the context's storage type; dlogits may be NULL
+ * (evaluation only). All pointers device. */
+int32_t varco_softmax_xent(varco_ctx* ctx, const void* logits, int64_t ld, const int32_t* labels, int64_t n_rows,
+                           int32_t n_classes, float scale, void* dlogits, int64_t ldd, float* row_loss,
+                           int32_t* row_correct, float* totals, varco_stream stream);
+
+/* The gradient step (SGD) of Section II: w[i] -= lr * dw[i] for n fp32 values (device pointers). Replicas
+ * that start equal and take this step with the summed gradient stay equal, which is what Algorithm 1's
+ * averaging of the workers' parameters amounts to. */
+int32_t varco_sgd_step(void* w, const void* dw, int64_t n, float lr, varco_stream stream);
+
+/* Section IV / Appendix "Scheduler": the compression ratio of iteration `step` of `n_steps`, as an exact
+ * rational num/den >= 1 for varco_set_ratio (host only, no device work). The ratio starts at c_max and never
+ * increases; it is clamped at c_min >= 1.
+ *   VARCO_SCHED_LINEAR           max(c_max - param * (c_max - c_min) * step / n_steps, c_min), param = slope
+ *   VARCO_SCHED_FIXED_INCREMENT  max(c_max - param * step, c_min), param = decrement per iteration
+ *   VARCO_SCHED_EXPONENTIAL      clamp(param ^ (n_steps - step + 1), c_min, c_max), param = integer base >= 2
+ * INVALID_ARG for c_min < 1, c_max < c_min, n_steps < 1, step < 0, a base < 2 or an unknown kind; SHAPE when
+ * the rational does not fit 32 bits. */
+enum { VARCO_SCHED_LINEAR = 0, VARCO_SCHED_FIXED_INCREMENT = 1, VARCO_SCHED_EXPONENTIAL = 2 };
+int32_t varco_schedule_ratio(int32_t kind, int64_t step, int64_t n_steps, uint32_t c_max, uint32_t c_min,
+                             uint32_t param, uint32_t* num, uint32_t* den);
+
 /* A plain device-to-device copy of `bytes` bytes (multiple of 16, 16-byte aligned pointers) by a kernel
  * of this library: the known-size reference against which hardware byte counters are scaled. */
 int32_t varco_calibration_copy(void* dst, const void* src, int64_t bytes, varco_stream stream);

@@ -27,7 +27,7 @@ EXPORTS = [
     "varco_begin_step", "varco_set_ratio", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
-    "varco_calibration_copy", "varco_sum_gradients",
+    "varco_calibration_copy", "varco_sum_gradients", "varco_softmax_xent", "varco_sgd_step", "varco_schedule_ratio",
 ]
 KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
                   "agg_bwd_halo", "reduce", "agg_bwd_halo_sum"]
@@ -97,6 +97,10 @@ def lib() -> C.CDLL:
         L.varco_reset_stats.argtypes = [vp]
         L.varco_calibration_copy.argtypes = [vp, vp, i64, vp]
         L.varco_sum_gradients.argtypes = [vp, vp, i64, vp]
+        L.varco_softmax_xent.argtypes = [vp, vp, i64, vp, i64, i32, C.c_float, vp, i64, vp, vp, vp, vp]
+        L.varco_sgd_step.argtypes = [vp, vp, i64, C.c_float, vp]
+        L.varco_schedule_ratio.argtypes = [i32, i64, i64, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32),
+                                           C.POINTER(C.c_uint32)]
         L.varco_profile_enable.argtypes = [vp, i32]
         L.varco_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         for name in EXPORTS:
@@ -131,6 +135,22 @@ def _stream(stream):
 def calibration_copy(dst, src, stream=None):
     """Copies the bytes of tensor `src` into `dst` with the library's plain copy kernel."""
     _check(lib().varco_calibration_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)))
+
+
+SCHED_LINEAR, SCHED_FIXED_INCREMENT, SCHED_EXPONENTIAL = 0, 1, 2
+
+
+def schedule_ratio(kind: int, step: int, n_steps: int, c_max: int, c_min: int, param: int):
+    """(num, den) of the compression ratio at iteration `step` (host only)."""
+    num, den = C.c_uint32(), C.c_uint32()
+    _check(lib().varco_schedule_ratio(kind, step, n_steps, c_max, c_min, param, C.byref(num), C.byref(den)))
+    return num.value, den.value
+
+
+def sgd_step(w, dw, lr: float, stream=None):
+    """w -= lr * dw (fp32 device tensors of equal size)."""
+    assert w.numel() == dw.numel() and w.dtype == dw.dtype
+    _check(lib().varco_sgd_step(_ptr(w), _ptr(dw), w.numel(), lr, _stream(stream)))
 
 
 def sum_gradients(dst, src, stream=None):
@@ -272,6 +292,13 @@ class Context:
     def accumulate_returned(self, layer, p, ret_ptr, ret_src, returned, dx_local, stream=None):
         _check(lib().varco_accumulate_returned(self._h, layer, p, _ptr(ret_ptr), _ptr(ret_src), _ptr(returned),
                                                _ptr(dx_local), _stream(stream)), self._h)
+
+    def softmax_xent(self, logits, labels, n_classes, scale, dlogits, row_loss, row_correct, totals, stream=None):
+        n_rows = logits.shape[0]
+        _check(lib().varco_softmax_xent(self._h, _ptr(logits), logits.stride(0) if n_rows else n_classes, _ptr(labels),
+                                        n_rows, n_classes, scale, _ptr(dlogits),
+                                        dlogits.stride(0) if dlogits is not None and n_rows else n_classes,
+                                        _ptr(row_loss), _ptr(row_correct), _ptr(totals), _stream(stream)), self._h)
 
     def stats(self) -> dict:
         s = Stats()

@@ -722,6 +722,66 @@ extern "C" int32_t varco_reset_stats(varco_ctx* ctx) {
     return VARCO_OK;
 }
 
+extern "C" int32_t varco_softmax_xent(varco_ctx* ctx, const void* logits, int64_t ld, const int32_t* labels, int64_t n_rows,
+                                      int32_t n_classes, float scale, void* dlogits, int64_t ldd, float* row_loss,
+                                      int32_t* row_correct, float* totals, varco_stream stream) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_softmax_xent: null context");
+    if (n_rows < 0 || n_classes < 1 || n_classes > VARCO_MAX_WIDTH)
+        return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_softmax_xent: row count or class count out of range");
+    if (ld < n_classes || (dlogits && ldd < n_classes))
+        return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_softmax_xent: leading dimension smaller than the class count");
+    if (n_rows == 0) return VARCO_OK;
+    if (!logits || !labels || !row_loss || !row_correct)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_softmax_xent: null pointer");
+    VARCO_HIP(ctx, varco_launch_softmax_xent(ctx->dtype, logits, ld, labels, n_rows, n_classes, scale, dlogits, ldd, row_loss,
+                                             row_correct, totals, static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_sgd_step(void* w, const void* dw, int64_t n, float lr, varco_stream stream) {
+    if (n < 0) return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_sgd_step: negative count");
+    if (n == 0) return VARCO_OK;
+    if (!w || !dw) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_sgd_step: null pointer");
+    VARCO_HIP(static_cast<const varco_ctx*>(nullptr),
+              varco_launch_sgd(static_cast<float*>(w), static_cast<const float*>(dw), n, lr, static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_schedule_ratio(int32_t kind, int64_t step, int64_t n_steps, uint32_t c_max, uint32_t c_min,
+                                        uint32_t param, uint32_t* num, uint32_t* den) {
+    if (!num || !den) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_schedule_ratio: null output");
+    if (c_min < 1 || c_max < c_min || n_steps < 1 || step < 0)
+        return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_schedule_ratio: need 1 <= c_min <= c_max, n_steps >= 1, step >= 0");
+    uint64_t n = c_min, d = 1;
+    if (kind == VARCO_SCHED_LINEAR) {
+        // c_max - slope (c_max - c_min) step / K over the common denominator K, in 128-bit integers
+        const __int128 top = __int128(c_max) * n_steps - __int128(param) * (c_max - c_min) * step;
+        if (top > __int128(c_min) * n_steps) {
+            if (top > __int128(0xFFFFFFFFu) || n_steps > int64_t(0xFFFFFFFFu))
+                return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_schedule_ratio: ratio does not fit 32-bit integers");
+            const uint64_t g = std::gcd(uint64_t(top), uint64_t(n_steps));
+            n = uint64_t(top) / g, d = uint64_t(n_steps) / g;
+        }
+    } else if (kind == VARCO_SCHED_FIXED_INCREMENT) {
+        const __int128 v = __int128(c_max) - __int128(param) * step;
+        n = v > __int128(c_min) ? uint64_t(v) : c_min;
+    } else if (kind == VARCO_SCHED_EXPONENTIAL) {
+        if (param < 2) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_schedule_ratio: the base must be an integer >= 2");
+        const int64_t exponent = std::max<int64_t>(n_steps - step + 1, 0);
+        uint64_t value = 1;
+        bool capped = false;
+        for (int64_t i = 0; i < exponent && !capped; ++i) {
+            value *= param;              // value < c_max <= 2^32 before the product: no overflow in 64 bits
+            capped = value >= c_max;
+        }
+        n = capped ? c_max : std::max<uint64_t>(value, c_min);
+    } else {
+        return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_schedule_ratio: unknown schedule");
+    }
+    *num = uint32_t(n), *den = uint32_t(d);
+    return VARCO_OK;
+}
+
 extern "C" int32_t varco_sum_gradients(void* dst, const void* src, int64_t n, varco_stream stream) {
     if (n < 0) return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_sum_gradients: negative count");
     if (n == 0) return VARCO_OK;

@@ -163,3 +163,10 @@ hipError_t varco_launch_gemm_bf16(const GemmArgs& g, hipStream_t stream, const L
 // out[r][c] (bf16, row pitch `pitch` >= cols, zero beyond cols) = transpose ? h[c][r] : h[r][c] for r < rows.
 hipError_t varco_launch_prep_weight(const float* h, int64_t ld, int32_t rows, int32_t cols, int32_t pitch, bool transpose,
                                     void* out, hipStream_t stream);
+
+// Loss and update of a training iteration (kernels_train.hip). row_loss / row_correct: n_rows each; totals
+// (2 floats) may be null.
+hipError_t varco_launch_softmax_xent(int dtype, const void* logits, int64_t ld, const int32_t* labels, int64_t n_rows,
+                                     int32_t n_classes, float scale, void* dlogits, int64_t ldd, float* row_loss,
+                                     int32_t* row_correct, float* totals, hipStream_t stream);
+hipError_t varco_launch_sgd(float* w, const float* dw, int64_t n, float lr, hipStream_t stream);

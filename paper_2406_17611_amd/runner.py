@@ -213,6 +213,48 @@ class PartitionedNetwork:
                             vb.sum_gradients(self.dh0[l], extra0[l], streams[0])
                             extra0[l].zero_()
 
+    # ------------------------------------------------------------------ training (Algorithm 1's iteration)
+    def set_labels(self, labels_global: np.ndarray, train_mask: np.ndarray):
+        """Class labels of all nodes and which of them are training nodes (the rest is held out)."""
+        order = np.concatenate([hp.local_gid for hp in self.host_parts]).astype(np.int64)
+        lab = np.asarray(labels_global, dtype=np.int32)[order]
+        tr = np.asarray(train_mask, dtype=bool)[order]
+        self.labels_train = torch.from_numpy(np.where(tr, lab, -1).astype(np.int32)).to(self.device)
+        self.labels_test = torch.from_numpy(np.where(tr, -1, lab).astype(np.int32)).to(self.device)
+        self.n_train, self.n_test = int(tr.sum()), int((~tr).sum())
+        self._row_loss = torch.empty(self.n_total, dtype=torch.float32, device=self.device)
+        self._row_correct = torch.empty(self.n_total, dtype=torch.int32, device=self.device)
+        self._totals = torch.zeros(2, dtype=torch.float32, device=self.device)
+
+    def loss(self, train: bool = True, with_gradient: bool = True, stream=None):
+        """Cross-entropy of the last layer's output on the training (or held-out) nodes, partition by partition;
+        with_gradient writes the upstream gradient of the backward pass. Returns the device tensor
+        [risk, number of correct rows] (read it after synchronising)."""
+        labels = self.labels_train if train else self.labels_test
+        scale = 1.0 / max(1, self.n_train if train else self.n_test)
+        c = self.widths[-1]
+        self._totals.zero_()
+        for q in range(self.P):
+            r = self.rows(q)
+            self.ctx.softmax_xent(self.x[self.L][r], labels[r], c, scale, self.dx[self.L][r] if with_gradient else None,
+                                  self._row_loss[r], self._row_correct[r], self._totals, stream)
+        return self._totals
+
+    def sgd(self, lr: float, stream=None):
+        for l in range(self.L):
+            vb.sgd_step(self.h1[l], self.dh1[l], lr, stream)
+            if self.h0[l] is not None:
+                vb.sgd_step(self.h0[l], self.dh0[l], lr, stream)
+
+    def train_step(self, step: int, ratio, lr: float, stream=None):
+        """Forward with the compressed exchange, loss, backward, summed weight gradients, gradient step."""
+        self.zero_grads()
+        self.forward(step, ratio, stream)
+        totals = self.loss(True, True, stream)
+        self.backward(stream)
+        self.sgd(lr, stream)
+        return totals
+
     def zero_grads(self):
         for l in range(self.L):
             self.dh1[l].zero_()

@@ -1,0 +1,168 @@
+"""GPU parity of the rest of Algorithm 1's iteration (loss, weight-gradient sum, gradient step, schedule) and of
+whole training iterations against the oracle, on a labelled block-model graph."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_common import KEY, TOL, assert_close, both_partitions, dev
+from oracle import layer as olayer
+from oracle import mask as omask
+from oracle import train as otrain
+from oracle.rounding import round_bf16, round_f32
+from paper_2406_17611_amd import binding as vb
+from paper_2406_17611_amd import synth
+from paper_2406_17611_amd.runner import PartitionedNetwork
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n_classes", [3, 47, 200])
+def test_cross_entropy_kernel(n_classes, dtype):
+    rng = np.random.default_rng(n_classes)
+    n = 3001
+    bf16 = dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    z = rng.standard_normal((n, n_classes + 3)) * 4
+    z = (round_bf16(z) if bf16 else round_f32(z)).astype(np.float32)
+    y = rng.integers(-1, n_classes, size=n).astype(np.int32)
+    scale = 1.0 / int((y >= 0).sum())
+    loss_ref, d_ref, correct_ref = otrain.softmax_xent(z[:, :n_classes], y, scale)
+    ctx = vb.Context([8, n_classes], [0], vb.CONV_GCN, 1, KEY, vb.BF16 if bf16 else vb.F32)
+    zd = dev(z, tdt)
+    d = torch.full((n, n_classes), float("nan"), dtype=tdt, device="cuda")
+    row_loss = torch.empty(n, dtype=torch.float32, device="cuda")
+    row_correct = torch.empty(n, dtype=torch.int32, device="cuda")
+    totals = torch.tensor([1.5, 2.0], dtype=torch.float32, device="cuda")       # accumulated into
+    ctx.softmax_xent(zd[:, :n_classes], dev(y), n_classes, scale, d, row_loss, row_correct, totals)
+    got = totals.cpu().numpy()
+    assert abs(got[0] - 1.5 - loss_ref) <= 1e-5 * abs(loss_ref) + 1e-6
+    assert int(round(got[1] - 2.0)) == correct_ref == int(row_correct.sum().item())
+    assert_close(d.float().cpu().numpy(), d_ref, "dlogits", 2.0 ** -8 if bf16 else TOL)   # one bf16 rounding: 2^-9
+    assert np.all(d.float().cpu().numpy()[y < 0] == 0.0)
+    # evaluation only: no gradient buffer
+    totals.zero_()
+    ctx.softmax_xent(zd[:, :n_classes], dev(y), n_classes, scale, None, row_loss, row_correct, None)
+    assert abs(float(row_loss.double().sum().item()) * scale - loss_ref) <= 1e-5 * abs(loss_ref)
+    ctx.close()
+
+
+def test_gradient_step_and_gradient_sum_kernels():
+    rng = np.random.default_rng(2)
+    w = rng.standard_normal(100003).astype(np.float32)
+    g = rng.standard_normal(100003).astype(np.float32)
+    wd, gd = dev(w), dev(g)
+    vb.sgd_step(wd, gd, 0.125)
+    assert np.array_equal(wd.cpu().numpy(), w - np.float32(0.125) * g)        # one fp32 multiply-subtract: exact match
+    vb.sum_gradients(wd, gd)
+    assert np.array_equal(wd.cpu().numpy(), (w - np.float32(0.125) * g) + g)
+
+
+def _task_network(conv, dtype, n_streams=1):
+    t = synth.labelled_sbm(n_blocks=4, block_size=400, p_in=0.03, p_out=0.003, width=16, hidden=32, n_parts=4,
+                           conv=conv)
+    g = t.graph
+    host, orc = both_partitions(g, t.part, t.n_parts)
+    net = PartitionedNetwork(host, t.widths, conv, KEY, dtype=dtype, n_streams=n_streams)
+    feats = round_bf16(t.features).astype(np.float32) if dtype == "bf16" else t.features
+    net.set_inputs(feats)
+    net.set_labels(t.labels, t.train)
+    L = len(t.widths) - 1
+    h1 = [synth.glorot(t.widths[l], t.widths[l + 1], synth.SEED_WEIGHT, 2 * l) for l in range(L)]
+    h0 = [synth.glorot(t.widths[l], t.widths[l + 1], synth.SEED_WEIGHT, 2 * l + 1) for l in range(L)] \
+        if conv == "sage" else None
+    return t, feats, host, orc, net, h1, h0
+
+
+@pytest.mark.parametrize("conv,dtype", [("sage", "f32"), ("gcn", "f32"), ("sage", "bf16")])
+def test_training_iterations_match_the_oracle(conv, dtype):
+    """Three iterations on a falling schedule. Every iteration starts from the oracle's weights; the forward pass
+    runs free on both sides; then, as in the network tests, the device takes the ReLU gates on the oracle's stored
+    activations, and loss, upstream gradient, weight gradients and updated weights are compared."""
+    t, feats, host, orc, net, h1, h0 = _task_network(conv, dtype)
+    L = net.L
+    bf16 = dtype == "bf16"
+    stored = round_bf16 if bf16 else round_f32
+    tol = 2.0 ** -6 if bf16 else TOL
+    acts = [olayer.RELU] * (L - 1) + [olayer.IDENTITY]
+    weights = [(h1[l].astype(np.float64), h0[l].astype(np.float64) if h0 is not None else None) for l in range(L)]
+    labels = np.where(t.train, t.labels, -1)
+    lab = [labels[p.local_gid] for p in orc]
+    x0 = [feats[p.local_gid] for p in orc]
+    scale, lr = 1.0 / int(t.train.sum()), 0.4
+    for step in range(3):
+        ratio = omask.linear_ratio(8, 1, 2, 4, step)
+        assert ratio == vb.schedule_ratio(vb.SCHED_LINEAR, step, 4, 8, 1, 2)
+        keep = [omask.keep_count(w, *ratio) for w in t.widths[:-1]]
+        w32 = [(np.float32(a), np.float32(b) if b is not None else None) for a, b in weights]   # what the device holds
+        ref_w, ref_loss, ref_correct, fwd, bwd, dlast = otrain.train_step(
+            orc, x0, [(a.astype(np.float64), b.astype(np.float64) if b is not None else None) for a, b in w32], acts,
+            keep, KEY, step, lab, scale, lr, round_store=stored)
+        net.set_weights([a for a, _ in w32], [b for _, b in w32] if conv == "sage" else None)
+        net.zero_grads()
+        net.forward(step, ratio)
+        torch.cuda.synchronize()
+        logits_ref = np.empty((t.graph.n, t.widths[-1]))
+        for p in orc:
+            logits_ref[p.local_gid] = fwd["x"][-1][p.q]
+        assert_close(net.to_global(net.x[L]), logits_ref, f"step {step} logits", tol)
+        for l in range(L + 1):
+            net.x[l].copy_(torch.from_numpy(np.vstack(fwd["x"][l]).astype(np.float32)))
+        for l in range(L):
+            net.m[l].copy_(torch.from_numpy(np.vstack(fwd["m"][l]).astype(np.float32)))
+        totals = net.loss(train=True, with_gradient=True)
+        torch.cuda.synchronize()
+        got = totals.cpu().numpy()
+        assert abs(got[0] - ref_loss) <= 1e-5 * abs(ref_loss) and int(round(got[1])) == ref_correct
+        assert_close(net.dx[L].float().cpu().numpy(), np.vstack(dlast), f"step {step} dlogits", 2.0 ** -8 if bf16 else TOL)
+        net.dx[L].copy_(torch.from_numpy(np.vstack(dlast).astype(np.float32)))
+        net.backward()
+        net.sgd(lr)
+        torch.cuda.synchronize()
+        def updated_bound(w_ref, g_ref):
+            # H_new = H - lr dH with H identical on both sides: the error of dH (within tol, norm-wise) scaled by lr,
+            # expressed relative to H_new, plus the fp32 rounding of the update itself
+            return tol * lr * np.abs(g_ref).max() / np.abs(w_ref).max() + 1e-6
+
+        for l in range(L):
+            assert_close(net.dh1[l].cpu().numpy(), bwd["dh"][l][0], f"step {step} dH1_{l}", tol)
+            assert_close(net.h1[l].cpu().numpy(), ref_w[l][0], f"step {step} H1_{l} after the update",
+                         updated_bound(ref_w[l][0], bwd["dh"][l][0]))
+            if conv == "sage":
+                assert_close(net.dh0[l].cpu().numpy(), bwd["dh"][l][1], f"step {step} dH0_{l}", tol)
+                assert_close(net.h0[l].cpu().numpy(), ref_w[l][1], f"step {step} H0_{l} after the update",
+                             updated_bound(ref_w[l][1], bwd["dh"][l][1]))
+        weights = ref_w
+
+
+@pytest.mark.parametrize("n_streams", [1, 2])
+def test_free_running_training_learns_and_tracks_the_oracle(n_streams):
+    """40 iterations, nothing injected: the risk falls, held-out accuracy ends high, and the device's run stays close
+    to the oracle's own free run (same seeds; small differences may grow through ReLU decisions, hence loose bounds)."""
+    t, feats, host, orc, net, h1, h0 = _task_network("sage", "f32", n_streams)
+    net.set_weights(h1, h0)
+    L = net.L
+    acts = [olayer.RELU] * (L - 1) + [olayer.IDENTITY]
+    weights = [(h1[l].astype(np.float64), h0[l].astype(np.float64)) for l in range(L)]
+    labels = np.where(t.train, t.labels, -1)
+    lab = [labels[p.local_gid] for p in orc]
+    x0 = [feats[p.local_gid] for p in orc]
+    scale, lr, n_steps = 1.0 / int(t.train.sum()), 0.5, 40
+    dev_loss, ref_loss = [], []
+    for step in range(n_steps):
+        ratio = vb.schedule_ratio(vb.SCHED_LINEAR, step, n_steps, 16, 1, 3)
+        keep = [omask.keep_count(w, *ratio) for w in t.widths[:-1]]
+        weights, loss, *_ = otrain.train_step(orc, x0, weights, acts, keep, KEY, step, lab, scale, lr)
+        ref_loss.append(loss)
+        totals = net.train_step(step, ratio, lr)
+        torch.cuda.synchronize()
+        dev_loss.append(float(totals.cpu().numpy()[0]))
+    assert dev_loss[-1] < 0.6 * dev_loss[0]
+    assert np.allclose(dev_loss, ref_loss, rtol=2e-3)
+    net.forward(n_steps, (1, 1))
+    totals = net.loss(train=False, with_gradient=False)
+    torch.cuda.synchronize()
+    acc = float(totals.cpu().numpy()[1]) / net.n_test
+    assert acc > 0.85, acc
+    for l in range(L):
+        assert_close(net.h1[l].cpu().numpy(), weights[l][0], f"H1_{l} after {n_steps} iterations", 5e-3)

@@ -157,3 +157,20 @@ def test_calls_on_unregistered_partition_are_state_errors():
     assert L.varco_compress(ctx._h, 0, None, None, 0, None, 8, None, None) == vb.OK     # empty input is a no-op
     assert L.varco_begin_step(None, 0) == vb.ERR_INVALID_ARG
     ctx.close()
+
+
+def test_schedules_match_the_oracle_exactly():
+    for step in range(0, 301, 7):
+        assert vb.schedule_ratio(vb.SCHED_LINEAR, step, 300, 128, 1, 5) == omask.linear_ratio(128, 1, 5, 300, step)
+        assert vb.schedule_ratio(vb.SCHED_LINEAR, step, 300, 16, 2, 1) == omask.linear_ratio(16, 2, 1, 300, step)
+        assert vb.schedule_ratio(vb.SCHED_FIXED_INCREMENT, step, 300, 64, 1, 1) == omask.fixed_increment_ratio(64, -1, 1, step)
+        assert vb.schedule_ratio(vb.SCHED_EXPONENTIAL, step, 300, 128, 1, 2) == omask.exponential_ratio(2, 128, 1, 300, step)
+    for step in range(0, 11):
+        assert vb.schedule_ratio(vb.SCHED_EXPONENTIAL, step, 10, 100, 5, 3) == omask.exponential_ratio(3, 100, 5, 10, step)
+    num, den = vb.schedule_ratio(vb.SCHED_LINEAR, 50, 99, 16, 1, 1)                       # the 16-partition configuration:
+    assert num * 99 == (1584 - 15 * 50) * den and (num, den) == (278, 33)                 # (1584 - 15 t) / 99 in lowest terms
+    for args in ((vb.SCHED_LINEAR, 0, 0, 8, 1, 1), (vb.SCHED_LINEAR, -1, 10, 8, 1, 1), (vb.SCHED_LINEAR, 0, 10, 1, 2, 1),
+                 (vb.SCHED_LINEAR, 0, 10, 8, 0, 1), (vb.SCHED_EXPONENTIAL, 0, 10, 8, 1, 1), (7, 0, 10, 8, 1, 1)):
+        with pytest.raises(vb.VarcoError) as e:
+            vb.schedule_ratio(*args)
+        assert e.value.code == vb.ERR_INVALID_ARG

@@ -166,3 +166,14 @@ def test_free_running_training_learns_and_tracks_the_oracle(n_streams):
     assert acc > 0.85, acc
     for l in range(L):
         assert_close(net.h1[l].cpu().numpy(), weights[l][0], f"H1_{l} after {n_steps} iterations", 5e-3)
+
+
+def test_accuracy_against_bytes_demo_runs():
+    from paper_2406_17611_amd import train_demo
+    task = synth.labelled_sbm(n_blocks=3, block_size=300, p_in=0.03, p_out=0.004, width=16, hidden=16, n_parts=3)
+    full = train_demo.run(task, "full", lambda s: (1, 1), steps=6, lr=0.5, every=3)
+    none = train_demo.run(task, "none", lambda s: (1, 0), steps=6, lr=0.5, every=3)
+    half = train_demo.run(task, "fixed 2", lambda s: (2, 1), steps=6, lr=0.5, every=3)
+    assert none["bytes_sent"] == 0 and 0 < half["bytes_sent"] < full["bytes_sent"]
+    assert full["bytes_sent"] == 2 * half["bytes_sent"]            # widths 16 and 16: k halves exactly at ratio 2
+    assert len(full["curve"]) == 2 and 0.0 <= full["final_test_accuracy"] <= 1.0

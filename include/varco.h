@@ -190,6 +190,40 @@ int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx
                         const void* x_local, const void* m_saved, const void* h1, const void* h0, void* dh1,
                         void* dh0, void* dx_local, void* dz_halo, varco_stream stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Building blocks of the general K-tap layer of eq. (1)-(2), X_l = rho( sum_{k<K} S^k X_{l-1} H_{l,k} ): every
+ * application of S (hop k = 1..K-1) has an exchange of its own, Y_k = S_q [Y_{k-1,loc} ; compressed halo rows
+ * of Y_{k-1}], and the transform is a sum of dense products. varco_layer_fwd / varco_layer_bwd are these calls
+ * fused for K <= 2.
+ *
+ * A `layer` argument of varco_compress, varco_decompress, varco_accumulate_returned and a `tap` argument below
+ * may be VARCO_TAP(layer, hop): hop >= 1 selects the kept positions of that hop's exchange (hop 0 is the plain
+ * layer index; each hop draws positions of its own). The ratio and k are the layer's.
+ */
+#define VARCO_TAP(layer, hop) ((layer) + VARCO_MAX_LAYERS * (hop))
+
+/* One hop forward: y_out = S_q [y_local ; decompress(z_in[halo_zrow])], all n_local x width[layer]; z_in as in
+ * varco_layer_fwd (compressed boundary rows of y, all owners). Counts n_halo * k elements handed off forward. */
+int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, const void* y_local, const void* z_in, void* y_out,
+                            varco_stream stream);
+/* One hop backward: [g_local ; c_halo] = S_q^T g_out; g_local (n_local x width[layer]) is overwritten and
+ * dz_halo[s, j] = c_halo[s, pi_v(j)], j < k (n_halo x k) is what goes back to the owners (they add it with
+ * varco_accumulate_returned on the same tap). Counts n_halo * k elements handed off backward. */
+int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, const void* g_out, void* g_local, void* dz_halo,
+                            varco_stream stream);
+/* Dense products of layer `layer` on n_rows rows (storage type for y, c, dx_out, x_out, g_out; weights fp32
+ * width[layer] x width[layer+1]):
+ *   varco_transform_fwd         c (+)= y h; when apply_act != 0 the layer's activation is applied to the result
+ *   varco_transform_bwd_weight  dh += y^T dz,  dz = dx_out * [x_out > 0] for a ReLU layer (x_out may be NULL otherwise)
+ *   varco_transform_bwd_input   g_out (+)= dz h^T
+ * accumulate != 0 adds to what c / g_out hold. */
+int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* y, const void* h, void* c,
+                            int32_t accumulate, int32_t apply_act, varco_stream stream);
+int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* y, const void* dx_out,
+                                   const void* x_out, void* dh, varco_stream stream);
+int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* dx_out, const void* x_out,
+                                  const void* h, void* g_out, int32_t accumulate, varco_stream stream);
+
 /* Owner side of the backward exchange for partition p, all consumers at once (Section III: in the backward
  * pass the exchange runs from consumers to owners; Algorithm 1: errors cross machines): for every
  * boundary row b of p, v = its node id,

@@ -28,6 +28,8 @@ EXPORTS = [
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
     "varco_calibration_copy", "varco_sum_gradients", "varco_softmax_xent", "varco_sgd_step", "varco_schedule_ratio",
+    "varco_aggregate_fwd", "varco_aggregate_bwd", "varco_transform_fwd", "varco_transform_bwd_weight",
+    "varco_transform_bwd_input",
 ]
 KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
                   "agg_bwd_halo", "reduce", "agg_bwd_halo_sum"]
@@ -101,6 +103,11 @@ def lib() -> C.CDLL:
         L.varco_sgd_step.argtypes = [vp, vp, i64, C.c_float, vp]
         L.varco_schedule_ratio.argtypes = [i32, i64, i64, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32),
                                            C.POINTER(C.c_uint32)]
+        L.varco_aggregate_fwd.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.varco_aggregate_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.varco_transform_fwd.argtypes = [vp, i32, i64, vp, vp, vp, i32, i32, vp]
+        L.varco_transform_bwd_weight.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp]
+        L.varco_transform_bwd_input.argtypes = [vp, i32, i64, vp, vp, vp, vp, i32, vp]
         L.varco_profile_enable.argtypes = [vp, i32]
         L.varco_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         for name in EXPORTS:
@@ -138,6 +145,11 @@ def calibration_copy(dst, src, stream=None):
 
 
 SCHED_LINEAR, SCHED_FIXED_INCREMENT, SCHED_EXPONENTIAL = 0, 1, 2
+
+
+def tap(layer: int, hop: int) -> int:
+    """Address of hop `hop` of a K-tap layer (VARCO_TAP of the header)."""
+    return layer + MAX_LAYERS * hop
 
 
 def schedule_ratio(kind: int, step: int, n_steps: int, c_max: int, c_min: int, param: int):
@@ -292,6 +304,25 @@ class Context:
     def accumulate_returned(self, layer, p, ret_ptr, ret_src, returned, dx_local, stream=None):
         _check(lib().varco_accumulate_returned(self._h, layer, p, _ptr(ret_ptr), _ptr(ret_src), _ptr(returned),
                                                _ptr(dx_local), _stream(stream)), self._h)
+
+    def aggregate_fwd(self, tap, q, y_local, z_in, y_out, stream=None):
+        _check(lib().varco_aggregate_fwd(self._h, tap, q, _ptr(y_local), _ptr(z_in), _ptr(y_out), _stream(stream)), self._h)
+
+    def aggregate_bwd(self, tap, q, g_out, g_local, dz_halo, stream=None):
+        _check(lib().varco_aggregate_bwd(self._h, tap, q, _ptr(g_out), _ptr(g_local), _ptr(dz_halo), _stream(stream)),
+               self._h)
+
+    def transform_fwd(self, layer, y, h, c, accumulate, apply_act, stream=None):
+        _check(lib().varco_transform_fwd(self._h, layer, y.shape[0], _ptr(y), _ptr(h), _ptr(c), int(accumulate),
+                                         int(apply_act), _stream(stream)), self._h)
+
+    def transform_bwd_weight(self, layer, y, dx_out, x_out, dh, stream=None):
+        _check(lib().varco_transform_bwd_weight(self._h, layer, y.shape[0], _ptr(y), _ptr(dx_out), _ptr(x_out), _ptr(dh),
+                                                _stream(stream)), self._h)
+
+    def transform_bwd_input(self, layer, dx_out, x_out, h, g_out, accumulate, stream=None):
+        _check(lib().varco_transform_bwd_input(self._h, layer, dx_out.shape[0], _ptr(dx_out), _ptr(x_out), _ptr(h),
+                                               _ptr(g_out), int(accumulate), _stream(stream)), self._h)
 
     def softmax_xent(self, logits, labels, n_classes, scale, dlogits, row_loss, row_correct, totals, stream=None):
         n_rows = logits.shape[0]

@@ -108,9 +108,11 @@ uint64_t mix64(uint64_t x) {   // splitmix64 output function
     return x;
 }
 
-MaskRule make_rule(const varco_ctx* ctx, int32_t layer) {
+// hop > 0: the exchange before the hop-th application of the shift operator inside a K-tap layer draws
+// positions of its own (as if it were layer index layer + 16 * hop).
+MaskRule make_rule(const varco_ctx* ctx, int32_t layer, int32_t hop = 0) {
     const LayerState& ls = ctx->layers[layer];
-    const uint64_t inner = mix64(ctx->step + 0x9E3779B97F4A7C15ull * uint64_t(layer + 1));
+    const uint64_t inner = mix64(ctx->step + 0x9E3779B97F4A7C15ull * uint64_t(layer + VARCO_MAX_LAYERS * hop + 1));
     const uint64_t s = mix64(ctx->key ^ inner);
     MaskRule r;
     r.s0 = uint32_t(s & 0xFFFFFFFFull);
@@ -277,6 +279,18 @@ int32_t check_layer(const varco_ctx* ctx, int32_t layer, const char* fn) {
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, m.c_str());
     }
     return VARCO_OK;
+}
+
+// Splits a tap address VARCO_TAP(layer, hop) = layer + 16 * hop and checks the layer.
+int32_t split_tap(const varco_ctx* ctx, int32_t* layer, int32_t* hop, const char* fn) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "null context");
+    if (*layer < 0 || *layer >= VARCO_MAX_LAYERS * VARCO_MAX_LAYERS) {
+        std::string m = std::string(fn) + ": layer out of range";
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, m.c_str());
+    }
+    *hop = *layer / VARCO_MAX_LAYERS;
+    *layer = *layer % VARCO_MAX_LAYERS;
+    return check_layer(ctx, *layer, fn);
 }
 
 int32_t check_part(const varco_ctx* ctx, int32_t q, const char* fn) {
@@ -500,14 +514,15 @@ extern "C" int32_t varco_get_keep(const varco_ctx* ctx, int32_t layer, int32_t* 
 
 extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
                                   int64_t n_rows, const void* x, int64_t ldx, void* z, varco_stream stream) {
-    if (int32_t rc = check_layer(ctx, layer, "varco_compress")) return rc;
+    int32_t hop = 0;
+    if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_compress")) return rc;
     if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: negative row count");
     if (n_rows == 0 || ctx->layers[layer].k == 0) return VARCO_OK;   // k = 0: nothing is sent
     if (!gids || !x || !z) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_compress: null pointer");
     if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: ldx is smaller than the layer width");
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;   // the step's positions of this layer are now in use
-    const MaskRule rule = make_rule(ctx, layer);
+    const MaskRule rule = make_rule(ctx, layer, hop);
     const double bytes = double(n_rows) * (rule.width + rule.k) * ctx->elem_bytes();
     VARCO_HIP(ctx, varco_launch_compress(ctx->dtype, rule, gids, rows, n_rows, x, ldx, z, static_cast<hipStream_t>(stream),
                                          ctx->tag(VARCO_K_COMPRESS, bytes, 0)));
@@ -517,7 +532,8 @@ extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* 
 extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
                                     int64_t n_rows, const void* z, void* x, int64_t ldx, int32_t accumulate,
                                     varco_stream stream) {
-    if (int32_t rc = check_layer(ctx, layer, "varco_decompress")) return rc;
+    int32_t hop = 0;
+    if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_decompress")) return rc;
     if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: negative row count");
     if (accumulate != 0 && accumulate != 1) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: accumulate must be 0 or 1");
     if (n_rows == 0 || (accumulate && ctx->layers[layer].k == 0)) return VARCO_OK;
@@ -526,7 +542,7 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
     if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: ldx is smaller than the layer width");
     if (int32_t rc = ensure_tables(ctx)) return rc;
     ctx->layers[layer].ran_forward = true;
-    const MaskRule rule = make_rule(ctx, layer);
+    const MaskRule rule = make_rule(ctx, layer, hop);
     const double bytes = (accumulate ? double(n_rows) * rule.k * 3.0 : double(n_rows) * (rule.width + rule.k)) * ctx->elem_bytes();
     VARCO_HIP(ctx, varco_launch_decompress(ctx->dtype, rule, gids, rows, n_rows, z, x, ldx, accumulate,
                                            static_cast<hipStream_t>(stream), ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));
@@ -688,17 +704,177 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     return VARCO_OK;
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Building blocks of a general K-tap layer: one hop of aggregation (forward / transposed) and the dense
+// products, as separate calls.
+// ---------------------------------------------------------------------------------------------------------
+
+extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, const void* y_local, const void* z_in,
+                                       void* y_out, varco_stream stream) {
+    int32_t layer = tap, hop = 0;
+    if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_aggregate_fwd")) return rc;
+    if (int32_t rc = check_part(ctx, q, "varco_aggregate_fwd")) return rc;
+    const PartState& ps = ctx->parts[q];
+    const varco_partition_desc& d = ps.d;
+    if (d.n_local > 0 && (!y_local || !y_out)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_fwd: null pointer");
+    if (d.n_halo > 0 && !z_in && ctx->layers[layer].k > 0)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_fwd: z_in is null but the partition has halo nodes");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* wsp = nullptr;
+    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    const int32_t fi = ctx->widths[layer];
+    const MaskRule rule = make_rule(ctx, layer, hop);
+    ctx->layers[layer].ran_forward = true;
+    const double es = ctx->elem_bytes();
+    const double bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
+                         double(d.n_halo) * rule.k * es;
+    VARCO_HIP(ctx, varco_launch_spmm(ctx->dtype, ps.fwd, ps.edges, nullptr, d.vals, y_local, z_in, rule, y_out, 0, wsp->spmm,
+                                     st, ctx->tag(VARCO_K_AGG_FWD, bytes, 0)));
+    ctx->stats.fwd_elems[layer] += int64_t(d.n_halo) * rule.k;
+    ctx->stats.full_fwd_elems[layer] += int64_t(d.n_halo) * fi;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, const void* g_out, void* g_local,
+                                       void* dz_halo, varco_stream stream) {
+    int32_t layer = tap, hop = 0;
+    if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_aggregate_bwd")) return rc;
+    if (int32_t rc = check_part(ctx, q, "varco_aggregate_bwd")) return rc;
+    const PartState& ps = ctx->parts[q];
+    const varco_partition_desc& d = ps.d;
+    const int32_t nl = d.n_local;
+    if (nl == 0) return VARCO_OK;
+    if (!g_out || !g_local) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_bwd: null pointer");
+    if (d.n_halo > 0 && !dz_halo && ctx->layers[layer].k > 0)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_bwd: dz_halo is null but the partition has halo nodes");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* wsp = nullptr;
+    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    Workspace& ws = *wsp;
+    const int dt = ctx->dtype;
+    const double es = ctx->elem_bytes();
+    const int32_t fi = ctx->widths[layer];
+    const MaskRule rule = make_rule(ctx, layer, hop);
+    const MaskRule dense_rule = full_rule(fi);
+    const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
+    const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
+    const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, dense_rule, g_local, 0,
+                                     ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
+    if (d.n_halo > 0 && rule.k > 0) {
+        if (rule.k == rule.width) {
+            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, dense_rule, dz_halo,
+                                             nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
+        } else {
+            const size_t need = (size_t(d.nnz - ps.nnz_t_local) * rule.k * size_t(es) + 3) / 4;   // in floats
+            if (need > ws.prod_elems) VARCO_HIP(ctx, grow(ws.prod, ws.prod_elems, need + need / 4));
+            VARCO_HIP(ctx, varco_launch_halo_grad(dt, ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local), g_out,
+                                                  rule, ws.prod, dz_halo, nl, ws.spmm, st,
+                                                  ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
+                                                  ctx->tag(VARCO_K_AGG_BWD_HALO_SUM, th_out_bytes, 0)));
+        }
+        ctx->stats.bwd_elems[layer] += int64_t(d.n_halo) * rule.k;
+        ctx->stats.full_bwd_elems[layer] += int64_t(d.n_halo) * fi;
+    }
+    return VARCO_OK;
+}
+
+namespace {
+
+// Shared checks of the dense-product calls; gate = x_out when the layer's activation is ReLU.
+int32_t transform_prologue(varco_ctx* ctx, int32_t layer, int64_t n_rows, hipStream_t st, const char* fn, Workspace** ws) {
+    if (int32_t rc = check_layer(ctx, layer, fn)) return rc;
+    if (n_rows < 0 || n_rows >= (int64_t(1) << 31)) {
+        std::string m = std::string(fn) + ": row count out of range";
+        return varco_fail(ctx, VARCO_ERR_SHAPE, m.c_str());
+    }
+    return workspace_for(ctx, st, ws);
+}
+
+}  // namespace
+
+extern "C" int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* y, const void* h, void* c,
+                                       int32_t accumulate, int32_t apply_act, varco_stream stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* ws = nullptr;
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, st, "varco_transform_fwd", &ws)) return rc;
+    if (n_rows == 0) return VARCO_OK;
+    if (!y || !h || !c) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_fwd: null pointer");
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+    const int dt = ctx->dtype;
+    GemmArgs g;
+    g.m = int32_t(n_rows), g.n = fo, g.k = fi;
+    g.a.ptr = y, g.a.ld = fi, g.a.dtype = dt;
+    g.b.ptr = h, g.b.ld = fo;
+    g.c = c, g.ldc = fo, g.c_dtype = dt;
+    g.accumulate = accumulate != 0;
+    g.relu = apply_act != 0 && ctx->act[layer] == VARCO_ACT_RELU;
+    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(*ws, h, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
+    VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * double(g.m) * g.n * g.k)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* y,
+                                              const void* dx_out, const void* x_out, void* dh, varco_stream stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* ws = nullptr;
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, st, "varco_transform_bwd_weight", &ws)) return rc;
+    if (n_rows == 0) return VARCO_OK;
+    if (!y || !dx_out || !dh || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_weight: null pointer");
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+    const int dt = ctx->dtype;
+    GemmArgs g;
+    g.m = fi, g.n = fo, g.k = int32_t(n_rows);
+    g.a.ptr = y, g.a.ld = fi, g.a.transposed = true, g.a.dtype = dt;
+    g.b.ptr = dx_out, g.b.gate = ctx->act[layer] == VARCO_ACT_RELU ? x_out : nullptr, g.b.ld = fo, g.b.dtype = dt;
+    g.c = dh, g.ldc = fo;
+    g.accumulate = true;
+    g.partial = ws->gemm;
+    g.split_k = gemm_split_for(fi, fo, n_rows, varco_gemm_bf16_usable(g));
+    if (size_t(g.split_k) * fi * fo > ws->gemm_elems) {   // rows beyond what the registered partitions sized
+        const int64_t fit = int64_t(ws->gemm_elems / (size_t(fi) * fo));
+        if (fit < 1) return varco_fail(ctx, VARCO_ERR_STATE, "varco_transform_bwd_weight: workspace too small (register a partition first)");
+        g.split_k = int32_t(fit);
+    }
+    VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(n_rows))));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* dx_out,
+                                             const void* x_out, const void* h, void* g_out, int32_t accumulate,
+                                             varco_stream stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* ws = nullptr;
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, st, "varco_transform_bwd_input", &ws)) return rc;
+    if (n_rows == 0) return VARCO_OK;
+    if (!dx_out || !h || !g_out || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_input: null pointer");
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+    const int dt = ctx->dtype;
+    GemmArgs g;
+    g.m = int32_t(n_rows), g.n = fi, g.k = fo;
+    g.a.ptr = dx_out, g.a.gate = ctx->act[layer] == VARCO_ACT_RELU ? x_out : nullptr, g.a.ld = fo, g.a.dtype = dt;
+    g.b.ptr = h, g.b.ld = fo, g.b.transposed = true;
+    g.c = g_out, g.ldc = fi, g.c_dtype = dt;
+    g.accumulate = accumulate != 0;
+    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(*ws, h, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
+    VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(n_rows))));
+    return VARCO_OK;
+}
+
 extern "C" int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int32_t p, const int32_t* ret_ptr,
                                              const int32_t* ret_src, const void* returned, void* dx_local,
                                              varco_stream stream) {
-    if (int32_t rc = check_layer(ctx, layer, "varco_accumulate_returned")) return rc;
+    int32_t hop = 0;
+    if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_accumulate_returned")) return rc;
     if (int32_t rc = check_part(ctx, p, "varco_accumulate_returned")) return rc;
     const PartState& ps = ctx->parts[p];
     if (ps.d.n_boundary == 0 || ctx->layers[layer].k == 0) return VARCO_OK;
     if (!ret_ptr || !ret_src || !returned || !dx_local)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_accumulate_returned: null pointer");
     ctx->layers[layer].ran_forward = true;
-    const MaskRule rule = make_rule(ctx, layer);
+    const MaskRule rule = make_rule(ctx, layer, hop);
     // rows returned are not known on the host; attribute the owner-side read-modify-write of k values per row
     const double bytes = double(ps.d.n_boundary) * rule.k * 3.0 * ctx->elem_bytes();
     VARCO_HIP(ctx, varco_launch_accumulate_returned(ctx->dtype, rule, ps.boundary_gid, ps.d.boundary_rows, ps.d.n_boundary,

@@ -264,3 +264,86 @@ class PartitionedNetwork:
     def step(self, step: int, ratio=None, stream=None):
         self.forward(step, ratio, stream)
         self.backward(stream)
+
+
+class KTapNetwork(PartitionedNetwork):
+    """General K-tap layers, X_l = rho( sum_{k<K} S^k X_{l-1} H_{l,k} ) (eq. (1)-(2)), driven through the library's
+    building-block calls: every hop k = 1..K-1 has a compressed exchange of its own (tap address (layer, hop)),
+    the transform is a sum of K dense products, and the backward pass walks the hops in reverse, handing the
+    errors of halo rows back to their owners at every hop. Same buffers and bookkeeping as PartitionedNetwork."""
+
+    def __init__(self, host_parts, widths, n_taps: int, mask_key: int, device="cuda", dtype="f32"):
+        super().__init__(host_parts, widths, "sage", mask_key, device, True, dtype, 1)
+        assert n_taps >= 1
+        self.K = n_taps
+        f32 = dict(dtype=torch.float32, device=self.device)
+        act = dict(dtype=self.act_dtype, device=self.device)
+        self.h = [[torch.empty((self.widths[l], self.widths[l + 1]), **f32) for _ in range(n_taps)] for l in range(self.L)]
+        self.dh = [[torch.zeros_like(w) for w in hs] for hs in self.h]
+        # y[l][hop] = S^hop X_l rows (hop 0 is x[l] itself)
+        self.y = [[self.x[l]] + [torch.empty((self.n_total, self.widths[l]), **act) for _ in range(1, n_taps)]
+                  for l in range(self.L)]
+        wmax = max(self.widths[:-1])
+        self._g = [torch.empty(self.n_total * wmax, **act) for _ in range(2)]
+
+    def set_tap_weights(self, weights):
+        for l in range(self.L):
+            for hop in range(self.K):
+                self.h[l][hop].copy_(torch.from_numpy(weights[l][hop]).to(self.device))
+
+    def zero_grads(self):
+        for hs in self.dh:
+            for w in hs:
+                w.zero_()
+
+    def forward(self, step: int, ratio=None, stream=None):
+        ctx = self.ctx
+        ctx.begin_step(step)
+        if ratio is not None:
+            ctx.set_ratio(-1, ratio[0], ratio[1])
+        self._ensure_buffers()
+        for l in range(self.L):
+            fi, k = self.widths[l], ctx.keep(l)
+            for hop in range(1, self.K):
+                tap, src = vb.tap(l, hop), self.y[l][hop - 1]
+                for p, hp in enumerate(self.host_parts):
+                    if hp.n_boundary:
+                        ctx.compress(tap, self.boundary_gid[p], self.dev_parts[p]["boundary_rows"], hp.n_boundary,
+                                     src[self.rows(p)], fi, self.z[l][hp.z_row_offset * k:], stream)
+                for q in range(self.P):
+                    r = self.rows(q)
+                    ctx.aggregate_fwd(tap, q, src[r], self.z[l], self.y[l][hop][r], stream)
+            for q in range(self.P):
+                r = self.rows(q)
+                for hop in range(self.K):
+                    ctx.transform_fwd(l, self.y[l][hop][r], self.h[l][hop], self.x[l + 1][r], hop > 0, hop == self.K - 1,
+                                      stream)
+
+    def backward(self, stream=None):
+        ctx = self.ctx
+        for l in range(self.L - 1, -1, -1):
+            fi, k = self.widths[l], ctx.keep(l)
+            for q in range(self.P):
+                r = self.rows(q)
+                for hop in range(self.K):
+                    ctx.transform_bwd_weight(l, self.y[l][hop][r], self.dx[l + 1][r], self.x[l + 1][r], self.dh[l][hop], stream)
+            if l == 0:
+                continue
+            bufs = [b[:self.n_total * fi].view(self.n_total, fi) for b in self._g]
+            cur = self.dx[l] if self.K == 1 else bufs[0]
+            for q in range(self.P):
+                r = self.rows(q)
+                ctx.transform_bwd_input(l, self.dx[l + 1][r], self.x[l + 1][r], self.h[l][self.K - 1], cur[r], False, stream)
+            for hop in range(self.K - 1, 0, -1):
+                tap = vb.tap(l, hop)
+                nxt = self.dx[l] if hop == 1 else (bufs[1] if cur is bufs[0] else bufs[0])
+                for q in range(self.P):
+                    r = self.rows(q)
+                    dzh = self.dz_halo[l][int(self.halo_off[q]) * k:] if self.n_halo[q] else None
+                    ctx.aggregate_bwd(tap, q, cur[r], nxt[r], dzh, stream)
+                    ctx.transform_bwd_input(l, self.dx[l + 1][r], self.x[l + 1][r], self.h[l][hop - 1], nxt[r], True, stream)
+                for p in range(self.P):
+                    if self.host_parts[p].n_boundary:
+                        ctx.accumulate_returned(tap, p, self.ret_ptr[p], self.ret_src[p], self.dz_halo[l],
+                                                nxt[self.rows(p)], stream)
+                cur = nxt

@@ -239,8 +239,9 @@ int32_t ensure_tables(varco_ctx* ctx) {
 }
 
 // bf16 copy of a weight matrix in workspace slot 0 or 1, rows = the product's output index, pitch padded to 8.
-hipError_t prep_weight(Workspace& ws, const void* h, int32_t fi, int32_t fo, bool transpose, int slot, hipStream_t st,
-                       const void** out, int64_t* pitch) {
+hipError_t prep_weight(VarcoProfiler& prof, Workspace& ws, const void* h, int32_t fi, int32_t fo, bool transpose, int slot,
+                       hipStream_t st, const void** out, int64_t* pitch) {
+    prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
     const int32_t rows = transpose ? fo : fi, cols = transpose ? fi : fo;
     const int32_t p = pad8(cols);
     char* dst = reinterpret_cast<char*>(ws.w) + size_t(slot) * ws.w_elems * 2;
@@ -381,10 +382,7 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     for (Workspace& w : ctx->ws)
         for (float* p : {w.dm, w.spmm, w.gemm, w.prod, w.w})
             if (p) (void)hipFree(p);
-    for (VarcoProfiler::Rec& r : ctx->prof.recs) {
-        (void)hipEventDestroy(r.start);
-        (void)hipEventDestroy(r.stop);
-    }
+    for (hipEvent_t e : ctx->prof.events) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
     delete ctx;
     return VARCO_OK;
@@ -514,6 +512,7 @@ extern "C" int32_t varco_get_keep(const varco_ctx* ctx, int32_t layer, int32_t* 
 
 extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
                                   int64_t n_rows, const void* x, int64_t ldx, void* z, varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     int32_t hop = 0;
     if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_compress")) return rc;
     if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: negative row count");
@@ -532,6 +531,7 @@ extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* 
 extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
                                     int64_t n_rows, const void* z, void* x, int64_t ldx, int32_t accumulate,
                                     varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     int32_t hop = 0;
     if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_decompress")) return rc;
     if (n_rows < 0) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: negative row count");
@@ -552,6 +552,7 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
 extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_local, const void* z_in,
                                    const void* h1, const void* h0, void* x_out, void* z_out, void* m_saved,
                                    varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     if (int32_t rc = check_layer(ctx, layer, "varco_layer_fwd")) return rc;
     if (int32_t rc = check_part(ctx, q, "varco_layer_fwd")) return rc;
     const PartState& ps = ctx->parts[q];
@@ -593,8 +594,8 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     g.c = x_out, g.ldc = fo, g.c_dtype = dt;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
     if (dt == VARCO_BF16 && d.n_local > 0) {   // weights as bf16, [output column][reduction index]
-        VARCO_HIP(ctx, prep_weight(ws, h1, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
-        if (sage) VARCO_HIP(ctx, prep_weight(ws, h0, fi, fo, true, 1, st, &g.b2_prep, &g.b2_prep_ld));
+        VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h1, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
+        if (sage) VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h0, fi, fo, true, 1, st, &g.b2_prep, &g.b2_prep_ld));
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
@@ -613,6 +614,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
 extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx_out, const void* x_out,
                                    const void* x_local, const void* m_saved, const void* h1, const void* h0,
                                    void* dh1, void* dh0, void* dx_local, void* dz_halo, varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     if (int32_t rc = check_layer(ctx, layer, "varco_layer_bwd")) return rc;
     if (int32_t rc = check_part(ctx, q, "varco_layer_bwd")) return rc;
     const PartState& ps = ctx->parts[q];
@@ -663,7 +665,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
         g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
         g.c = ws.dm, g.ldc = fi, g.c_dtype = dt;
-        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ws, h1, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
+        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h1, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
@@ -698,7 +700,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = h0, g.b.ld = fo, g.b.transposed = true;
         g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
         g.accumulate = true;
-        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ws, h0, fi, fo, false, 1, st, &g.b_prep, &g.b_prep_ld));
+        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h0, fi, fo, false, 1, st, &g.b_prep, &g.b_prep_ld));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     return VARCO_OK;
@@ -711,6 +713,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
 
 extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, const void* y_local, const void* z_in,
                                        void* y_out, varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     int32_t layer = tap, hop = 0;
     if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_aggregate_fwd")) return rc;
     if (int32_t rc = check_part(ctx, q, "varco_aggregate_fwd")) return rc;
@@ -737,6 +740,7 @@ extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, c
 
 extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, const void* g_out, void* g_local,
                                        void* dz_halo, varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     int32_t layer = tap, hop = 0;
     if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_aggregate_bwd")) return rc;
     if (int32_t rc = check_part(ctx, q, "varco_aggregate_bwd")) return rc;
@@ -784,6 +788,7 @@ namespace {
 // Shared checks of the dense-product calls; gate = x_out when the layer's activation is ReLU.
 int32_t transform_prologue(varco_ctx* ctx, int32_t layer, int64_t n_rows, hipStream_t st, const char* fn, Workspace** ws) {
     if (int32_t rc = check_layer(ctx, layer, fn)) return rc;
+    ctx->prof.interrupt();   // events are shared between the launches of one call only
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31)) {
         std::string m = std::string(fn) + ": row count out of range";
         return varco_fail(ctx, VARCO_ERR_SHAPE, m.c_str());
@@ -809,7 +814,7 @@ extern "C" int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_
     g.c = c, g.ldc = fo, g.c_dtype = dt;
     g.accumulate = accumulate != 0;
     g.relu = apply_act != 0 && ctx->act[layer] == VARCO_ACT_RELU;
-    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(*ws, h, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
+    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, *ws, h, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * double(g.m) * g.n * g.k)));
     return VARCO_OK;
 }
@@ -858,7 +863,7 @@ extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int6
     g.b.ptr = h, g.b.ld = fo, g.b.transposed = true;
     g.c = g_out, g.ldc = fi, g.c_dtype = dt;
     g.accumulate = accumulate != 0;
-    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(*ws, h, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
+    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, *ws, h, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(n_rows))));
     return VARCO_OK;
 }
@@ -866,6 +871,7 @@ extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int6
 extern "C" int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int32_t p, const int32_t* ret_ptr,
                                              const int32_t* ret_src, const void* returned, void* dx_local,
                                              varco_stream stream) {
+    if (ctx) ctx->prof.interrupt();   // events are shared between the launches of one call only
     int32_t hop = 0;
     if (int32_t rc = split_tap(ctx, &layer, &hop, "varco_accumulate_returned")) return rc;
     if (int32_t rc = check_part(ctx, p, "varco_accumulate_returned")) return rc;
@@ -988,16 +994,18 @@ extern "C" int32_t varco_profile_read(varco_ctx* ctx, varco_profile* out, int32_
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_profile_read: null context");
     if (!out) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_profile_read: null output");
     for (VarcoProfiler::Rec& r : ctx->prof.recs) {
-        VARCO_HIP(ctx, hipEventSynchronize(r.stop));
+        if (r.stop < 0) continue;
+        VARCO_HIP(ctx, hipEventSynchronize(ctx->prof.events[r.stop]));
         float ms = 0.f;
-        VARCO_HIP(ctx, hipEventElapsedTime(&ms, r.start, r.stop));
+        VARCO_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof.events[r.start], ctx->prof.events[r.stop]));
         ctx->prof_ms[r.cls] += ms;
         ctx->prof_bytes[r.cls] += r.bytes;
         ctx->prof_flops[r.cls] += r.flops;
         ctx->prof_launches[r.cls] += 1;
-        ctx->prof.pool.push_back(r.start);
-        ctx->prof.pool.push_back(r.stop);
     }
+    for (hipEvent_t e : ctx->prof.events) ctx->prof.pool.push_back(e);
+    ctx->prof.events.clear();
+    ctx->prof.last_stop = -1;
     ctx->prof.recs.clear();
     for (int c = 0; c < VARCO_K_COUNT; ++c) {
         out->launches[c] = ctx->prof_launches[c];

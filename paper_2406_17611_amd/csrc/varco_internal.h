@@ -8,36 +8,48 @@
 
 #include "varco.h"
 
-// Brackets kernel launches with HIP events on the launch stream (see varco_profile_enable).
+// Brackets kernel launches with HIP events on the launch stream (see varco_profile_enable). When a launch
+// follows the previous bracketed launch on the same stream, the previous stop event doubles as its start
+// event: an event record is a marker in the queue that keeps the next kernel from starting early, so half as
+// many markers disturb the run half as much.
 struct VarcoProfiler {
     struct Rec {
         int cls;
-        hipEvent_t start, stop;
+        int start, stop;     // indices into `events`
         double bytes, flops;
     };
     bool on = false;
     std::vector<Rec> recs;
-    std::vector<hipEvent_t> pool;
-    hipEvent_t get() {
-        if (!pool.empty()) {
-            hipEvent_t e = pool.back();
-            pool.pop_back();
-            return e;
-        }
+    std::vector<hipEvent_t> events;   // recorded since the last read
+    std::vector<hipEvent_t> pool;     // free
+    hipStream_t last_stream = nullptr;
+    int last_stop = -1;               // event index of the last stop record, still the tail of last_stream's queue
+    int record(hipStream_t st) {
         hipEvent_t e = nullptr;
-        (void)hipEventCreate(&e);
-        return e;
+        if (!pool.empty()) {
+            e = pool.back();
+            pool.pop_back();
+        } else {
+            (void)hipEventCreate(&e);
+        }
+        (void)hipEventRecord(e, st);
+        events.push_back(e);
+        return int(events.size()) - 1;
     }
     void begin(int cls, hipStream_t st, double bytes, double flops) {
         if (!on) return;
-        Rec r{cls, get(), get(), bytes, flops};
-        (void)hipEventRecord(r.start, st);
-        recs.push_back(r);
+        const int start = (last_stop >= 0 && last_stream == st) ? last_stop : record(st);
+        recs.push_back(Rec{cls, start, -1, bytes, flops});
+        last_stop = -1;
     }
     void end(hipStream_t st) {
         if (!on) return;
-        (void)hipEventRecord(recs.back().stop, st);
+        recs.back().stop = record(st);
+        last_stream = st;
+        last_stop = recs.back().stop;
     }
+    // An untimed launch went to `st`: the next bracket on it needs a start event of its own.
+    void interrupt() { last_stop = -1; }
 };
 // Work attributed to one launch, handed from the API layer to the launchers.
 struct LaunchTag {

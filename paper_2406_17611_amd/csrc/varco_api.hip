@@ -786,14 +786,14 @@ extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, c
 namespace {
 
 // Shared checks of the dense-product calls; gate = x_out when the layer's activation is ReLU.
-int32_t transform_prologue(varco_ctx* ctx, int32_t layer, int64_t n_rows, hipStream_t st, const char* fn, Workspace** ws) {
+int32_t transform_prologue(varco_ctx* ctx, int32_t layer, int64_t n_rows, const char* fn) {
     if (int32_t rc = check_layer(ctx, layer, fn)) return rc;
     ctx->prof.interrupt();   // events are shared between the launches of one call only
     if (n_rows < 0 || n_rows >= (int64_t(1) << 31)) {
         std::string m = std::string(fn) + ": row count out of range";
         return varco_fail(ctx, VARCO_ERR_SHAPE, m.c_str());
     }
-    return workspace_for(ctx, st, ws);
+    return VARCO_OK;
 }
 
 }  // namespace
@@ -802,9 +802,10 @@ extern "C" int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_
                                        int32_t accumulate, int32_t apply_act, varco_stream stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* ws = nullptr;
-    if (int32_t rc = transform_prologue(ctx, layer, n_rows, st, "varco_transform_fwd", &ws)) return rc;
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, "varco_transform_fwd")) return rc;
     if (n_rows == 0) return VARCO_OK;
     if (!y || !h || !c) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_fwd: null pointer");
+    if (int32_t rc = workspace_for(ctx, st, &ws)) return rc;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const int dt = ctx->dtype;
     GemmArgs g;
@@ -823,10 +824,11 @@ extern "C" int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int
                                               const void* dx_out, const void* x_out, void* dh, varco_stream stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* ws = nullptr;
-    if (int32_t rc = transform_prologue(ctx, layer, n_rows, st, "varco_transform_bwd_weight", &ws)) return rc;
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, "varco_transform_bwd_weight")) return rc;
     if (n_rows == 0) return VARCO_OK;
     if (!y || !dx_out || !dh || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_weight: null pointer");
+    if (int32_t rc = workspace_for(ctx, st, &ws)) return rc;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const int dt = ctx->dtype;
     GemmArgs g;
@@ -851,10 +853,11 @@ extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int6
                                              varco_stream stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* ws = nullptr;
-    if (int32_t rc = transform_prologue(ctx, layer, n_rows, st, "varco_transform_bwd_input", &ws)) return rc;
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, "varco_transform_bwd_input")) return rc;
     if (n_rows == 0) return VARCO_OK;
     if (!dx_out || !h || !g_out || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_input: null pointer");
+    if (int32_t rc = workspace_for(ctx, st, &ws)) return rc;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const int dt = ctx->dtype;
     GemmArgs g;

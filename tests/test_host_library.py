@@ -174,3 +174,30 @@ def test_schedules_match_the_oracle_exactly():
         with pytest.raises(vb.VarcoError) as e:
             vb.schedule_ratio(*args)
         assert e.value.code == vb.ERR_INVALID_ARG
+
+
+def test_host_checkable_errors_of_the_building_block_and_training_calls():
+    ctx = vb.Context([8, 4, 3], [1, 0], vb.CONV_SAGE, 2, 1)
+    L = vb.lib()
+    h = ctx._h
+    assert L.varco_aggregate_fwd(h, vb.tap(0, 1), 1, None, None, None, None) == vb.ERR_STATE        # not registered
+    assert L.varco_aggregate_fwd(h, vb.tap(2, 1), 0, None, None, None, None) == vb.ERR_INVALID_ARG  # no such layer
+    assert L.varco_aggregate_bwd(h, -1, 0, None, None, None, None) == vb.ERR_INVALID_ARG
+    assert L.varco_aggregate_bwd(h, 16 * 16, 0, None, None, None, None) == vb.ERR_INVALID_ARG       # hop out of range
+    assert L.varco_compress(h, vb.tap(1, 3), None, None, 0, None, 8, None, None) == vb.OK            # hop addresses are accepted
+    assert L.varco_transform_fwd(h, 2, 10, None, None, None, 0, 0, None) == vb.ERR_INVALID_ARG      # layer
+    assert L.varco_transform_fwd(h, 0, -1, None, None, None, 0, 0, None) == vb.ERR_SHAPE
+    assert L.varco_transform_fwd(h, 0, 10, None, None, None, 0, 0, None) == vb.ERR_INVALID_ARG      # null pointers
+    assert L.varco_transform_fwd(h, 0, 0, None, None, None, 0, 0, None) == vb.OK                    # no rows: no-op
+    assert L.varco_transform_bwd_weight(h, 0, 10, None, None, None, None, None) == vb.ERR_INVALID_ARG
+    assert L.varco_transform_bwd_input(h, 1, 10, None, None, None, None, 0, None) == vb.ERR_INVALID_ARG
+    assert L.varco_softmax_xent(h, None, 3, None, 10, 3, 1.0, None, 3, None, None, None, None) == vb.ERR_INVALID_ARG
+    assert L.varco_softmax_xent(h, None, 2, None, 10, 3, 1.0, None, 3, None, None, None, None) == vb.ERR_SHAPE   # ld < classes
+    assert L.varco_softmax_xent(h, None, 3, None, -1, 3, 1.0, None, 3, None, None, None, None) == vb.ERR_SHAPE
+    assert L.varco_softmax_xent(h, None, 3, None, 0, 3, 1.0, None, 3, None, None, None, None) == vb.OK
+    assert L.varco_softmax_xent(None, None, 3, None, 0, 3, 1.0, None, 3, None, None, None, None) == vb.ERR_INVALID_ARG
+    assert L.varco_sgd_step(None, None, 5, 0.1, None) == vb.ERR_INVALID_ARG
+    assert L.varco_sgd_step(None, None, -5, 0.1, None) == vb.ERR_SHAPE
+    assert L.varco_sgd_step(None, None, 0, 0.1, None) == vb.OK
+    assert L.varco_sum_gradients(None, None, 5, None) == vb.ERR_INVALID_ARG
+    ctx.close()

@@ -141,6 +141,20 @@ def test_layer_parity_at_the_maximum_width(fi, fo, dtype):
     _run_layer_case(g, part, 2, "sage", fi, fo, (8, 1), vb.ACT_RELU, seed=fi + 1, dtype=dtype)
 
 
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+def test_layer_parity_on_a_directed_operator(conv):
+    # an operator with an arbitrary (non-symmetric) pattern and values: S and S^T must not be confused anywhere
+    rng = np.random.default_rng(123)
+    n = 1200
+    pattern = rng.random((n, n)) < 0.006
+    rowptr = np.concatenate(([0], np.cumsum(pattern.sum(axis=1)))).astype(np.int64)
+    colidx = np.nonzero(pattern)[1].astype(np.int32)
+    vals = rng.standard_normal(colidx.shape[0]).astype(np.float32)
+    g = synth.Graph(n, rowptr, colidx, vals, 0, False)
+    part = rng.integers(0, 3, size=n).astype(np.int32)              # uneven parts
+    _run_layer_case(g, part, 3, conv, 96, 40, (4, 1), vb.ACT_RELU, seed=8)
+
+
 def test_layer_parity_single_partition_has_no_exchange():
     g = synth.small_random_graph(900, 8.0, "gcn", seed=2)
     part = np.zeros(g.n, dtype=np.int32)

@@ -59,6 +59,27 @@ def test_partition_builder_handles_empty_partition_and_isolated_nodes():
     assert hp[1].n_local == 0 and hp[1].nnz == 0
 
 
+def test_partition_builder_matches_oracle_on_random_directed_graphs():
+    """Random small operators that need not be symmetric (the builder and the oracle must agree on any sparsity
+    pattern with ascending columns): uneven and empty partitions, isolated nodes, self-loops, dense rows."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=60, deadline=None)
+    @given(st.integers(1, 40), st.integers(1, 6), st.floats(0.0, 0.6), st.integers(0, 2**31 - 1))
+    def check(n, n_parts, density, seed):
+        rng = np.random.default_rng(seed)
+        pattern = rng.random((n, n)) < density
+        rowptr = np.concatenate(([0], np.cumsum(pattern.sum(axis=1)))).astype(np.int64)
+        colidx = np.nonzero(pattern)[1].astype(np.int32)               # ascending within a row
+        vals = rng.standard_normal(colidx.shape[0]).astype(np.float32)
+        part = rng.integers(0, n_parts, size=n).astype(np.int32)       # any map: uneven, possibly empty parts
+        hp = vb.partition_build(n, rowptr, colidx, vals, part, n_parts)
+        op = opart.build_partitions(n, rowptr, colidx, vals, part, n_parts)
+        _assert_same(hp, op)
+
+    check()
+
+
 @pytest.mark.parametrize("name", ["tiny", "medium", "medium_bfs16"])
 def test_partition_builder_matches_oracle_on_configs(name):
     w = synth.make_workload(name)

@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--ratio", default=None, help="num/den, default: the configuration's ratio")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the partitions of a layer are dealt to (kernels of different partitions overlap)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a HIP graph (no per-launch host work; per-kernel timing is not available)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-baseline-only", action="store_true")
     args = ap.parse_args()
@@ -146,19 +148,37 @@ def main():
     vb.calibration_copy(cal_dst, cal_src)
     del cal_src, cal_dst
 
-    for s in range(args.warmup):
-        net.step(s, ratio)
-    torch.cuda.synchronize()
-    net.ctx.reset_stats()
-    net.ctx.profile_enable(True)
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        net.step(args.warmup + s, ratio)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    prof = net.ctx.profile_read()
-    net.ctx.profile_enable(False)
-    stats = net.ctx.stats()
+    if args.graph:
+        graph = net.capture_step(ratio)
+        net.ctx.reset_stats()
+        net.step(None, ratio)               # one eager step, so that the exchange counters below describe a step
+        per_step = net.ctx.stats()
+        for s in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = {}
+        stats = dict(per_step)
+        for key in ("fwd_elems", "bwd_elems", "full_fwd_elems", "full_bwd_elems"):
+            stats[key] = [v * args.steps for v in per_step[key]]
+    else:
+        for s in range(args.warmup):
+            net.step(s, ratio)
+        torch.cuda.synchronize()
+        net.ctx.reset_stats()
+        net.ctx.profile_enable(True)
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            net.step(args.warmup + s, ratio)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = net.ctx.profile_read()
+        net.ctx.profile_enable(False)
+        stats = net.ctx.stats()
     ms_per_step = dt * 1e3 / args.steps
     edges_per_step = L * net.nnz_total
     assert all(torch.isfinite(t).all().item() for t in net.dh1), "non-finite weight gradient"
@@ -178,11 +198,13 @@ def main():
             ach = p["bytes"] / p["ms"] / 1e6
             entry.update(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
         kernels[name] = entry
-    dominant = max((n for n in kernels if n != "reduce"), key=lambda n: kernels[n]["ms_per_step"])
-    d = kernels[dominant]
-    roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
-                "unit": d["unit"], "frac": d["frac"], "traffic": measured_traffic(w.name, dominant),
-                "avg_launch_ms": d["avg_launch_ms"]}
+    roofline = None                     # graph replays are not bracketed per launch
+    if kernels:
+        dominant = max((n for n in kernels if n != "reduce"), key=lambda n: kernels[n]["ms_per_step"])
+        d = kernels[dominant]
+        roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
+                    "unit": d["unit"], "frac": d["frac"], "traffic": measured_traffic(w.name, dominant),
+                    "avg_launch_ms": d["avg_launch_ms"]}
 
     bpe = stats["bytes_per_elem"]
     out = {
@@ -196,6 +218,7 @@ def main():
         "config": {"workload": w.name, "nodes": g.n, "directed_entries": g.nnz, "partitions": w.n_parts,
                    "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
                    "keep": [net.ctx.keep(l) for l in range(L)], "layers": L, "streams": args.streams,
+                   "hip_graph": bool(args.graph),
                    "edges_counted_per_step": edges_per_step},
         "roofline": roofline,
         "kernels": kernels,

@@ -24,7 +24,7 @@
  *   - Node ids, row ids and counts are int32 (graphs below 2^31 nodes / entries per partition); element
  *     offsets are 64-bit inside the library.
  *   - A context is not thread-safe (one host thread issues its calls). Layer calls may be issued on up
- *     to 4 different streams, whose work then may overlap on the device: the library keeps one workspace
+ *     to 8 different streams, whose work then may overlap on the device: the library keeps one workspace
  *     set per stream (created on the stream's first call, which may synchronise the device). The caller
  *     orders dependent work across streams (events), and gives calls that may overlap different output
  *     buffers; dh1 / dh0 in particular are read-modify-written (see varco_sum_gradients).
@@ -138,6 +138,21 @@ const char* varco_last_error(const varco_ctx* ctx);
 /* Algorithm 1's iteration counter t: part of the mask key, so that the kept positions are redrawn every
  * step. Also closes the previous step (ratios may change again). */
 int32_t varco_begin_step(varco_ctx* ctx, uint64_t step);
+
+/* Step state on the device, for callers that capture a sequence of calls in a HIP graph and replay it for
+ * later steps (kernel arguments are frozen at capture, the iteration counter must not be).
+ *   varco_step_table_enable  allocates (first call only: not capturable) a device copy of the step and of the
+ *                            key words derived from it, fills it for the current step on `stream`; from then
+ *                            on every kernel takes the key words of the kept positions from that table.
+ *   varco_set_step           varco_begin_step that also refreshes the table on `stream` (works in either mode).
+ *   varco_advance_step       step += 1 on the device by one small kernel on `stream` (capturable: each replay
+ *                            moves on by one step), and on the host; otherwise like varco_begin_step.
+ * With the table enabled varco_begin_step is a STATE error. The table is shared by all streams: work of the
+ * previous step must be ordered before the call that changes the step. Host-side counters (varco_get_stats)
+ * and the host's copy of the step count calls, not graph replays. */
+int32_t varco_step_table_enable(varco_ctx* ctx, varco_stream stream);
+int32_t varco_set_step(varco_ctx* ctx, uint64_t step, varco_stream stream);
+int32_t varco_advance_step(varco_ctx* ctx, varco_stream stream);
 
 /* Section IV / Algorithm 1 (the step that updates the compression rate): ratio r = num/den >= 1 of layer `layer`'s input
  * (-1 = every layer). k = max(1, ceil(width*den/num)); r = 1 keeps everything (lossless). den = 0 (num >= 1)

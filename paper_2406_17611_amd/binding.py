@@ -28,6 +28,7 @@ EXPORTS = [
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
     "varco_calibration_copy", "varco_sum_gradients", "varco_softmax_xent", "varco_sgd_step", "varco_schedule_ratio",
+    "varco_step_table_enable", "varco_set_step", "varco_advance_step",
     "varco_aggregate_fwd", "varco_aggregate_bwd", "varco_transform_fwd", "varco_transform_bwd_weight",
     "varco_transform_bwd_input",
 ]
@@ -103,6 +104,9 @@ def lib() -> C.CDLL:
         L.varco_sgd_step.argtypes = [vp, vp, i64, C.c_float, vp]
         L.varco_schedule_ratio.argtypes = [i32, i64, i64, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32),
                                            C.POINTER(C.c_uint32)]
+        L.varco_step_table_enable.argtypes = [vp, vp]
+        L.varco_set_step.argtypes = [vp, u64, vp]
+        L.varco_advance_step.argtypes = [vp, vp]
         L.varco_aggregate_fwd.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.varco_aggregate_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp]
         L.varco_transform_fwd.argtypes = [vp, i32, i64, vp, vp, vp, i32, i32, vp]
@@ -240,6 +244,7 @@ class Context:
         self.widths = list(widths)
         self.n_layers = len(act)
         self.n_partitions = n_partitions
+        self.step_on_device = False
         self._keep = {}          # device tensors of registered partitions (kept alive)
         self.parts = {}
 
@@ -275,6 +280,16 @@ class Context:
 
     def begin_step(self, step: int):
         _check(lib().varco_begin_step(self._h, step), self._h)
+
+    def step_table_enable(self, stream=None):
+        _check(lib().varco_step_table_enable(self._h, _stream(stream)), self._h)
+        self.step_on_device = True
+
+    def set_step(self, step: int, stream=None):
+        _check(lib().varco_set_step(self._h, step, _stream(stream)), self._h)
+
+    def advance_step(self, stream=None):
+        _check(lib().varco_advance_step(self._h, _stream(stream)), self._h)
 
     def set_ratio(self, layer: int, num: int, den: int = 1):
         _check(lib().varco_set_ratio(self._h, layer, num, den), self._h)

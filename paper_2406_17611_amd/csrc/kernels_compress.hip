@@ -147,6 +147,27 @@ __global__ __launch_bounds__(kBlock) void sum_gradients_kernel(float* __restrict
     for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) dst[i] += src[i];
 }
 
+__device__ __forceinline__ uint64_t mix64_device(uint64_t x) {   // splitmix64 output function
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+
+// One workgroup of 256 threads, thread t = tap address t.
+__global__ __launch_bounds__(kBlock) void step_table_kernel(uint64_t* d_step, uint32_t* table, uint64_t key, int set,
+                                                            uint64_t value) {
+    const uint64_t step = set ? value : *d_step + 1;
+    __syncthreads();                       // every thread has read the old step before it is replaced
+    if (threadIdx.x == 0) *d_step = step;
+    const uint64_t inner = mix64_device(step + 0x9E3779B97F4A7C15ull * uint64_t(threadIdx.x + 1));
+    const uint64_t s = mix64_device(key ^ inner);
+    table[2 * threadIdx.x] = uint32_t(s & 0xFFFFFFFFull);
+    table[2 * threadIdx.x + 1] = uint32_t(s >> 32);
+}
+
 int group_log2(uint32_t elems) {
     int l = 0;
     while ((1u << l) < elems && l < 6) ++l;
@@ -262,5 +283,11 @@ hipError_t varco_launch_sum_gradients(float* dst, const float* src, int64_t n, h
     const int64_t want = (n + kBlock - 1) / kBlock;
     hipLaunchKernelGGL(sum_gradients_kernel, dim3(unsigned(want < 256 * 16 ? want : 256 * 16)), dim3(kBlock), 0, stream, dst,
                        src, n);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_step_table(uint64_t* d_step, uint32_t* table, uint64_t key, int set, uint64_t value,
+                                   hipStream_t stream) {
+    hipLaunchKernelGGL(step_table_kernel, dim3(1), dim3(kBlock), 0, stream, d_step, table, key, set, value);
     return hipGetLastError();
 }

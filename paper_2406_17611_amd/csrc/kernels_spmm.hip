@@ -185,8 +185,8 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
             srow = ed.src;
             is_halo = ed.gid >= 0;
             if (sparse && is_halo) {
-                const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ p.rule.s0);
-                const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
+                const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ varco_key0(p.rule));
+                const uint32_t h2 = varco_mix32(h1 ^ varco_key1(p.rule));
                 mab = uint32_t(lunits[__umulhi(h2, p.rule.n_units)]) | (__umulhi(h1, p.rule.width) << 16);
             }
         } else {
@@ -379,8 +379,8 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs<T> p)
         const uint64_t hmask = __ballot(is_halo);
         uint32_t mab = 0;
         if (is_halo) {
-            const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ p.rule.s0);
-            const uint32_t h2 = varco_mix32(h1 ^ p.rule.s1);
+            const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ varco_key0(p.rule));
+            const uint32_t h2 = varco_mix32(h1 ^ varco_key1(p.rule));
             mab = uint32_t(lunits[__umulhi(h2, p.rule.n_units)]) | (__umulhi(h1, p.rule.width) << 16);
         }
         const int cnt = min(64, it.e1 - base);

@@ -20,13 +20,17 @@ __device__ __forceinline__ uint32_t varco_mod_width(uint32_t x, uint32_t width, 
     return r >= width ? r - width : r;
 }
 
+// The two key words of the rule's step, layer and hop: kernel arguments, or the device-resident step table.
+__device__ __forceinline__ uint32_t varco_key0(const MaskRule& rule) { return rule.words ? rule.words[0] : rule.s0; }
+__device__ __forceinline__ uint32_t varco_key1(const MaskRule& rule) { return rule.words ? rule.words[1] : rule.s1; }
+
 struct MaskAffine {
     uint32_t a, b, a_inv;
 };
 
 __device__ __forceinline__ MaskAffine varco_affine(const MaskRule& rule, uint32_t gid) {
-    const uint32_t h1 = varco_mix32(gid ^ rule.s0);
-    const uint32_t h2 = varco_mix32(h1 ^ rule.s1);
+    const uint32_t h1 = varco_mix32(gid ^ varco_key0(rule));
+    const uint32_t h2 = varco_mix32(h1 ^ varco_key1(rule));
     const uint32_t u = __umulhi(h2, rule.n_units);
     MaskAffine m;
     m.b = __umulhi(h1, rule.width);

@@ -47,7 +47,7 @@ struct Workspace {
     float* prod = nullptr;      size_t prod_elems = 0;      // halo-gradient products: (halo entries) x k elements
     float* w = nullptr;         size_t w_elems = 0;         // bf16 copies of the two weights of a layer call
 };
-constexpr int kMaxStreams = 4;
+constexpr int kMaxStreams = 8;
 
 std::mutex g_err_mutex;
 std::string g_global_error;
@@ -60,6 +60,8 @@ struct varco_ctx {
     std::vector<int32_t> widths, act;
     std::vector<LayerState> layers;
     std::vector<PartState> parts;
+    uint64_t* d_step = nullptr;      // device-resident step state (varco_step_table_enable), or null
+    uint32_t* d_table = nullptr;     // its key words: 2 per tap address
     Workspace ws[kMaxStreams];
     size_t need_dm = 0, need_spmm = 0, need_gemm = 0, need_w = 0;   // what the registered partitions ask for
     varco_stats stats{};
@@ -123,6 +125,7 @@ MaskRule make_rule(const varco_ctx* ctx, int32_t layer, int32_t hop = 0) {
     r.width_magic = r.width == 1 ? 0xFFFFFFFFu : uint32_t((uint64_t(1) << 32) / r.width);
     r.units = ls.units;
     r.units_inv = ls.units_inv;
+    r.words = ctx->d_table ? ctx->d_table + 2 * (layer + VARCO_MAX_LAYERS * hop) : nullptr;
     return r;
 }
 
@@ -133,6 +136,7 @@ MaskRule full_rule(int32_t width) {
     r.k = uint32_t(width);
     r.n_units = 1;
     r.width_magic = width == 1 ? 0xFFFFFFFFu : uint32_t((uint64_t(1) << 32) / uint32_t(width));
+    r.words = nullptr;
     return r;
 }
 
@@ -261,7 +265,7 @@ int32_t workspace_for(varco_ctx* ctx, hipStream_t st, Workspace** out) {
                 ws = &w;
                 break;
             }
-        if (!ws) return varco_fail(ctx, VARCO_ERR_STATE, "layer calls were issued on more streams than the context supports (4)");
+        if (!ws) return varco_fail(ctx, VARCO_ERR_STATE, "layer calls were issued on more streams than the context supports (8)");
         ws->used = true;
         ws->stream = st;
     }
@@ -382,6 +386,8 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     for (Workspace& w : ctx->ws)
         for (float* p : {w.dm, w.spmm, w.gemm, w.prod, w.w})
             if (p) (void)hipFree(p);
+    if (ctx->d_step) (void)hipFree(ctx->d_step);
+    if (ctx->d_table) (void)hipFree(ctx->d_table);
     for (hipEvent_t e : ctx->prof.events) (void)hipEventDestroy(e);
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
     delete ctx;
@@ -480,8 +486,39 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
 
 extern "C" int32_t varco_begin_step(varco_ctx* ctx, uint64_t step) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_begin_step: null context");
+    if (ctx->d_table)
+        return varco_fail(ctx, VARCO_ERR_STATE, "varco_begin_step: the step lives on the device; use varco_set_step or varco_advance_step");
     ctx->step = step;
     for (LayerState& ls : ctx->layers) ls.ran_forward = false;
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_step_table_enable(varco_ctx* ctx, varco_stream stream) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_step_table_enable: null context");
+    if (!ctx->d_table) {
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_step), sizeof(uint64_t)));
+        VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_table),
+                                 2 * VARCO_MAX_LAYERS * VARCO_MAX_LAYERS * sizeof(uint32_t)));
+    }
+    VARCO_HIP(ctx, varco_launch_step_table(ctx->d_step, ctx->d_table, ctx->key, 1, ctx->step, static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_set_step(varco_ctx* ctx, uint64_t step, varco_stream stream) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_set_step: null context");
+    ctx->step = step;
+    for (LayerState& ls : ctx->layers) ls.ran_forward = false;
+    if (ctx->d_table)
+        VARCO_HIP(ctx, varco_launch_step_table(ctx->d_step, ctx->d_table, ctx->key, 1, step, static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_advance_step(varco_ctx* ctx, varco_stream stream) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_advance_step: null context");
+    if (!ctx->d_table) return varco_fail(ctx, VARCO_ERR_STATE, "varco_advance_step: call varco_step_table_enable first");
+    ctx->step += 1;
+    for (LayerState& ls : ctx->layers) ls.ran_forward = false;
+    VARCO_HIP(ctx, varco_launch_step_table(ctx->d_step, ctx->d_table, ctx->key, 0, 0, static_cast<hipStream_t>(stream)));
     return VARCO_OK;
 }
 

@@ -75,6 +75,7 @@ struct MaskRule {
     uint32_t width_magic;       // floor(2^32 / width), 0xFFFFFFFF for width 1
     const uint16_t* units;      // device: ascending multipliers coprime with width
     const uint16_t* units_inv;  // device: their inverses modulo width
+    const uint32_t* words;      // device, or null: when set, (s0, s1) are read from here instead (step table)
 };
 
 // One unit of SpMM work: entries [e0, e1) of CSR row `row`; dst < 0 writes the output row directly, else
@@ -114,6 +115,11 @@ hipError_t varco_launch_accumulate_returned(int dtype, const MaskRule& rule, con
 
 hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 hipError_t varco_launch_sum_gradients(float* dst, const float* src, int64_t n, hipStream_t stream);
+
+// Device-resident step state: *d_step = the step (set to `value` when set != 0, else incremented), and
+// table[2 t], table[2 t + 1] = the two key words of tap address t (0 .. 255) for that step and `key`.
+hipError_t varco_launch_step_table(uint64_t* d_step, uint32_t* table, uint64_t key, int set, uint64_t value,
+                                   hipStream_t stream);
 
 hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
                                     const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream);

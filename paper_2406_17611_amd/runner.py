@@ -94,17 +94,25 @@ class PartitionedNetwork:
 
     @staticmethod
     def _join(streams):
-        """Every stream waits for everything issued so far on all of them."""
+        """Every stream waits for everything issued so far on all of them. Written as fork - join - fork from the
+        first stream, so that under graph capture every event is recorded on a stream that is already part of the
+        capture."""
         if len(streams) == 1:
             return
-        events = []
-        for st in streams:
+        main, others = streams[0], streams[1:]
+
+        def fork():
+            e = torch.cuda.Event()
+            e.record(main)
+            for st in others:
+                st.wait_event(e)
+
+        fork()
+        for st in others:
             e = torch.cuda.Event()
             e.record(st)
-            events.append(e)
-        for st in streams:
-            for e in events:
-                st.wait_event(e)
+            main.wait_event(e)
+        fork()
 
     # ------------------------------------------------------------------ data placement
     def rows(self, q):
@@ -149,7 +157,10 @@ class PartitionedNetwork:
         """Forward of all layers and partitions for training step `step`. `ratio` = (num, den) for every layer
         or a list of per-layer pairs: Algorithm 1 updates the rate at the step boundary."""
         ctx = self.ctx
-        ctx.begin_step(step)
+        if step is None:
+            ctx.advance_step(stream)        # the step lives on the device (graph replay): next step
+        else:
+            ctx.set_step(step, stream)
         if ratio is not None:
             if isinstance(ratio[0], (tuple, list)):
                 for l, (num, den) in enumerate(ratio):
@@ -255,6 +266,25 @@ class PartitionedNetwork:
         self.sgd(lr, stream)
         return totals
 
+    # ------------------------------------------------------------------ HIP graph of one step
+    def capture_step(self, ratio):
+        """Captures "advance to the next step, forward, backward" at a fixed ratio into a HIP graph and returns it
+        (torch.cuda.CUDAGraph): every replay() is one more step, without per-launch host work. The step counter
+        and the key words of the kept positions live on the device from here on (varco_step_table_enable); the
+        ratio, i.e. every k, is frozen into the graph. Set the step the first replay should follow with
+        ctx.set_step(step). Host-side exchange counters do not see replays."""
+        side = torch.cuda.Stream(device=self.device)
+        side.wait_stream(torch.cuda.current_stream(self.device))
+        with torch.cuda.stream(side):
+            self.ctx.step_table_enable()
+            self.step(None, ratio)          # warm-up on the capture stream: its workspace set and all buffers exist
+        torch.cuda.current_stream(self.device).wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            self.step(None, ratio)
+        return graph
+
     def zero_grads(self):
         for l in range(self.L):
             self.dh1[l].zero_()
@@ -298,7 +328,7 @@ class KTapNetwork(PartitionedNetwork):
 
     def forward(self, step: int, ratio=None, stream=None):
         ctx = self.ctx
-        ctx.begin_step(step)
+        ctx.set_step(step, stream)
         if ratio is not None:
             ctx.set_ratio(-1, ratio[0], ratio[1])
         self._ensure_buffers()

@@ -95,6 +95,9 @@ def main():
     ap.add_argument("--ratio", default=None, help="num/den, default: the configuration's ratio")
     ap.add_argument("--streams", type=int, default=1,
                     help="HIP streams the partitions of a layer are dealt to (kernels of different partitions overlap)")
+    ap.add_argument("--matmul-terms", type=int, default=None, choices=[0, 2, 3],
+                    help="fp32 storage only: form of the dense products (library default 3; 0 = fp32 matrix instructions; "
+                         "2 = lower precision, not a valid headline setting)")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a HIP graph (no per-launch host work; per-kernel timing is not available)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -133,6 +136,8 @@ def main():
     t0 = time.time()
     L = len(w.widths) - 1
     net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY, dtype=w.dtype, n_streams=args.streams)
+    if args.matmul_terms is not None:
+        net.ctx.set_matmul_terms(args.matmul_terms)
     net.set_inputs(synth.features(g.n, w.widths[0], synth.SEED_FEAT))
     net.set_weights([synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l) for l in range(L)],
                     [synth.glorot(w.widths[l], w.widths[l + 1], synth.SEED_WEIGHT, 2 * l + 1) for l in range(L)])
@@ -192,7 +197,12 @@ def main():
                  "avg_launch_ms": avg_ms}
         if name in MFMA_CLASSES:
             ach = p["flops"] / p["ms"] / 1e9
-            peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_FP32_PEAK_TFLOPS
+            if w.dtype == "bf16":
+                peak = MFMA_BF16_PEAK_TFLOPS
+            else:
+                # fp32 products from bf16 terms: 6 (3) bf16 matrix instructions per algorithmic product-sum
+                terms = 3 if args.matmul_terms is None else args.matmul_terms
+                peak = {0: MFMA_FP32_PEAK_TFLOPS, 3: MFMA_BF16_PEAK_TFLOPS / 6, 2: MFMA_BF16_PEAK_TFLOPS / 3}[terms]
             entry.update(bound="mfma", achieved=ach, peak=peak, unit="TFLOP/s", frac=ach / peak)
         else:
             ach = p["bytes"] / p["ms"] / 1e6
@@ -219,6 +229,7 @@ def main():
                    "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
                    "keep": [net.ctx.keep(l) for l in range(L)], "layers": L, "streams": args.streams,
                    "hip_graph": bool(args.graph),
+                   "matmul_terms": (3 if args.matmul_terms is None else args.matmul_terms) if w.dtype == "f32" else None,
                    "edges_counted_per_step": edges_per_step},
         "roofline": roofline,
         "kernels": kernels,

@@ -154,6 +154,17 @@ int32_t varco_step_table_enable(varco_ctx* ctx, varco_stream stream);
 int32_t varco_set_step(varco_ctx* ctx, uint64_t step, varco_stream stream);
 int32_t varco_advance_step(varco_ctx* ctx, varco_stream stream);
 
+/* How the dense products of eq. (2) (X H, and the two gradient products) are formed for fp32 storage
+ * (the paper fixes no arithmetic; VARCO_BF16 contexts ignore this). terms = 3 (the default): each fp32 operand
+ * is written exactly as a sum of three bf16 numbers and the six largest cross products are formed on the bf16
+ * matrix units with fp32 accumulation; the dropped products are below 2^-24 of each full product, so the result
+ * has the accuracy of fp32 arithmetic at well under half the cost. terms = 0: fp32 matrix instructions
+ * throughout (also used, whatever the setting, for shapes the expanded form cannot take: rows not 16-byte
+ * aligned). terms = 2: two terms, three products, relative error about 2^-16 per product (a faster,
+ * lower-precision setting nothing in this library selects by itself). INVALID_ARG for other values. Takes
+ * effect from the next call on. */
+int32_t varco_set_matmul_terms(varco_ctx* ctx, int32_t terms);
+
 /* Section IV / Algorithm 1 (the step that updates the compression rate): ratio r = num/den >= 1 of layer `layer`'s input
  * (-1 = every layer). k = max(1, ceil(width*den/num)); r = 1 keeps everything (lossless). den = 0 (num >= 1)
  * is the unbounded ratio, k = 0: nothing of that layer's input is exchanged, forward or backward (the

@@ -351,6 +351,12 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
         if (e != hipSuccess || split <= 1) return e;
         return launch_reduce(ga, split, stream, tag);
     }
+    if (varco_gemm_split_usable(ga)) {
+        int32_t split = 1;
+        const hipError_t e = varco_launch_gemm_split(ga, stream, tag, &split);
+        if (e != hipSuccess || split <= 1) return e;
+        return launch_reduce(ga, split, stream, tag);
+    }
     // A is M x K: k-contiguous as stored unless transposed. B is K x N: k-contiguous only when transposed.
     const bool a_kc = !ga.a.transposed, b_kc = ga.b.transposed;
     const bool a_gate = ga.a.gate != nullptr, b_gate = ga.b.gate != nullptr;

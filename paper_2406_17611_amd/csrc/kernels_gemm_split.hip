@@ -1,0 +1,604 @@
+// Dense feature transform of eq. (2) and its gradients for fp32-stored activations, computed on the bf16
+// matrix cores from exact bf16 expansions of the fp32 operands:
+//     x = x0 + x1 + x2,   x0 = bf16(x), x1 = bf16(x - x0), x2 = bf16(x - x0 - x1)
+// (each difference is exact in fp32, and three 8-bit significands cover the 24 bits of x), so
+//     a * b = a0 b0 + (a0 b1 + a1 b0) + (a1 b1 + a0 b2 + a2 b0) + terms below 2^-24 |a b|.
+// The six kept products are exact in the fp32 accumulators of v_mfma_f32_32x32x16_bf16, which leaves the
+// result with the accuracy of an fp32 product-sum; six bf16 instructions cost 6/16 of the fp32 matrix
+// instructions that cover the same reduction steps. TERMS = 2 keeps x0 + x1 and three products (relative
+// error about 2^-16 per product); the library does not use it by default.
+//
+// One 256-thread workgroup (4 wavefronts) computes a 128 x 128 tile of C (128 x 64 for outputs at most 64
+// columns wide), a wavefront 64 x 64 (32 x 64). Two workgroups share a compute unit, so that one's
+// conversions and LDS writes overlap the other's matrix instructions. A tile of 32 reduction steps is
+// fetched into registers while the previous one is multiplied, then expanded and written to LDS as TERMS
+// planes of bf16 rows (one output index per row, reduction index contiguous, 80-byte pitch).
+//   "NT" products (transform, input gradient): A has the reduction index contiguous and is expanded here;
+//        B is the library's own expanded copy of the weights (varco_launch_prep_weight_split), zero-padded
+//        to whole tiles and copied as is.
+//   "TN" products (weight gradient, reduction over nodes): both operands have the node index as the slow
+//        one; a thread loads an 8 (nodes) x 4 (columns) block with eight 16-byte loads, expands it, transposes
+//        it in registers and writes four 16-byte LDS rows per plane. Half the threads serve A, half B.
+// The ReLU mask of the backward pass is applied before the expansion, the activation in the epilogue.
+#include <type_traits>
+
+#include "elem.h"
+#include "varco_internal.h"
+
+namespace {
+
+constexpr int BK = 32;
+constexpr int kThreads = 256;
+constexpr int kPitch = BK + 8;   // bf16 elements per LDS row (80 bytes)
+constexpr int kPrepRows = 128;   // expanded weight copies are padded to this many rows (the widest B tile) and to BK columns
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct SplitOperand {
+    const void* ptr;      // fp32 matrix, or the expanded bf16 copy of a weight matrix
+    const float* gate;
+    int64_t ld;
+    int64_t plane;        // elements between the planes of an expanded copy
+};
+
+struct SplitGemm {
+    int32_t m, n, k, k2;
+    SplitOperand a, b, a2, b2;
+    float* c;
+    int64_t ldc;
+    int32_t accumulate, relu;
+    int32_t split_k, tiles_per_split;
+    float* partial;
+    int32_t tiles_m, tiles_n;
+    int32_t inner, outer;            // tiles along the fast and the slow direction of the workgroup order
+    int32_t pair_inner;              // the two tiles of a workgroup are neighbours along the fast (1) or slow (0) direction
+    int32_t inner_units, outer_units;   // workgroups along either direction
+};
+
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values rounded to bf16 (nearest even) by one packed conversion; `lo` in the low half.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const floatx2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Expansion of two fp32 values: w[p] holds term p of both (x0 in the low half).
+template <int TERMS>
+__device__ __forceinline__ void expand_pair(float x0, float x1, uint32_t (&w)[TERMS]) {
+#pragma unroll
+    for (int p = 0; p < TERMS; ++p) {
+        w[p] = pack_bf16(x0, x1);
+        if (p + 1 < TERMS) {
+            x0 -= __uint_as_float(w[p] << 16);
+            x1 -= __uint_as_float(w[p] & 0xFFFF0000u);
+        }
+    }
+}
+
+__device__ __forceinline__ float4 gate4(float4 x, float4 y) {
+    x.x = y.x > 0.f ? x.x : 0.f, x.y = y.y > 0.f ? x.y : 0.f;
+    x.z = y.z > 0.f ? x.z : 0.f, x.w = y.w > 0.f ? x.w : 0.f;
+    return x;
+}
+
+// Consecutive groups of lanes write consecutive tile rows; with an 80-byte pitch rows r and r + 1 overlap in
+// four LDS banks while rows r and r + 4 tile all of them, so the q-th row group of a wavefront goes to row
+// (q with its low three bits rotated): 0 4 1 5 2 6 3 7.
+__device__ __forceinline__ int tile_row(int q) { return (q & ~7) | ((q & 1) << 2) | ((q >> 1) & 3); }
+
+template <typename T>
+__device__ __forceinline__ T load_at(const void* base, uint32_t byte_offset) {
+    return *reinterpret_cast<const T*>(static_cast<const char*>(base) + byte_offset);
+}
+
+// ---- fp32 operand with the reduction index contiguous: chunks of CH floats ----
+// Addresses are a per-tile base (uniform) plus a 32-bit offset per chunk that does not change along the
+// reduction. Rows beyond the matrix are clamped to its last row (their results are never stored); chunks
+// beyond the reduction length re-read the tile's first chunk of the same row, and meet zeros in B.
+template <int ROWS, int CH, bool GATE>
+struct RowRegs {
+    static constexpr int PER_ROW = BK / CH;
+    static constexpr int N = ROWS * PER_ROW / kThreads;
+    float4 v[N][CH / 4];
+    float4 g[GATE ? N : 1][CH / 4];
+};
+
+template <int ROWS, int CH>
+struct RowPlan {
+    static constexpr int PER_ROW = BK / CH;
+    static constexpr int N = ROWS * PER_ROW / kThreads;
+    uint32_t off[N];     // bytes from the tile base
+    __device__ __forceinline__ void init(int tid, int32_t i0, int32_t extent, int64_t ld) {
+#pragma unroll
+        for (int h = 0; h < N; ++h) {
+            const int c = tid + h * kThreads;
+            const int32_t r = min(tile_row(c / PER_ROW), extent - 1 - i0);
+            off[h] = uint32_t(r * ld + (c % PER_ROW) * CH) * 4u;
+        }
+    }
+};
+
+template <int ROWS, int CH, bool GATE>
+__device__ __forceinline__ void load_rows(int tid, const float* base, const float* gate, const RowPlan<ROWS, CH>& plan,
+                                          int32_t k_left, RowRegs<ROWS, CH, GATE>& r) {
+    using R = RowRegs<ROWS, CH, GATE>;
+#pragma unroll
+    for (int h = 0; h < R::N; ++h) {
+        const int kc = ((tid + h * kThreads) % R::PER_ROW) * CH;
+        const uint32_t off = kc < k_left ? plan.off[h] : plan.off[h] - uint32_t(kc) * 4u;   // k_left is a multiple of CH
+#pragma unroll
+        for (int u = 0; u < CH / 4; ++u) {
+            r.v[h][u] = load_at<float4>(base, off + 16u * u);
+            if (GATE) r.g[h][u] = load_at<float4>(gate, off + 16u * u);
+        }
+    }
+}
+
+template <int TERMS, int ROWS, int CH, bool GATE>
+__device__ __forceinline__ void store_rows(int tid, const RowRegs<ROWS, CH, GATE>& r, uint16_t* s) {
+    using R = RowRegs<ROWS, CH, GATE>;
+#pragma unroll
+    for (int h = 0; h < R::N; ++h) {
+        const int c = tid + h * kThreads;
+        uint32_t w[CH / 2][TERMS];
+#pragma unroll
+        for (int u = 0; u < CH / 4; ++u) {
+            float4 x = r.v[h][u];
+            if (GATE) x = gate4(x, r.g[h][u]);
+            expand_pair<TERMS>(x.x, x.y, w[2 * u]);
+            expand_pair<TERMS>(x.z, x.w, w[2 * u + 1]);
+        }
+        uint16_t* dst = s + tile_row(c / R::PER_ROW) * kPitch + (c % R::PER_ROW) * CH;
+#pragma unroll
+        for (int p = 0; p < TERMS; ++p) {
+            if constexpr (CH == 8)
+                *reinterpret_cast<uint4*>(dst + p * ROWS * kPitch) = make_uint4(w[0][p], w[1][p], w[2][p], w[3][p]);
+            else
+                *reinterpret_cast<uint2*>(dst + p * ROWS * kPitch) = make_uint2(w[0][p], w[1][p]);
+        }
+    }
+}
+
+// ---- expanded bf16 weight copy [term][row][pitch]: chunks of 8 elements, copied unchanged ----
+// The copy is zero-padded to whole tiles (rows to kPrepRows, pitch to BK), so no chunk needs a bounds check.
+template <int TERMS, int ROWS>
+struct PrepRegs {
+    static constexpr int PER_ROW = BK / 8;
+    static constexpr int N = TERMS * ROWS * PER_ROW / kThreads;
+    uint4 v[N];
+};
+
+template <int TERMS, int ROWS>
+struct PrepPlan {
+    static constexpr int PER_ROW = BK / 8;
+    static constexpr int N = TERMS * ROWS * PER_ROW / kThreads;
+    uint32_t off[N];     // bytes from the tile base
+    __device__ __forceinline__ void init(int tid, int64_t pitch, int64_t plane) {
+#pragma unroll
+        for (int h = 0; h < N; ++h) {
+            const int c = tid + h * kThreads;
+            const int p = c / (ROWS * PER_ROW), rc = c % (ROWS * PER_ROW);
+            off[h] = uint32_t(p * plane + tile_row(rc / PER_ROW) * pitch + (rc % PER_ROW) * 8) * 2u;
+        }
+    }
+};
+
+template <int TERMS, int ROWS>
+__device__ __forceinline__ void load_prep(const uint16_t* base, const PrepPlan<TERMS, ROWS>& plan, PrepRegs<TERMS, ROWS>& r) {
+#pragma unroll
+    for (int h = 0; h < PrepRegs<TERMS, ROWS>::N; ++h) r.v[h] = load_at<uint4>(base, plan.off[h]);
+}
+
+template <int TERMS, int ROWS>
+__device__ __forceinline__ void store_prep(int tid, const PrepRegs<TERMS, ROWS>& r, uint16_t* s) {
+    using R = PrepRegs<TERMS, ROWS>;
+#pragma unroll
+    for (int h = 0; h < R::N; ++h) {
+        const int c = tid + h * kThreads;
+        const int p = c / (ROWS * R::PER_ROW), rc = c % (ROWS * R::PER_ROW);
+        *reinterpret_cast<uint4*>(s + p * ROWS * kPitch + tile_row(rc / R::PER_ROW) * kPitch + (rc % R::PER_ROW) * 8) = r.v[h];
+    }
+}
+
+// ---- fp32 operand with the output index contiguous: one 8 (reduction) x 4 (output) block per thread ----
+// Block b of an operand's tile covers reduction steps 8 * (b % 4) .. + 7 and output indices 4 * (b / 4) .. + 3:
+// eight consecutive lanes then write two LDS rows that are four rows apart, all four 16-byte chunks of each,
+// which touches every LDS bank once. Output indices beyond the matrix are clamped (their results are never
+// stored). In the last, partial tile of the reduction the node index is clamped and A is zeroed beyond it.
+// (HAS_GATE: the kernel masks one of its operands; GATE below: this operand is the masked one.)
+template <bool HAS_GATE>
+struct ColRegs {
+    float4 v[8];
+    float4 g[HAS_GATE ? 8 : 1];
+};
+
+__device__ __forceinline__ uint32_t col_offset(int b, int32_t i0, int32_t extent) {
+    return uint32_t(min(i0 + (b >> 2) * 4, extent - 4) - i0) * 4u;      // bytes; extent is a multiple of 4
+}
+
+template <bool GATE, bool TAIL, bool ZERO, bool HAS_GATE>
+__device__ __forceinline__ void load_cols(const float* base, const float* gate, int b, uint32_t col_off, uint32_t ld_bytes,
+                                          int32_t k_left, ColRegs<HAS_GATE>& r) {
+    const int kb = (b & 3) * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const int node = TAIL ? min(kb + kk, k_left - 1) : kb + kk;
+        const uint32_t off = uint32_t(node) * ld_bytes + col_off;
+        r.v[kk] = load_at<float4>(base, off);
+        if (GATE) r.g[kk] = load_at<float4>(gate, off);
+        if (TAIL && ZERO && kb + kk >= k_left) r.v[kk] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+
+template <int TERMS, int ROWS, bool GATE, bool HAS_GATE>
+__device__ __forceinline__ void store_cols(const ColRegs<HAS_GATE>& r, int b, uint16_t* s) {
+    uint32_t w[8][2][TERMS];                                  // [reduction step][output pair][term]
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        float4 x = r.v[kk];
+        if (GATE) x = gate4(x, r.g[kk]);
+        expand_pair<TERMS>(x.x, x.y, w[kk][0]);
+        expand_pair<TERMS>(x.z, x.w, w[kk][1]);
+    }
+    uint16_t* base = s + (b >> 2) * 4 * kPitch + (b & 3) * 8;
+#pragma unroll
+    for (int p = 0; p < TERMS; ++p) {
+#pragma unroll
+        for (int ii = 0; ii < 4; ++ii) {                      // output index i + ii: its 8 reduction steps
+            uint32_t o[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t e0 = w[2 * q][ii >> 1][p], e1 = w[2 * q + 1][ii >> 1][p];
+                o[q] = (ii & 1) ? ((e0 >> 16) | (e1 & 0xFFFF0000u)) : ((e0 & 0xFFFFu) | (e1 << 16));
+            }
+            *reinterpret_cast<uint4*>(base + p * ROWS * kPitch + ii * kPitch) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+    }
+}
+
+__device__ __forceinline__ bf16x8 fragment(const uint16_t* s, int row, int koff) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(s + row * kPitch + koff));
+}
+
+template <int TMB, int TNB, int PA, int PB>
+__device__ __forceinline__ void multiply(const bf16x8 (&fa)[3][TMB], const bf16x8 (&fb)[3][TNB], floatx16 (&acc)[TMB][TNB]) {
+#pragma unroll
+    for (int i = 0; i < TMB; ++i)
+#pragma unroll
+        for (int j = 0; j < TNB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[PA][i], fb[PB][j], acc[i][j], 0, 0, 0);
+}
+
+// All wavefronts of the workgroup meet here (same fences as __syncthreads); the two halves of a workgroup call
+// it from different places, always the same number of times.
+__device__ __forceinline__ void workgroup_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+// TN: both operands stored with the output index contiguous (weight gradient), else A with the reduction
+// index contiguous and B an expanded weight copy. WM x WN wavefronts per tile, each TMB x TNB blocks of
+// 32 x 32. A_CH: floats per chunk of A (NT only). GATE masks A (NT) or B (TN).
+//
+// A workgroup is two groups of four wavefronts, each with a tile and LDS buffers of its own, that alternate
+// between two phases half a step apart: while one group multiplies the fragments of its current tile, the
+// other waits for its next tile's global loads, expands them and writes them to LDS. A compute unit's four
+// SIMDs each hold one wavefront of either group, so the matrix cores always have a wavefront in its multiply
+// phase while the conversions, LDS writes and load latency of the other are hidden behind it.
+template <int TERMS, bool TN, int WM, int WN, int TMB, int TNB, int A_CH, bool GATE>
+__global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g) {
+    static_assert(TERMS == 2 || TERMS == 3, "two or three bf16 terms per operand");
+    constexpr int BM = 32 * TMB * WM, BN = 32 * TNB * WN;
+    static_assert(BM + BN <= kThreads, "one 8 x 4 block per thread in the TN layout");
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2][TERMS * (BM + BN) * kPitch];
+    const int grp = threadIdx.x / kThreads, tid = threadIdx.x % kThreads;
+    uint16_t* const sa = smem[grp];
+    uint16_t* const sb = smem[grp] + TERMS * BM * kPitch;
+
+    // workgroup -> pair of tiles: tiles that share streamed data go to one XCD (workgroups are dealt to the 8
+    // XCDs round-robin), so that the streamed operand is fetched into a single L2
+    const int32_t xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+    const int32_t in_u = within % g.inner_units, out_u = (within / g.inner_units) * 8 + xcd;
+    if (out_u >= g.outer_units) return;        // whole workgroup leaves together: no barrier is skipped
+    const int32_t tiles1 = (g.k + BK - 1) / BK;
+    const int32_t tiles2 = (g.k2 + BK - 1) / BK;
+    // tile and range of reduction tiles of either group (a group without a tile has an empty range)
+    auto tile_of = [&](int which, int32_t& in, int32_t& out, int32_t& t_begin, int32_t& t_end) {
+        in = g.pair_inner ? in_u * 2 + which : in_u;
+        out = g.pair_inner ? out_u : out_u * 2 + which;
+        t_begin = 0, t_end = tiles1 + tiles2;
+        if (g.split_k > 1) {
+            t_begin = out * g.tiles_per_split;
+            t_end = min(t_end, t_begin + g.tiles_per_split);
+        }
+        if (in >= g.inner || out >= g.outer) in = 0, out = 0, t_begin = 0, t_end = 0;
+    };
+    int32_t in, out, t_begin, t_end, o_in, o_out, o_begin, o_end;
+    tile_of(grp, in, out, t_begin, t_end);
+    tile_of(grp ^ 1, o_in, o_out, o_begin, o_end);
+    const int32_t my_steps = max(t_end - t_begin, 0);
+    const int32_t steps = max(my_steps, max(o_end - o_begin, 0));      // the same number in both groups
+    int32_t tm, tn, z;
+    if (g.split_k > 1) {
+        z = out, tm = in / g.tiles_n, tn = in % g.tiles_n;
+    } else {
+        z = 0, tm = out, tn = in;
+    }
+    const int32_t m0 = tm * BM, n0 = tn * BN;
+
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = (wave / WN) * (32 * TMB), wn = (wave % WN) * (32 * TNB);
+    const int lrow = lane & 31, lk = lane >> 5;
+
+    floatx16 acc[TMB][TNB];
+#pragma unroll
+    for (int i = 0; i < TMB; ++i)
+#pragma unroll
+        for (int j = 0; j < TNB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // staging registers and per-thread offsets of the two layouts (only one set is used per instantiation)
+    RowRegs<BM, A_CH, GATE && !TN> ra;
+    PrepRegs<TERMS, BN> rb;
+    ColRegs<GATE && TN> cr;           // a thread serves A or B, never both
+    RowPlan<BM, A_CH> plan_a;
+    PrepPlan<TERMS, BN> plan_b;
+    const bool serves_a = tid < BM, serves_b = tid >= BM && tid < BM + BN;   // TN: uniform per wavefront
+    uint32_t col_off = 0;
+    if constexpr (TN) {
+        if (serves_a) col_off = col_offset(tid, m0, g.m);
+        if (serves_b) col_off = col_offset(tid - BM, n0, g.n);
+    } else {
+        plan_a.init(tid, m0, g.m, g.a.ld);        // a chained second product has the same leading dimensions
+        plan_b.init(tid, g.b.ld, g.b.plane);
+    }
+
+    auto fetch = [&](int32_t t) {
+        const bool first = t < tiles1;
+        const int32_t k0 = (first ? t : t - tiles1) * BK, k_left = (first ? g.k : g.k2) - k0;
+        if constexpr (TN) {
+            const float* abase = static_cast<const float*>(g.a.ptr) + int64_t(k0) * g.a.ld + m0;
+            const float* bbase = static_cast<const float*>(g.b.ptr) + int64_t(k0) * g.b.ld + n0;
+            const float* gbase = GATE ? g.b.gate + int64_t(k0) * g.b.ld + n0 : nullptr;
+            const uint32_t lda = uint32_t(g.a.ld) * 4u, ldb = uint32_t(g.b.ld) * 4u;
+            if (k_left >= BK) {
+                if (serves_a) load_cols<false, false, false>(abase, nullptr, tid, col_off, lda, k_left, cr);
+                if (serves_b) load_cols<GATE, false, false>(bbase, gbase, tid - BM, col_off, ldb, k_left, cr);
+            } else {
+                if (serves_a) load_cols<false, true, true>(abase, nullptr, tid, col_off, lda, k_left, cr);
+                if (serves_b) load_cols<GATE, true, false>(bbase, gbase, tid - BM, col_off, ldb, k_left, cr);
+            }
+        } else {
+            const float* abase = static_cast<const float*>(first ? g.a.ptr : g.a2.ptr) + int64_t(m0) * g.a.ld + k0;
+            const float* gbase = GATE ? g.a.gate + int64_t(m0) * g.a.ld + k0 : nullptr;   // never with a second product
+            const uint16_t* bbase = static_cast<const uint16_t*>(first ? g.b.ptr : g.b2.ptr) + int64_t(n0) * g.b.ld + k0;
+            load_rows<BM, A_CH, GATE>(tid, abase, gbase, plan_a, k_left, ra);
+            load_prep<TERMS, BN>(bbase, plan_b, rb);
+        }
+    };
+    auto stash = [&]() {
+        if constexpr (TN) {
+            if (serves_a) store_cols<TERMS, BM, false>(cr, tid, sa);
+            if (serves_b) store_cols<TERMS, BN, GATE>(cr, tid - BM, sb);
+        } else {
+            store_rows<TERMS, BM, A_CH, GATE>(tid, ra, sa);
+            store_prep<TERMS, BN>(tid, rb, sb);
+        }
+    };
+    auto compute = [&]() {
+        // the multiplying wavefront goes first on its SIMD: the other group's conversions fill the gaps
+        __builtin_amdgcn_s_setprio(3);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            const int koff = s * 16 + lk * 8;
+            bf16x8 fa[3][TMB], fb[3][TNB];
+#pragma unroll
+            for (int p = 0; p < TERMS; ++p) {
+#pragma unroll
+                for (int i = 0; i < TMB; ++i) fa[p][i] = fragment(sa + p * BM * kPitch, wm + i * 32 + lrow, koff);
+#pragma unroll
+                for (int j = 0; j < TNB; ++j) fb[p][j] = fragment(sb + p * BN * kPitch, wn + j * 32 + lrow, koff);
+            }
+            multiply<TMB, TNB, 0, 0>(fa, fb, acc);
+            multiply<TMB, TNB, 0, 1>(fa, fb, acc);
+            multiply<TMB, TNB, 1, 0>(fa, fb, acc);
+            if constexpr (TERMS == 3) {
+                multiply<TMB, TNB, 1, 1>(fa, fb, acc);
+                multiply<TMB, TNB, 0, 2>(fa, fb, acc);
+                multiply<TMB, TNB, 2, 0>(fa, fb, acc);
+            }
+        }
+        __builtin_amdgcn_s_setprio(0);
+    };
+
+    // Barrier k (k = 1, 2, ...) ends phase k. Group 0 writes tile `it` to LDS in phase 2 it + 1 and multiplies
+    // it in phase 2 it + 2; group 1 does the same one phase later. Both groups pass 2 steps + 1 barriers.
+    if (my_steps > 0) fetch(t_begin);
+    if (grp == 1) workgroup_barrier();
+    for (int32_t it = 0; it < steps; ++it) {
+        if (it < my_steps) {
+            stash();
+            if (it + 1 < my_steps) fetch(t_begin + it + 1);
+        }
+        workgroup_barrier();
+        if (it < my_steps) compute();
+        workgroup_barrier();   // the tile's fragments have been read: the next one may overwrite them
+    }
+    if (grp == 0) workgroup_barrier();
+    if (my_steps == 0) return;         // a group without a tile; no barrier follows
+
+    // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32)
+    const bool to_partial = g.split_k > 1;
+    float* pout = g.partial + int64_t(z) * g.m * g.n;
+#pragma unroll
+    for (int i = 0; i < TMB; ++i) {
+#pragma unroll
+        for (int j = 0; j < TNB; ++j) {
+            const int32_t col = n0 + wn + j * 32 + lrow;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                if (row < g.m && col < g.n) {
+                    float x = acc[i][j][v];
+                    if (to_partial) {
+                        pout[int64_t(row) * g.n + col] = x;
+                    } else {
+                        float* dst = g.c + int64_t(row) * g.ldc + col;
+                        if (g.accumulate) x += *dst;
+                        if (g.relu) x = fmaxf(x, 0.f);
+                        *dst = x;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// out[p][r][c] (bf16, `rows_padded` rows of `pitch` elements, zero beyond rows x cols) = term p of
+// (transpose ? h[c][r] : h[r][c]).
+template <int TERMS>
+__global__ __launch_bounds__(kThreads) void prep_weight_split_kernel(const float* __restrict__ h, int64_t ld, int32_t rows,
+                                                                     int32_t cols, int32_t rows_padded, int32_t pitch,
+                                                                     int32_t transpose, uint16_t* __restrict__ out) {
+    const int64_t idx = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t plane = int64_t(rows_padded) * pitch;
+    if (idx >= plane) return;
+    const int32_t r = int32_t(idx / pitch), c = int32_t(idx % pitch);
+    float x = 0.f;
+    if (r < rows && c < cols) x = transpose ? h[int64_t(c) * ld + r] : h[int64_t(r) * ld + c];
+#pragma unroll
+    for (int p = 0; p < TERMS; ++p) {
+        const uint16_t t = float_to_bf16(x);
+        out[p * plane + idx] = t;
+        x -= __uint_as_float(uint32_t(t) << 16);
+    }
+}
+
+bool aligned_to(const void* p, uintptr_t bytes) { return (reinterpret_cast<uintptr_t>(p) & (bytes - 1)) == 0; }
+
+template <class F>
+void with_flag(bool b, F&& f) {
+    if (b)
+        f(std::true_type{});
+    else
+        f(std::false_type{});
+}
+
+}  // namespace
+
+hipError_t varco_launch_prep_weight_split(int terms, const float* h, int64_t ld, int32_t rows, int32_t cols,
+                                          int32_t rows_padded, int32_t pitch, bool transpose, void* out, hipStream_t stream) {
+    const int64_t total = int64_t(rows_padded) * pitch;
+    if (total == 0) return hipSuccess;
+    if (terms != 2 && terms != 3) return hipErrorInvalidValue;
+    if (rows_padded < rows || rows_padded % kPrepRows != 0 || pitch < cols || pitch % BK != 0) return hipErrorInvalidValue;
+    const dim3 grid(unsigned((total + kThreads - 1) / kThreads));
+    if (terms == 3)
+        hipLaunchKernelGGL(prep_weight_split_kernel<3>, grid, dim3(kThreads), 0, stream, h, ld, rows, cols, rows_padded,
+                           pitch, transpose ? 1 : 0, static_cast<uint16_t*>(out));
+    else
+        hipLaunchKernelGGL(prep_weight_split_kernel<2>, grid, dim3(kThreads), 0, stream, h, ld, rows, cols, rows_padded,
+                           pitch, transpose ? 1 : 0, static_cast<uint16_t*>(out));
+    return hipGetLastError();
+}
+
+bool varco_gemm_split_usable(const GemmArgs& ga) {
+    if (ga.f32_terms != 2 && ga.f32_terms != 3) return false;
+    if (ga.m <= 0 || ga.n <= 0) return false;
+    if (ga.a.dtype != VARCO_F32 || ga.c_dtype != VARCO_F32) return false;
+    auto ok16 = [](const GemmOperand& o) { return aligned_to(o.ptr, 16) && aligned_to(o.gate, 16) && o.ld % 4 == 0; };
+    if (!ga.a.transposed) {   // NT: needs the library's expanded weight copy [term][rows][pitch], padded to whole tiles
+        auto prep_ok = [&](const void* p, int64_t ld, int64_t plane, int32_t k) {
+            return p && aligned_to(p, 16) && ld % BK == 0 && ld >= k && plane == (int64_t(ga.n) + kPrepRows - 1) / kPrepRows * kPrepRows * ld;
+        };
+        if (!prep_ok(ga.b_prep, ga.b_prep_ld, ga.b_prep_plane, ga.k)) return false;
+        if (ga.b.gate || ga.k % 4 != 0 || !ok16(ga.a)) return false;
+        if (ga.k2 > 0) {   // a chained product shares the first one's leading dimensions and is never masked
+            if (!prep_ok(ga.b2_prep, ga.b2_prep_ld, ga.b2_prep_plane, ga.k2) || ga.b2_prep_ld != ga.b_prep_ld) return false;
+            if (ga.k2 % 4 != 0 || !ok16(ga.a2) || ga.a2.ld != ga.a.ld || ga.a.gate || ga.a2.gate || ga.a2.dtype != VARCO_F32 ||
+                ga.a2.transposed)
+                return false;
+        }
+        return true;
+    }
+    // TN: weight gradient
+    if (ga.b.transposed || ga.b.dtype != VARCO_F32 || ga.k2 > 0 || ga.a.gate) return false;
+    return ok16(ga.a) && ok16(ga.b) && ga.m % 4 == 0 && ga.n % 4 == 0;
+}
+
+hipError_t varco_launch_gemm_split(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag, int32_t* split_used) {
+    const bool tn = ga.a.transposed;
+    const bool narrow = ga.n <= 64;
+    const int bm = 128, bn = narrow ? 64 : 128;
+    const bool a8 = !tn && ga.k % 8 == 0 && (ga.k2 == 0 || ga.k2 % 8 == 0);
+    const bool gate = tn ? ga.b.gate != nullptr : ga.a.gate != nullptr;
+
+    SplitGemm g;
+    g.m = ga.m, g.n = ga.n, g.k = ga.k, g.k2 = ga.k2;
+    auto f32 = [](const void* p) { return static_cast<const float*>(p); };
+    g.a = {ga.a.ptr, f32(ga.a.gate), ga.a.ld, 0};
+    g.a2 = {ga.a2.ptr, f32(ga.a2.gate), ga.a2.ld, 0};
+    if (tn) {
+        g.b = {ga.b.ptr, f32(ga.b.gate), ga.b.ld, 0};
+        g.b2 = {nullptr, nullptr, 0, 0};
+    } else {
+        g.b = {ga.b_prep, nullptr, ga.b_prep_ld, ga.b_prep_plane};
+        g.b2 = {ga.b2_prep, nullptr, ga.b2_prep_ld, ga.b2_prep_plane};
+    }
+    g.c = static_cast<float*>(ga.c);
+    g.ldc = ga.ldc;
+    g.accumulate = ga.accumulate ? 1 : 0;
+    g.relu = ga.relu ? 1 : 0;
+    g.tiles_m = (ga.m + bm - 1) / bm;
+    g.tiles_n = (ga.n + bn - 1) / bn;
+    const int32_t k_tiles = (ga.k + BK - 1) / BK + (ga.k2 + BK - 1) / BK;
+    int32_t split = ga.split_k < 1 ? 1 : ga.split_k;
+    if (split > k_tiles) split = k_tiles < 1 ? 1 : k_tiles;
+    g.tiles_per_split = (k_tiles + split - 1) / split;
+    split = g.tiles_per_split > 0 ? (k_tiles + g.tiles_per_split - 1) / g.tiles_per_split : 1;
+    if (split < 1) split = 1;
+    g.split_k = split;
+    g.partial = ga.partial;
+    if (split > 1 && !ga.partial) return hipErrorInvalidValue;
+    if (split > 1) {
+        g.inner = g.tiles_m * g.tiles_n;
+        g.outer = split;
+    } else {
+        g.inner = g.tiles_n;
+        g.outer = g.tiles_m;
+    }
+    g.pair_inner = g.inner >= 2 ? 1 : 0;
+    g.inner_units = g.pair_inner ? (g.inner + 1) / 2 : g.inner;
+    g.outer_units = g.pair_inner ? g.outer : (g.outer + 1) / 2;
+    const int64_t blocks = int64_t((g.outer_units + 7) / 8 * 8) * g.inner_units;
+    if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
+    const dim3 grid{unsigned(blocks)};
+    *split_used = split;
+
+    tag.begin(stream);
+    with_flag(ga.f32_terms == 3, [&](auto t3) {
+        with_flag(narrow, [&](auto nr) {
+            with_flag(gate, [&](auto gt) {
+                constexpr int T = decltype(t3)::value ? 3 : 2;
+                constexpr bool NR = decltype(nr)::value, GT = decltype(gt)::value;
+                constexpr int WM = NR ? 4 : 2, WN = NR ? 1 : 2, TMB = NR ? 1 : 2, TNB = 2;
+                if (tn) {
+                    hipLaunchKernelGGL((gemm_split_kernel<T, true, WM, WN, TMB, TNB, 4, GT>), grid, dim3(2 * kThreads), 0, stream, g);
+                } else if (a8) {
+                    hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 8, GT>), grid, dim3(2 * kThreads), 0, stream, g);
+                } else {
+                    hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 4, GT>), grid, dim3(2 * kThreads), 0, stream, g);
+                }
+            });
+        });
+    });
+    tag.end(stream);
+    return hipGetLastError();
+}

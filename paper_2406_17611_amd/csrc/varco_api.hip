@@ -56,6 +56,7 @@ std::string g_global_error;
 
 struct varco_ctx {
     int32_t n_layers = 0, n_parts = 0, conv = 0, dtype = 0;
+    int32_t f32_terms = 3;           // fp32 storage: bf16 terms per operand on the matrix cores (0: fp32 instructions)
     uint64_t key = 0, step = 0;
     std::vector<int32_t> widths, act;
     std::vector<LayerState> layers;
@@ -217,17 +218,23 @@ hipError_t grow(float*& buf, size_t& have, size_t want) {
 // Number of slabs the node dimension of a weight-gradient product is cut into: the workgroups of one launch
 // should fill the chip exactly once (three 256-thread workgroups of the GEMM kernel are resident per
 // compute unit, 256 compute units), so that no partly filled second round is left over.
-// (The bf16 kernel has 256-row tiles, 32 reduction steps per tile and two resident workgroups per unit.)
-int32_t gemm_split_for(int32_t m, int32_t n, int64_t k, bool bf16_kernel) {
-    const int64_t bm = bf16_kernel || n <= 64 ? 256 : 128, bn = n <= 64 ? 64 : 128;   // tile shapes of the GEMM kernels
+// (The bf16 kernel has 256-row tiles, the kernel on expanded fp32 operands 128-row tiles; both take 32
+// reduction steps per tile and have two resident workgroups per unit.)
+enum GemmKind { kGemmF32 = 0, kGemmBf16 = 1, kGemmExpanded = 2 };
+int32_t gemm_split_for(int32_t m, int32_t n, int64_t k, int kind) {
+    const int64_t bm = kind == kGemmBf16 || (kind == kGemmF32 && n <= 64) ? 256 : 128, bn = n <= 64 ? 64 : 128;
     const int64_t tiles = ((m + bm - 1) / bm) * ((n + bn - 1) / bn);
-    const int64_t k_tiles = bf16_kernel ? (k + 31) / 32 : (k + 15) / 16;
-    int64_t split = std::max<int64_t>(1, ((bf16_kernel ? 2 : 3) * 256) / tiles);
+    const int64_t k_tiles = kind == kGemmF32 ? (k + 15) / 16 : (k + 31) / 32;
+    int64_t split = std::max<int64_t>(1, ((kind == kGemmF32 ? 3 : 2) * 256) / tiles);
     split = std::min<int64_t>(split, std::max<int64_t>(1, k_tiles / 8));
     return int32_t(split);
 }
+int gemm_kind(const GemmArgs& g) {
+    return varco_gemm_bf16_usable(g) ? kGemmBf16 : varco_gemm_split_usable(g) ? kGemmExpanded : kGemmF32;
+}
 
 int32_t pad8(int32_t x) { return (x + 7) / 8 * 8; }
+int32_t pad_to(int32_t x, int32_t m) { return (x + m - 1) / m * m; }
 
 // Uploads the multiplier tables of every layer on first use (varco_create itself touches no device).
 int32_t ensure_tables(varco_ctx* ctx) {
@@ -242,16 +249,25 @@ int32_t ensure_tables(varco_ctx* ctx) {
     return VARCO_OK;
 }
 
-// bf16 copy of a weight matrix in workspace slot 0 or 1, rows = the product's output index, pitch padded to 8.
-hipError_t prep_weight(VarcoProfiler& prof, Workspace& ws, const void* h, int32_t fi, int32_t fo, bool transpose, int slot,
-                       hipStream_t st, const void** out, int64_t* pitch) {
-    prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
+// Copy of a weight matrix in the form the bf16 matrix-core kernels take, in workspace slot 0 or 1 (B or B2
+// of `g`): rows = the product's output index, pitch padded to 8; bf16 storage: one rounded copy; fp32 storage:
+// the terms of the exact bf16 expansion, one plane each. Nothing to do when fp32 instructions are used.
+hipError_t prep_weight(varco_ctx* ctx, Workspace& ws, const void* h, int32_t fi, int32_t fo, bool transpose, int slot,
+                       bool as_b2, hipStream_t st, GemmArgs& g) {
+    const bool bf16 = ctx->dtype == VARCO_BF16;
+    if (!bf16 && ctx->f32_terms == 0) return hipSuccess;
+    ctx->prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
     const int32_t rows = transpose ? fo : fi, cols = transpose ? fi : fo;
-    const int32_t p = pad8(cols);
+    const int32_t p = bf16 ? pad8(cols) : pad_to(cols, 32);
     char* dst = reinterpret_cast<char*>(ws.w) + size_t(slot) * ws.w_elems * 2;
-    *out = dst;
-    *pitch = p;
-    return varco_launch_prep_weight(static_cast<const float*>(h), fo, rows, cols, p, transpose, dst, st);
+    (as_b2 ? g.b2_prep : g.b_prep) = dst;
+    (as_b2 ? g.b2_prep_ld : g.b_prep_ld) = p;
+    if (bf16) return varco_launch_prep_weight(static_cast<const float*>(h), fo, rows, cols, p, transpose, dst, st);
+    const int32_t rows_padded = pad_to(rows, 128);   // whole tiles: the kernel reads the copy without bounds checks
+    (as_b2 ? g.b2_prep_plane : g.b_prep_plane) = int64_t(rows_padded) * p;
+    g.f32_terms = ctx->f32_terms;
+    return varco_launch_prep_weight_split(ctx->f32_terms, static_cast<const float*>(h), fo, rows, cols, rows_padded, p,
+                                          transpose, dst, st);
 }
 
 // The workspace set of `st`, created on the stream's first call and brought up to the registered sizes.
@@ -350,6 +366,20 @@ extern "C" int32_t varco_create(const varco_config* cfg, varco_ctx** out) {
     ctx->layers.resize(cfg->n_layers);
     ctx->parts.resize(cfg->n_partitions);
     ctx->stats.bytes_per_elem = cfg->dtype == VARCO_BF16 ? 2 : 4;
+    {   // two slots of bf16 weights, either orientation: rows padded to 8 elements (bf16 storage), or three
+        // terms each, padded to 128 rows of a multiple of 32 elements (fp32 storage)
+        const bool bf16 = ctx->dtype == VARCO_BF16;
+        int64_t slot = 0;
+        for (int32_t l = 0; l < ctx->n_layers; ++l) {
+            const int32_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
+            if (bf16)
+                slot = std::max({slot, int64_t(fo) * pad8(fi), int64_t(fi) * pad8(fo)});
+            else
+                slot = std::max({slot, int64_t(pad_to(fo, 128)) * pad_to(fi, 32), int64_t(pad_to(fi, 128)) * pad_to(fo, 32)});
+        }
+        // in floats: 2 slots x 2 bytes (x 3 terms) = 4 (12) bytes per element
+        ctx->need_w = size_t(slot) * (bf16 ? 1 : 3);
+    }
     for (int32_t l = 0; l < ctx->n_layers; ++l) {
         LayerState& ls = ctx->layers[l];
         const int32_t w = ctx->widths[l];
@@ -465,17 +495,8 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     int64_t gemm_elems = 0;
     for (int32_t l = 0; l < ctx->n_layers; ++l) {
         const int32_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
-        gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl, false)) * fi * fo);
-        if (ctx->dtype == VARCO_BF16)
-            gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl, true)) * fi * fo);
-    }
-    if (ctx->dtype == VARCO_BF16) {   // two slots of bf16 weights, either orientation, rows padded to 8 elements
-        int64_t slot = 0;
-        for (int32_t l = 0; l < ctx->n_layers; ++l) {
-            const int64_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
-            slot = std::max({slot, fo * pad8(int32_t(fi)), fi * pad8(int32_t(fo))});
-        }
-        ctx->need_w = std::max(ctx->need_w, size_t(slot));   // in floats: 2 slots x 2 bytes = 4 bytes per element
+        for (int kind : {kGemmF32, kGemmBf16, kGemmExpanded})
+            gemm_elems = std::max<int64_t>(gemm_elems, int64_t(gemm_split_for(fi, fo, nl, kind)) * fi * fo);
     }
     ctx->need_dm = std::max(ctx->need_dm, size_t(nl) * wmax);
     ctx->need_spmm = std::max(ctx->need_spmm, size_t(max_partials) * wmax);
@@ -519,6 +540,14 @@ extern "C" int32_t varco_advance_step(varco_ctx* ctx, varco_stream stream) {
     ctx->step += 1;
     for (LayerState& ls : ctx->layers) ls.ran_forward = false;
     VARCO_HIP(ctx, varco_launch_step_table(ctx->d_step, ctx->d_table, ctx->key, 0, 0, static_cast<hipStream_t>(stream)));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_set_matmul_terms(varco_ctx* ctx, int32_t terms) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_set_matmul_terms: null context");
+    if (terms != 0 && terms != 2 && terms != 3)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_matmul_terms: terms must be 0, 2 or 3");
+    ctx->f32_terms = terms;
     return VARCO_OK;
 }
 
@@ -630,9 +659,9 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     }
     g.c = x_out, g.ldc = fo, g.c_dtype = dt;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
-    if (dt == VARCO_BF16 && d.n_local > 0) {   // weights as bf16, [output column][reduction index]
-        VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h1, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
-        if (sage) VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h0, fi, fo, true, 1, st, &g.b2_prep, &g.b2_prep_ld));
+    if (d.n_local > 0) {   // weights as bf16, [output column][reduction index]
+        VARCO_HIP(ctx, prep_weight(ctx, ws, h1, fi, fo, true, 0, false, st, g));
+        if (sage) VARCO_HIP(ctx, prep_weight(ctx, ws, h0, fi, fo, true, 1, true, st, g));
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
@@ -687,7 +716,8 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         const LaunchTag wtag = ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl));
         for (int tap = 0; tap < (sage ? 2 : 1); ++tap) {
             if (tap == 1) g.a.ptr = x_local, g.c = dh0;
-            g.split_k = gemm_split_for(fi, fo, nl, varco_gemm_bf16_usable(g));
+            g.f32_terms = dt == VARCO_F32 ? ctx->f32_terms : 0;
+            g.split_k = gemm_split_for(fi, fo, nl, gemm_kind(g));
             if (size_t(g.split_k) * fi * fo > ws.gemm_elems)
                 return varco_fail(ctx, VARCO_ERR_STATE, "varco_layer_bwd: workspace too small");
             VARCO_HIP(ctx, varco_launch_gemm(g, st, wtag));
@@ -702,7 +732,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
         g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
         g.c = ws.dm, g.ldc = fi, g.c_dtype = dt;
-        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h1, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
+        VARCO_HIP(ctx, prep_weight(ctx, ws, h1, fi, fo, false, 0, false, st, g));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
@@ -737,7 +767,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = h0, g.b.ld = fo, g.b.transposed = true;
         g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
         g.accumulate = true;
-        if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, ws, h0, fi, fo, false, 1, st, &g.b_prep, &g.b_prep_ld));
+        VARCO_HIP(ctx, prep_weight(ctx, ws, h0, fi, fo, false, 1, false, st, g));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     return VARCO_OK;
@@ -852,7 +882,7 @@ extern "C" int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_
     g.c = c, g.ldc = fo, g.c_dtype = dt;
     g.accumulate = accumulate != 0;
     g.relu = apply_act != 0 && ctx->act[layer] == VARCO_ACT_RELU;
-    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, *ws, h, fi, fo, true, 0, st, &g.b_prep, &g.b_prep_ld));
+    VARCO_HIP(ctx, prep_weight(ctx, *ws, h, fi, fo, true, 0, false, st, g));
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * double(g.m) * g.n * g.k)));
     return VARCO_OK;
 }
@@ -875,7 +905,8 @@ extern "C" int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int
     g.c = dh, g.ldc = fo;
     g.accumulate = true;
     g.partial = ws->gemm;
-    g.split_k = gemm_split_for(fi, fo, n_rows, varco_gemm_bf16_usable(g));
+    g.f32_terms = dt == VARCO_F32 ? ctx->f32_terms : 0;
+    g.split_k = gemm_split_for(fi, fo, n_rows, gemm_kind(g));
     if (size_t(g.split_k) * fi * fo > ws->gemm_elems) {   // rows beyond what the registered partitions sized
         const int64_t fit = int64_t(ws->gemm_elems / (size_t(fi) * fo));
         if (fit < 1) return varco_fail(ctx, VARCO_ERR_STATE, "varco_transform_bwd_weight: workspace too small (register a partition first)");
@@ -903,7 +934,7 @@ extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int6
     g.b.ptr = h, g.b.ld = fo, g.b.transposed = true;
     g.c = g_out, g.ldc = fi, g.c_dtype = dt;
     g.accumulate = accumulate != 0;
-    if (dt == VARCO_BF16) VARCO_HIP(ctx, prep_weight(ctx->prof, *ws, h, fi, fo, false, 0, st, &g.b_prep, &g.b_prep_ld));
+    VARCO_HIP(ctx, prep_weight(ctx, *ws, h, fi, fo, false, 0, false, st, g));
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(n_rows))));
     return VARCO_OK;
 }

@@ -163,6 +163,11 @@ struct GemmArgs {
     const void* b_prep = nullptr;
     const void* b2_prep = nullptr;
     int64_t b_prep_ld = 0, b2_prep_ld = 0;
+    // fp32 operands on the bf16 matrix cores: 0 = no (fp32 matrix instructions); 2 or 3 = each operand is
+    // expanded into that many bf16 terms, and b_prep / b2_prep are expanded copies made by
+    // varco_launch_prep_weight_split, [term][n][pitch] with `plane` elements between terms
+    int32_t f32_terms = 0;
+    int64_t b_prep_plane = 0, b2_prep_plane = 0;
     void* c = nullptr;
     int c_dtype = VARCO_F32;
     int64_t ldc = 0;
@@ -181,6 +186,15 @@ hipError_t varco_launch_gemm_bf16(const GemmArgs& g, hipStream_t stream, const L
 // out[r][c] (bf16, row pitch `pitch` >= cols, zero beyond cols) = transpose ? h[c][r] : h[r][c] for r < rows.
 hipError_t varco_launch_prep_weight(const float* h, int64_t ld, int32_t rows, int32_t cols, int32_t pitch, bool transpose,
                                     void* out, hipStream_t stream);
+
+// fp32 operands as sums of bf16 terms on the bf16 matrix cores (kernels_gemm_split.hip); same contract as
+// the bf16 path above.
+bool varco_gemm_split_usable(const GemmArgs& g);
+hipError_t varco_launch_gemm_split(const GemmArgs& g, hipStream_t stream, const LaunchTag& tag, int32_t* split_used);
+// out[p][r][c] (bf16; rows_padded rows, a multiple of 128, of pitch elements, a multiple of 32; zero beyond
+// rows x cols) = term p of the expansion of (transpose ? h[c][r] : h[r][c]).
+hipError_t varco_launch_prep_weight_split(int terms, const float* h, int64_t ld, int32_t rows, int32_t cols,
+                                          int32_t rows_padded, int32_t pitch, bool transpose, void* out, hipStream_t stream);
 
 // Loss and update of a training iteration (kernels_train.hip). row_loss / row_correct: n_rows each; totals
 // (2 floats) may be null.

@@ -1,0 +1,73 @@
+"""GPU accuracy of the dense products of eq. (2) in their three forms for fp32 storage (fp32 matrix
+instructions; fp32 operands expanded into three or two bf16 terms on the bf16 matrix units), through the
+building-block calls of the C ABI, against fp64 products of the same inputs (numpy matmul on the CPU).
+
+terms = 3 must be as accurate as fp32 arithmetic itself, not merely inside the 1e-4 parity bound: the
+bound asserted is the one derived for an fp32 product-sum of this length."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_common import KEY, assert_close, dev
+from paper_2406_17611_amd import binding as vb
+from paper_2406_17611_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+# rows: several 128-row tiles and a ragged tail; widths: multiples of 8, of 4 only, and one that forces the
+# fallback (47: rows not 16-byte aligned)
+SHAPES = [(1000, 256, 256), (777, 100, 256), (1301, 256, 47), (515, 136, 72), (64, 32, 512), (130, 47, 64)]
+
+
+def _ctx(fi, fo, act, terms):
+    ctx = vb.Context([fi, fo], [act], vb.CONV_GCN, 1, KEY)
+    ctx.set_matmul_terms(terms)
+    return ctx
+
+
+def _bound(terms, length):
+    # fp32 accumulation over `length` products: error grows like sqrt(length) * 2^-24 norm-wise; the
+    # two-term form adds its 2^-16 per-product truncation
+    u = 2.0 ** -24 * max(4.0, np.sqrt(length))
+    return 8 * u if terms in (0, 3) else 2.0 ** -14
+
+
+@pytest.mark.parametrize("terms", [3, 0, 2])
+@pytest.mark.parametrize("n,fi,fo", SHAPES)
+def test_transform_products(n, fi, fo, terms):
+    rng = np.random.default_rng(1000 * fi + fo + n)
+    # values over many binades, both signs, some exact zeros: every term of the expansion is exercised
+    y = (rng.standard_normal((n, fi)) * np.exp2(rng.integers(-6, 7, size=(n, fi)))).astype(np.float32)
+    y[rng.random((n, fi)) < 0.05] = 0.0
+    h = synth.glorot(fi, fo, 7, fi + fo).astype(np.float32)
+    c0 = rng.standard_normal((n, fo)).astype(np.float32)
+    dxo = (rng.standard_normal((n, fo)) / n).astype(np.float32)
+    ctx = _ctx(fi, fo, vb.ACT_RELU, terms)
+    tol = _bound(terms, max(fi, fo))
+
+    # forward: C = relu(C0 + Y H)
+    c = dev(c0)
+    ctx.transform_fwd(0, dev(y), dev(h), c, True, True)
+    torch.cuda.synchronize()
+    ref_c = np.maximum(c0.astype(np.float64) + y.astype(np.float64) @ h.astype(np.float64), 0.0)
+    assert_close(c.cpu().numpy(), ref_c, "relu(C0 + Y H)", tol)
+
+    # gradients, with the ReLU mask taken on a stored activation that both sides share
+    xo = np.maximum(rng.standard_normal((n, fo)), 0.0).astype(np.float32)
+    dz = dxo.astype(np.float64) * (xo > 0)
+    dh = torch.zeros(fi, fo, device="cuda")
+    ctx2 = _ctx(fi, fo, vb.ACT_RELU, terms)
+    # the split of the node dimension needs a partial buffer: sized by a registered partition
+    g = synth.small_random_graph(max(n, 8), 3.0, "gcn", seed=5)
+    host = vb.partition_build(g.n, g.rowptr, g.colidx, g.vals, np.zeros(g.n, dtype=np.int32), 1)
+    ctx2.register_partition(0, host[0])
+    ctx2.transform_bwd_weight(0, dev(y), dev(dxo), dev(xo), dh)
+    torch.cuda.synchronize()
+    assert_close(dh.cpu().numpy(), y.astype(np.float64).T @ dz, "Y^T dZ", _bound(terms, n))
+
+    gin0 = rng.standard_normal((n, fi)).astype(np.float32)
+    gin = dev(gin0)
+    ctx.transform_bwd_input(0, dev(dxo), dev(xo), dev(h), gin, True)
+    torch.cuda.synchronize()
+    assert_close(gin.cpu().numpy(), gin0.astype(np.float64) + dz @ h.astype(np.float64).T, "G0 + dZ H^T",
+                 max(tol, 2.0 ** -22))

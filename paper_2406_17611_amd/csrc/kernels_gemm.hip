@@ -293,6 +293,153 @@ __global__ __launch_bounds__(kThreads) void gemm_reduce_kernel(const float* part
 // Loads of 4 elements are legal for an operand when its base (and gate) are aligned to them, its leading
 // dimension is a multiple of 4 and groups of 4 consecutive elements never straddle the matrix edge. `rows`
 // is the extent of the non-reduction index (M for A, N for B), `red` the reduction length.
+// ---- short reductions: C (+)= A B^T with at most 64 reduction steps and densely stored rows of A (the input
+// gradient of the last layer, whose output width is the number of classes) ----
+// The general kernel would spend its time in prologue and epilogue here, and rows of, say, 47 elements are
+// not 16-byte aligned; the product itself is bound by writing C. A workgroup copies its 128 rows of A, which
+// are one contiguous range of memory, into LDS with 16-byte loads (masked and widened to fp32 on the way;
+// the row pitch stays k, which is odd-friendly: a column of 32 rows touches 32 different banks). Each
+// wavefront owns 64 columns of C: their weights sit in registers as MFMA operands for the whole kernel, and
+// for each block of 32 rows the wavefront reads its A operands from LDS and issues the fp32 matrix
+// instructions of the whole reduction.
+constexpr int kSmallRows = 128;
+
+template <typename T>
+__device__ __forceinline__ void load_chunk(const T* p, float (&x)[16 / sizeof(T)]) {
+    if constexpr (sizeof(T) == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        x[0] = v.x, x[1] = v.y, x[2] = v.z, x[3] = v.w;
+    } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[2 * i] = __uint_as_float(u[i] << 16), x[2 * i + 1] = __uint_as_float(u[i] & 0xFFFF0000u);
+    }
+}
+
+template <typename T, int KSTEPS, bool GATE>
+__global__ __launch_bounds__(kThreads, 2) void gemm_small_k_kernel(const T* __restrict__ a, const T* __restrict__ gate,
+                                                                   const float* __restrict__ b, int64_t ldb, T* __restrict__ c,
+                                                                   int64_t ldc, int32_t m, int32_t n, int32_t k,
+                                                                   int32_t accumulate) {
+    constexpr int VE = 16 / int(sizeof(T));                       // elements per 16-byte load
+    __shared__ __attribute__((aligned(16))) float tile[kSmallRows * 2 * KSTEPS + 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lcol = lane & 31, lk = lane >> 5;
+    const int32_t r0 = blockIdx.x * kSmallRows, rows = min(kSmallRows, m - r0);
+    const int32_t c0 = blockIdx.y * 256 + wave * 64;
+
+    // weights of this wavefront's two column blocks: lane holds B[2 s + lane / 32][column]
+    float w[2][KSTEPS];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int32_t col = c0 + cb * 32 + lcol;
+#pragma unroll
+        for (int s2 = 0; s2 < KSTEPS; ++s2) {
+            const int kk = 2 * s2 + lk;
+            w[cb][s2] = col < n && kk < k ? b[int64_t(col) * ldb + kk] : 0.f;
+        }
+    }
+
+    // the rows of this tile as one contiguous range, read in 16-byte chunks on 16-byte boundaries (the range
+    // may start `skew` elements into a chunk; A and its mask have the same skew, checked by the launcher)
+    const int32_t n_el = rows * k;
+    const T* src = a + int64_t(r0) * k;
+    const T* gsrc = GATE ? gate + int64_t(r0) * k : nullptr;
+    const int32_t skew = int32_t((reinterpret_cast<uintptr_t>(src) & 15u) / sizeof(T));
+    for (int32_t e0 = threadIdx.x * VE - skew; e0 < n_el; e0 += kThreads * VE) {
+        float x[VE], y[VE];
+        if (e0 >= 0 && e0 + VE <= n_el) {
+            load_chunk<T>(src + e0, x);
+            if (GATE) load_chunk<T>(gsrc + e0, y);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VE; ++i) {
+                const bool in = e0 + i >= 0 && e0 + i < n_el;
+                x[i] = in ? Elem<T>::load(src + e0 + i) : 0.f;
+                if (GATE) y[i] = in ? Elem<T>::load(gsrc + e0 + i) : 0.f;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < VE; ++i) {
+            if (GATE) x[i] = y[i] > 0.f ? x[i] : 0.f;
+            if (e0 + i >= 0 && e0 + i < n_el) tile[e0 + i] = x[i];
+        }
+    }
+    __syncthreads();
+    if (c0 >= n) return;               // no barrier follows
+
+    for (int rb = 0; rb * 32 < rows; ++rb) {
+        const int32_t lrow = min(rb * 32 + lcol, rows - 1);          // rows past the end repeat the last one; never stored
+        floatx16 acc[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
+        float af[KSTEPS];
+#pragma unroll
+        for (int s2 = 0; s2 < KSTEPS; ++s2) {
+            const int kk = 2 * s2 + lk;
+            const float x = tile[lrow * k + kk];                     // in bounds: the tile has 64 spare floats
+            af[s2] = kk < k ? x : 0.f;
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < KSTEPS; ++s2)
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) acc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[s2], w[cb][s2], acc[cb], 0, 0, 0);
+        // accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int32_t col = c0 + cb * 32 + lcol;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t row = rb * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
+                if (row < rows && col < n) {
+                    T* dst = c + int64_t(r0 + row) * ldc + col;
+                    float x = acc[cb][v];
+                    if (accumulate) x += Elem<T>::load(dst);
+                    Elem<T>::store(dst, x);
+                }
+            }
+        }
+    }
+}
+
+// A [m x k] with k contiguous and rows densely stored, B = fp32 weights stored [n x k], no chained product,
+// no split, no activation.
+bool small_k_usable(const GemmArgs& ga) {
+    const uintptr_t pa = reinterpret_cast<uintptr_t>(ga.a.ptr), pg = reinterpret_cast<uintptr_t>(ga.a.gate);
+    const uintptr_t es = ga.a.dtype == VARCO_BF16 ? 2 : 4;
+    const bool same_skew = !ga.a.gate || (pa & 15u) == (pg & 15u);     // A and its mask are read with the same chunking
+    return !ga.a.transposed && ga.b.transposed && ga.k >= 1 && ga.k <= 64 && ga.a.ld == ga.k && ga.k2 == 0 && !ga.b.gate &&
+           !ga.relu && ga.b.dtype == VARCO_F32 && ga.a.dtype == ga.c_dtype && ga.split_k <= 1 && pa % es == 0 && same_skew;
+}
+
+template <typename T>
+void launch_small_k(const GemmArgs& ga, hipStream_t stream) {
+    const dim3 grid(unsigned((ga.m + kSmallRows - 1) / kSmallRows), unsigned((ga.n + 255) / 256));
+    const int steps = (ga.k + 15) / 16 * 8;       // reduction steps of two, in units the kernel is instantiated for
+    auto go = [&](auto sc, auto gt) {
+        hipLaunchKernelGGL((gemm_small_k_kernel<T, decltype(sc)::value, decltype(gt)::value>), grid, dim3(kThreads), 0, stream,
+                           static_cast<const T*>(ga.a.ptr), static_cast<const T*>(ga.a.gate), static_cast<const float*>(ga.b.ptr),
+                           ga.b.ld, static_cast<T*>(ga.c), ga.ldc, ga.m, ga.n, ga.k, ga.accumulate ? 1 : 0);
+    };
+    auto with_gate = [&](auto sc) {
+        if (ga.a.gate)
+            go(sc, std::true_type{});
+        else
+            go(sc, std::false_type{});
+    };
+    if (steps == 8)
+        with_gate(std::integral_constant<int, 8>{});
+    else if (steps == 16)
+        with_gate(std::integral_constant<int, 16>{});
+    else if (steps == 24)
+        with_gate(std::integral_constant<int, 24>{});
+    else
+        with_gate(std::integral_constant<int, 32>{});
+}
+
 bool vector_ok(const GemmOperand& o, bool k_contig, int32_t rows, int32_t red) {
     if (!o.ptr) return true;
     const uintptr_t mask = (o.dtype == VARCO_BF16 ? 8u : 16u) - 1u;
@@ -345,6 +492,15 @@ hipError_t launch_reduce(const GemmArgs& ga, int32_t split, hipStream_t stream, 
 
 hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag) {
     if (ga.m == 0 || ga.n == 0) return hipSuccess;
+    if (small_k_usable(ga)) {
+        tag.begin(stream);
+        if (ga.a.dtype == VARCO_BF16)
+            launch_small_k<bf16_t>(ga, stream);
+        else
+            launch_small_k<float>(ga, stream);
+        tag.end(stream);
+        return hipGetLastError();
+    }
     if (varco_gemm_bf16_usable(ga)) {
         int32_t split = 1;
         const hipError_t e = varco_launch_gemm_bf16(ga, stream, tag, &split);

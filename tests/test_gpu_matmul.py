@@ -71,3 +71,32 @@ def test_transform_products(n, fi, fo, terms):
     torch.cuda.synchronize()
     assert_close(gin.cpu().numpy(), gin0.astype(np.float64) + dz @ h.astype(np.float64).T, "G0 + dZ H^T",
                  max(tol, 2.0 ** -22))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("first_row", [0, 1, 3])
+def test_input_gradient_short_reduction(first_row, dtype):
+    """dZ H^T with 47 reduction steps (the class logits' gradient) on row ranges that start at any row of a
+    larger tensor, so that the rows are neither 16-byte aligned nor is the range's start; masked and not."""
+    from oracle.rounding import round_bf16
+    n, fi, fo = 700, 256, 47
+    rng = np.random.default_rng(40 + first_row)
+    bf16 = dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    rnd = (lambda a: round_bf16(a).astype(np.float32)) if bf16 else (lambda a: a.astype(np.float32))
+    h = synth.glorot(fi, fo, 9, 1).astype(np.float32)
+    dxo_all = rnd(rng.standard_normal((n + first_row, fo)))
+    xo_all = rnd(np.maximum(rng.standard_normal((n + first_row, fo)), 0.0))
+    dxo_d, xo_d = dev(dxo_all, tdt), dev(xo_all, tdt)
+    tol = 2.0 ** -7 if bf16 else 8 * 2.0 ** -24 * np.sqrt(fo)
+    for act in (vb.ACT_IDENTITY, vb.ACT_RELU):
+        ctx = vb.Context([fi, fo], [act], vb.CONV_GCN, 1, KEY, vb.BF16 if bf16 else vb.F32)
+        g0 = rnd(rng.standard_normal((n, fi)))
+        gout = dev(g0, tdt)
+        ctx.transform_bwd_input(0, dxo_d[first_row:], xo_d[first_row:], dev(h), gout, True)
+        torch.cuda.synchronize()
+        dz = dxo_all[first_row:].astype(np.float64)
+        if act == vb.ACT_RELU:
+            dz = dz * (xo_all[first_row:] > 0)
+        ref = g0.astype(np.float64) + dz @ h.astype(np.float64).T
+        assert_close(gout.float().cpu().numpy(), ref, f"G0 + dZ H^T from row {first_row}", tol)

@@ -288,7 +288,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_bf16_kernel(GemmDev g) {
         __syncthreads();
     }
 
-    // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32)
+    // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32).
+    // When C is added to, the old values of a block are fetched by loads that are all issued before the first
+    // one is used (from clamped, always valid addresses), not one round trip per element.
     const bool to_partial = g.split_k > 1;
     TC* cout = static_cast<TC*>(g.c);
     float* pout = g.partial + int64_t(z) * g.m * g.n;
@@ -297,20 +299,31 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_bf16_kernel(GemmDev g) {
 #pragma unroll
         for (int j = 0; j < TNB; ++j) {
             const int32_t col = n0 + wn + j * 32 + lrow;
+            const int32_t row0 = m0 + wm + i * 32 + 4 * lk;
+            const bool col_ok = col < g.n;
+            if (to_partial) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
+                    if (col_ok && row < g.m) pout[int64_t(row) * g.n + col] = acc[i][j][v];
+                }
+                continue;
+            }
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) old[v] = 0.f;
+            if (g.accumulate) {
+                const TC* cbase = cout + min(col, g.n - 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    old[v] = Elem<TC>::load(cbase + int64_t(min(row0 + 8 * (v >> 2) + (v & 3), g.m - 1)) * g.ldc);
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int32_t row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                if (row < g.m && col < g.n) {
-                    float x = acc[i][j][v];
-                    if (to_partial) {
-                        pout[int64_t(row) * g.n + col] = x;
-                    } else {
-                        TC* dst = cout + int64_t(row) * g.ldc + col;
-                        if (g.accumulate) x += Elem<TC>::load(dst);
-                        if (g.relu) x = fmaxf(x, 0.f);
-                        Elem<TC>::store(dst, x);
-                    }
-                }
+                const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
+                float x = acc[i][j][v] + old[v];
+                if (g.relu) x = fmaxf(x, 0.f);
+                if (col_ok && row < g.m) Elem<TC>::store(cout + int64_t(row) * g.ldc + col, x);
             }
         }
     }

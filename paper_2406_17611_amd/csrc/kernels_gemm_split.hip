@@ -434,7 +434,9 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
     if (grp == 0) workgroup_barrier();
     if (my_steps == 0) return;         // a group without a tile; no barrier follows
 
-    // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32)
+    // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32).
+    // When C is added to, the old values of a block are fetched by loads that are all issued before the first
+    // one is used (from clamped, always valid addresses), not one round trip per element.
     const bool to_partial = g.split_k > 1;
     float* pout = g.partial + int64_t(z) * g.m * g.n;
 #pragma unroll
@@ -442,20 +444,30 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
 #pragma unroll
         for (int j = 0; j < TNB; ++j) {
             const int32_t col = n0 + wn + j * 32 + lrow;
+            const int32_t row0 = m0 + wm + i * 32 + 4 * lk;
+            const bool col_ok = col < g.n;
+            if (to_partial) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
+                    if (col_ok && row < g.m) pout[int64_t(row) * g.n + col] = acc[i][j][v];
+                }
+                continue;
+            }
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) old[v] = 0.f;
+            if (g.accumulate) {
+                const float* cbase = g.c + min(col, g.n - 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) old[v] = cbase[int64_t(min(row0 + 8 * (v >> 2) + (v & 3), g.m - 1)) * g.ldc];
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int32_t row = m0 + wm + i * 32 + 8 * (v >> 2) + 4 * lk + (v & 3);
-                if (row < g.m && col < g.n) {
-                    float x = acc[i][j][v];
-                    if (to_partial) {
-                        pout[int64_t(row) * g.n + col] = x;
-                    } else {
-                        float* dst = g.c + int64_t(row) * g.ldc + col;
-                        if (g.accumulate) x += *dst;
-                        if (g.relu) x = fmaxf(x, 0.f);
-                        *dst = x;
-                    }
-                }
+                const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
+                float x = acc[i][j][v] + old[v];
+                if (g.relu) x = fmaxf(x, 0.f);
+                if (col_ok && row < g.m) g.c[int64_t(row) * g.ldc + col] = x;
             }
         }
     }

@@ -136,7 +136,11 @@ int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const varco_partitio
 const char* varco_last_error(const varco_ctx* ctx);
 
 /* Algorithm 1's iteration counter t: part of the mask key, so that the kept positions are redrawn every
- * step. Also closes the previous step (ratios may change again). */
+ * step. Also closes the previous step (ratios may change again).
+ * Weights belong to a step: Algorithm 1 updates the parameters between iterations, and the library may keep
+ * converted copies of the weight matrices it is given (per stream, keyed by their address) until the next
+ * varco_begin_step / varco_set_step / varco_advance_step. A caller that changes a weight matrix in place calls
+ * one of these before using it again; a sequence captured into a HIP graph starts with varco_advance_step. */
 int32_t varco_begin_step(varco_ctx* ctx, uint64_t step);
 
 /* Step state on the device, for callers that capture a sequence of calls in a HIP graph and replay it for

@@ -45,7 +45,13 @@ struct Workspace {
     float* spmm = nullptr;      size_t spmm_elems = 0;      // partial rows of split CSR rows
     float* gemm = nullptr;      size_t gemm_elems = 0;      // split-K partial products
     float* prod = nullptr;      size_t prod_elems = 0;      // halo-gradient products: (halo entries) x k elements
-    float* w = nullptr;         size_t w_elems = 0;         // bf16 copies of the two weights of a layer call
+    float* w = nullptr;         size_t w_elems = 0;         // converted copies of the weights, one slot per (layer, weight, orientation)
+    struct WeightTag {          // what a slot holds: made from `h` during step epoch `epoch` in the form `terms`
+        const void* h = nullptr;
+        uint64_t epoch = 0;
+        int32_t terms = -1;
+    };
+    std::vector<WeightTag> w_tags;
 };
 constexpr int kMaxStreams = 8;
 
@@ -57,6 +63,8 @@ std::string g_global_error;
 struct varco_ctx {
     int32_t n_layers = 0, n_parts = 0, conv = 0, dtype = 0;
     int32_t f32_terms = 3;           // fp32 storage: bf16 terms per operand on the matrix cores (0: fp32 instructions)
+    uint64_t weight_epoch = 1;       // converted weight copies are reused within an epoch (= a step)
+    std::vector<size_t> w_slot;      // offset (bf16 elements) of every slot in a workspace's weight buffer, and the total
     uint64_t key = 0, step = 0;
     std::vector<int32_t> widths, act;
     std::vector<LayerState> layers;
@@ -249,25 +257,33 @@ int32_t ensure_tables(varco_ctx* ctx) {
     return VARCO_OK;
 }
 
-// Copy of a weight matrix in the form the bf16 matrix-core kernels take, in workspace slot 0 or 1 (B or B2
-// of `g`): rows = the product's output index, pitch padded to 8; bf16 storage: one rounded copy; fp32 storage:
-// the terms of the exact bf16 expansion, one plane each. Nothing to do when fp32 instructions are used.
-hipError_t prep_weight(varco_ctx* ctx, Workspace& ws, const void* h, int32_t fi, int32_t fo, bool transpose, int slot,
-                       bool as_b2, hipStream_t st, GemmArgs& g) {
+// Copy of a weight matrix in the form the bf16 matrix-core kernels take (B or B2 of `g`): rows = the product's
+// output index, pitch padded; bf16 storage: one rounded copy; fp32 storage: the terms of the exact bf16
+// expansion, one plane each. Nothing to do when fp32 instructions are used. Every (layer, weight, orientation)
+// has a slot of its own in the stream's workspace, and a copy made earlier in the same step from the same
+// pointer is reused: the weights of a step do not change (they are updated between steps).
+hipError_t prep_weight(varco_ctx* ctx, Workspace& ws, int32_t layer, const void* h, int32_t fi, int32_t fo, bool transpose,
+                       int which, bool as_b2, hipStream_t st, GemmArgs& g) {
     const bool bf16 = ctx->dtype == VARCO_BF16;
     if (!bf16 && ctx->f32_terms == 0) return hipSuccess;
-    ctx->prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
+    const int32_t terms = bf16 ? 1 : ctx->f32_terms;
     const int32_t rows = transpose ? fo : fi, cols = transpose ? fi : fo;
     const int32_t p = bf16 ? pad8(cols) : pad_to(cols, 32);
-    char* dst = reinterpret_cast<char*>(ws.w) + size_t(slot) * ws.w_elems * 2;
+    const int32_t rows_padded = bf16 ? rows : pad_to(rows, 128);   // whole tiles: the kernel reads the copy without bounds checks
+    const size_t slot = (size_t(layer) * 2 + which) * 2 + (transpose ? 0 : 1);
+    uint16_t* dst = reinterpret_cast<uint16_t*>(ws.w) + ctx->w_slot[slot];
     (as_b2 ? g.b2_prep : g.b_prep) = dst;
     (as_b2 ? g.b2_prep_ld : g.b_prep_ld) = p;
+    if (!bf16) {
+        (as_b2 ? g.b2_prep_plane : g.b_prep_plane) = int64_t(rows_padded) * p;
+        g.f32_terms = terms;
+    }
+    Workspace::WeightTag& tag = ws.w_tags[slot];
+    if (tag.h == h && tag.epoch == ctx->weight_epoch && tag.terms == terms) return hipSuccess;
+    tag.h = h, tag.epoch = ctx->weight_epoch, tag.terms = terms;
+    ctx->prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
     if (bf16) return varco_launch_prep_weight(static_cast<const float*>(h), fo, rows, cols, p, transpose, dst, st);
-    const int32_t rows_padded = pad_to(rows, 128);   // whole tiles: the kernel reads the copy without bounds checks
-    (as_b2 ? g.b2_prep_plane : g.b_prep_plane) = int64_t(rows_padded) * p;
-    g.f32_terms = ctx->f32_terms;
-    return varco_launch_prep_weight_split(ctx->f32_terms, static_cast<const float*>(h), fo, rows, cols, rows_padded, p,
-                                          transpose, dst, st);
+    return varco_launch_prep_weight_split(terms, static_cast<const float*>(h), fo, rows, cols, rows_padded, p, transpose, dst, st);
 }
 
 // The workspace set of `st`, created on the stream's first call and brought up to the registered sizes.
@@ -289,6 +305,7 @@ int32_t workspace_for(varco_ctx* ctx, hipStream_t st, Workspace** out) {
     VARCO_HIP(ctx, grow(ws->spmm, ws->spmm_elems, ctx->need_spmm));
     VARCO_HIP(ctx, grow(ws->gemm, ws->gemm_elems, ctx->need_gemm));
     VARCO_HIP(ctx, grow(ws->w, ws->w_elems, ctx->need_w));
+    if (ws->w_tags.empty()) ws->w_tags.resize(size_t(ctx->n_layers) * 4);
     *out = ws;
     return VARCO_OK;
 }
@@ -366,19 +383,21 @@ extern "C" int32_t varco_create(const varco_config* cfg, varco_ctx** out) {
     ctx->layers.resize(cfg->n_layers);
     ctx->parts.resize(cfg->n_partitions);
     ctx->stats.bytes_per_elem = cfg->dtype == VARCO_BF16 ? 2 : 4;
-    {   // two slots of bf16 weights, either orientation: rows padded to 8 elements (bf16 storage), or three
-        // terms each, padded to 128 rows of a multiple of 32 elements (fp32 storage)
+    {   // converted weight copies: a slot per (layer, weight, orientation); bf16 storage: rows padded to 8 elements;
+        // fp32 storage: three terms each, padded to 128 rows of a multiple of 32 elements
         const bool bf16 = ctx->dtype == VARCO_BF16;
-        int64_t slot = 0;
+        size_t total = 0;
         for (int32_t l = 0; l < ctx->n_layers; ++l) {
             const int32_t fi = ctx->widths[l], fo = ctx->widths[l + 1];
-            if (bf16)
-                slot = std::max({slot, int64_t(fo) * pad8(fi), int64_t(fi) * pad8(fo)});
-            else
-                slot = std::max({slot, int64_t(pad_to(fo, 128)) * pad_to(fi, 32), int64_t(pad_to(fi, 128)) * pad_to(fo, 32)});
+            const size_t fwd = bf16 ? size_t(fo) * pad8(fi) : size_t(3) * pad_to(fo, 128) * pad_to(fi, 32);
+            const size_t bwd = bf16 ? size_t(fi) * pad8(fo) : size_t(3) * pad_to(fi, 128) * pad_to(fo, 32);
+            for (int which = 0; which < 2; ++which)
+                for (size_t sz : {fwd, bwd}) {
+                    ctx->w_slot.push_back(total);
+                    total += (sz + 7) / 8 * 8;       // slots stay 16-byte aligned
+                }
         }
-        // in floats: 2 slots x 2 bytes (x 3 terms) = 4 (12) bytes per element
-        ctx->need_w = size_t(slot) * (bf16 ? 1 : 3);
+        ctx->need_w = (total + 1) / 2;               // in floats
     }
     for (int32_t l = 0; l < ctx->n_layers; ++l) {
         LayerState& ls = ctx->layers[l];
@@ -510,6 +529,7 @@ extern "C" int32_t varco_begin_step(varco_ctx* ctx, uint64_t step) {
     if (ctx->d_table)
         return varco_fail(ctx, VARCO_ERR_STATE, "varco_begin_step: the step lives on the device; use varco_set_step or varco_advance_step");
     ctx->step = step;
+    ctx->weight_epoch += 1;
     for (LayerState& ls : ctx->layers) ls.ran_forward = false;
     return VARCO_OK;
 }
@@ -528,6 +548,7 @@ extern "C" int32_t varco_step_table_enable(varco_ctx* ctx, varco_stream stream) 
 extern "C" int32_t varco_set_step(varco_ctx* ctx, uint64_t step, varco_stream stream) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_set_step: null context");
     ctx->step = step;
+    ctx->weight_epoch += 1;
     for (LayerState& ls : ctx->layers) ls.ran_forward = false;
     if (ctx->d_table)
         VARCO_HIP(ctx, varco_launch_step_table(ctx->d_step, ctx->d_table, ctx->key, 1, step, static_cast<hipStream_t>(stream)));
@@ -538,6 +559,7 @@ extern "C" int32_t varco_advance_step(varco_ctx* ctx, varco_stream stream) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_advance_step: null context");
     if (!ctx->d_table) return varco_fail(ctx, VARCO_ERR_STATE, "varco_advance_step: call varco_step_table_enable first");
     ctx->step += 1;
+    ctx->weight_epoch += 1;
     for (LayerState& ls : ctx->layers) ls.ran_forward = false;
     VARCO_HIP(ctx, varco_launch_step_table(ctx->d_step, ctx->d_table, ctx->key, 0, 0, static_cast<hipStream_t>(stream)));
     return VARCO_OK;
@@ -548,6 +570,7 @@ extern "C" int32_t varco_set_matmul_terms(varco_ctx* ctx, int32_t terms) {
     if (terms != 0 && terms != 2 && terms != 3)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_matmul_terms: terms must be 0, 2 or 3");
     ctx->f32_terms = terms;
+    ctx->weight_epoch += 1;
     return VARCO_OK;
 }
 
@@ -660,8 +683,8 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     g.c = x_out, g.ldc = fo, g.c_dtype = dt;
     g.relu = ctx->act[layer] == VARCO_ACT_RELU;
     if (d.n_local > 0) {   // weights as bf16, [output column][reduction index]
-        VARCO_HIP(ctx, prep_weight(ctx, ws, h1, fi, fo, true, 0, false, st, g));
-        if (sage) VARCO_HIP(ctx, prep_weight(ctx, ws, h0, fi, fo, true, 1, true, st, g));
+        VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h1, fi, fo, true, 0, false, st, g));
+        if (sage) VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h0, fi, fo, true, 1, true, st, g));
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
     // boundary rows of the output, compressed for the next layer's exchange
@@ -732,7 +755,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.a.ptr = dx_out, g.a.gate = gate, g.a.ld = fo, g.a.dtype = dt;
         g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
         g.c = ws.dm, g.ldc = fi, g.c_dtype = dt;
-        VARCO_HIP(ctx, prep_weight(ctx, ws, h1, fi, fo, false, 0, false, st, g));
+        VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h1, fi, fo, false, 0, false, st, g));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     // transposed aggregation: local rows in full, halo rows only at their kept positions
@@ -767,7 +790,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         g.b.ptr = h0, g.b.ld = fo, g.b.transposed = true;
         g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
         g.accumulate = true;
-        VARCO_HIP(ctx, prep_weight(ctx, ws, h0, fi, fo, false, 1, false, st, g));
+        VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h0, fi, fo, false, 1, false, st, g));
         VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
     }
     return VARCO_OK;
@@ -882,7 +905,7 @@ extern "C" int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_
     g.c = c, g.ldc = fo, g.c_dtype = dt;
     g.accumulate = accumulate != 0;
     g.relu = apply_act != 0 && ctx->act[layer] == VARCO_ACT_RELU;
-    VARCO_HIP(ctx, prep_weight(ctx, *ws, h, fi, fo, true, 0, false, st, g));
+    VARCO_HIP(ctx, prep_weight(ctx, *ws, layer, h, fi, fo, true, 0, false, st, g));
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * double(g.m) * g.n * g.k)));
     return VARCO_OK;
 }
@@ -934,7 +957,7 @@ extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int6
     g.b.ptr = h, g.b.ld = fo, g.b.transposed = true;
     g.c = g_out, g.ldc = fi, g.c_dtype = dt;
     g.accumulate = accumulate != 0;
-    VARCO_HIP(ctx, prep_weight(ctx, *ws, h, fi, fo, false, 0, false, st, g));
+    VARCO_HIP(ctx, prep_weight(ctx, *ws, layer, h, fi, fo, false, 0, false, st, g));
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(n_rows))));
     return VARCO_OK;
 }

@@ -100,3 +100,31 @@ def test_input_gradient_short_reduction(first_row, dtype):
             dz = dz * (xo_all[first_row:] > 0)
         ref = g0.astype(np.float64) + dz @ h.astype(np.float64).T
         assert_close(gout.float().cpu().numpy(), ref, f"G0 + dZ H^T from row {first_row}", tol)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_weights_changed_between_steps_are_seen(dtype):
+    """The library may keep converted copies of the weights during a step; after an in-place update and the
+    next step call the new values must be used (both orientations: transform and input gradient)."""
+    n, fi, fo = 300, 64, 96
+    rng = np.random.default_rng(77)
+    bf16 = dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    tol = 2.0 ** -7 if bf16 else 1e-5
+    ctx = vb.Context([fi, fo], [vb.ACT_IDENTITY], vb.CONV_GCN, 1, KEY, vb.BF16 if bf16 else vb.F32)
+    y = torch.from_numpy(rng.standard_normal((n, fi)).astype(np.float32)).to(tdt).cuda()
+    d = torch.from_numpy(rng.standard_normal((n, fo)).astype(np.float32)).to(tdt).cuda()
+    h = dev(synth.glorot(fi, fo, 3, 0))
+    c = torch.empty(n, fo, dtype=tdt, device="cuda")
+    gin = torch.empty(n, fi, dtype=tdt, device="cuda")
+    for step in range(3):
+        ctx.set_step(step)
+        for _ in range(2):          # the second call of a step may reuse the first one's copies
+            ctx.transform_fwd(0, y, h, c, False, False)
+            ctx.transform_bwd_input(0, d, None, h, gin, False)
+        torch.cuda.synchronize()
+        hh = h.cpu().numpy().astype(np.float64)
+        assert_close(c.float().cpu().numpy(), y.float().cpu().numpy().astype(np.float64) @ hh, f"Y H at step {step}", tol)
+        assert_close(gin.float().cpu().numpy(), d.float().cpu().numpy().astype(np.float64) @ hh.T, f"dZ H^T at step {step}", tol)
+        h.mul_(-1.5).add_(0.01)     # in-place update, same address
+    torch.cuda.synchronize()

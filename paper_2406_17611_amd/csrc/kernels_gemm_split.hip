@@ -8,11 +8,11 @@
 // instructions that cover the same reduction steps. TERMS = 2 keeps x0 + x1 and three products (relative
 // error about 2^-16 per product); the library does not use it by default.
 //
-// One 256-thread workgroup (4 wavefronts) computes a 128 x 128 tile of C (128 x 64 for outputs at most 64
-// columns wide), a wavefront 64 x 64 (32 x 64). Two workgroups share a compute unit, so that one's
-// conversions and LDS writes overlap the other's matrix instructions. A tile of 32 reduction steps is
-// fetched into registers while the previous one is multiplied, then expanded and written to LDS as TERMS
-// planes of bf16 rows (one output index per row, reduction index contiguous, 80-byte pitch).
+// A group of four wavefronts computes a 128 x 128 tile of C (128 x 64 for outputs at most 64 columns wide), a
+// wavefront 64 x 64 (32 x 64). A workgroup is two such groups with a tile each; while one multiplies, the
+// other fetches, expands and writes its next stage (see the kernel). A stage of 32 reduction steps is fetched
+// into registers one phase ahead, then expanded and written to LDS as TERMS planes of bf16 rows (one output
+// index per row, reduction index contiguous, 80-byte pitch).
 //   "NT" products (transform, input gradient): A has the reduction index contiguous and is expanded here;
 //        B is the library's own expanded copy of the weights (varco_launch_prep_weight_split), zero-padded
 //        to whole tiles and copied as is.

@@ -289,44 +289,67 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_bf16_kernel(GemmDev g) {
     }
 
     // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32).
-    // When C is added to, the old values of a block are fetched by loads that are all issued before the first
-    // one is used (from clamped, always valid addresses), not one round trip per element.
-    const bool to_partial = g.split_k > 1;
-    TC* cout = static_cast<TC*>(g.c);
-    float* pout = g.partial + int64_t(z) * g.m * g.n;
+    // A tile that lies wholly inside C takes a path without per-element tests, with addresses formed from one
+    // 64-bit base per lane plus 32-bit multiples of the row pitch. When C is added to, the old values of a
+    // block are fetched by loads that are all issued before the first one is used (from clamped, always valid
+    // addresses), not one round trip per element.
+    const int32_t col_base = n0 + wn + lrow;
+    if (g.split_k > 1) {
+        float* pout = g.partial + int64_t(z) * g.m * g.n;
 #pragma unroll
-    for (int i = 0; i < TMB; ++i) {
+        for (int i = 0; i < TMB; ++i)
 #pragma unroll
-        for (int j = 0; j < TNB; ++j) {
-            const int32_t col = n0 + wn + j * 32 + lrow;
-            const int32_t row0 = m0 + wm + i * 32 + 4 * lk;
-            const bool col_ok = col < g.n;
-            if (to_partial) {
+            for (int j = 0; j < TNB; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
-                    if (col_ok && row < g.m) pout[int64_t(row) * g.n + col] = acc[i][j][v];
+                    const int32_t row = m0 + wm + i * 32 + 4 * lk + 8 * (v >> 2) + (v & 3), col = col_base + j * 32;
+                    if (row < g.m && col < g.n) pout[int64_t(row) * g.n + col] = acc[i][j][v];
                 }
-                continue;
-            }
-            float old[16];
+        return;
+    }
+    TC* const base = static_cast<TC*>(g.c);
+    const bool add_old = g.accumulate, relu = g.relu;
+    auto finish = [&](auto guard) {
+        constexpr bool GUARD = decltype(guard)::value;
+        TC* const out0 = base + int64_t(m0 + wm) * g.ldc + col_base;          // interior tiles only
 #pragma unroll
-            for (int v = 0; v < 16; ++v) old[v] = 0.f;
-            if (g.accumulate) {
-                const TC* cbase = cout + min(col, g.n - 1);
+        for (int i = 0; i < TMB; ++i) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    old[v] = Elem<TC>::load(cbase + int64_t(min(row0 + 8 * (v >> 2) + (v & 3), g.m - 1)) * g.ldc);
-            }
+            for (int j = 0; j < TNB; ++j) {
+                TC* ptr[16];
+                bool ok[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
-                float x = acc[i][j][v] + old[v];
-                if (g.relu) x = fmaxf(x, 0.f);
-                if (col_ok && row < g.m) Elem<TC>::store(cout + int64_t(row) * g.ldc + col, x);
+                for (int v = 0; v < 16; ++v) {
+                    const int32_t r = i * 32 + 4 * lk + 8 * (v >> 2) + (v & 3);        // row inside the wavefront's part
+                    if constexpr (GUARD) {
+                        const int32_t row = m0 + wm + r, col = col_base + j * 32;
+                        ok[v] = row < g.m && col < g.n;
+                        ptr[v] = base + int64_t(min(row, g.m - 1)) * g.ldc + min(col, g.n - 1);
+                    } else {
+                        ok[v] = true;
+                        ptr[v] = out0 + j * 32 + uint32_t(r) * uint32_t(g.ldc);        // a tile spans < 2^32 elements
+                    }
+                }
+                float old[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) old[v] = 0.f;
+                if (add_old) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) old[v] = Elem<TC>::load(ptr[v]);
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float x = acc[i][j][v] + old[v];
+                    if (relu) x = fmaxf(x, 0.f);
+                    if (ok[v]) Elem<TC>::store(ptr[v], x);
+                }
             }
         }
-    }
+    };
+    if (m0 + BM <= g.m && n0 + BN <= g.n)
+        finish(std::false_type{});
+    else
+        finish(std::true_type{});
 }
 
 // out[r][c] (bf16, pitch `pitch` >= cols, zero beyond cols) = transpose ? h[c][r] : h[r][c], h fp32 with

@@ -435,42 +435,56 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
     if (my_steps == 0) return;         // a group without a tile; no barrier follows
 
     // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32).
-    // When C is added to, the old values of a block are fetched by loads that are all issued before the first
-    // one is used (from clamped, always valid addresses), not one round trip per element.
+    // Addresses are one 64-bit base per lane plus 32-bit multiples of the row pitch; a tile that lies wholly
+    // inside C (all but the last row and column of tiles) takes a path without per-element tests. When C is
+    // added to, the old values of a block are fetched by loads that are all issued before the first one is used
+    // (from clamped, always valid addresses), not one round trip per element.
     const bool to_partial = g.split_k > 1;
-    float* pout = g.partial + int64_t(z) * g.m * g.n;
+    const int32_t col_base = n0 + wn + lrow;
+    const int64_t pitch = to_partial ? int64_t(g.n) : g.ldc;
+    float* const base = to_partial ? g.partial + int64_t(z) * g.m * g.n : g.c;
+    const bool add_old = !to_partial && g.accumulate, relu = !to_partial && g.relu;
+    auto finish = [&](auto guard) {
+        constexpr bool GUARD = decltype(guard)::value;
+        float* const out0 = base + int64_t(m0 + wm) * pitch + col_base;      // interior tiles only
 #pragma unroll
-    for (int i = 0; i < TMB; ++i) {
+        for (int i = 0; i < TMB; ++i) {
 #pragma unroll
-        for (int j = 0; j < TNB; ++j) {
-            const int32_t col = n0 + wn + j * 32 + lrow;
-            const int32_t row0 = m0 + wm + i * 32 + 4 * lk;
-            const bool col_ok = col < g.n;
-            if (to_partial) {
+            for (int j = 0; j < TNB; ++j) {
+                float* ptr[16];
+                bool ok[16];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
-                    if (col_ok && row < g.m) pout[int64_t(row) * g.n + col] = acc[i][j][v];
+                    const int32_t r = i * 32 + 4 * lk + 8 * (v >> 2) + (v & 3);        // row inside the wavefront's part
+                    if constexpr (GUARD) {
+                        const int32_t row = m0 + wm + r, col = col_base + j * 32;
+                        ok[v] = row < g.m && col < g.n;
+                        ptr[v] = base + int64_t(min(row, g.m - 1)) * pitch + min(col, g.n - 1);
+                    } else {
+                        ok[v] = true;
+                        ptr[v] = out0 + j * 32 + uint32_t(r) * uint32_t(pitch);        // a tile spans < 2^32 elements
+                    }
                 }
-                continue;
-            }
-            float old[16];
+                float old[16];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) old[v] = 0.f;
-            if (g.accumulate) {
-                const float* cbase = g.c + min(col, g.n - 1);
+                for (int v = 0; v < 16; ++v) old[v] = 0.f;
+                if (add_old) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) old[v] = cbase[int64_t(min(row0 + 8 * (v >> 2) + (v & 3), g.m - 1)) * g.ldc];
-            }
+                    for (int v = 0; v < 16; ++v) old[v] = *ptr[v];
+                }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
-                float x = acc[i][j][v] + old[v];
-                if (g.relu) x = fmaxf(x, 0.f);
-                if (col_ok && row < g.m) g.c[int64_t(row) * g.ldc + col] = x;
+                for (int v = 0; v < 16; ++v) {
+                    float x = acc[i][j][v] + old[v];
+                    if (relu) x = fmaxf(x, 0.f);
+                    if (ok[v]) *ptr[v] = x;
+                }
             }
         }
-    }
+    };
+    if (m0 + BM <= g.m && n0 + BN <= g.n)
+        finish(std::false_type{});
+    else
+        finish(std::true_type{});
 }
 
 // out[p][r][c] (bf16, `rows_padded` rows of `pitch` elements, zero beyond rows x cols) = term p of

@@ -18,6 +18,8 @@
 // the caller's column indices, so that a halo entry needs no dependent index lookups before its data load.
 #include <algorithm>
 
+#include <type_traits>
+
 #include "elem.h"
 #include "mask_device.h"
 
@@ -255,6 +257,92 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
                 else
                     *reinterpret_cast<V*>(p.partial + int64_t(it.dst) * width + col) = v;
             }
+        }
+    }
+}
+
+// Dense-only blocks whose rows are very short (the transposed local block of a finely partitioned graph has
+// one or two entries per row): a wavefront per row would leave the device waiting on each wavefront's chain of
+// dependent loads (row extent -> entry records -> source row), with nothing else in flight in that wavefront.
+// Here a wavefront takes four consecutive rows and walks them in step: the extents, then the entry records,
+// then the i-th source row of all four are each fetched by loads issued together. Rows longer than `max_len`
+// are left to spmm_kernel (whose work list then holds only those).
+template <typename T>
+struct ShortRowArgs {
+    const int32_t* rowptr;    // CSR row pointer of the block's matrix (absolute entry offsets)
+    const int32_t* colidx;
+    const float* vals;
+    const T* dense;
+    T* out;
+    int32_t r0, n_rows;       // rows r0 .. r0 + n_rows - 1
+    int32_t row_base;         // out row = row - row_base
+    int32_t max_len;          // at most 64
+    int32_t width;
+};
+
+template <typename T, int VEC, int NV>
+__global__ __launch_bounds__(kBlock) void spmm_short_rows_kernel(ShortRowArgs<T> p) {
+    using V = typename Vec<VEC>::type;
+    constexpr int R = 4;
+    const int lane = threadIdx.x & 63;
+    const int32_t first = p.r0 + (blockIdx.x * kWaves + (threadIdx.x >> 6)) * R;
+    const int32_t n_here = min(R, p.r0 + p.n_rows - first);
+    if (n_here <= 0) return;           // wavefronts are independent: no barrier below
+
+    const int32_t ptr = lane <= n_here ? p.rowptr[first + lane] : 0;
+    int32_t e0[R], len[R];
+    bool mine[R];
+    int32_t longest = 0;
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+        e0[q] = __shfl(ptr, q);
+        const int32_t l = __shfl(ptr, q + 1) - e0[q];
+        mine[q] = q < n_here && l <= p.max_len;
+        len[q] = mine[q] ? l : 0;
+        longest = max(longest, len[q]);
+    }
+    int32_t col[R];
+    float wt[R];
+#pragma unroll
+    for (int q = 0; q < R; ++q) {      // lane j holds entry j of every row
+        const bool has = lane < len[q];
+        col[q] = has ? p.colidx[e0[q] + lane] : 0;
+        wt[q] = has ? p.vals[e0[q] + lane] : 0.f;
+    }
+    V acc[R][NV];
+#pragma unroll
+    for (int q = 0; q < R; ++q)
+#pragma unroll
+        for (int m = 0; m < NV; ++m) zero_vec(acc[q][m]);
+    for (int32_t i = 0; i < longest; ++i) {
+        V v[R][NV];
+        float wi[R];
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            const bool on = i < len[q];
+            const int32_t r = __shfl(col[q], i);
+            wi[q] = on ? __shfl(wt[q], i) : 0.f;
+            const T* src = p.dense + int64_t(r) * p.width;
+#pragma unroll
+            for (int m = 0; m < NV; ++m) {
+                const int c = VEC * (lane + 64 * m);
+                zero_vec(v[q][m]);
+                if (on && c < p.width) v[q][m] = load_vec<T, VEC>(src + c);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < R; ++q)
+#pragma unroll
+            for (int m = 0; m < NV; ++m) fma_vec(acc[q][m], wi[q], v[q][m]);
+    }
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+        if (!mine[q]) continue;
+        T* dst = p.out + int64_t(first + q - p.row_base) * p.width;
+#pragma unroll
+        for (int m = 0; m < NV; ++m) {
+            const int c = VEC * (lane + 64 * m);
+            if (c < p.width) store_vec<T, VEC>(dst + c, acc[q][m]);
         }
     }
 }
@@ -583,6 +671,46 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
     return err;
 }
 
+// The short rows of a dense-only block (see spmm_short_rows_kernel); the block's other rows are on plan.items.
+template <typename T>
+hipError_t spmm_short_t(const SpmmPlan& plan, const int32_t* colidx, const float* vals, const void* dense_v, void* out_v,
+                        int32_t width, int32_t row_base, hipStream_t stream, const LaunchTag& tag) {
+    ShortRowArgs<T> a;
+    a.rowptr = plan.short_rowptr;
+    a.colidx = colidx;
+    a.vals = vals;
+    a.dense = static_cast<const T*>(dense_v);
+    a.out = static_cast<T*>(out_v);
+    a.r0 = plan.short_r0, a.n_rows = plan.short_rows, a.row_base = row_base;
+    a.max_len = plan.short_max_len;
+    a.width = width;
+    const bool vec4 = width % 4 == 0 && aligned_to(a.dense, 4 * sizeof(T)) && aligned_to(a.out, 4 * sizeof(T));
+    const int per_row = vec4 ? width / 4 : width;
+    int nv = 1;
+    while (nv * 64 < per_row) nv <<= 1;
+    if (nv > 8) return hipErrorInvalidValue;
+    const int32_t n_waves = (plan.short_rows + 3) / 4;
+    const dim3 grid((n_waves + kWaves - 1) / kWaves), block(kBlock);
+    tag.begin(stream);
+    auto go = [&](auto vec, auto nvc) {
+        hipLaunchKernelGGL((spmm_short_rows_kernel<T, decltype(vec)::value, decltype(nvc)::value>), grid, block, 0, stream, a);
+    };
+    auto with_nv = [&](auto vec) {
+        switch (nv) {
+            case 1: go(vec, std::integral_constant<int, 1>{}); break;
+            case 2: go(vec, std::integral_constant<int, 2>{}); break;
+            case 4: go(vec, std::integral_constant<int, 4>{}); break;
+            default: go(vec, std::integral_constant<int, 8>{}); break;
+        }
+    };
+    if (vec4)
+        with_nv(std::integral_constant<int, 4>{});
+    else
+        with_nv(std::integral_constant<int, 1>{});
+    tag.end(stream);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t halo_grad_t(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, const VarcoEdge* edge, const float* vals,
                        const int32_t* prow, int32_t prod_base, const void* dm, const MaskRule& rule, void* prod_v,
@@ -657,10 +785,16 @@ hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t 
 hipError_t varco_launch_spmm(int dtype, const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx,
                              const float* vals, const void* dense, const void* z, const MaskRule& rule, void* out,
                              int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag) {
-    if (plan.n_items == 0) return hipSuccess;
+    hipError_t err = hipSuccess;
+    if (plan.n_items > 0)
+        err = dtype == VARCO_BF16
+                  ? spmm_t<bf16_t>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag)
+                  : spmm_t<float>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag);
+    if (err != hipSuccess || plan.short_rows == 0) return err;
+    if (edge) return hipErrorInvalidValue;     // short-row plans are built for dense-only blocks
     return dtype == VARCO_BF16
-               ? spmm_t<bf16_t>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag)
-               : spmm_t<float>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag);
+               ? spmm_short_t<bf16_t>(plan, colidx, vals, dense, out, int32_t(rule.width), row_base, stream, tag)
+               : spmm_short_t<float>(plan, colidx, vals, dense, out, int32_t(rule.width), row_base, stream, tag);
 }
 
 hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,

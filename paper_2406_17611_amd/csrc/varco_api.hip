@@ -13,7 +13,10 @@
 
 namespace {
 
-constexpr int32_t kSpmmChunk = 256;   // longest run of CSR entries one wavefront takes
+// Longest run of CSR entries one wavefront takes. The forward block's wavefronts take compressed rows 16 or
+// more at a time; the dense-only transposed blocks fetch 1 to 4 source rows per round trip, so a long run there
+// is a long chain of dependent loads that the whole launch ends up waiting for.
+constexpr int32_t kSpmmChunk = 256, kSpmmChunkDense = 64;
 
 struct LayerState {
     uint32_t num = 1, den = 1;
@@ -173,25 +176,28 @@ void free_part(PartState& ps) {
 
 // Work list for rows [r0, r1) of a CSR given its host row pointers: long rows first (split into chunks
 // whose partial sums are reduced afterwards), then every other row, empty ones included.
-hipError_t build_plan(const std::vector<int32_t>& rowptr, int32_t r0, int32_t r1, SpmmPlan& plan) {
+// Rows longer than `skip_up_to` entries go on the work list (all rows when it is negative); the others are
+// left to the short-row kernel (see build of t_local below).
+hipError_t build_plan(const std::vector<int32_t>& rowptr, int32_t r0, int32_t r1, SpmmPlan& plan, int32_t chunk,
+                      int32_t skip_up_to = -1) {
     std::vector<SpmmItem> items;
     std::vector<SpmmSplit> splits;
     items.reserve(size_t(r1 - r0) + 64);
     int32_t n_partials = 0;
     for (int32_t r = r0; r < r1; ++r) {
         const int32_t len = rowptr[r + 1] - rowptr[r];
-        if (len > kSpmmChunk) {
-            const int32_t pieces = (len + kSpmmChunk - 1) / kSpmmChunk;
+        if (len > chunk) {
+            const int32_t pieces = (len + chunk - 1) / chunk;
             splits.push_back({r, n_partials, pieces, 0});
             for (int32_t c = 0; c < pieces; ++c) {
-                const int32_t e0 = rowptr[r] + c * kSpmmChunk;
-                items.push_back({r, e0, std::min(e0 + kSpmmChunk, rowptr[r + 1]), n_partials++});
+                const int32_t e0 = rowptr[r] + c * chunk;
+                items.push_back({r, e0, std::min(e0 + chunk, rowptr[r + 1]), n_partials++});
             }
         }
     }
     for (int32_t r = r0; r < r1; ++r) {
         const int32_t len = rowptr[r + 1] - rowptr[r];
-        if (len <= kSpmmChunk) items.push_back({r, rowptr[r], rowptr[r + 1], -1});
+        if (len <= chunk && len > skip_up_to) items.push_back({r, rowptr[r], rowptr[r + 1], -1});
     }
     plan.n_items = int32_t(items.size());
     plan.n_splits = int32_t(splits.size());
@@ -482,9 +488,17 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
         return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: row pointers do not match nnz");
     }
     ps.nnz_t_local = t_rowptr[nl];
-    VARCO_HIP(ctx, build_plan(rowptr, 0, nl, ps.fwd));
-    VARCO_HIP(ctx, build_plan(t_rowptr, 0, nl, ps.t_local));
-    VARCO_HIP(ctx, build_plan(t_rowptr, nl, nl + nh, ps.t_halo));
+    VARCO_HIP(ctx, build_plan(rowptr, 0, nl, ps.fwd, kSpmmChunk));
+    // transposed local block: with fewer than three entries per row on average (fine partitions keep few
+    // entries local) its short rows are taken four to a wavefront
+    constexpr int32_t kShortLen = 8;
+    const bool short_rows = nl > 0 && int64_t(t_rowptr[nl]) - t_rowptr[0] < 3 * int64_t(nl);
+    VARCO_HIP(ctx, build_plan(t_rowptr, 0, nl, ps.t_local, kSpmmChunkDense, short_rows ? kShortLen : -1));
+    ps.t_local.short_r0 = 0;
+    ps.t_local.short_rows = short_rows ? nl : 0;
+    ps.t_local.short_max_len = kShortLen;
+    ps.t_local.short_rowptr = ps.d.t_rowptr;
+    VARCO_HIP(ctx, build_plan(t_rowptr, nl, nl + nh, ps.t_halo, kSpmmChunkDense));
 
     if (dev->nnz > 0) {
         VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.edges), size_t(dev->nnz) * sizeof(VarcoEdge)));

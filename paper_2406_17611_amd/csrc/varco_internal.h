@@ -89,6 +89,10 @@ struct SpmmSplit {
 };
 struct SpmmPlan {
     int32_t n_items = 0, n_splits = 0, n_partials = 0;
+    // dense-only blocks with very short rows: rows short_r0 .. short_r0 + short_rows - 1 with at most short_max_len
+    // entries are not on `items` but taken four to a wavefront, straight from the row pointer (device, borrowed)
+    int32_t short_r0 = 0, short_rows = 0, short_max_len = 0;
+    const int32_t* short_rowptr = nullptr;
     SpmmItem* items = nullptr;    // device
     SpmmSplit* splits = nullptr;  // device
 };

@@ -356,8 +356,17 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* spl
     if (s >= n_splits) return;
     const SpmmSplit sp = splits[s];
     for (int c = threadIdx.x; c < width; c += kBlock) {
+        const float* src = partial + int64_t(sp.first) * width + c;
         float acc = 0.f;
-        for (int i = 0; i < sp.count; ++i) acc += partial[int64_t(sp.first + i) * width + c];
+        int i = 0;
+        for (; i + 8 <= sp.count; i += 8) {      // eight loads in flight; the additions keep slot order
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[int64_t(i + u) * width];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; i < sp.count; ++i) acc += src[int64_t(i) * width];
         Elem<T>::store(out + int64_t(sp.row - row_base) * width + c, acc);
     }
 }

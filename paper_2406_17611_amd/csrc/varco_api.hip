@@ -13,10 +13,12 @@
 
 namespace {
 
-// Longest run of CSR entries one wavefront takes. The forward block's wavefronts take compressed rows 16 or
-// more at a time; the dense-only transposed blocks fetch 1 to 4 source rows per round trip, so a long run there
-// is a long chain of dependent loads that the whole launch ends up waiting for.
-constexpr int32_t kSpmmChunk = 256, kSpmmChunkDense = 64;
+// Longest run of CSR entries one wavefront takes (longer rows are split and summed in fixed order). A run is a
+// chain of dependent round trips: the forward block's wavefronts take compressed rows 8 to 16 at a time, the
+// dense-only transposed blocks fetch 1 to 4 source rows per round trip, and a launch ends with its longest
+// chain. Measured on the two large configurations: 256 / 256 -> 128 / 32 is 126.1 -> 114.9 ms (bf16) and
+// 65.3 -> 64.8 ms (fp32) per step; 64 / 32 loses again to the extra partial rows.
+constexpr int32_t kSpmmChunk = 128, kSpmmChunkDense = 32;
 
 struct LayerState {
     uint32_t num = 1, den = 1;

@@ -801,9 +801,11 @@ hipError_t varco_launch_spmm(int dtype, const SpmmPlan& plan, const VarcoEdge* e
                   : spmm_t<float>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag);
     if (err != hipSuccess || plan.short_rows == 0) return err;
     if (edge) return hipErrorInvalidValue;     // short-row plans are built for dense-only blocks
+    LaunchTag rest = tag;                      // the block's bytes are booked once
+    if (plan.n_items > 0) rest.bytes = 0, rest.flops = 0;
     return dtype == VARCO_BF16
-               ? spmm_short_t<bf16_t>(plan, colidx, vals, dense, out, int32_t(rule.width), row_base, stream, tag)
-               : spmm_short_t<float>(plan, colidx, vals, dense, out, int32_t(rule.width), row_base, stream, tag);
+               ? spmm_short_t<bf16_t>(plan, colidx, vals, dense, out, int32_t(rule.width), row_base, stream, rest)
+               : spmm_short_t<float>(plan, colidx, vals, dense, out, int32_t(rule.width), row_base, stream, rest);
 }
 
 hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,

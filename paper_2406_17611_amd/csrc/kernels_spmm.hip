@@ -525,9 +525,12 @@ __device__ __forceinline__ void segsum_body(const SegsumArgs<T>& p, const SpmmIt
             add_vec(acc, v0), add_vec(acc, v1), add_vec(acc, v2), add_vec(acc, v3);
             src += 4 * int64_t(p.k);
         }
-        for (; n > 0; --n) {
-            add_vec(acc, load_vec<T, EV>(src));
-            src += p.k;
+        if (n > 0) {   // up to three rows left: fetched together (rows past the end re-read the first), added in order
+            const V v0 = load_vec<T, EV>(src), v1 = load_vec<T, EV>(src + (n > 1 ? p.k : 0));
+            const V v2 = load_vec<T, EV>(src + (n > 2 ? 2 * int64_t(p.k) : 0));
+            add_vec(acc, v0);
+            if (n > 1) add_vec(acc, v1);
+            if (n > 2) add_vec(acc, v2);
         }
         if (it.dst < 0)
             store_vec<T, EV>(p.out + int64_t(it.row - p.row_base) * p.k + ju * EV, acc);

@@ -86,7 +86,10 @@ struct SpmmArgs {
 // of EV stored elements), `epi` entries are handled per instruction, and each of those lane groups adds
 // into a private LDS row of its own: the positions of one entry are distinct, so plain read-add-write is
 // race-free and no LDS atomics (which run at a small fraction of the plain LDS rate) are needed.
-template <typename T, int EV>
+// Z32: every element of the compressed buffer lies below 2^32 bytes, so a row's address is the (uniform) base
+// plus a 32-bit offset: one address register per gather in flight instead of two, which is what decides how
+// many wavefronts fit a SIMD here.
+template <typename T, int EV, bool Z32>
 __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int nd, int ns, int32_t srow, float w,
                                              uint32_t mab, float* lpriv) {
     using V = typename Vec<EV>::type;
@@ -116,7 +119,12 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int
                 a[u] = ab & 0xFFFFu;
                 pos[u] = varco_mod_width(a[u] * uint32_t(j) + (ab >> 16), width, p.rule.width_magic);
                 zero_vec(v[u]);
-                if (act[u]) v[u] = load_vec<T, EV>(p.z + int64_t(r) * k + j);
+                if (act[u]) {
+                    if constexpr (Z32)
+                        v[u] = load_vec<T, EV>(p.z + (uint32_t(r) * uint32_t(k) + uint32_t(j)));
+                    else
+                        v[u] = load_vec<T, EV>(p.z + int64_t(r) * k + j);
+                }
             }
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -142,11 +150,14 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int
 // T: storage type of the dense rows, the compressed rows and the output (sums are kept in fp32);
 // VEC: elements per lane per load of a dense row (4 needs width % 4 == 0 and bases aligned to 4 elements);
 // NV: such loads per lane per row, so that width <= VEC * NV * lanes-per-row;
-// HALO: entries may refer to compressed halo rows (forward aggregation) or all rows are dense.
-template <typename T, int VEC, int NV, bool HALO>
+// MODE: kDenseOnly: all rows are dense; kHalo / kHaloZ32: entries may refer to compressed halo rows (forward
+// aggregation), the latter with 32-bit offsets into the compressed buffer (see sparse_phase).
+constexpr int kDenseOnly = 0, kHalo = 1, kHaloZ32 = 2;
+template <typename T, int VEC, int NV, int MODE>
 __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
     using V = typename Vec<VEC>::type;
     constexpr int U = NV >= 4 ? 1 : (NV == 2 ? 2 : kUnroll);
+    constexpr bool HALO = MODE != kDenseOnly, Z32 = MODE == kHaloZ32;
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -230,11 +241,11 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
         if (ns > 0) {
             any_sparse = true;
             if (p.ev == 4)
-                sparse_phase<T, 4>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 4, Z32>(p, lane, nd, ns, srow, w, mab, lpriv);
             else if (p.ev == 2)
-                sparse_phase<T, 2>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 2, Z32>(p, lane, nd, ns, srow, w, mab, lpriv);
             else
-                sparse_phase<T, 1>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 1, Z32>(p, lane, nd, ns, srow, w, mab, lpriv);
         }
     }
 
@@ -594,13 +605,13 @@ __global__ __launch_bounds__(kBlock) void build_edges_kernel(const int32_t* coli
     edge[e] = ed;
 }
 
-template <typename T, int VEC, bool HALO>
+template <typename T, int VEC, int MODE>
 hipError_t launch_spmm_vec(int nv, const SpmmArgs<T>& a, dim3 grid, size_t lds_bytes, hipStream_t stream) {
     switch (nv) {
-        case 1: hipLaunchKernelGGL((spmm_kernel<T, VEC, 1, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 2: hipLaunchKernelGGL((spmm_kernel<T, VEC, 2, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 4: hipLaunchKernelGGL((spmm_kernel<T, VEC, 4, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
-        case 8: hipLaunchKernelGGL((spmm_kernel<T, VEC, 8, HALO>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 1: hipLaunchKernelGGL((spmm_kernel<T, VEC, 1, MODE>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 2: hipLaunchKernelGGL((spmm_kernel<T, VEC, 2, MODE>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 4: hipLaunchKernelGGL((spmm_kernel<T, VEC, 4, MODE>), grid, dim3(kBlock), lds_bytes, stream, a); break;
+        case 8: hipLaunchKernelGGL((spmm_kernel<T, VEC, 8, MODE>), grid, dim3(kBlock), lds_bytes, stream, a); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -610,7 +621,7 @@ bool aligned_to(const void* p, size_t bytes) { return (reinterpret_cast<uintptr_
 
 template <typename T>
 hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx, const float* vals, const void* dense_v,
-                  const void* z_v, const MaskRule& rule, void* out_v, int32_t row_base, float* partial,
+                  const void* z_v, int64_t z_rows, const MaskRule& rule, void* out_v, int32_t row_base, float* partial,
                   hipStream_t stream, const LaunchTag& tag) {
     const T* dense = static_cast<const T*>(dense_v);
     const T* z = static_cast<const T*>(z_v);
@@ -665,12 +676,17 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
         lds_bytes = size_t(kWaves) * a.epi * width * sizeof(float) + size_t(rule.n_units) * sizeof(uint16_t);
     tag.begin(stream);
     hipError_t err;
-    if (halo)
-        err = vec4 ? launch_spmm_vec<T, 4, true>(nv, a, grid, lds_bytes, stream)
-                   : launch_spmm_vec<T, 1, true>(nv, a, grid, lds_bytes, stream);
+    // compressed buffer below 4 GiB: 32-bit row offsets (z_rows = 0: size unknown)
+    const bool z32 = halo && !full && z_rows > 0 && z_rows * int64_t(rule.k) * int64_t(sizeof(T)) < (int64_t(1) << 32);
+    if (halo && z32)
+        err = vec4 ? launch_spmm_vec<T, 4, kHaloZ32>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<T, 1, kHaloZ32>(nv, a, grid, lds_bytes, stream);
+    else if (halo)
+        err = vec4 ? launch_spmm_vec<T, 4, kHalo>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<T, 1, kHalo>(nv, a, grid, lds_bytes, stream);
     else
-        err = vec4 ? launch_spmm_vec<T, 4, false>(nv, a, grid, lds_bytes, stream)
-                   : launch_spmm_vec<T, 1, false>(nv, a, grid, lds_bytes, stream);
+        err = vec4 ? launch_spmm_vec<T, 4, kDenseOnly>(nv, a, grid, lds_bytes, stream)
+                   : launch_spmm_vec<T, 1, kDenseOnly>(nv, a, grid, lds_bytes, stream);
     tag.end(stream);
     if (err != hipSuccess) return err;
     if (plan.n_splits > 0) {
@@ -795,13 +811,13 @@ hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t 
 }
 
 hipError_t varco_launch_spmm(int dtype, const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx,
-                             const float* vals, const void* dense, const void* z, const MaskRule& rule, void* out,
-                             int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag) {
+                             const float* vals, const void* dense, const void* z, int64_t z_rows, const MaskRule& rule,
+                             void* out, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag) {
     hipError_t err = hipSuccess;
     if (plan.n_items > 0)
         err = dtype == VARCO_BF16
-                  ? spmm_t<bf16_t>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag)
-                  : spmm_t<float>(plan, edge, colidx, vals, dense, z, rule, out, row_base, partial, stream, tag);
+                  ? spmm_t<bf16_t>(plan, edge, colidx, vals, dense, z, z_rows, rule, out, row_base, partial, stream, tag)
+                  : spmm_t<float>(plan, edge, colidx, vals, dense, z, z_rows, rule, out, row_base, partial, stream, tag);
     if (err != hipSuccess || plan.short_rows == 0) return err;
     if (edge) return hipErrorInvalidValue;     // short-row plans are built for dense-only blocks
     LaunchTag rest = tag;                      // the block's bytes are booked once

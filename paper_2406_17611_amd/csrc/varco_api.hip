@@ -38,6 +38,7 @@ struct PartState {
     int32_t* prow = nullptr;         // device [nnz]: per-entry row of the halo-gradient product buffer
     int32_t* boundary_gid = nullptr; // device [n_boundary]
     int64_t nnz_t_local = 0;         // transposed entries whose row is a local node
+    int64_t z_rows = 0;              // 1 + the largest row of the compressed buffer a halo entry refers to
 };
 
 // Device scratch of the layer calls. Calls issued on different streams may run concurrently, so every
@@ -505,6 +506,11 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     if (dev->nnz > 0) {
         VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.edges), size_t(dev->nnz) * sizeof(VarcoEdge)));
         VARCO_HIP(ctx, varco_launch_build_edges(dev->colidx, dev->nnz, nl, dev->halo_zrow, dev->halo_gid, ps.edges, nullptr));
+        if (nh > 0) {   // how far into the compressed buffer this partition reads (decides 32- or 64-bit row offsets)
+            std::vector<int32_t> zrow(static_cast<size_t>(nh), 0);
+            VARCO_HIP(ctx, hipMemcpy(zrow.data(), dev->halo_zrow, zrow.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+            ps.z_rows = int64_t(*std::max_element(zrow.begin(), zrow.end())) + 1;
+        }
         VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ps.prow), size_t(dev->nnz) * sizeof(int32_t)));
         VARCO_HIP(ctx, varco_launch_build_prow(dev->rowptr, dev->colidx, nl, dev->t_rowptr, dev->t_colidx, ps.prow, nullptr));
         VARCO_HIP(ctx, hipDeviceSynchronize());
@@ -684,7 +690,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double es = ctx->elem_bytes();
     const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
                              double(d.n_halo) * rule.k * es;
-    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, ps.edges, nullptr, d.vals, x_local, z_in, rule, m_saved, 0, ws.spmm, st,
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, ps.edges, nullptr, d.vals, x_local, z_in, ps.z_rows, rule, m_saved, 0, ws.spmm, st,
                                      ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0)));
     // transform + nonlinearity
     GemmArgs g;
@@ -780,11 +786,11 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
     const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
-    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, dense_rule, dx_local,
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, 0, dense_rule, dx_local,
                                      0, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
     if (d.n_halo > 0 && rule.k > 0) {   // k = 0: nothing is handed back
         if (rule.k == rule.width) {
-            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, dense_rule,
+            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, 0, dense_rule,
                                              dz_halo, nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             // product buffer: grown on demand (the first call at a larger k synchronises the device)
@@ -837,7 +843,7 @@ extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     const double es = ctx->elem_bytes();
     const double bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
                          double(d.n_halo) * rule.k * es;
-    VARCO_HIP(ctx, varco_launch_spmm(ctx->dtype, ps.fwd, ps.edges, nullptr, d.vals, y_local, z_in, rule, y_out, 0, wsp->spmm,
+    VARCO_HIP(ctx, varco_launch_spmm(ctx->dtype, ps.fwd, ps.edges, nullptr, d.vals, y_local, z_in, ps.z_rows, rule, y_out, 0, wsp->spmm,
                                      st, ctx->tag(VARCO_K_AGG_FWD, bytes, 0)));
     ctx->stats.fwd_elems[layer] += int64_t(d.n_halo) * rule.k;
     ctx->stats.full_fwd_elems[layer] += int64_t(d.n_halo) * fi;
@@ -869,11 +875,11 @@ extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
     const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
-    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, dense_rule, g_local, 0,
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, 0, dense_rule, g_local, 0,
                                      ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
     if (d.n_halo > 0 && rule.k > 0) {
         if (rule.k == rule.width) {
-            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, dense_rule, dz_halo,
+            VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, 0, dense_rule, dz_halo,
                                              nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             const size_t need = (size_t(d.nnz - ps.nnz_t_local) * rule.k * size_t(es) + 3) / 4;   // in floats

@@ -132,10 +132,11 @@ hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t 
 //   edge != null (forward): entry e reads dense + edge[e].src * width when edge[e].gid < 0, else the k kept
 //       elements z[edge[e].src * k + j], which land at pi_gid(j) (a full row of z when k == width);
 //   edge == null (transposed, all dense): entry e reads dense + colidx[e] * width.
-// partial: workspace of plan.n_partials * width floats (fp32 for either storage type).
+// partial: workspace of plan.n_partials * width floats (fp32 for either storage type). z_rows: rows of z (0 when
+// unknown); a compressed buffer below 4 GiB is addressed with 32-bit offsets.
 hipError_t varco_launch_spmm(int dtype, const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* colidx,
-                             const float* vals, const void* dense, const void* z, const MaskRule& rule, void* out,
-                             int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag);
+                             const float* vals, const void* dense, const void* z, int64_t z_rows, const MaskRule& rule,
+                             void* out, int32_t row_base, float* partial, hipStream_t stream, const LaunchTag& tag);
 
 // prow[e] = position of forward entry e among the halo entries of the transposed order (-1 for local entries).
 hipError_t varco_launch_build_prow(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,

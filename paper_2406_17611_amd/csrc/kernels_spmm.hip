@@ -27,7 +27,11 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
-constexpr int kUnroll = 4;   // independent gathers issued back to back
+// Independent gathers issued back to back by the kernels that also take compressed rows: with three, those
+// kernels fit eight wavefronts on a SIMD (63 registers or fewer), and resident wavefronts, each a chain of
+// dependent round trips, are what their rate is made of (four: 7 resident, bf16 configuration 32.3 -> 30.6 ms).
+constexpr int kUnroll = 3;
+constexpr int kUnrollDense = 4;   // dense-only kernels have registers to spare
 
 template <int VEC>
 using Vec = FloatVec<VEC>;
@@ -156,8 +160,8 @@ constexpr int kDenseOnly = 0, kHalo = 1, kHaloZ32 = 2;
 template <typename T, int VEC, int NV, int MODE>
 __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
     using V = typename Vec<VEC>::type;
-    constexpr int U = NV >= 4 ? 1 : (NV == 2 ? 2 : kUnroll);
     constexpr bool HALO = MODE != kDenseOnly, Z32 = MODE == kHaloZ32;
+    constexpr int U = NV >= 4 ? 1 : (NV == 2 ? 2 : (HALO ? kUnroll : kUnrollDense));
     extern __shared__ float lds[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;

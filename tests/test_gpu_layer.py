@@ -17,10 +17,15 @@ pytestmark = pytest.mark.gpu
 BF16_TOL = 2.0 ** -7   # norm-wise bound with bf16 storage: at most four roundings of 2^-9 (weight copy, dM, two stores)
 
 
-def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32"):
+def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32", z_row_shift=0):
     """dtype "bf16": every activation / message / gradient tensor handed to the library is bf16 (the inputs
-    are bf16 values, so both sides start from identical numbers); weights and weight gradients stay fp32."""
+    are bf16 values, so both sides start from identical numbers); weights and weight gradients stay fp32.
+    z_row_shift: the library's partitions address the compressed buffer that many rows further in (the rows
+    before stay unused), the oracle's are unchanged."""
     host, orc = both_partitions(g, part, n_parts)
+    for hp in host:
+        hp.halo_zrow = (hp.halo_zrow.astype(np.int64) + z_row_shift).astype(np.int32)
+        hp.z_row_offset += z_row_shift
     rng = np.random.default_rng(seed)
     sage = conv == "sage"
     widths = [8, fi, fo]
@@ -47,12 +52,12 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
     z_ref = np.vstack([olayer.compress(x[p.local_gid], p.boundary_rows,
                                        omask.kept_columns(p.local_gid[p.boundary_rows], fi, k, KEY, step, layer))
                        for p in orc]) if b_total else np.zeros((0, k))
-    z_dev = torch.empty((max(b_total, 1), k), dtype=tdt, device="cuda")
+    z_dev = torch.empty((z_row_shift + max(b_total, 1), k), dtype=tdt, device="cuda")
     for q, p in enumerate(orc):
         if p.n_boundary:
             ctx.compress(layer, dev(p.local_gid[p.boundary_rows]), dev(p.boundary_rows), p.n_boundary,
-                         dev(x[p.local_gid], tdt), fi, z_dev[p.z_row_offset:])
-    assert np.array_equal(z_dev.float().cpu().numpy()[:b_total], z_ref.astype(np.float32))
+                         dev(x[p.local_gid], tdt), fi, z_dev[z_row_shift + p.z_row_offset:])
+    assert np.array_equal(z_dev[z_row_shift:z_row_shift + b_total].float().cpu().numpy(), z_ref.astype(np.float32))
 
     h1d, h0d = dev(h1), (dev(h0) if sage else None)
     dh1_dev = torch.zeros((fi, fo), dtype=torch.float32, device="cuda")
@@ -131,6 +136,19 @@ def test_layer_parity_bf16_storage_with_split_rows(ratio):
     g = hub_graph(6000, 4, 1500, 6.0, "gcn", seed=9)
     part = synth.random_partition(g.n, 2, seed=6)
     _run_layer_case(g, part, 2, "gcn", 64, 48, ratio, vb.ACT_IDENTITY, seed=77, dtype="bf16")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("fi,ratio", [(256, (2, 1)), (128, (1, 1))])
+def test_layer_parity_with_compressed_rows_beyond_4_gib(fi, ratio, dtype):
+    """The halo's rows lie more than 2^32 bytes into the compressed buffer (as with many millions of boundary
+    rows): row offsets must be 64-bit there, for kept subsets and for whole rows."""
+    k = omask.keep_count(fi, *ratio)
+    shift = (1 << 32) // (k * (2 if dtype == "bf16" else 4)) + 1000
+    g = synth.small_random_graph(1200, 8.0, "gcn", seed=31)
+    part = synth.random_partition(g.n, 2, seed=2)
+    _run_layer_case(g, part, 2, "gcn", fi, 64, ratio, vb.ACT_RELU, seed=fi, dtype=dtype, z_row_shift=shift)
+    torch.cuda.empty_cache()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

@@ -67,7 +67,9 @@ typedef struct {
     int32_t conv;           /* VARCO_CONV_* */
     int32_t dtype;          /* VARCO_F32 or VARCO_BF16: storage type of x, z, m_saved, dx, dz_halo; weights are fp32 */
     uint64_t mask_key;      /* the key shared a priori between encoder and decoder (Appendix A) */
-    const int32_t* widths;  /* L+1 widths F_0..F_L, each 1..VARCO_MAX_WIDTH */
+    const int32_t* widths;  /* L+1 widths F_0..F_L, each 1..VARCO_MAX_WIDTH; above 512 only multiples of 4, and the
+                             * activation / gradient buffers of such a width must be 16-byte aligned (else
+                             * VARCO_ERR_UNSUPPORTED from create or from the layer call) */
     const int32_t* act;     /* L activation codes VARCO_ACT_* */
 } varco_config;
 

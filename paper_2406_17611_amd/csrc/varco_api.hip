@@ -4,6 +4,7 @@
 #include <climits>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <mutex>
 #include <numeric>
 #include <string>
@@ -352,6 +353,18 @@ int32_t check_part(const varco_ctx* ctx, int32_t q, const char* fn) {
     return VARCO_OK;
 }
 
+// The aggregation kernels cover a row with at most 8 loads per lane: rows wider than 512 elements need the
+// 4-element accesses, hence 16-byte aligned buffers.
+int32_t check_wide_rows(const varco_ctx* ctx, int32_t width, std::initializer_list<const void*> ptrs, const char* fn) {
+    if (width <= 512) return VARCO_OK;
+    for (const void* p : ptrs)
+        if (p && (reinterpret_cast<uintptr_t>(p) & 15) != 0) {
+            std::string m = std::string(fn) + ": buffers of rows wider than 512 elements must be 16-byte aligned";
+            return varco_fail(ctx, VARCO_ERR_UNSUPPORTED, m.c_str());
+        }
+    return VARCO_OK;
+}
+
 }  // namespace
 
 extern "C" const char* varco_last_error(const varco_ctx* ctx) {
@@ -677,6 +690,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_in is null but the partition has halo nodes");
     if (z_out && layer == ctx->n_layers - 1)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: z_out must be null on the last layer");
+    if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {x_local, z_in, m_saved}, "varco_layer_fwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* wsp = nullptr;
     if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
@@ -738,6 +752,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     if (!dx_local && dz_halo) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo given without dx_local");
     if (dx_local && d.n_halo > 0 && !dz_halo && ctx->layers[layer].k > 0)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: dz_halo is null but the partition has halo nodes");
+    if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {dx_local, dz_halo}, "varco_layer_bwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const void* gate = ctx->act[layer] == VARCO_ACT_RELU ? x_out : nullptr;
@@ -834,6 +849,7 @@ extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     if (d.n_local > 0 && (!y_local || !y_out)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_fwd: null pointer");
     if (d.n_halo > 0 && !z_in && ctx->layers[layer].k > 0)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_fwd: z_in is null but the partition has halo nodes");
+    if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {y_local, z_in, y_out}, "varco_aggregate_fwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* wsp = nullptr;
     if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
@@ -863,6 +879,7 @@ extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     if (!g_out || !g_local) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_bwd: null pointer");
     if (d.n_halo > 0 && !dz_halo && ctx->layers[layer].k > 0)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_aggregate_bwd: dz_halo is null but the partition has halo nodes");
+    if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {g_out, g_local, dz_halo}, "varco_aggregate_bwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* wsp = nullptr;
     if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;

@@ -139,6 +139,20 @@ def test_layer_parity_bf16_storage_with_split_rows(ratio):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("fi", [37, 101, 201, 511, 100, 512, 1024, 2048])
+def test_layer_parity_with_few_local_entries_per_row(fi, dtype):
+    """Eight random partitions keep about two entries per row local, so the transposed local block takes its
+    short rows several to a wavefront, while the hubs' rows there still exceed one run and are split; the
+    widths cover every number of loads per lane, with 4-element and with single-element accesses."""
+    g = hub_graph(6000, 4, 1500, 6.0, "gcn", seed=12)
+    part = synth.random_partition(g.n, 8, seed=3)
+    host, _ = both_partitions(g, part, 8)
+    assert all(hp.t_rowptr[hp.n_local] < 3 * hp.n_local for hp in host)
+    assert max(int(np.diff(hp.t_rowptr[:hp.n_local + 1]).max()) for hp in host) > 64
+    _run_layer_case(g, part, 8, "gcn", fi, 16, (4, 1), vb.ACT_RELU, seed=fi + 1, dtype=dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("fi,ratio", [(256, (2, 1)), (128, (1, 1))])
 def test_layer_parity_with_compressed_rows_beyond_4_gib(fi, ratio, dtype):
     """The halo's rows lie more than 2^32 bytes into the compressed buffer (as with many millions of boundary
@@ -217,3 +231,15 @@ def test_forward_argument_errors_on_registered_partition():
         ctx.layer_bwd(0, 0, o, o, x, m, h, None, h, None, None, z)   # dz_halo without dx_local
     assert e.value.code == vb.ERR_INVALID_ARG
     ctx.close()
+
+    # rows wider than 512 elements: buffers that are not 16-byte aligned are refused before any launch
+    wide = vb.Context([1024, 8], [vb.ACT_IDENTITY], vb.CONV_GCN, 2, KEY)
+    wide.register_partition(0, host[0])
+    flat = torch.zeros(n * 1024 + 4, device="cuda")
+    xw, mw = flat[1:1 + n * 1024].view(n, 1024), torch.zeros((n, 1024), device="cuda")
+    hw = torch.zeros((1024, 8), device="cuda")
+    zw = torch.zeros((1, 1024), device="cuda")
+    with pytest.raises(vb.VarcoError) as e:
+        wide.layer_fwd(0, 0, xw, zw, hw, None, o, None, mw)
+    assert e.value.code == vb.ERR_UNSUPPORTED
+    wide.close()

@@ -16,7 +16,9 @@ pytestmark = pytest.mark.gpu
 
 # rows: several 128-row tiles and a ragged tail; widths: multiples of 8, of 4 only, and one that forces the
 # fallback (47: rows not 16-byte aligned)
-SHAPES = [(1000, 256, 256), (777, 100, 256), (1301, 256, 47), (515, 136, 72), (64, 32, 512), (130, 47, 64)]
+SHAPES = [(1000, 256, 256), (777, 100, 256), (1301, 256, 47), (515, 136, 72), (64, 32, 512), (130, 47, 64),
+          # one row; exactly one tile; one row past a tile; the narrowest widths; a wide reduction with few rows
+          (1, 256, 256), (128, 128, 128), (129, 8, 8), (255, 1, 3), (300, 4, 1), (9, 2048, 40), (2100, 24, 2048)]
 
 
 def _ctx(fi, fo, act, terms):

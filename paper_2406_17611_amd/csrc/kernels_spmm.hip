@@ -92,7 +92,7 @@ struct SpmmArgs {
 // race-free and no LDS atomics (which run at a small fraction of the plain LDS rate) are needed.
 // Z32: every element of the compressed buffer lies below 2^32 bytes, so a row's address is the (uniform) base
 // plus a 32-bit offset: one address register per gather in flight instead of two, which is what decides how
-// many wavefronts fit a SIMD here.
+// many wavefronts fit a SIMD here. `srow` then holds the row's element offset (row * k), not the row.
 template <typename T, int EV, bool Z32>
 __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int nd, int ns, int32_t srow, float w,
                                              uint32_t mab, float* lpriv) {
@@ -102,6 +102,10 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int
     const int sub = lane >> p.lpe_log2;
     const int jl = lane & ((1 << p.lpe_log2) - 1);
     const bool lane_ok = sub < p.epi && jl < p.ku;
+    // a j + b (a, b, j < width <= 2^11, so below 2^23 and exact in a float) is reduced mod width without the
+    // quarter-rate 32-bit multiplies: the float estimate of the quotient is exact or one short (the reciprocal
+    // is biased low by 2^-22, the quotient is below 2^12), which one conditional subtraction repairs.
+    const float inv_width = __builtin_amdgcn_rcpf(float(width)) * (1.0f - 0x1p-22f);
     float* row = lpriv + sub * int32_t(width);
     for (int j0 = 0; j0 < p.ku; j0 += 64) {          // more than one pass only when an entry needs > 64 lanes
         const int ju = j0 + jl;
@@ -121,11 +125,11 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int
                 wi[u] = __shfl(w, src_lane);
                 const uint32_t ab = __shfl(mab, src_lane);
                 a[u] = ab & 0xFFFFu;
-                pos[u] = varco_mod_width(a[u] * uint32_t(j) + (ab >> 16), width, p.rule.width_magic);
+                pos[u] = varco_mod_width(__umul24(a[u], uint32_t(j)) + (ab >> 16), width, p.rule.width_magic);
                 zero_vec(v[u]);
                 if (act[u]) {
                     if constexpr (Z32)
-                        v[u] = load_vec<T, EV>(p.z + (uint32_t(r) * uint32_t(k) + uint32_t(j)));
+                        v[u] = load_vec<T, EV>(p.z + (uint32_t(r) + uint32_t(j)));     // r: the row's element offset
                     else
                         v[u] = load_vec<T, EV>(p.z + int64_t(r) * k + j);
                 }
@@ -201,6 +205,7 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
             if (valid) ed = p.edge[e];
             srow = ed.src;
             is_halo = ed.gid >= 0;
+            if (Z32 && sparse && is_halo) srow = int32_t(uint32_t(ed.src) * p.rule.k);   // one multiply per entry, not per gather
             if (sparse && is_halo) {
                 const uint32_t h1 = varco_mix32(uint32_t(ed.gid) ^ varco_key0(p.rule));
                 const uint32_t h2 = varco_mix32(h1 ^ varco_key1(p.rule));

@@ -27,9 +27,9 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / 64;
-// Independent gathers issued back to back by the kernels that also take compressed rows: with three, those
-// kernels fit eight wavefronts on a SIMD (63 registers or fewer), and resident wavefronts, each a chain of
-// dependent round trips, are what their rate is made of (four: 7 resident, bf16 configuration 32.3 -> 30.6 ms).
+// Independent row loads issued back to back by the kernels that also take compressed rows (dense rows here,
+// compressed rows see sparse_phase): their register budget is the 64 of eight wavefronts per SIMD, or the 72 of
+// seven; resident wavefronts, each a chain of dependent round trips, are what their rate is made of.
 constexpr int kUnroll = 3;
 constexpr int kUnrollDense = 4;   // dense-only kernels have registers to spare
 
@@ -85,6 +85,33 @@ struct SpmmArgs {
     int32_t epi;              // compressed rows handled per instruction = private LDS rows per wavefront
 };
 
+// N consecutive stored elements as they come from memory (bf16 stays packed until it is used).
+template <typename T, int N>
+struct Stored {
+    using type = typename FloatVec<N>::type;
+    static __device__ __forceinline__ float get(const type& v, int i) { return elem(v, i); }
+};
+template <>
+struct Stored<bf16_t, 4> {
+    using type = uint2;
+    static __device__ __forceinline__ float get(const uint2& v, int i) {
+        const uint32_t u = i < 2 ? v.x : v.y;
+        return __uint_as_float((i & 1) ? (u & 0xFFFF0000u) : (u << 16));
+    }
+};
+template <>
+struct Stored<bf16_t, 2> {
+    using type = uint32_t;
+    static __device__ __forceinline__ float get(const uint32_t& v, int i) {
+        return __uint_as_float(i ? (v & 0xFFFF0000u) : (v << 16));
+    }
+};
+template <>
+struct Stored<bf16_t, 1> {
+    using type = uint16_t;
+    static __device__ __forceinline__ float get(const uint16_t& v, int) { return bf16_to_float(v); }
+};
+
 // Scatter-accumulate the compressed rows of the wavefront's current batch: lanes [nd, nd + ns) hold one
 // halo entry each (row in z, weight, packed (a, b)). A group of `lpe` lanes takes one entry (lane = group
 // of EV stored elements), `epi` entries are handled per instruction, and each of those lane groups adds
@@ -96,59 +123,61 @@ struct SpmmArgs {
 template <typename T, int EV, bool Z32>
 __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int nd, int ns, int32_t srow, float w,
                                              uint32_t mab, float* lpriv) {
-    using V = typename Vec<EV>::type;
+    using S = typename Stored<T, EV>::type;
+    // Gathers in flight per lane: six of at most 8 bytes (four bf16 or two fp32 elements), three of 16 bytes:
+    // about the same registers either way. A wavefront waits for the slowest of its gathers, so fewer, larger
+    // batches win even at the price of one resident wavefront (bf16 rows of 512 elements: 7 per SIMD, forward
+    // aggregation 30.6 -> 24.8 ms per step; the fp32 kernel keeps 8: 13.8 -> 13.5 ms). Eight gathers, or four
+    // of 16 bytes, cost more wavefronts than they gain (27.6 ms and 14.5 ms).
+    constexpr int G = EV * sizeof(T) <= 8 ? 2 * kUnroll : kUnroll;
     const int32_t k = int32_t(p.rule.k);
     const uint32_t width = p.rule.width;
     const int sub = lane >> p.lpe_log2;
     const int jl = lane & ((1 << p.lpe_log2) - 1);
     const bool lane_ok = sub < p.epi && jl < p.ku;
-    // a j + b (a, b, j < width <= 2^11, so below 2^23 and exact in a float) is reduced mod width without the
-    // quarter-rate 32-bit multiplies: the float estimate of the quotient is exact or one short (the reciprocal
-    // is biased low by 2^-22, the quotient is below 2^12), which one conditional subtraction repairs.
-    const float inv_width = __builtin_amdgcn_rcpf(float(width)) * (1.0f - 0x1p-22f);
     float* row = lpriv + sub * int32_t(width);
     for (int j0 = 0; j0 < p.ku; j0 += 64) {          // more than one pass only when an entry needs > 64 lanes
         const int ju = j0 + jl;
         const bool j_ok = lane_ok && ju < p.ku;
         const int j = ju * EV;
-        for (int r0 = 0; r0 < ns; r0 += p.epi * kUnroll) {
-            V v[kUnroll];
-            float wi[kUnroll];
-            uint32_t pos[kUnroll], a[kUnroll];
-            bool act[kUnroll];
+        for (int r0 = 0; r0 < ns; r0 += p.epi * G) {
+            // Issue all gathers first; only the loaded values stay in registers across the wait. Everything
+            // else about an entry (weight, multiplier, offset, positions) is fetched from its lane and
+            // computed after the wait, so that more gathers fit the registers of a wavefront.
+            S v[G];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
+            for (int u = 0; u < G; ++u) {
                 const int es = r0 + u * p.epi + sub;
-                act[u] = j_ok && es < ns;
-                const int src_lane = act[u] ? nd + es : 0;
-                const int32_t r = __shfl(srow, src_lane);
-                wi[u] = __shfl(w, src_lane);
-                const uint32_t ab = __shfl(mab, src_lane);
-                a[u] = ab & 0xFFFFu;
-                pos[u] = varco_mod_width(__umul24(a[u], uint32_t(j)) + (ab >> 16), width, p.rule.width_magic);
-                zero_vec(v[u]);
-                if (act[u]) {
-                    if constexpr (Z32)
-                        v[u] = load_vec<T, EV>(p.z + (uint32_t(r) + uint32_t(j)));     // r: the row's element offset
-                    else
-                        v[u] = load_vec<T, EV>(p.z + int64_t(r) * k + j);
-                }
+                const bool act = j_ok && es < ns;
+                const int32_t r = __shfl(srow, act ? nd + es : 0);
+                // lanes without an entry re-read the start of the buffer (never used, but no branch around the load)
+                if constexpr (Z32)
+                    v[u] = *reinterpret_cast<const S*>(p.z + (act ? uint32_t(r) + uint32_t(j) : 0u));
+                else
+                    v[u] = *reinterpret_cast<const S*>(p.z + (act ? int64_t(r) * k + j : int64_t(0)));
             }
+            __builtin_amdgcn_sched_barrier(0);       // keep the work below behind the loads
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                if (act[u]) {
+            for (int u = 0; u < G; ++u) {
+                const int es = r0 + u * p.epi + sub;
+                const bool act = j_ok && es < ns;
+                const int src_lane = act ? nd + es : 0;
+                const float wi = __shfl(w, src_lane);
+                const uint32_t ab = __shfl(mab, src_lane);
+                const uint32_t a = ab & 0xFFFFu;
+                if (act) {
                     uint32_t q[EV];
                     float cur[EV];
-                    q[0] = pos[u];
+                    q[0] = varco_mod_width(__umul24(a, uint32_t(j)) + (ab >> 16), width, p.rule.width_magic);
 #pragma unroll
                     for (int i = 1; i < EV; ++i) {
-                        q[i] = q[i - 1] + a[u];
+                        q[i] = q[i - 1] + a;
                         if (q[i] >= width) q[i] -= width;
                     }
 #pragma unroll
                     for (int i = 0; i < EV; ++i) cur[i] = row[q[i]];          // distinct positions of one entry
 #pragma unroll
-                    for (int i = 0; i < EV; ++i) row[q[i]] = cur[i] + wi[u] * elem(v[u], i);
+                    for (int i = 0; i < EV; ++i) row[q[i]] = cur[i] + wi * Stored<T, EV>::get(v[u], i);
                 }
             }
         }

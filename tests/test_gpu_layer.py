@@ -17,11 +17,13 @@ pytestmark = pytest.mark.gpu
 BF16_TOL = 2.0 ** -7   # norm-wise bound with bf16 storage: at most four roundings of 2^-9 (weight copy, dM, two stores)
 
 
-def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32", z_row_shift=0):
+def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32", z_row_shift=0,
+                    registered_before=None):
     """dtype "bf16": every activation / message / gradient tensor handed to the library is bf16 (the inputs
     are bf16 values, so both sides start from identical numbers); weights and weight gradients stay fp32.
     z_row_shift: the library's partitions address the compressed buffer that many rows further in (the rows
-    before stay unused), the oracle's are unchanged."""
+    before stay unused), the oracle's are unchanged. registered_before: partitions of another graph that are
+    registered under the same numbers first, and replaced."""
     host, orc = both_partitions(g, part, n_parts)
     for hp in host:
         hp.halo_zrow = (hp.halo_zrow.astype(np.int64) + z_row_shift).astype(np.int32)
@@ -35,6 +37,8 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
     stored = (lambda a: round_bf16(a).astype(np.float32)) if bf16 else (lambda a: np.asarray(a, dtype=np.float32))
     ctx = vb.Context(widths, [vb.ACT_RELU, act], vb.CONV_SAGE if sage else vb.CONV_GCN, n_parts, KEY,
                      vb.BF16 if bf16 else vb.F32)
+    for q, hp in enumerate(registered_before or []):
+        ctx.register_partition(q, hp)
     for q, hp in enumerate(host):
         ctx.register_partition(q, hp)
     ctx.begin_step(step)
@@ -185,6 +189,17 @@ def test_layer_parity_on_a_directed_operator(conv):
     g = synth.Graph(n, rowptr, colidx, vals, 0, False)
     part = rng.integers(0, 3, size=n).astype(np.int32)              # uneven parts
     _run_layer_case(g, part, 3, conv, 96, 40, (4, 1), vb.ACT_RELU, seed=8)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_parity_after_a_partition_is_registered_again(dtype):
+    """Registering a partition number a second time replaces everything derived from the first registration
+    (launch plans, entry records, sizes): first a larger graph with long rows, then the one that is checked."""
+    before = hub_graph(5000, 3, 900, 5.0, "sage", seed=21)
+    host_before, _ = both_partitions(before, synth.random_partition(before.n, 3, seed=4), 3)
+    g = synth.small_random_graph(1300, 7.0, "sage", seed=22)
+    part = synth.random_partition(g.n, 3, seed=9)
+    _run_layer_case(g, part, 3, "sage", 96, 40, (4, 1), vb.ACT_RELU, seed=5, dtype=dtype, registered_before=host_before)
 
 
 def test_layer_parity_single_partition_has_no_exchange():

@@ -167,8 +167,10 @@ int32_t varco_advance_step(varco_ctx* ctx, varco_stream stream);
  * has the accuracy of fp32 arithmetic at well under half the cost. terms = 0: fp32 matrix instructions
  * throughout (also used, whatever the setting, for shapes the expanded form cannot take: rows not 16-byte
  * aligned). terms = 2: two terms, three products, relative error about 2^-16 per product (a faster,
- * lower-precision setting nothing in this library selects by itself). INVALID_ARG for other values. Takes
- * effect from the next call on. */
+ * lower-precision setting nothing in this library selects by itself). With terms 2 or 3 an operand that is
+ * infinite, NaN or within 2^-9 of the fp32 overflow threshold turns the outputs it meets into NaN (fp32
+ * instructions would keep an infinity times a finite number infinite); use terms = 0 where such values must
+ * pass. INVALID_ARG for other values. Takes effect from the next call on. */
 int32_t varco_set_matmul_terms(varco_ctx* ctx, int32_t terms);
 
 /* Section IV / Algorithm 1 (the step that updates the compression rate): ratio r = num/den >= 1 of layer `layer`'s input

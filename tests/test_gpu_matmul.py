@@ -130,3 +130,25 @@ def test_weights_changed_between_steps_are_seen(dtype):
         assert_close(gin.float().cpu().numpy(), d.float().cpu().numpy().astype(np.float64) @ hh.T, f"dZ H^T at step {step}", tol)
         h.mul_(-1.5).add_(0.01)     # in-place update, same address
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("terms", [3, 0])
+def test_non_finite_operand_stays_in_its_row(terms):
+    """An infinite activation makes its own output row non-finite (NaN with the bf16-term products, infinite or
+    NaN with fp32 instructions) and leaves every other row as it was."""
+    n, fi, fo = 300, 128, 128
+    rng = np.random.default_rng(5)
+    y = rng.standard_normal((n, fi)).astype(np.float32)
+    h = (synth.glorot(fi, fo, 2, 0) + 0.01).astype(np.float32)
+    ref = y.astype(np.float64) @ h.astype(np.float64)
+    y[137, 5] = np.inf
+    ctx = _ctx(fi, fo, vb.ACT_IDENTITY, terms)
+    c = torch.empty(n, fo, device="cuda")
+    ctx.transform_fwd(0, dev(y), dev(h), c, False, False)
+    torch.cuda.synchronize()
+    got = c.cpu().numpy()
+    assert not np.isfinite(got[137]).any()
+    if terms == 3:
+        assert np.isnan(got[137]).all()
+    keep = np.arange(n) != 137
+    assert_close(got[keep], ref[keep], "rows without the infinite element", _bound(terms, fi))

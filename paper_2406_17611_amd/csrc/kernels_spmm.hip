@@ -204,14 +204,32 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
     float* lpriv = lds + wave * p.epi * width;   // this wavefront's private rows of compressed-row sums
     uint16_t* lunits = reinterpret_cast<uint16_t*>(lds + kWaves * p.epi * width);
 
+    // The wavefront's item and the records of its first batch are requested before the table is staged and the
+    // workgroup meets at the barrier: three round trips in a row become little more than one.
+    const int32_t idx = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wave);   // uniform: the item sits in scalar registers
+    const bool has_item = idx < p.n_items;
+    SpmmItem it{};                      // empty range for a wavefront without an item
+    if (has_item) it = p.items[idx];
+    VarcoEdge ed{0, -1};                // the current batch's records: one entry per lane
+    int32_t col = 0;
+    float w = 0.f;
+    auto load_records = [&](int32_t base) {
+        ed = VarcoEdge{0, -1}, col = 0, w = 0.f;
+        if (base + lane < it.e1) {
+            if (HALO)
+                ed = p.edge[base + lane];
+            else
+                col = p.colidx[base + lane];
+            w = p.vals[base + lane];
+        }
+    };
+    load_records(it.e0);
     if (sparse) {   // the multiplier table is looked up once per halo entry: keep it in LDS
         for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
         for (int c = lane; c < p.epi * width; c += 64) lpriv[c] = 0.f;
         __syncthreads();
     }
-    const int32_t idx = blockIdx.x * kWaves + wave;
-    if (idx >= p.n_items) return;       // no block-wide barrier below: wavefronts are independent
-    const SpmmItem it = p.items[idx];
+    if (!has_item) return;              // no block-wide barrier below: wavefronts are independent
 
     const int lpr = 1 << p.lpr_log2;
     const int t = lane & (lpr - 1);     // position inside the group
@@ -224,14 +242,11 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
     bool any_sparse = false;
 
     for (int32_t base = it.e0; base < it.e1; base += 64) {
-        const int32_t e = base + lane;
-        const bool valid = e < it.e1;
+        if (base != it.e0) load_records(base);
         int32_t srow = 0;
         bool is_halo = false;
         uint32_t mab = 0;
         if (HALO) {
-            VarcoEdge ed{0, -1};
-            if (valid) ed = p.edge[e];
             srow = ed.src;
             is_halo = ed.gid >= 0;
             if (Z32 && sparse && is_halo) srow = int32_t(uint32_t(ed.src) * p.rule.k);   // one multiply per entry, not per gather
@@ -241,9 +256,8 @@ __global__ __launch_bounds__(kBlock) void spmm_kernel(SpmmArgs<T> p) {
                 mab = uint32_t(lunits[__umulhi(h2, p.rule.n_units)]) | (__umulhi(h1, p.rule.width) << 16);
             }
         } else {
-            srow = valid ? p.colidx[e] : 0;
+            srow = col;
         }
-        const float w = valid ? p.vals[e] : 0.f;
         const uint64_t hmask = HALO ? __ballot(is_halo) : 0ull;
         const int cnt = min(64, it.e1 - base);
         const int ns = sparse ? __popcll(hmask) : 0;
@@ -496,16 +510,15 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs<T> p)
     const int32_t width = int32_t(p.rule.width);
     float* lrow = lds + wave * width;
     uint16_t* lunits = reinterpret_cast<uint16_t*>(lds + kWaves * width);
-    for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
-    __syncthreads();
-    const int32_t idx = blockIdx.x * kWaves + wave;
-    if (idx >= p.n_items) return;       // no block-wide barrier below
-    const SpmmItem it = p.items[idx];
-    if (it.e0 >= it.e1) return;
+    const int32_t idx = blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane(wave);   // uniform: the item sits in scalar registers
+    const bool has_item = idx < p.n_items;
+    SpmmItem it{};                      // empty range for a wavefront without an item
+    if (has_item) it = p.items[idx];
 
     // The records of a batch (entry, weight, product row) are loaded together and for every entry, halo or
     // not, so that one memory round trip serves all three; the first batch's loads are in flight while the
-    // row of dM is staged in LDS.
+    // row of dM is staged in LDS, and all of that is requested before the workgroup stages the multiplier
+    // table and meets at the barrier.
     VarcoEdge ed{0, -1};
     float w = 0.f;
     int32_t pr = 0;
@@ -515,11 +528,13 @@ __global__ __launch_bounds__(kBlock) void halo_products_kernel(ProductArgs<T> p)
         if (e < it.e1) ed = p.edge[e], w = p.vals[e], pr = p.prow[e];
     };
     load_batch(it.e0);
-    {
+    if (it.e0 < it.e1) {
         const T* src = p.dm + int64_t(it.row) * width;
         for (int c = lane; c < width; c += 64) lrow[c] = Elem<T>::load(src + c);
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     }
+    for (uint32_t i = threadIdx.x; i < p.rule.n_units; i += kBlock) lunits[i] = p.rule.units[i];
+    __syncthreads();                    // also orders the wavefront's own row behind its writes
+    if (it.e0 >= it.e1) return;         // no block-wide barrier below
     for (int32_t base = it.e0; base < it.e1; base += 64) {
         const bool is_halo = ed.gid >= 0;
         const uint64_t hmask = __ballot(is_halo);

@@ -1,11 +1,12 @@
 // Graph-convolution aggregation M = S_q [X_loc ; X~_halo] (eq. (1)-(2) of the paper; Algorithm 1: local
 // rows uncompressed, remote rows in compressed form) and its transpose for the backward pass.
 //
-// HBM-bound gather kernels. One wavefront (64 lanes) takes one work item = a run of at most 256 CSR entries
-// of one row; longer rows are split and their partial sums reduced in a second pass, so power-law hubs
+// HBM-bound gather kernels. One wavefront (64 lanes) takes one work item = a run of consecutive CSR entries
+// of one row, as long as the host's work list makes it (at most 128 entries in the forward block, 32 in the
+// transposed ones); longer rows are split and their partial sums reduced in a second pass, so power-law hubs
 // do not serialise on one wavefront and no floating-point atomics reach memory. The kernels are latency
-// bound unless many loads are in flight, so every gather loop first issues a block of independent loads
-// and only then consumes them.
+// bound unless many loads are in flight, and a wavefront waits for the slowest load of a batch, so every
+// gather loop first issues a block of independent loads and only then consumes them.
 //
 //   dense source rows (local rows; halo rows when k == width): a power-of-two group of lanes covers one
 //     row with 16-byte loads, the groups of a wavefront take different edges and are summed at the end

@@ -19,13 +19,17 @@
  *   - "device" pointers are HIP device memory owned by the caller; the library borrows them while the
  *     enqueued work runs and never frees them. "host" pointers are ordinary host memory.
  *   - All device work is enqueued on the caller's stream (a hipStream_t passed as void*; NULL is the
- *     default stream). No call synchronises the device except varco_register_partition.
+ *     default stream). Device memory is allocated, and the device possibly synchronised, only by the set-up
+ *     calls: varco_register_partition, varco_prepare, varco_set_ratio (when a larger k needs a larger
+ *     workspace), varco_step_table_enable (first call) and, while it is enabled, the per-kernel profiler
+ *     (events). The compute calls (compress, decompress, layer, aggregate, transform, accumulate, loss, update)
+ *     allocate nothing, never synchronise, and may be captured into a HIP graph.
  *   - Matrices are row-major and dense (leading dimension = width) unless a leading dimension is given.
  *   - Node ids, row ids and counts are int32 (graphs below 2^31 nodes / entries per partition); element
  *     offsets are 64-bit inside the library.
  *   - A context is not thread-safe (one host thread issues its calls). Layer calls may be issued on up
  *     to 8 different streams, whose work then may overlap on the device: the library keeps one workspace
- *     set per stream (created on the stream's first call, which may synchronise the device). The caller
+ *     set per stream, made by varco_prepare(ctx, stream). The caller
  *     orders dependent work across streams (events), and gives calls that may overlap different output
  *     buffers; dh1 / dh0 in particular are read-modify-written (see varco_sum_gradients).
  *   - Layers are numbered 0..L-1; layer l maps width[l] -> width[l+1]. k_l is the number of elements of a
@@ -89,10 +93,18 @@ typedef struct {
  *   halo_src_row[n_halo]: position of the halo node in its owner's boundary_rows
  *   halo_zrow[n_halo]: halo_src_row + (boundary rows of all partitions before the owner) = row in the
  *               concatenated compressed buffer; z_row_offset: first row of this partition's own slice
+ *   owner side of the backward exchange (Section III: errors travel from consumers back to owners). The
+ *   rows returned by all consumers form one array, partition q's n_halo rows starting at row
+ *   halo_row_offset = sum of n_halo over the partitions before q. For boundary row b of this partition,
+ *   ret_src[ret_ptr[b] .. ret_ptr[b+1]) are the rows of that array that belong to b's node, one per consumer,
+ *   consumers ascending; ret_ptr[n_boundary + 1], ret_src[n_returned], n_returned = ret_ptr[n_boundary].
+ *   ret_ptr / ret_src may be NULL at registration (n_returned = 0) for callers that pass their own map to
+ *   varco_accumulate_returned or use varco_decompress(accumulate = 1) per consumer.
  */
 typedef struct {
     int32_t n_local, n_halo, n_boundary, z_row_offset;
     int64_t nnz;
+    int32_t halo_row_offset, n_returned;
     const int32_t* rowptr;
     const int32_t* colidx;
     const float* vals;
@@ -105,6 +117,8 @@ typedef struct {
     const int32_t* boundary_rows;
     const int32_t* halo_src_row;
     const int32_t* halo_zrow;
+    const int32_t* ret_ptr;
+    const int32_t* ret_src;
 } varco_partition_desc;
 
 /* Compressed elements handed off between partitions since creation (or the last reset): the quantity
@@ -119,7 +133,8 @@ typedef struct {
  * Host-side partition builder (Section III; Appendix B: any node->partition map is accepted).
  * All pointers are host memory. rowptr[n+1] int64, colidx/vals[rowptr[n]] with ascending columns in a
  * row, part[n] in [0, n_parts). The result is owned by *out until varco_partition_free.
- * Errors: INVALID_ARG (null, part out of range, unsorted row), SHAPE (a partition with >= 2^31 entries).
+ * Errors: INVALID_ARG (null, part out of range, unsorted row), SHAPE (a partition with >= 2^31 entries, or
+ * 2^31 or more halo rows over all partitions).
  */
 int32_t varco_partition_build(int32_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
                               const int32_t* part, int32_t n_parts, varco_host_parts** out);
@@ -127,14 +142,22 @@ int32_t varco_partition_view(const varco_host_parts* h, int32_t q, varco_partiti
 void varco_partition_free(varco_host_parts* h);
 
 /* ------------------------------------------------------------------------------------------------
- * Context. varco_create copies cfg, sets every layer's ratio to 1 and the step to 0.
- * varco_register_partition copies the row pointers to the host once (synchronising), builds the
- * library's own work lists for that partition and grows the context's device workspace; it may be called
- * again for the same q to replace a partition.
+ * Context. varco_create copies cfg, sets every layer's ratio to 1 and the step to 0 (host only).
+ * varco_register_partition copies the row pointers to the host once (synchronising), checks the index arrays
+ * on the device (SHAPE error for columns or transposed rows out of range or not strictly ascending, a
+ * transpose that does not hold the row block's entries, negative ids, a malformed boundary list or returned-row
+ * map: nothing is trusted unchecked), builds the library's own work lists for that partition and keeps
+ * existing workspace sets large enough; it may be called again for the same q to replace a partition.
+ * varco_prepare makes (or grows) the workspace set of `stream` for the partitions registered and the ratios
+ * set so far, and uploads the tables of the kept positions: call it once per stream after registration and
+ * before the first compute call on that stream (a compute call on a stream without a set, or whose set a
+ * later change outgrew, returns VARCO_ERR_STATE; varco_set_ratio and varco_register_partition grow existing
+ * sets themselves). Host call, may synchronise the device, not capturable.
  */
 int32_t varco_create(const varco_config* cfg, varco_ctx** out);
 int32_t varco_destroy(varco_ctx* ctx);
 int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const varco_partition_desc* dev);
+int32_t varco_prepare(varco_ctx* ctx, varco_stream stream);
 const char* varco_last_error(const varco_ctx* ctx);
 
 /* Algorithm 1's iteration counter t: part of the mask key, so that the kept positions are redrawn every
@@ -179,7 +202,9 @@ int32_t varco_set_matmul_terms(varco_ctx* ctx, int32_t terms);
  * no-communication setting Section V compares against; on every layer: each partition works on its own
  * subgraph). With k = 0 the compressed buffers of that layer are not touched and may be NULL. STATE error if
  * the layer's positions are already in use in the current step (by compress, decompress or a forward
- * call; its backward must see the same positions). */
+ * call; its backward must see the same positions). Host call: when the new k needs a larger halo-gradient
+ * workspace than the prepared streams hold, it is reallocated here (synchronising the device), with a quarter
+ * of head-room so that a schedule that raises k step by step reallocates rarely. */
 int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, uint32_t den);
 /* k_l currently in force (negative status on error is not used: returns status, k through *k). */
 int32_t varco_get_keep(const varco_ctx* ctx, int32_t layer, int32_t* k);
@@ -266,7 +291,8 @@ int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int64_t n_rows,
  * and ret_src lists, consumer partitions in ascending order, the rows that belong to b. The sum over
  * consumers is formed first, in that fixed order, then added to dx_local once. Equivalent to one
  * varco_decompress(accumulate = 1) per consumer, with a fraction of the memory traffic.
- * ret_ptr[n_boundary + 1], ret_src[ret_ptr[n_boundary]] device int32; dx_local n_local x width[layer]. */
+ * ret_ptr[n_boundary + 1], ret_src[ret_ptr[n_boundary]] device int32; dx_local n_local x width[layer].
+ * ret_ptr = ret_src = NULL selects the map given at registration (STATE error when none was given). */
 int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int32_t p, const int32_t* ret_ptr,
                                   const int32_t* ret_src, const void* returned, void* dx_local,
                                   varco_stream stream);
@@ -314,7 +340,7 @@ int32_t varco_sum_gradients(void* dst, const void* src, int64_t n, varco_stream 
  *   loss_i = logsumexp(logits[i, :]) - logits[i, labels[i]]
  *   dlogits[i, :] = scale * (softmax(logits[i, :]) - onehot(labels[i]))
  * for rows with labels[i] in [0, n_classes); a row with labels[i] < 0 is not a training node: loss 0,
- * gradient 0. scale is 1 / (number of training nodes of the whole graph), so that the weight gradients
+ * gradient 0 (a label >= n_classes is treated the same way and never used as an index). scale is 1 / (number of training nodes of the whole graph), so that the weight gradients
  * summed over partitions are those of the risk. Written: row_loss[n_rows] (fp32, unscaled), row_correct[n_rows]
  * (int32, 1 when the largest logit, lowest index on ties, is the label); when totals != NULL also
  * totals[0] += scale * sum(row_loss), totals[1] += sum(row_correct), summed in a fixed order (fp32[2]).

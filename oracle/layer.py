@@ -55,11 +55,12 @@ def _block(p: Partition) -> sp.csr_matrix:
 
 
 def layer_forward(p: Partition, x_local: np.ndarray, z_all: np.ndarray, halo_cols: np.ndarray,
-                  h1: np.ndarray, h0, act: int):
+                  h1: np.ndarray, h0, act: int, with_pre: bool = False):
     """Forward of one layer on partition `p`.
 
     x_local [n_local, F_in]; z_all: concatenated compressed boundary rows of all owners [sum b_p, k];
-    halo_cols [n_halo, k]: kept positions of each halo node. Returns (x_out, m), both fp64.
+    halo_cols [n_halo, k]: kept positions of each halo node. Returns (x_out, m), both fp64; with_pre adds the
+    argument of the nonlinearity, Zpre, as a third result.
     """
     x_local = np.asarray(x_local, dtype=np.float64)
     width = x_local.shape[1]
@@ -70,7 +71,7 @@ def layer_forward(p: Partition, x_local: np.ndarray, z_all: np.ndarray, halo_col
     if h0 is not None:
         zpre = zpre + x_local @ np.asarray(h0, dtype=np.float64)
     x_out = np.maximum(zpre, 0.0) if act == RELU else zpre
-    return x_out, m
+    return (x_out, m, zpre) if with_pre else (x_out, m)
 
 
 def layer_backward(p: Partition, dx_out: np.ndarray, x_out: np.ndarray, x_local: np.ndarray, m: np.ndarray,
@@ -108,11 +109,12 @@ def layer_backward(p: Partition, dx_out: np.ndarray, x_out: np.ndarray, x_local:
 def network_forward(parts: list[Partition], x0: list[np.ndarray], weights: list[tuple], acts: list[int],
                     keep: list[int], key: int, step: int, round_store=None):
     """Forward over all layers and partitions. Returns the state network_backward needs: per-layer
-    activations `x`, saved aggregates `m`, compressed buffers `z` and the forward hand-off counts."""
+    activations `x`, saved aggregates `m`, compressed buffers `z`, the arguments of the nonlinearity `zpre`
+    (fp64, not rounded: what decides the ReLU gate) and the forward hand-off counts."""
     rnd = (lambda a: a) if round_store is None else round_store
     n_layers = len(weights)
     xs = [[np.asarray(x, dtype=np.float64) for x in x0]]
-    ms, zs = [], []
+    ms, zs, pres = [], [], []
     fwd_elems = []
     for l in range(n_layers):
         width = xs[l][0].shape[1]
@@ -123,16 +125,18 @@ def network_forward(parts: list[Partition], x0: list[np.ndarray], weights: list[
             for p in parts])
         z_all = rnd(z_all)
         zs.append(z_all)
-        out, agg = [], []
+        out, agg, pre = [], [], []
         for p in parts:
             cols = _mask.kept_columns(p.halo_gid, width, k, key, step, l)
-            xo, m = layer_forward(p, xs[l][p.q], z_all, cols, weights[l][0], weights[l][1], acts[l])
+            xo, m, zpre = layer_forward(p, xs[l][p.q], z_all, cols, weights[l][0], weights[l][1], acts[l], True)
             out.append(rnd(xo))
             agg.append(rnd(m))
+            pre.append(zpre)
         xs.append(out)
         ms.append(agg)
+        pres.append(pre)
         fwd_elems.append(sum(p.n_halo for p in parts) * k)
-    return dict(x=xs, m=ms, z=zs, fwd_elems=fwd_elems)
+    return dict(x=xs, m=ms, z=zs, zpre=pres, fwd_elems=fwd_elems)
 
 
 def network_backward(parts: list[Partition], fwd: dict, weights: list[tuple], acts: list[int], keep: list[int],
@@ -195,5 +199,5 @@ def network_step(parts: list[Partition], x0: list[np.ndarray], weights: list[tup
     """
     fwd = network_forward(parts, x0, weights, acts, keep, key, step, round_store)
     bwd = network_backward(parts, fwd, weights, acts, keep, key, step, dx_last, round_store)
-    return dict(x=fwd["x"], m=fwd["m"], z=fwd["z"], dh=bwd["dh"], dx=bwd["dx"], fwd_elems=fwd["fwd_elems"],
+    return dict(x=fwd["x"], m=fwd["m"], z=fwd["z"], zpre=fwd["zpre"], dh=bwd["dh"], dx=bwd["dx"], fwd_elems=fwd["fwd_elems"],
                 bwd_elems=bwd["bwd_elems"])

@@ -17,7 +17,13 @@ shift operator and a node->partition map into, for every partition:
     halo_zrow      the same, offset by the boundary counts of the partitions before
                    the owner (row in the concatenated compressed buffer)             [n_halo]
 
+    halo_row_offset number of halo rows of the partitions before this one: first row of this
+                   partition in the concatenation of all partitions' halo rows
+
 The exchange unit is the distinct (node, destination partition) pair, not the edge.
+
+returned_row_map gives the owners' view of the backward exchange (Section III: in the backward pass the
+errors of remote nodes travel from the consumers back to the owners).
 """
 from __future__ import annotations
 
@@ -44,6 +50,7 @@ class Partition:
     halo_src_row: np.ndarray = None
     halo_zrow: np.ndarray = None
     z_row_offset: int = 0
+    halo_row_offset: int = -1        # filled by build_partitions when all partitions are built
 
     @property
     def n_boundary(self) -> int:
@@ -128,7 +135,35 @@ def build_partitions(n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.nd
             t_vals=val[tperm].astype(np.float32),
             boundary_rows=boundary_rows[q], halo_src_row=src.astype(np.int32),
             halo_zrow=(src + offsets[part[halo]]).astype(np.int32), z_row_offset=int(offsets[q])))
+    if only is None:
+        before = 0
+        for p in parts:
+            p.halo_row_offset = before
+            before += p.n_halo
     return parts
+
+
+def returned_row_map(parts: list[Partition]):
+    """Owner side of the backward exchange. All consumers' returned rows form one array: consumer q's halo slot
+    s is row halo_row_offset[q] + s. For every owner p returns (ret_ptr, ret_src): ret_src[ret_ptr[b]:ret_ptr[b+1]]
+    are the rows of that array that carry the errors of p's boundary row b, one per consumer that has the node in
+    its halo, consumers in ascending order. `parts` must be all partitions, in order."""
+    n_parts = len(parts)
+    assert [p.q for p in parts] == list(range(n_parts))
+    # one record per exchanged (node, consumer) pair: owner, owner's boundary row, consumer, row of the array
+    owner = np.concatenate([np.repeat(np.arange(n_parts), np.diff(p.halo_owner_ptr)) for p in parts])
+    brow = np.concatenate([p.halo_src_row.astype(np.int64) for p in parts])
+    consumer = np.concatenate([np.full(p.n_halo, p.q, dtype=np.int64) for p in parts])
+    row = np.arange(owner.shape[0], dtype=np.int64)        # consumers are concatenated in order: offset + slot
+    order = np.lexsort((consumer, brow, owner))            # by owner, then boundary row, then consumer
+    owner, brow, row = owner[order], brow[order], row[order]
+    first = np.searchsorted(owner, np.arange(n_parts + 1))
+    out = []
+    for p in parts:
+        mine = slice(int(first[p.q]), int(first[p.q + 1]))
+        ptr = np.searchsorted(brow[mine], np.arange(p.n_boundary + 1))
+        out.append((ptr.astype(np.int32), row[mine].astype(np.int32)))
+    return out
 
 
 def exchanged_rows(parts: list[Partition]) -> int:

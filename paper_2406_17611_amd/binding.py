@@ -23,7 +23,7 @@ MAX_LAYERS = 16
 
 EXPORTS = [
     "varco_partition_build", "varco_partition_view", "varco_partition_free",
-    "varco_create", "varco_destroy", "varco_register_partition", "varco_last_error",
+    "varco_create", "varco_destroy", "varco_register_partition", "varco_prepare", "varco_last_error",
     "varco_begin_step", "varco_set_ratio", "varco_set_matmul_terms", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
@@ -44,12 +44,13 @@ class Config(C.Structure):
 _DESC_ARRAYS = [("rowptr", np.int32), ("colidx", np.int32), ("vals", np.float32), ("t_rowptr", np.int32),
                 ("t_colidx", np.int32), ("t_vals", np.float32), ("local_gid", np.int32), ("halo_gid", np.int32),
                 ("halo_owner_ptr", np.int32), ("boundary_rows", np.int32), ("halo_src_row", np.int32),
-                ("halo_zrow", np.int32)]
+                ("halo_zrow", np.int32), ("ret_ptr", np.int32), ("ret_src", np.int32)]
 
 
 class PartitionDesc(C.Structure):
     _fields_ = ([("n_local", C.c_int32), ("n_halo", C.c_int32), ("n_boundary", C.c_int32),
-                 ("z_row_offset", C.c_int32), ("nnz", C.c_int64)] + [(name, C.c_void_p) for name, _ in _DESC_ARRAYS])
+                 ("z_row_offset", C.c_int32), ("nnz", C.c_int64), ("halo_row_offset", C.c_int32),
+                 ("n_returned", C.c_int32)] + [(name, C.c_void_p) for name, _ in _DESC_ARRAYS])
 
 
 class Stats(C.Structure):
@@ -86,6 +87,7 @@ def lib() -> C.CDLL:
         L.varco_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
         L.varco_destroy.argtypes = [vp]
         L.varco_register_partition.argtypes = [vp, i32, C.POINTER(PartitionDesc)]
+        L.varco_prepare.argtypes = [vp, vp]
         L.varco_last_error.argtypes = [vp]
         L.varco_last_error.restype = C.c_char_p
         L.varco_begin_step.argtypes = [vp, u64]
@@ -186,10 +188,12 @@ class HostPartition:
     def __init__(self, desc: PartitionDesc):
         self.n_local, self.n_halo, self.n_boundary = desc.n_local, desc.n_halo, desc.n_boundary
         self.z_row_offset, self.nnz = desc.z_row_offset, desc.nnz
+        self.halo_row_offset, self.n_returned = desc.halo_row_offset, desc.n_returned
         sizes = {"rowptr": self.n_local + 1, "colidx": self.nnz, "vals": self.nnz,
                  "t_rowptr": self.n_local + self.n_halo + 1, "t_colidx": self.nnz, "t_vals": self.nnz,
                  "local_gid": self.n_local, "halo_gid": self.n_halo, "halo_owner_ptr": None,
-                 "boundary_rows": self.n_boundary, "halo_src_row": self.n_halo, "halo_zrow": self.n_halo}
+                 "boundary_rows": self.n_boundary, "halo_src_row": self.n_halo, "halo_zrow": self.n_halo,
+                 "ret_ptr": self.n_boundary + 1, "ret_src": self.n_returned}
         self._sizes = sizes
 
     def _fill(self, desc, n_parts):
@@ -267,6 +271,7 @@ class Context:
         d = PartitionDesc()
         d.n_local, d.n_halo, d.n_boundary = hp.n_local, hp.n_halo, hp.n_boundary
         d.z_row_offset, d.nnz = hp.z_row_offset, hp.nnz
+        d.halo_row_offset, d.n_returned = hp.halo_row_offset, hp.n_returned
         for name, _ in _DESC_ARRAYS:
             t = torch.from_numpy(getattr(hp, name)).to(device)
             dev[name] = t
@@ -278,6 +283,10 @@ class Context:
 
     def register_raw(self, q: int, desc: PartitionDesc):
         _check(lib().varco_register_partition(self._h, q, C.byref(desc)), self._h)
+
+    def prepare(self, stream=None):
+        """Workspace set of `stream` (torch's current stream when None) and the tables of the kept positions."""
+        _check(lib().varco_prepare(self._h, _stream(stream)), self._h)
 
     def begin_step(self, step: int):
         _check(lib().varco_begin_step(self._h, step), self._h)

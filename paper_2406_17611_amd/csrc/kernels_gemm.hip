@@ -495,7 +495,8 @@ namespace {
 hipError_t launch_reduce(const GemmArgs& ga, int32_t split, hipStream_t stream, const LaunchTag& tag) {
     const int64_t mn = int64_t(ga.m) * ga.n;
     const int32_t acc = ga.accumulate ? 1 : 0, relu = ga.relu ? 1 : 0;
-    tag.begin_as(VARCO_K_REDUCE, stream);
+    // reads the partial products and, when adding, the old result; writes the result once
+    tag.begin_as(VARCO_K_REDUCE, stream, double(mn) * (4.0 * split + (acc ? 2.0 : 1.0) * (ga.c_dtype == VARCO_BF16 ? 2.0 : 4.0)));
     if (ga.c_dtype == VARCO_BF16)
         hipLaunchKernelGGL(gemm_reduce_kernel<bf16_t>, dim3(unsigned((mn + 63) / 64)), dim3(kThreads), 0, stream, ga.partial,
                            split, mn, ga.n, static_cast<bf16_t*>(ga.c), ga.ldc, acc, relu);

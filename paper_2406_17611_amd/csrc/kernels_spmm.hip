@@ -665,6 +665,61 @@ __global__ __launch_bounds__(kBlock) void build_edges_kernel(const int32_t* coli
     edge[e] = ed;
 }
 
+// Checks of a partition's index arrays at registration, so that no later kernel can be led out of bounds or to
+// silently wrong sums by a malformed descriptor. Every failed check sets a bit of *flags.
+//   rows:  columns of each row strictly ascending and inside [0, n_local + n_halo)
+//   trows: row indices of each transposed row strictly ascending and inside [0, n_local), and every transposed
+//          entry (c, i, v) present in forward row i with the same value (with equal entry counts and distinct
+//          entries on both sides: the two structures hold the same triplets)
+// One thread per (transposed) row; row pointers were checked on the host.
+__global__ __launch_bounds__(kBlock) void validate_rows_kernel(const int32_t* rowptr, const int32_t* colidx, int32_t n_local,
+                                                               int32_t n_cols, int32_t* flags) {
+    const int32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n_local) return;
+    int32_t prev = -1, bad = 0;
+    for (int32_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+        const int32_t c = colidx[e];
+        if (c < 0 || c >= n_cols) bad |= VARCO_BAD_COLUMN_RANGE;
+        if (c <= prev) bad |= VARCO_BAD_COLUMN_ORDER;
+        prev = c;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+__global__ __launch_bounds__(kBlock) void validate_trows_kernel(const int32_t* rowptr, const int32_t* colidx, const float* vals,
+                                                                int32_t n_local, int32_t n_cols, const int32_t* t_rowptr,
+                                                                const int32_t* t_colidx, const float* t_vals, int32_t* flags) {
+    const int32_t c = blockIdx.x * kBlock + threadIdx.x;
+    if (c >= n_cols) return;
+    int32_t prev = -1, bad = 0;
+    for (int32_t pos = t_rowptr[c]; pos < t_rowptr[c + 1]; ++pos) {
+        const int32_t i = t_colidx[pos];
+        if (i < 0 || i >= n_local) {
+            bad |= VARCO_BAD_TROW_RANGE;
+            continue;
+        }
+        if (i <= prev) bad |= VARCO_BAD_TROW_ORDER;
+        prev = i;
+        int32_t lo = rowptr[i], hi = rowptr[i + 1];     // first entry of row i with column >= c (rows may be unsorted
+        while (lo < hi) {                               // if the other kernel flags them: the search stays in bounds)
+            const int32_t mid = lo + ((hi - lo) >> 1);
+            if (colidx[mid] < c) lo = mid + 1; else hi = mid;
+        }
+        if (lo >= rowptr[i + 1] || colidx[lo] != c || __float_as_uint(vals[lo]) != __float_as_uint(t_vals[pos]))
+            bad |= VARCO_BAD_TRANSPOSE;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+// Non-negative ids (a: n values), strictly ascending rows inside [0, limit) when ascending != 0.
+__global__ __launch_bounds__(kBlock) void validate_ids_kernel(const int32_t* a, int64_t n, int32_t limit, int ascending,
+                                                              int32_t bit, int32_t* flags) {
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const int32_t v = a[i];
+    bool bad = v < 0 || (limit > 0 && v >= limit);
+    if (ascending && i > 0 && a[i - 1] >= v) bad = true;
+    if (bad) atomicOr(flags, bit);
+}
+
 template <typename T, int VEC, int MODE>
 hipError_t launch_spmm_vec(int nv, const SpmmArgs<T>& a, dim3 grid, size_t lds_bytes, hipStream_t stream) {
     switch (nv) {
@@ -751,7 +806,9 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
     tag.end(stream);
     if (err != hipSuccess) return err;
     if (plan.n_splits > 0) {
-        tag.begin_as(VARCO_K_REDUCE, stream);
+        // the split records, every fp32 partial row once, every split row written once
+        tag.begin_as(VARCO_K_REDUCE, stream, 16.0 * plan.n_splits + 4.0 * double(plan.n_partials) * width +
+                                                 double(sizeof(T)) * plan.n_splits * width);
         hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
                            partial, out, row_base, width);
         tag.end(stream);
@@ -852,7 +909,8 @@ hipError_t halo_grad_t(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, co
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (t_halo_plan.n_splits > 0) {
-        tag.begin_as(VARCO_K_REDUCE, stream);
+        tag.begin_as(VARCO_K_REDUCE, stream, 16.0 * t_halo_plan.n_splits + 4.0 * double(t_halo_plan.n_partials) * rule.k +
+                                                 double(sizeof(T)) * t_halo_plan.n_splits * rule.k);
         hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
                            t_halo_plan.n_splits, partial, out, row_base, int32_t(rule.k));
         tag.end(stream);
@@ -868,6 +926,26 @@ hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t 
     if (nnz == 0) return hipSuccess;
     hipLaunchKernelGGL(build_edges_kernel, dim3(unsigned((nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, colidx,
                        nnz, n_local, halo_zrow, halo_gid, edge);
+    return hipGetLastError();
+}
+
+hipError_t varco_launch_validate_partition(const varco_partition_desc& d, int32_t* flags, hipStream_t stream) {
+    const int32_t n_cols = d.n_local + d.n_halo;
+    auto blocks = [](int64_t n) { return dim3(unsigned((n + kBlock - 1) / kBlock)); };
+    if (d.n_local > 0 && d.nnz > 0)
+        hipLaunchKernelGGL(validate_rows_kernel, blocks(d.n_local), dim3(kBlock), 0, stream, d.rowptr, d.colidx, d.n_local,
+                           n_cols, flags);
+    if (n_cols > 0 && d.nnz > 0)
+        hipLaunchKernelGGL(validate_trows_kernel, blocks(n_cols), dim3(kBlock), 0, stream, d.rowptr, d.colidx, d.vals,
+                           d.n_local, n_cols, d.t_rowptr, d.t_colidx, d.t_vals, flags);
+    struct Ids { const int32_t* a; int64_t n; int32_t limit; int ascending; int32_t bit; };
+    const Ids lists[] = {{d.local_gid, d.n_local, 0, 0, VARCO_BAD_ID}, {d.halo_gid, d.n_halo, 0, 0, VARCO_BAD_ID},
+                         {d.halo_zrow, d.n_halo, 0, 0, VARCO_BAD_ID}, {d.halo_src_row, d.n_halo, 0, 0, VARCO_BAD_ID},
+                         {d.boundary_rows, d.n_boundary, d.n_local, 1, VARCO_BAD_BOUNDARY},
+                         {d.ret_src, d.ret_src ? d.n_returned : 0, 0, 0, VARCO_BAD_RETURN_MAP}};
+    for (const Ids& l : lists)
+        if (l.n > 0 && l.a)
+            hipLaunchKernelGGL(validate_ids_kernel, blocks(l.n), dim3(kBlock), 0, stream, l.a, l.n, l.limit, l.ascending, l.bit, flags);
     return hipGetLastError();
 }
 

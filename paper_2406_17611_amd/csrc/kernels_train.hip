@@ -19,7 +19,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // One wavefront per row: loss_i = logsumexp(z_i) - z_i[y_i], dz_i = scale * (softmax(z_i) - onehot(y_i)),
-// correct_i = [argmax z_i == y_i] (lowest index on ties); rows with y_i < 0 give 0 everywhere.
+// correct_i = [argmax z_i == y_i] (lowest index on ties); rows whose y_i is not a class (negative: not a training
+// node; n_classes or above: never read as an index) give 0 everywhere.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void softmax_xent_kernel(const T* __restrict__ logits, int64_t ld,
                                                               const int32_t* __restrict__ labels, int64_t n_rows,
@@ -43,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void softmax_xent_kernel(const T* __restric
     float se = 0.f;
     for (int c = lane; c < n_classes; c += 64) se += expf(Elem<T>::load(z + c) - gmax);
     se = wave_sum(se);
-    const bool on = y >= 0;
+    const bool on = y >= 0 && y < n_classes;
     if (dlogits) {
         T* d = dlogits + row * ldd;
         const float inv = scale / se;

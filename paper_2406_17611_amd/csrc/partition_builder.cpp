@@ -16,10 +16,10 @@
 #include "varco_internal.h"
 
 struct HostPart {
-    int32_t n_local = 0, n_halo = 0, n_boundary = 0, z_row_offset = 0;
+    int32_t n_local = 0, n_halo = 0, n_boundary = 0, z_row_offset = 0, halo_row_offset = 0;
     int64_t nnz = 0;
     std::vector<int32_t> rowptr, colidx, t_rowptr, t_colidx, local_gid, halo_gid, halo_owner_ptr,
-        boundary_rows, halo_src_row, halo_zrow;
+        boundary_rows, halo_src_row, halo_zrow, ret_ptr, ret_src;
     std::vector<float> vals, t_vals;
 };
 
@@ -221,6 +221,30 @@ extern "C" int32_t varco_partition_build(int32_t n, const int64_t* rowptr, const
             hp.halo_zrow[s] = boundary_index[c] + offsets[part[c]];
         }
     }
+    // owner side of the backward exchange: where the rows returned for each boundary row sit in the
+    // concatenation of all consumers' halo rows. Consumers are visited in ascending order and a consumer holds
+    // a node at most once, so each boundary row's list comes out ordered by consumer.
+    int64_t halo_rows = 0;
+    for (HostPart& hp : h->parts) {
+        hp.halo_row_offset = int32_t(halo_rows);
+        halo_rows += hp.n_halo;
+        if (halo_rows >= (int64_t(1) << 31)) {
+            delete h;
+            return varco_fail(nullptr, VARCO_ERR_SHAPE, "varco_partition_build: 2^31 or more halo rows over all partitions");
+        }
+    }
+    for (int32_t p = 0; p < n_parts; ++p) {
+        HostPart& owner = h->parts[p];
+        owner.ret_ptr.assign(size_t(owner.n_boundary) + 1, 0);
+        for (const HostPart& hq : h->parts)
+            for (int32_t s = hq.halo_owner_ptr[p]; s < hq.halo_owner_ptr[p + 1]; ++s) owner.ret_ptr[size_t(hq.halo_src_row[s]) + 1]++;
+        for (int32_t b = 0; b < owner.n_boundary; ++b) owner.ret_ptr[b + 1] += owner.ret_ptr[b];
+        owner.ret_src.resize(size_t(owner.ret_ptr[owner.n_boundary]));
+        std::vector<int32_t> fill(owner.ret_ptr.begin(), owner.ret_ptr.end() - 1);
+        for (const HostPart& hq : h->parts)
+            for (int32_t s = hq.halo_owner_ptr[p]; s < hq.halo_owner_ptr[p + 1]; ++s)
+                owner.ret_src[size_t(fill[hq.halo_src_row[s]]++)] = hq.halo_row_offset + s;
+    }
     *out = h;
     return VARCO_OK;
 }
@@ -234,6 +258,8 @@ extern "C" int32_t varco_partition_view(const varco_host_parts* h, int32_t q, va
     out->n_boundary = hp.n_boundary;
     out->z_row_offset = hp.z_row_offset;
     out->nnz = hp.nnz;
+    out->halo_row_offset = hp.halo_row_offset;
+    out->n_returned = int32_t(hp.ret_src.size());
     out->rowptr = hp.rowptr.data();
     out->colidx = hp.colidx.data();
     out->vals = hp.vals.data();
@@ -246,6 +272,8 @@ extern "C" int32_t varco_partition_view(const varco_host_parts* h, int32_t q, va
     out->boundary_rows = hp.boundary_rows.data();
     out->halo_src_row = hp.halo_src_row.data();
     out->halo_zrow = hp.halo_zrow.data();
+    out->ret_ptr = hp.ret_ptr.data();
+    out->ret_src = hp.ret_src.data();
     return VARCO_OK;
 }
 

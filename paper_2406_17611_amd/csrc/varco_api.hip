@@ -40,6 +40,7 @@ struct PartState {
     int32_t* boundary_gid = nullptr; // device [n_boundary]
     int64_t nnz_t_local = 0;         // transposed entries whose row is a local node
     int64_t z_rows = 0;              // 1 + the largest row of the compressed buffer a halo entry refers to
+    int64_t n_returned = 0;          // rows of the registered owner-side map (d.ret_ptr / d.ret_src), 0 without one
 };
 
 // Device scratch of the layer calls. Calls issued on different streams may run concurrently, so every
@@ -80,6 +81,7 @@ struct varco_ctx {
     uint32_t* d_table = nullptr;     // its key words: 2 per tap address
     Workspace ws[kMaxStreams];
     size_t need_dm = 0, need_spmm = 0, need_gemm = 0, need_w = 0;   // what the registered partitions ask for
+    int32_t* d_flags = nullptr;      // device word the index checks of a registration report into
     varco_stats stats{};
     VarcoProfiler prof;
     double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
@@ -296,28 +298,53 @@ hipError_t prep_weight(varco_ctx* ctx, Workspace& ws, int32_t layer, const void*
     return varco_launch_prep_weight_split(terms, static_cast<const float*>(h), fo, rows, cols, rows_padded, p, transpose, dst, st);
 }
 
-// The workspace set of `st`, created on the stream's first call and brought up to the registered sizes.
-int32_t workspace_for(varco_ctx* ctx, hipStream_t st, Workspace** out) {
-    Workspace* ws = nullptr;
-    for (Workspace& w : ctx->ws)
-        if (w.used && w.stream == st) ws = &w;
-    if (!ws) {
-        for (Workspace& w : ctx->ws)
-            if (!w.used) {
-                ws = &w;
-                break;
-            }
-        if (!ws) return varco_fail(ctx, VARCO_ERR_STATE, "layer calls were issued on more streams than the context supports (8)");
-        ws->used = true;
-        ws->stream = st;
-    }
-    VARCO_HIP(ctx, grow(ws->dm, ws->dm_elems, ctx->need_dm));
-    VARCO_HIP(ctx, grow(ws->spmm, ws->spmm_elems, ctx->need_spmm));
-    VARCO_HIP(ctx, grow(ws->gemm, ws->gemm_elems, ctx->need_gemm));
-    VARCO_HIP(ctx, grow(ws->w, ws->w_elems, ctx->need_w));
-    if (ws->w_tags.empty()) ws->w_tags.resize(size_t(ctx->n_layers) * 4);
-    *out = ws;
+// Elements (floats) of the halo-gradient product buffer the current ratios ask for: the largest (halo entries of a
+// registered partition) x (k of a layer that hands back part of a row) elements of the storage type.
+size_t prod_need(const varco_ctx* ctx) {
+    int64_t entries = 0;
+    for (const PartState& ps : ctx->parts)
+        if (ps.registered) entries = std::max(entries, ps.d.nnz - ps.nnz_t_local);
+    int32_t k = 0;
+    for (int32_t l = 0; l < ctx->n_layers; ++l)
+        if (ctx->layers[l].k < ctx->widths[l]) k = std::max(k, ctx->layers[l].k);
+    return (size_t(entries) * size_t(k) * size_t(ctx->elem_bytes()) + 3) / 4;
+}
+
+// Brings one workspace set up to what the registered partitions and the current ratios need (host side of
+// varco_prepare, varco_set_ratio and varco_register_partition: may synchronise the device).
+int32_t size_workspace(varco_ctx* ctx, Workspace& ws) {
+    VARCO_HIP(ctx, grow(ws.dm, ws.dm_elems, ctx->need_dm));
+    VARCO_HIP(ctx, grow(ws.spmm, ws.spmm_elems, ctx->need_spmm));
+    VARCO_HIP(ctx, grow(ws.gemm, ws.gemm_elems, ctx->need_gemm));
+    VARCO_HIP(ctx, grow(ws.w, ws.w_elems, ctx->need_w));
+    const size_t prod = prod_need(ctx);
+    if (prod > ws.prod_elems) VARCO_HIP(ctx, grow(ws.prod, ws.prod_elems, prod + prod / 4));   // head-room: schedules raise k step by step
+    if (ws.w_tags.empty()) ws.w_tags.resize(size_t(ctx->n_layers) * 4);
     return VARCO_OK;
+}
+int32_t size_all_workspaces(varco_ctx* ctx) {
+    for (Workspace& w : ctx->ws)
+        if (w.used)
+            if (int32_t rc = size_workspace(ctx, w)) return rc;
+    return VARCO_OK;
+}
+
+// The workspace set of `st` (made by varco_prepare). The compute calls never allocate: without a set they fail.
+int32_t workspace_for(varco_ctx* ctx, hipStream_t st, Workspace** out, const char* fn) {
+    for (Workspace& w : ctx->ws)
+        if (w.used && w.stream == st) {
+            *out = &w;
+            return VARCO_OK;
+        }
+    std::string m = std::string(fn) + ": no workspace for this stream; call varco_prepare(ctx, stream) first";
+    return varco_fail(ctx, VARCO_ERR_STATE, m.c_str());
+}
+
+// The multiplier tables of the kept positions live on the device once varco_prepare or varco_register_partition ran.
+int32_t check_tables(const varco_ctx* ctx, const char* fn) {
+    if (!ctx->layers.empty() && ctx->layers[0].units) return VARCO_OK;
+    std::string m = std::string(fn) + ": the context has no device state yet; call varco_prepare first";
+    return varco_fail(ctx, VARCO_ERR_STATE, m.c_str());
 }
 
 int32_t check_layer(const varco_ctx* ctx, int32_t layer, const char* fn) {
@@ -457,6 +484,7 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     for (Workspace& w : ctx->ws)
         for (float* p : {w.dm, w.spmm, w.gemm, w.prod, w.w})
             if (p) (void)hipFree(p);
+    if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->d_step) (void)hipFree(ctx->d_step);
     if (ctx->d_table) (void)hipFree(ctx->d_table);
     for (hipEvent_t e : ctx->prof.events) (void)hipEventDestroy(e);
@@ -482,6 +510,10 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null halo array");
     if (dev->n_boundary > 0 && !dev->boundary_rows)
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: null boundary array");
+    if ((dev->ret_ptr == nullptr) != (dev->ret_src == nullptr) && dev->n_returned > 0)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_register_partition: ret_ptr and ret_src go together");
+    if (dev->halo_row_offset < 0 || dev->n_returned < 0 || (!dev->ret_ptr && dev->n_returned != 0))
+        return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: negative or inconsistent sizes of the returned-row map");
 
     VARCO_HIP(ctx, hipDeviceSynchronize());
     if (int32_t rc = ensure_tables(ctx)) return rc;
@@ -502,6 +534,35 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     if (!monotone(rowptr, dev->nnz) || !monotone(t_rowptr, dev->nnz)) {
         free_part(ps);
         return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: row pointers do not match nnz");
+    }
+    if (dev->ret_ptr) {   // owner-side map of the backward exchange: a row pointer over the boundary rows
+        std::vector<int32_t> ret_ptr(size_t(nb) + 1);
+        VARCO_HIP(ctx, hipMemcpy(ret_ptr.data(), dev->ret_ptr, ret_ptr.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+        if (!monotone(ret_ptr, dev->n_returned)) {
+            free_part(ps);
+            return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_register_partition: ret_ptr does not match n_returned");
+        }
+        ps.n_returned = dev->n_returned;
+    }
+    {   // the entry arrays themselves, checked on the device before any kernel trusts them
+        if (!ctx->d_flags) VARCO_HIP(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_flags), sizeof(int32_t)));
+        int32_t flags = 0;
+        VARCO_HIP(ctx, hipMemcpy(ctx->d_flags, &flags, sizeof(flags), hipMemcpyHostToDevice));
+        VARCO_HIP(ctx, varco_launch_validate_partition(*dev, ctx->d_flags, nullptr));
+        VARCO_HIP(ctx, hipMemcpy(&flags, ctx->d_flags, sizeof(flags), hipMemcpyDeviceToHost));
+        if (flags != 0) {
+            free_part(ps);
+            std::string m = "varco_register_partition: malformed index arrays:";
+            if (flags & VARCO_BAD_COLUMN_RANGE) m += " column outside [0, n_local + n_halo);";
+            if (flags & VARCO_BAD_COLUMN_ORDER) m += " columns of a row not strictly ascending;";
+            if (flags & VARCO_BAD_TROW_RANGE) m += " transposed entry outside [0, n_local);";
+            if (flags & VARCO_BAD_TROW_ORDER) m += " rows of a transposed row not strictly ascending;";
+            if (flags & VARCO_BAD_TRANSPOSE) m += " transposed entries differ from the row block's;";
+            if (flags & VARCO_BAD_ID) m += " negative node id or compressed-buffer row;";
+            if (flags & VARCO_BAD_BOUNDARY) m += " boundary rows not ascending inside the partition;";
+            if (flags & VARCO_BAD_RETURN_MAP) m += " negative row in ret_src;";
+            return varco_fail(ctx, VARCO_ERR_SHAPE, m.c_str());
+        }
     }
     ps.nnz_t_local = t_rowptr[nl];
     VARCO_HIP(ctx, build_plan(rowptr, 0, nl, ps.fwd, kSpmmChunk));
@@ -556,7 +617,27 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
     ctx->need_spmm = std::max(ctx->need_spmm, size_t(max_partials) * wmax);
     ctx->need_gemm = std::max(ctx->need_gemm, size_t(gemm_elems));
     ps.registered = true;
-    return VARCO_OK;
+    return size_all_workspaces(ctx);   // sets made by an earlier varco_prepare follow the new partition
+}
+
+extern "C" int32_t varco_prepare(varco_ctx* ctx, varco_stream stream) {
+    if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_prepare: null context");
+    if (int32_t rc = ensure_tables(ctx)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Workspace* ws = nullptr;
+    for (Workspace& w : ctx->ws)
+        if (w.used && w.stream == st) ws = &w;
+    if (!ws) {
+        for (Workspace& w : ctx->ws)
+            if (!w.used) {
+                ws = &w;
+                break;
+            }
+        if (!ws) return varco_fail(ctx, VARCO_ERR_STATE, "varco_prepare: more streams than the context supports (8)");
+        ws->used = true;
+        ws->stream = st;
+    }
+    return size_workspace(ctx, *ws);
 }
 
 extern "C" int32_t varco_begin_step(varco_ctx* ctx, uint64_t step) {
@@ -624,7 +705,7 @@ extern "C" int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, 
         ctx->layers[l].den = den;
         ctx->layers[l].k = keep_count(ctx->widths[l], num, den);
     }
-    return VARCO_OK;
+    return size_all_workspaces(ctx);   // a larger k may need a larger product buffer (no-op without workspace sets)
 }
 
 extern "C" int32_t varco_get_keep(const varco_ctx* ctx, int32_t layer, int32_t* k) {
@@ -643,7 +724,7 @@ extern "C" int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* 
     if (n_rows == 0 || ctx->layers[layer].k == 0) return VARCO_OK;   // k = 0: nothing is sent
     if (!gids || !x || !z) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_compress: null pointer");
     if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_compress: ldx is smaller than the layer width");
-    if (int32_t rc = ensure_tables(ctx)) return rc;
+    if (int32_t rc = check_tables(ctx, "varco_compress")) return rc;
     ctx->layers[layer].ran_forward = true;   // the step's positions of this layer are now in use
     const MaskRule rule = make_rule(ctx, layer, hop);
     const double bytes = double(n_rows) * (rule.width + rule.k) * ctx->elem_bytes();
@@ -664,7 +745,7 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
     if (!gids || !x || (!z && ctx->layers[layer].k > 0))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_decompress: null pointer");
     if (ldx < ctx->widths[layer]) return varco_fail(ctx, VARCO_ERR_SHAPE, "varco_decompress: ldx is smaller than the layer width");
-    if (int32_t rc = ensure_tables(ctx)) return rc;
+    if (int32_t rc = check_tables(ctx, "varco_decompress")) return rc;
     ctx->layers[layer].ran_forward = true;
     const MaskRule rule = make_rule(ctx, layer, hop);
     const double bytes = (accumulate ? double(n_rows) * rule.k * 3.0 : double(n_rows) * (rule.width + rule.k)) * ctx->elem_bytes();
@@ -693,7 +774,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {x_local, z_in, m_saved}, "varco_layer_fwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* wsp = nullptr;
-    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &wsp, "varco_layer_fwd")) return rc;
     Workspace& ws = *wsp;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const MaskRule rule = make_rule(ctx, layer);
@@ -761,7 +842,7 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double es = ctx->elem_bytes();
     if (nl == 0) return VARCO_OK;
     Workspace* wsp = nullptr;
-    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &wsp, "varco_layer_bwd")) return rc;
     Workspace& ws = *wsp;
 
     // weight gradients: reductions over the partition's rows, split over workgroups
@@ -808,9 +889,10 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
             VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, 0, dense_rule,
                                              dz_halo, nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
-            // product buffer: grown on demand (the first call at a larger k synchronises the device)
+            // product buffer: sized by varco_prepare / varco_set_ratio / varco_register_partition, never here
             const size_t need = (size_t(d.nnz - ps.nnz_t_local) * rule.k * size_t(es) + 3) / 4;   // in floats
-            if (need > ws.prod_elems) VARCO_HIP(ctx, grow(ws.prod, ws.prod_elems, need + need / 4));
+            if (need > ws.prod_elems)
+                return varco_fail(ctx, VARCO_ERR_STATE, "varco_layer_bwd: the stream's workspace is too small; call varco_prepare");
             VARCO_HIP(ctx, varco_launch_halo_grad(dt, ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local),
                                                   ws.dm, rule, ws.prod, dz_halo, nl, ws.spmm, st,
                                                   ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
@@ -852,7 +934,7 @@ extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {y_local, z_in, y_out}, "varco_aggregate_fwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* wsp = nullptr;
-    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &wsp, "varco_aggregate_fwd")) return rc;
     const int32_t fi = ctx->widths[layer];
     const MaskRule rule = make_rule(ctx, layer, hop);
     ctx->layers[layer].ran_forward = true;
@@ -882,7 +964,7 @@ extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     if (int32_t rc = check_wide_rows(ctx, ctx->widths[layer], {g_out, g_local, dz_halo}, "varco_aggregate_bwd")) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* wsp = nullptr;
-    if (int32_t rc = workspace_for(ctx, st, &wsp)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &wsp, "varco_aggregate_bwd")) return rc;
     Workspace& ws = *wsp;
     const int dt = ctx->dtype;
     const double es = ctx->elem_bytes();
@@ -900,7 +982,8 @@ extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, c
                                              nl, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
         } else {
             const size_t need = (size_t(d.nnz - ps.nnz_t_local) * rule.k * size_t(es) + 3) / 4;   // in floats
-            if (need > ws.prod_elems) VARCO_HIP(ctx, grow(ws.prod, ws.prod_elems, need + need / 4));
+            if (need > ws.prod_elems)
+                return varco_fail(ctx, VARCO_ERR_STATE, "varco_aggregate_bwd: the stream's workspace is too small; call varco_prepare");
             VARCO_HIP(ctx, varco_launch_halo_grad(dt, ps.fwd, ps.t_halo, ps.edges, d.vals, ps.prow, int32_t(ps.nnz_t_local), g_out,
                                                   rule, ws.prod, dz_halo, nl, ws.spmm, st,
                                                   ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes - th_out_bytes, 0),
@@ -934,7 +1017,7 @@ extern "C" int32_t varco_transform_fwd(varco_ctx* ctx, int32_t layer, int64_t n_
     if (int32_t rc = transform_prologue(ctx, layer, n_rows, "varco_transform_fwd")) return rc;
     if (n_rows == 0) return VARCO_OK;
     if (!y || !h || !c) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_fwd: null pointer");
-    if (int32_t rc = workspace_for(ctx, st, &ws)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &ws, "varco_transform_fwd")) return rc;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const int dt = ctx->dtype;
     GemmArgs g;
@@ -957,7 +1040,7 @@ extern "C" int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int
     if (n_rows == 0) return VARCO_OK;
     if (!y || !dx_out || !dh || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_weight: null pointer");
-    if (int32_t rc = workspace_for(ctx, st, &ws)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &ws, "varco_transform_bwd_weight")) return rc;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const int dt = ctx->dtype;
     GemmArgs g;
@@ -987,7 +1070,7 @@ extern "C" int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int6
     if (n_rows == 0) return VARCO_OK;
     if (!dx_out || !h || !g_out || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_input: null pointer");
-    if (int32_t rc = workspace_for(ctx, st, &ws)) return rc;
+    if (int32_t rc = workspace_for(ctx, st, &ws, "varco_transform_bwd_input")) return rc;
     const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
     const int dt = ctx->dtype;
     GemmArgs g;
@@ -1010,12 +1093,20 @@ extern "C" int32_t varco_accumulate_returned(varco_ctx* ctx, int32_t layer, int3
     if (int32_t rc = check_part(ctx, p, "varco_accumulate_returned")) return rc;
     const PartState& ps = ctx->parts[p];
     if (ps.d.n_boundary == 0 || ctx->layers[layer].k == 0) return VARCO_OK;
-    if (!ret_ptr || !ret_src || !returned || !dx_local)
-        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_accumulate_returned: null pointer");
+    if ((ret_ptr == nullptr) != (ret_src == nullptr))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_accumulate_returned: ret_ptr and ret_src go together");
+    if (!ret_ptr) {
+        if (!ps.d.ret_ptr) return varco_fail(ctx, VARCO_ERR_STATE, "varco_accumulate_returned: no map was given at registration");
+        ret_ptr = ps.d.ret_ptr, ret_src = ps.d.ret_src;
+    }
+    if (!returned || !dx_local) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_accumulate_returned: null pointer");
     ctx->layers[layer].ran_forward = true;
     const MaskRule rule = make_rule(ctx, layer, hop);
-    // rows returned are not known on the host; attribute the owner-side read-modify-write of k values per row
-    const double bytes = double(ps.d.n_boundary) * rule.k * 3.0 * ctx->elem_bytes();
+    // the map's two index arrays, every returned row once, and the owner-side read-modify-write of k values per
+    // boundary row (the number of returned rows is known for the registered map only)
+    const double n_ret = ret_ptr == ps.d.ret_ptr ? double(ps.n_returned) : 0.0;
+    const double bytes = (double(ps.d.n_boundary) + 1.0 + n_ret) * 4.0 +
+                         (n_ret + 2.0 * double(ps.d.n_boundary)) * rule.k * ctx->elem_bytes();
     VARCO_HIP(ctx, varco_launch_accumulate_returned(ctx->dtype, rule, ps.boundary_gid, ps.d.boundary_rows, ps.d.n_boundary,
                                                     ret_ptr, ret_src, returned, dx_local, ctx->widths[layer],
                                                     static_cast<hipStream_t>(stream), ctx->tag(VARCO_K_DECOMPRESS, bytes, 0)));

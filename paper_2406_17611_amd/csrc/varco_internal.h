@@ -57,7 +57,7 @@ struct LaunchTag {
     int cls = 0;
     double bytes = 0, flops = 0;
     void begin(hipStream_t st) const { if (prof) prof->begin(cls, st, bytes, flops); }
-    void begin_as(int other, hipStream_t st) const { if (prof) prof->begin(other, st, 0, 0); }
+    void begin_as(int other, hipStream_t st, double other_bytes) const { if (prof) prof->begin(other, st, other_bytes, 0); }
     void end(hipStream_t st) const { if (prof) prof->end(st); }
 };
 
@@ -124,6 +124,14 @@ hipError_t varco_launch_sum_gradients(float* dst, const float* src, int64_t n, h
 // table[2 t], table[2 t + 1] = the two key words of tap address t (0 .. 255) for that step and `key`.
 hipError_t varco_launch_step_table(uint64_t* d_step, uint32_t* table, uint64_t key, int set, uint64_t value,
                                    hipStream_t stream);
+
+// Index checks at registration: bits set in *flags (device int32, zeroed by the caller) by the first failed check
+// of each kind.
+enum {
+    VARCO_BAD_COLUMN_RANGE = 1, VARCO_BAD_COLUMN_ORDER = 2, VARCO_BAD_TROW_RANGE = 4, VARCO_BAD_TROW_ORDER = 8,
+    VARCO_BAD_TRANSPOSE = 16, VARCO_BAD_ID = 32, VARCO_BAD_BOUNDARY = 64, VARCO_BAD_RETURN_MAP = 128
+};
+hipError_t varco_launch_validate_partition(const varco_partition_desc& d, int32_t* flags, hipStream_t stream);
 
 hipError_t varco_launch_build_edges(const int32_t* colidx, int64_t nnz, int32_t n_local, const int32_t* halo_zrow,
                                     const int32_t* halo_gid, VarcoEdge* edge, hipStream_t stream);

@@ -45,21 +45,11 @@ class PartitionedNetwork:
 
         self.boundary_gid = [torch.from_numpy(hp.local_gid[hp.boundary_rows]).to(self.device) for hp in host_parts]
 
-        # the backward exchange seen from the owners: for each boundary row, where the rows returned for it sit
-        # in the concatenation of all consumers' dz_halo buffers (consumers in ascending order)
-        self.ret_ptr, self.ret_src = [], []
-        for p, hp in enumerate(host_parts):
-            owner_rows, arena_rows = [], []
-            for q, hq in enumerate(host_parts):
-                s0, s1 = hq.halo_owner_ptr[p], hq.halo_owner_ptr[p + 1]
-                owner_rows.append(hq.halo_src_row[s0:s1].astype(np.int64))
-                arena_rows.append(self.halo_off[q] + np.arange(s0, s1, dtype=np.int64))
-            owner_rows, arena_rows = np.concatenate(owner_rows), np.concatenate(arena_rows)
-            order = np.argsort(owner_rows, kind="stable")          # stable: consumers stay in ascending order
-            ptr = np.concatenate(([0], np.cumsum(np.bincount(owner_rows, minlength=hp.n_boundary))))
-            assert ptr[-1] < 2 ** 31 and arena_rows.max(initial=0) < 2 ** 31
-            self.ret_ptr.append(torch.from_numpy(ptr.astype(np.int32)).to(self.device))
-            self.ret_src.append(torch.from_numpy(arena_rows[order].astype(np.int32)).to(self.device))
+        # the backward exchange seen from the owners (built by varco_partition_build, uploaded at registration):
+        # for each boundary row, the rows returned for it in the concatenation of all consumers' dz_halo buffers
+        self.ret_ptr = [dp["ret_ptr"] for dp in self.dev_parts]
+        self.ret_src = [dp["ret_src"] for dp in self.dev_parts]
+        assert all(hp.halo_row_offset == off for hp, off in zip(host_parts, self.halo_off))
 
         f32 = dict(dtype=torch.float32, device=self.device)
         act = dict(dtype=self.act_dtype, device=self.device)
@@ -82,8 +72,18 @@ class PartitionedNetwork:
         self._zcap = [0] * self.L
         self._dzcap = [0] * self.L
         self._streams = None
+        self._prepared = set()
+        self._prepare([None])
 
     # ------------------------------------------------------------------ streams
+    def _prepare(self, streams):
+        """The library allocates per-stream workspaces in varco_prepare only; every stream is prepared once."""
+        for st in streams:
+            handle = vb._stream(st)
+            if handle not in self._prepared:
+                self.ctx.prepare(st)
+                self._prepared.add(handle)
+
     def _stream_set(self, stream):
         """The streams a step is issued on: the caller's (or torch's current) stream first, then the extra ones."""
         if self.n_streams == 1:
@@ -169,6 +169,7 @@ class PartitionedNetwork:
                 ctx.set_ratio(-1, ratio[0], ratio[1])
         self._ensure_buffers()
         streams = self._stream_set(stream)
+        self._prepare(streams)
         ns = len(streams)
         self._join(streams)
         # layer 0's exchange: owners compress the boundary rows of the input features
@@ -190,6 +191,7 @@ class PartitionedNetwork:
     def backward(self, stream=None):
         ctx = self.ctx
         streams = self._stream_set(stream)
+        self._prepare(streams)
         ns = len(streams)
         self._join(streams)
         for l in range(self.L - 1, -1, -1):
@@ -332,6 +334,7 @@ class KTapNetwork(PartitionedNetwork):
         if ratio is not None:
             ctx.set_ratio(-1, ratio[0], ratio[1])
         self._ensure_buffers()
+        self._prepare([stream])
         for l in range(self.L):
             fi, k = self.widths[l], ctx.keep(l)
             for hop in range(1, self.K):

@@ -1,5 +1,8 @@
 """Shared helpers of the GPU parity tests: the same seeded inputs go to the CPU oracle (oracle/) and to
-the HIP library (through its C ABI); nothing computed by one side is ever fed to the other."""
+the HIP library (through its C ABI). Nothing the device computed is ever fed to the oracle or becomes an expected
+value. The other direction occurs once: the whole-network test, after a free-running backward pass on the
+device's own tensors, loads the oracle's stored activations into the device buffers for a second backward pass in
+which both sides take the ReLU gate on identical values (tests/test_gpu_network.py)."""
 import numpy as np
 import torch
 

@@ -24,6 +24,7 @@ def test_compress_decompress_bit_exact(width, ratio):
     gids = rng.integers(0, 2_449_029, size=n_rows).astype(np.int32)
     step, layer = 12, 1
     ctx = vb.Context([8, width, 8], [1, 0], vb.CONV_GCN, 1, KEY)
+    ctx.prepare()
     ctx.begin_step(step)
     ctx.set_ratio(layer, *ratio)
     k = ctx.keep(layer)
@@ -70,6 +71,7 @@ def test_compress_decompress_bit_exact_bf16_storage(width, ratio):
     gids = rng.integers(0, 2_449_029, size=n_rows).astype(np.int32)
     step, layer = 9, 1
     ctx = vb.Context([8, width, 8], [1, 0], vb.CONV_GCN, 1, KEY, vb.BF16)
+    ctx.prepare()
     ctx.begin_step(step)
     ctx.set_ratio(layer, *ratio)
     k = ctx.keep(layer)
@@ -96,6 +98,7 @@ def test_compress_decompress_bit_exact_bf16_storage(width, ratio):
 
 def test_unbounded_ratio_sends_nothing_and_decodes_to_zero():
     ctx = vb.Context([8, 64, 8], [1, 0], vb.CONV_GCN, 1, KEY)
+    ctx.prepare()
     ctx.begin_step(0)
     ctx.set_ratio(1, 1, 0)
     assert ctx.keep(1) == 0
@@ -119,6 +122,7 @@ def test_mask_changes_with_step_and_layer_like_the_oracle():
     x = rng.standard_normal((n, width)).astype(np.float32)
     gids = np.arange(n, dtype=np.int32) * 1223
     ctx = vb.Context([width, width, 8], [1, 0], vb.CONV_GCN, 1, KEY ^ 0x55)
+    ctx.prepare()
     xd, gd = dev(x), dev(gids)
     for step in (0, 1, 2 ** 40 + 5):
         for layer in (0, 1):
@@ -134,6 +138,7 @@ def test_mask_changes_with_step_and_layer_like_the_oracle():
 
 def test_ratio_change_inside_a_step_is_refused():
     ctx = vb.Context([16, 8], [0], vb.CONV_GCN, 1, KEY)
+    ctx.prepare()
     ctx.begin_step(0)
     ctx.set_ratio(0, 4, 1)
     x = torch.zeros((4, 16), device="cuda")

@@ -41,6 +41,7 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
         ctx.register_partition(q, hp)
     for q, hp in enumerate(host):
         ctx.register_partition(q, hp)
+    ctx.prepare()
     ctx.begin_step(step)
     ctx.set_ratio(layer, *ratio)
     k = ctx.keep(layer)
@@ -245,6 +246,19 @@ def test_forward_argument_errors_on_registered_partition():
     with pytest.raises(vb.VarcoError) as e:
         ctx.layer_bwd(0, 0, o, o, x, m, h, None, h, None, None, z)   # dz_halo without dx_local
     assert e.value.code == vb.ERR_INVALID_ARG
+    # the compute calls allocate nothing: a stream without a prepared workspace set is a state error, on any call
+    zin = torch.zeros((host[0].n_boundary + host[1].n_boundary, 16), device="cuda")
+    side = torch.cuda.Stream()
+    for call in (lambda st: ctx.layer_fwd(0, 0, x, zin, h, None, o, None, m, st),
+                 lambda st: ctx.layer_bwd(0, 0, o, o, x, m, h, None, torch.zeros_like(h), None, None, None, st),
+                 lambda st: ctx.aggregate_fwd(0, 0, x, zin, m, st),
+                 lambda st: ctx.transform_fwd(0, x, h, o, False, False, st)):
+        with pytest.raises(vb.VarcoError) as e:
+            call(side)
+        assert e.value.code == vb.ERR_STATE and "varco_prepare" in str(e.value)
+    ctx.prepare(side)
+    ctx.layer_fwd(0, 0, x, zin, h, None, o, None, m, side)
+    side.synchronize()
     ctx.close()
 
     # rows wider than 512 elements: buffers that are not 16-byte aligned are refused before any launch
@@ -258,3 +272,59 @@ def test_forward_argument_errors_on_registered_partition():
         wide.layer_fwd(0, 0, xw, zw, hw, None, o, None, mw)
     assert e.value.code == vb.ERR_UNSUPPORTED
     wide.close()
+
+
+def test_registration_rejects_malformed_index_arrays():
+    """Nothing in a descriptor is trusted unchecked: unsorted or out-of-range columns, a transpose that does not
+    hold the row block's entries, negative ids and a bad returned-row map are SHAPE errors at registration."""
+    import copy
+    g = synth.small_random_graph(400, 6.0, "gcn", seed=18)
+    part = synth.random_partition(g.n, 2, seed=2)
+    host, _ = both_partitions(g, part, 2)
+    ctx = vb.Context([16, 8], [vb.ACT_IDENTITY], vb.CONV_GCN, 2, KEY)
+    ctx.register_partition(0, host[0])                       # the well-formed partition is accepted
+    good = host[1]
+    row = int(np.argmax(np.diff(good.rowptr) >= 2))
+    e0 = int(good.rowptr[row])
+
+    def broken(change):
+        hp = copy.copy(good)
+        for name in ("colidx", "t_colidx", "t_vals", "halo_gid", "boundary_rows", "ret_src", "ret_ptr"):
+            setattr(hp, name, getattr(good, name).copy())
+        change(hp)
+        return hp
+
+    def swap_columns(hp):
+        hp.colidx[e0], hp.colidx[e0 + 1] = hp.colidx[e0 + 1], hp.colidx[e0]
+
+    def column_out_of_range(hp):
+        hp.colidx[int(good.rowptr[row + 1]) - 1] = good.n_local + good.n_halo
+
+    def transposed_row_out_of_range(hp):
+        hp.t_colidx[0] = good.n_local
+
+    def transposed_value_differs(hp):
+        hp.t_vals[3] = np.float32(hp.t_vals[3] * 2 + 1)
+
+    def negative_node_id(hp):
+        hp.halo_gid[0] = -5
+
+    def boundary_rows_descending(hp):
+        hp.boundary_rows[:2] = hp.boundary_rows[:2][::-1]
+
+    def negative_returned_row(hp):
+        hp.ret_src[0] = -1
+
+    def returned_pointer_too_short(hp):
+        hp.ret_ptr[-1] -= 1
+
+    for change, text in ((swap_columns, "ascending"), (column_out_of_range, "column outside"),
+                         (transposed_row_out_of_range, "transposed entry outside"),
+                         (transposed_value_differs, "differ from the row block"), (negative_node_id, "negative node id"),
+                         (boundary_rows_descending, "boundary rows"), (negative_returned_row, "ret_src"),
+                         (returned_pointer_too_short, "ret_ptr")):
+        with pytest.raises(vb.VarcoError) as e:
+            ctx.register_partition(1, broken(change))
+        assert e.value.code == vb.ERR_SHAPE and text in str(e.value), (change.__name__, str(e.value))
+    ctx.register_partition(1, good)
+    ctx.close()

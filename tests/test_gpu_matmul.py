@@ -24,6 +24,7 @@ SHAPES = [(1000, 256, 256), (777, 100, 256), (1301, 256, 47), (515, 136, 72), (6
 def _ctx(fi, fo, act, terms):
     ctx = vb.Context([fi, fo], [act], vb.CONV_GCN, 1, KEY)
     ctx.set_matmul_terms(terms)
+    ctx.prepare()
     return ctx
 
 
@@ -62,7 +63,7 @@ def test_transform_products(n, fi, fo, terms):
     # the split of the node dimension needs a partial buffer: sized by a registered partition
     g = synth.small_random_graph(max(n, 8), 3.0, "gcn", seed=5)
     host = vb.partition_build(g.n, g.rowptr, g.colidx, g.vals, np.zeros(g.n, dtype=np.int32), 1)
-    ctx2.register_partition(0, host[0])
+    ctx2.register_partition(0, host[0])       # (the prepared workspace set follows the registration)
     ctx2.transform_bwd_weight(0, dev(y), dev(dxo), dev(xo), dh)
     torch.cuda.synchronize()
     assert_close(dh.cpu().numpy(), y.astype(np.float64).T @ dz, "Y^T dZ", _bound(terms, n))
@@ -93,6 +94,7 @@ def test_input_gradient_short_reduction(first_row, dtype):
     tol = 2.0 ** -7 if bf16 else 8 * 2.0 ** -24 * np.sqrt(fo)
     for act in (vb.ACT_IDENTITY, vb.ACT_RELU):
         ctx = vb.Context([fi, fo], [act], vb.CONV_GCN, 1, KEY, vb.BF16 if bf16 else vb.F32)
+        ctx.prepare()
         g0 = rnd(rng.standard_normal((n, fi)))
         gout = dev(g0, tdt)
         ctx.transform_bwd_input(0, dxo_d[first_row:], xo_d[first_row:], dev(h), gout, True)
@@ -114,6 +116,7 @@ def test_weights_changed_between_steps_are_seen(dtype):
     tdt = torch.bfloat16 if bf16 else torch.float32
     tol = 2.0 ** -7 if bf16 else 1e-5
     ctx = vb.Context([fi, fo], [vb.ACT_IDENTITY], vb.CONV_GCN, 1, KEY, vb.BF16 if bf16 else vb.F32)
+    ctx.prepare()
     y = torch.from_numpy(rng.standard_normal((n, fi)).astype(np.float32)).to(tdt).cuda()
     d = torch.from_numpy(rng.standard_normal((n, fo)).astype(np.float32)).to(tdt).cuda()
     h = dev(synth.glorot(fi, fo, 3, 0))

@@ -37,6 +37,12 @@ def _assert_same(host_parts, oracle_parts):
             a, b = getattr(hp, name), getattr(op, name)
             assert a.dtype == b.dtype, name
             assert np.array_equal(a, b), name                      # bit-exact, values included
+        assert hp.halo_row_offset == op.halo_row_offset
+    # the owners' reverse map of the backward exchange
+    for hp, (ptr, src) in zip(host_parts, opart.returned_row_map(oracle_parts)):
+        assert hp.n_returned == src.shape[0]
+        for a, b in ((hp.ret_ptr, ptr), (hp.ret_src, src)):
+            assert a.dtype == b.dtype and np.array_equal(a, b)
 
 
 @pytest.mark.parametrize("conv", ["gcn", "sage"])
@@ -177,6 +183,27 @@ def test_calls_on_unregistered_partition_are_state_errors():
     assert rc == vb.ERR_INVALID_ARG
     assert L.varco_compress(ctx._h, 0, None, None, 0, None, 8, None, None) == vb.OK     # empty input is a no-op
     assert L.varco_begin_step(None, 0) == vb.ERR_INVALID_ARG
+    ctx.close()
+
+
+def test_compute_calls_never_allocate_and_fail_without_a_prepared_stream():
+    """The compute calls take their device state from varco_prepare / varco_register_partition; on a context that
+    never saw either they return a state error before touching any device (so this runs without a GPU)."""
+    ctx = vb.Context([8, 4, 3], [1, 0], vb.CONV_SAGE, 2, 1)
+    L = vb.lib()
+    a = np.zeros(64, dtype=np.float32)
+    p = a.ctypes.data
+    for rc in (L.varco_compress(ctx._h, 0, p, None, 2, p, 8, p, None),
+               L.varco_decompress(ctx._h, 0, p, None, 2, p, p, 8, 0, None),
+               L.varco_transform_fwd(ctx._h, 0, 2, p, p, p, 0, 0, None),
+               L.varco_transform_bwd_weight(ctx._h, 0, 2, p, p, p, p, None),
+               L.varco_transform_bwd_input(ctx._h, 0, 2, p, p, p, p, 0, None)):
+        assert rc == vb.ERR_STATE
+        assert b"varco_prepare" in L.varco_last_error(ctx._h)
+    assert L.varco_prepare(None, None) == vb.ERR_INVALID_ARG
+    # changing the ratio on a context without workspace sets stays a pure host call
+    ctx.set_ratio(-1, 4, 1)
+    assert ctx.keep(0) == 2
     ctx.close()
 
 

@@ -79,7 +79,35 @@ def test_relu_mask_ignored_is_caught(monkeypatch):
 def test_halo_read_from_wrong_owner_row_is_caught(monkeypatch):
     orig = olayer.layer_forward
 
-    def broken(p, x_local, z_all, halo_cols, h1, h0, act):
-        return orig(p, x_local, np.roll(z_all, 1, axis=0), halo_cols, h1, h0, act)
+    def broken(p, x_local, z_all, halo_cols, h1, h0, act, with_pre=False):
+        return orig(p, x_local, np.roll(z_all, 1, axis=0), halo_cols, h1, h0, act, with_pre)
     monkeypatch.setattr(olayer, "layer_forward", broken)
     _expect_failure(tl.test_ratio_one_equals_unpartitioned_dense_layer, "gcn", 3)
+
+
+def test_returned_rows_listed_in_the_wrong_order_or_without_offset_are_caught(monkeypatch):
+    import test_oracle_partition as tp
+    from oracle import partition as opart
+    from paper_2406_17611_amd import synth
+    g = synth.small_random_graph(300, 6.0, "gcn", seed=5)
+    part = synth.random_partition(g.n, 3, seed=6)
+    parts = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, part, 3)
+    tp._check_returned_row_map(g, part, parts)
+    orig = opart.returned_row_map
+
+    def descending_consumers(ps):
+        out = []
+        for ptr, src in orig(ps):
+            src = src.copy()
+            for b in range(ptr.shape[0] - 1):
+                src[ptr[b]:ptr[b + 1]] = src[ptr[b]:ptr[b + 1]][::-1]
+            out.append((ptr, src))
+        return out
+
+    monkeypatch.setattr(opart, "returned_row_map", descending_consumers)
+    _expect_failure(tp._check_returned_row_map, g, part, parts)
+    # slots without the offset of the consumers before them
+    monkeypatch.setattr(opart, "returned_row_map",
+                        lambda ps: [(ptr, src - np.int32(ps[1].halo_row_offset) * (src >= ps[1].halo_row_offset))
+                                    for ptr, src in orig(ps)])
+    _expect_failure(tp._check_returned_row_map, g, part, parts)

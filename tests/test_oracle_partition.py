@@ -71,6 +71,31 @@ def _check_structure(g, part, n_parts, parts):
             s0, s1 = p.halo_owner_ptr[o], p.halo_owner_ptr[o + 1]
             own = parts[o]
             assert np.array_equal(own.local_gid[own.boundary_rows[p.halo_src_row[s0:s1]]], p.halo_gid[s0:s1])
+    _check_returned_row_map(g, part, parts)
+
+
+def _check_returned_row_map(g, part, parts):
+    """The owners' view of the backward exchange, recounted from the global graph with plain sets: node v's errors
+    come back from exactly the partitions q != part[v] that own a row referencing v, one row each, listed by
+    ascending q; the row is q's halo slot of v, offset by the halo rows of the partitions before q."""
+    consumers_of = {}
+    for r in range(g.n):
+        for c in g.colidx[g.rowptr[r]:g.rowptr[r + 1]].tolist():
+            if part[c] != part[r]:
+                consumers_of.setdefault(c, set()).add(int(part[r]))
+    slot = [{int(v): s for s, v in enumerate(p.halo_gid.tolist())} for p in parts]
+    offset = np.concatenate(([0], np.cumsum([p.n_halo for p in parts])))
+    assert [p.halo_row_offset for p in parts] == offset[:-1].tolist()
+    total = 0
+    for p, (ptr, src) in zip(parts, opart.returned_row_map(parts)):
+        assert ptr.dtype == np.int32 and src.dtype == np.int32
+        assert ptr.shape == (p.n_boundary + 1,) and ptr[0] == 0 and ptr[-1] == src.shape[0]
+        for b, row in enumerate(p.boundary_rows.tolist()):
+            v = int(p.local_gid[row])
+            want = [int(offset[q]) + slot[q][v] for q in sorted(consumers_of[v])]
+            assert src[ptr[b]:ptr[b + 1]].tolist() == want
+        total += src.shape[0]
+    assert total == opart.exchanged_rows(parts)              # every exchanged pair is returned exactly once
 
 
 @pytest.mark.parametrize("conv", ["gcn", "sage"])

@@ -283,6 +283,22 @@ int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int64_t n_rows
 int32_t varco_transform_bwd_input(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* dx_out, const void* x_out,
                                   const void* h, void* g_out, int32_t accumulate, varco_stream stream);
 
+/* varco_transform_bwd_weight for callers that cannot allocate device memory and have no prepared stream: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, same kernels,
+ * same split of the reduction over the rows and therefore the same bits as varco_transform_bwd_weight on a stream
+ * whose workspace holds that split; but the partial products go to a static device array of the library (32 MiB
+ * per GPU, held until the process ends) instead of a workspace set, so the call needs no varco_prepare and
+ * allocates nothing. VARCO_ERR_SHAPE, with the sizes in the text, when width[layer] x width[layer+1] x (the
+ * split chosen for n_rows) x 4 bytes exceeds the array: fp32 storage always fits (256 x 256 weights over 32,768
+ * or more rows use all of it); bf16 storage, whose tiles are twice as tall, fits up to half its full split
+ * (512 x 512 weights: up to 8,447 rows). All calls on one GPU share
+ * the array: calls that may overlap on the device (different streams, different contexts, different host threads)
+ * race and must be ordered by the caller. Nothing in the array has to start at zero. The first call on a device
+ * (or varco_prepare) looks the array's address up once; that first call is not capturable. Not bracketed by the
+ * per-kernel profiler. */
+int32_t varco_transform_bwd_weight_static(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* y, const void* dx_out,
+                                          const void* x_out, void* dh, varco_stream stream);
+
 /* Owner side of the backward exchange for partition p, all consumers at once (Section III: in the backward
  * pass the exchange runs from consumers to owners; Algorithm 1: errors cross machines): for every
  * boundary row b of p, v = its node id,

@@ -30,7 +30,7 @@ EXPORTS = [
     "varco_calibration_copy", "varco_sum_gradients", "varco_softmax_xent", "varco_sgd_step", "varco_schedule_ratio",
     "varco_step_table_enable", "varco_set_step", "varco_advance_step",
     "varco_aggregate_fwd", "varco_aggregate_bwd", "varco_transform_fwd", "varco_transform_bwd_weight",
-    "varco_transform_bwd_input",
+    "varco_transform_bwd_input", "varco_transform_bwd_weight_static",
 ]
 KERNEL_CLASSES = ["compress", "decompress", "agg_fwd", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "agg_bwd_local",
                   "agg_bwd_halo", "reduce", "agg_bwd_halo_sum"]
@@ -115,6 +115,7 @@ def lib() -> C.CDLL:
         L.varco_transform_fwd.argtypes = [vp, i32, i64, vp, vp, vp, i32, i32, vp]
         L.varco_transform_bwd_weight.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp]
         L.varco_transform_bwd_input.argtypes = [vp, i32, i64, vp, vp, vp, vp, i32, vp]
+        L.varco_transform_bwd_weight_static.argtypes = [vp, i32, i64, vp, vp, vp, vp, vp]
         L.varco_profile_enable.argtypes = [vp, i32]
         L.varco_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         for name in EXPORTS:
@@ -347,6 +348,10 @@ class Context:
     def transform_bwd_weight(self, layer, y, dx_out, x_out, dh, stream=None):
         _check(lib().varco_transform_bwd_weight(self._h, layer, y.shape[0], _ptr(y), _ptr(dx_out), _ptr(x_out), _ptr(dh),
                                                 _stream(stream)), self._h)
+
+    def transform_bwd_weight_static(self, layer, y, dx_out, x_out, dh, stream=None):
+        _check(lib().varco_transform_bwd_weight_static(self._h, layer, y.shape[0], _ptr(y), _ptr(dx_out), _ptr(x_out),
+                                                       _ptr(dh), _stream(stream)), self._h)
 
     def transform_bwd_input(self, layer, dx_out, x_out, h, g_out, accumulate, stream=None):
         _check(lib().varco_transform_bwd_input(self._h, layer, dx_out.shape[0], _ptr(dx_out), _ptr(x_out), _ptr(h),

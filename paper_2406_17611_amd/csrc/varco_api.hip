@@ -66,6 +66,33 @@ constexpr int kMaxStreams = 8;
 std::mutex g_err_mutex;
 std::string g_global_error;
 
+// Scratch of the entry point that allocates nothing (varco_transform_bwd_weight_static): the partial products of
+// the split reduction. One copy per GPU, held until the process ends. In host code the array's name is only a
+// handle: its device address is looked up once per device (scratch_of_current_device) and that pointer is what
+// kernels are given.
+constexpr size_t kScratchFloats = size_t(8) << 20;             // 32 MiB
+static __device__ __align__(256) float scratch[kScratchFloats];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t scratch_of_current_device(float** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        float* ptr = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
 }  // namespace
 
 struct varco_ctx {
@@ -623,6 +650,10 @@ extern "C" int32_t varco_register_partition(varco_ctx* ctx, int32_t q, const var
 extern "C" int32_t varco_prepare(varco_ctx* ctx, varco_stream stream) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_prepare: null context");
     if (int32_t rc = ensure_tables(ctx)) return rc;
+    {   // the static scratch array's address on this device, for varco_transform_bwd_weight_static
+        float* unused = nullptr;
+        VARCO_HIP(ctx, scratch_of_current_device(&unused));
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     Workspace* ws = nullptr;
     for (Workspace& w : ctx->ws)
@@ -1058,6 +1089,39 @@ extern "C" int32_t varco_transform_bwd_weight(varco_ctx* ctx, int32_t layer, int
         g.split_k = int32_t(fit);
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(n_rows))));
+    return VARCO_OK;
+}
+
+extern "C" int32_t varco_transform_bwd_weight_static(varco_ctx* ctx, int32_t layer, int64_t n_rows, const void* y,
+                                                     const void* dx_out, const void* x_out, void* dh, varco_stream stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int32_t rc = transform_prologue(ctx, layer, n_rows, "varco_transform_bwd_weight_static")) return rc;
+    if (n_rows == 0) return VARCO_OK;
+    if (!y || !dx_out || !dh || (!x_out && ctx->act[layer] == VARCO_ACT_RELU))
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_transform_bwd_weight_static: null pointer");
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+    const int dt = ctx->dtype;
+    GemmArgs g;
+    g.m = fi, g.n = fo, g.k = int32_t(n_rows);
+    g.a.ptr = y, g.a.ld = fi, g.a.transposed = true, g.a.dtype = dt;
+    g.b.ptr = dx_out, g.b.gate = ctx->act[layer] == VARCO_ACT_RELU ? x_out : nullptr, g.b.ld = fo, g.b.dtype = dt;
+    g.c = dh, g.ldc = fo;
+    g.accumulate = true;
+    g.f32_terms = dt == VARCO_F32 ? ctx->f32_terms : 0;
+    g.split_k = gemm_split_for(fi, fo, n_rows, gemm_kind(g));
+    const size_t need = g.split_k > 1 ? size_t(g.split_k) * fi * fo : 0;
+    if (need > kScratchFloats) {
+        char msg[256];
+        std::snprintf(msg, sizeof msg,
+                      "varco_transform_bwd_weight_static: %d x %d weights over %lld rows need %zu bytes of scratch, the static "
+                      "array holds %zu; use varco_transform_bwd_weight", fi, fo, static_cast<long long>(n_rows),
+                      need * sizeof(float), kScratchFloats * sizeof(float));
+        return varco_fail(ctx, VARCO_ERR_SHAPE, msg);
+    }
+    float* ptr = nullptr;
+    VARCO_HIP(ctx, scratch_of_current_device(&ptr));
+    g.partial = ptr;   // every element of every slab the reduction reads is written first: nothing to clear
+    VARCO_HIP(ctx, varco_launch_gemm(g, st, LaunchTag{}));   // not bracketed by profiler events (they would be created here)
     return VARCO_OK;
 }
 

@@ -38,21 +38,29 @@ def log(*a):
 
 def measured_traffic(workload, kernel_class):
     """HBM bytes per launch of a kernel class from the committed rocprofv3 counter summary (FETCH_SIZE and
-    WRITE_SIZE, each scaled by what the same counter reads for the library's plain copy of known size), or None."""
+    WRITE_SIZE, each scaled by what the same counter reads for the library's plain copy of known size), or None;
+    and whether that summary was collected on the kernel sources of this tree (it carries their hash)."""
+    from paper_2406_17611_amd.profile_summary import kernel_sources_hash
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
-            rec = json.load(f)[workload][kernel_class]
-        return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+            doc = json.load(f)
+        rec = doc[workload][kernel_class]
+        current = doc.get("kernel_sources_sha256", {}).get(workload) == kernel_sources_hash()
+        if not current:
+            log(f"[bench] warning: profiles/hbm_traffic.json was collected on other kernel sources than this tree's "
+                f"({workload}); the roofline's traffic figure may be stale")
+        return rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"], current
     except (OSError, KeyError, ValueError):
-        return None
+        return None, None
 
 
-def cpu_baseline(w, ratio, budget_note=""):
-    """The CPU oracle, as it stands, on a bounded sample of the same workload: one partition, the middle
-    (hidden -> hidden) layer, forward + backward. Returns the dict reported under "cpu_baseline"."""
+def cpu_baseline(w, ratio, budget_s=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the hidden (middle) layer, forward +
+    backward, partition after partition in turn until `budget_s` seconds are spent (all partitions when they fit).
+    Returns the dict reported under "cpu_baseline"."""
     import numpy as np
-    from threadpoolctl import threadpool_info, threadpool_limits
+    from threadpoolctl import threadpool_limits
 
     from oracle import layer as olayer
     from oracle import mask as omask
@@ -60,30 +68,42 @@ def cpu_baseline(w, ratio, budget_note=""):
     from paper_2406_17611_amd import synth
 
     g = w.graph
-    cores = min(os.cpu_count() or 1, 16)
+    blas_threads = min(os.cpu_count() or 1, 16)
     layer = 1 if len(w.widths) > 2 else 0
     fi, fo = w.widths[layer], w.widths[layer + 1]
     k = omask.keep_count(fi, *ratio)
-    p = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, w.part, w.n_parts, only=[0])[0]
-    rng = np.random.default_rng(1)
-    x = rng.standard_normal((p.n_local, fi)).astype(np.float32)
-    z_all = rng.standard_normal((int(p.halo_zrow.max(initial=-1)) + 1, k)).astype(np.float32)
-    if w.dtype == "bf16":   # the oracle of the bf16 configuration: fp64 arithmetic on bf16-valued inputs
-        from oracle.rounding import round_bf16
-        x, z_all = round_bf16(x), round_bf16(z_all)
     h1 = synth.glorot(fi, fo, synth.SEED_WEIGHT, 2 * layer)
     h0 = synth.glorot(fi, fo, synth.SEED_WEIGHT, 2 * layer + 1) if w.conv == "sage" else None
-    dxo = rng.standard_normal((p.n_local, fo)).astype(np.float32)
-    with threadpool_limits(limits=cores):
-        t0 = time.perf_counter()
-        cols = omask.kept_columns(p.halo_gid, fi, k, synth.MASK_KEY, 0, layer)
-        xo, m = olayer.layer_forward(p, x, z_all, cols, h1, h0, olayer.RELU)
-        olayer.layer_backward(p, dxo, xo, x, m, cols, h1, h0, olayer.RELU, True)
-        dt = time.perf_counter() - t0
-    return {"value": p.nnz / dt / 1e9, "unit": "GEdges/s", "cores": cores, "kind": "oracle",
-            "sample": f"partition 0 of {w.n_parts}, layer {layer + 1} of {len(w.widths) - 1} ({fi}->{fo}, k={k}), "
-                      f"forward+backward, {p.nnz} directed entries, {dt:.1f} s; numpy/scipy fp64, BLAS threads "
-                      f"capped at {cores} (the sparse products run on one){budget_note}"}
+    rng = np.random.default_rng(1)
+    wall = cpu = 0.0
+    entries = done = 0
+    for q in range(w.n_parts):
+        # index structures and inputs of the partition: preparation, not part of the layer step
+        p = opart.build_partitions(g.n, g.rowptr, g.colidx, g.vals, w.part, w.n_parts, only=[q])[0]
+        x = rng.standard_normal((p.n_local, fi)).astype(np.float32)
+        z_all = rng.standard_normal((int(p.halo_zrow.max(initial=-1)) + 1, k)).astype(np.float32)
+        if w.dtype == "bf16":   # the oracle of the bf16 configuration: fp64 arithmetic on bf16-valued inputs
+            from oracle.rounding import round_bf16
+            x, z_all = round_bf16(x), round_bf16(z_all)
+        dxo = rng.standard_normal((p.n_local, fo)).astype(np.float32)
+        with threadpool_limits(limits=blas_threads):
+            t0, c0 = time.perf_counter(), time.process_time()
+            cols = omask.kept_columns(p.halo_gid, fi, k, synth.MASK_KEY, 0, layer)
+            xo, m = olayer.layer_forward(p, x, z_all, cols, h1, h0, olayer.RELU)
+            olayer.layer_backward(p, dxo, xo, x, m, cols, h1, h0, olayer.RELU, True)
+            wall += time.perf_counter() - t0
+            cpu += time.process_time() - c0
+        entries += p.nnz
+        done += 1
+        del p, x, z_all, dxo, xo, m, cols
+        if wall >= budget_s:
+            break
+    busy = cpu / wall
+    return {"value": entries / wall / 1e9, "unit": "GEdges/s", "cores": max(1, int(round(busy))), "kind": "oracle",
+            "sample": f"partitions 0..{done - 1} of {w.n_parts} in turn, layer {layer + 1} of {len(w.widths) - 1} "
+                      f"({fi}->{fo}, k={k}), forward+backward, {entries} directed entries in {wall:.1f} s; numpy/scipy "
+                      f"fp64 oracle: {busy:.1f} host threads busy on average (process CPU time / wall time; the dense "
+                      f"products may use up to {blas_threads} BLAS threads, the sparse products run on one)"}
 
 
 def main():
@@ -167,6 +187,7 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         prof = {}
+        profiled_ms_per_step = None
         stats = dict(per_step)
         for key in ("fwd_elems", "bwd_elems", "full_fwd_elems", "full_bwd_elems"):
             stats[key] = [v * args.steps for v in per_step[key]]
@@ -175,15 +196,26 @@ def main():
             net.step(s, ratio)
         torch.cuda.synchronize()
         net.ctx.reset_stats()
-        net.ctx.profile_enable(True)
+        # the headline: exactly K steps, nothing but the step's own launches between the two synchronisations
         t0 = time.perf_counter()
         for s in range(args.steps):
             net.step(args.warmup + s, ratio)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        prof = net.ctx.profile_read()
-        net.ctx.profile_enable(False)
         stats = net.ctx.stats()
+        # per-kernel table and roofline: a second pass of the same steps with every launch bracketed by HIP events
+        # on its launch stream (outside the headline's timed region: the brackets cost about 1 % of a step)
+        prof = {}
+        profiled_ms_per_step = None
+        if args.streams == 1:
+            net.ctx.profile_enable(True)
+            t1 = time.perf_counter()
+            for s in range(args.steps):
+                net.step(args.warmup + args.steps + s, ratio)
+            torch.cuda.synchronize()
+            profiled_ms_per_step = (time.perf_counter() - t1) * 1e3 / args.steps
+            prof = net.ctx.profile_read()
+            net.ctx.profile_enable(False)
     ms_per_step = dt * 1e3 / args.steps
     edges_per_step = L * net.nnz_total
     assert all(torch.isfinite(t).all().item() for t in net.dh1), "non-finite weight gradient"
@@ -207,14 +239,24 @@ def main():
         else:
             ach = p["bytes"] / p["ms"] / 1e6
             entry.update(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
+            if p["stream_bytes"] != p["bytes"]:
+                # the same launches priced on one source-row fetch per entry (no cache between rows)
+                entry.update(streaming_achieved=p["stream_bytes"] / p["ms"] / 1e6,
+                             streaming_frac=p["stream_bytes"] / p["ms"] / 1e6 / HBM_PEAK_GBS)
         kernels[name] = entry
-    roofline = None                     # graph replays are not bracketed per launch
+    roofline = None                     # graph replays and overlapping streams are not bracketed per launch
     if kernels:
         dominant = max((n for n in kernels if n != "reduce"), key=lambda n: kernels[n]["ms_per_step"])
         d = kernels[dominant]
+        traffic, current = measured_traffic(w.name, dominant)
         roofline = {"kernel": dominant, "bound": d["bound"], "achieved": d["achieved"], "peak": d["peak"],
-                    "unit": d["unit"], "frac": d["frac"], "traffic": measured_traffic(w.name, dominant),
-                    "avg_launch_ms": d["avg_launch_ms"]}
+                    "unit": d["unit"], "frac": d["frac"], "traffic": traffic, "avg_launch_ms": d["avg_launch_ms"]}
+        if traffic is not None:
+            roofline["traffic_from"] = "profiles/hbm_traffic.json" + ("" if current else " (collected on other kernel sources)")
+            roofline["traffic_gbs"] = traffic / d["avg_launch_ms"] / 1e6
+        if "streaming_frac" in d:
+            roofline["streaming_achieved"] = d["streaming_achieved"]
+            roofline["streaming_frac"] = d["streaming_frac"]
 
     bpe = stats["bytes_per_elem"]
     out = {
@@ -229,10 +271,13 @@ def main():
                    "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
                    "keep": [net.ctx.keep(l) for l in range(L)], "layers": L, "streams": args.streams,
                    "hip_graph": bool(args.graph),
+                   "timed": f"{args.streams} stream{'s' if args.streams > 1 else ''}, " +
+                            ("HIP graph replay" if args.graph else "eager launches") + ", no per-launch events",
                    "matmul_terms": (3 if args.matmul_terms is None else args.matmul_terms) if w.dtype == "f32" else None,
                    "edges_counted_per_step": edges_per_step},
         "roofline": roofline,
         "kernels": kernels,
+        "profiled_pass_ms_per_step": profiled_ms_per_step,
         "exchanged_bytes_per_step": {
             "forward": sum(stats["fwd_elems"]) * bpe // args.steps,
             "backward": sum(stats["bwd_elems"]) * bpe // args.steps,

@@ -342,6 +342,9 @@ typedef struct {
     double ms[VARCO_K_COUNT];
     double bytes[VARCO_K_COUNT];
     double flops[VARCO_K_COUNT];
+    double stream_bytes[VARCO_K_COUNT];   /* the same launches' bytes when no cache serves a re-read: the gather kernels
+                                           * (aggregation forward, transposed local block) fetch one source row per entry
+                                           * instead of each row once; equal to bytes for the streaming kernels */
 } varco_profile;
 /* dst[i] += src[i] for n fp32 values (device pointers). Algorithm 1: the weight gradients computed on the
  * partitions are summed before the update; a caller that lets overlapping layer calls accumulate into one

@@ -61,7 +61,7 @@ class Stats(C.Structure):
 
 class Profile(C.Structure):
     _fields_ = [("launches", C.c_int64 * 10), ("ms", C.c_double * 10), ("bytes", C.c_double * 10),
-                ("flops", C.c_double * 10)]
+                ("flops", C.c_double * 10), ("stream_bytes", C.c_double * 10)]
 
 
 class VarcoError(RuntimeError):
@@ -382,5 +382,6 @@ class Context:
         """Per kernel class: launches, total ms, algorithmic bytes and flops of the bracketed launches."""
         p = Profile()
         _check(lib().varco_profile_read(self._h, C.byref(p), int(reset)), self._h)
-        return {name: dict(launches=p.launches[i], ms=p.ms[i], bytes=p.bytes[i], flops=p.flops[i])
+        return {name: dict(launches=p.launches[i], ms=p.ms[i], bytes=p.bytes[i], flops=p.flops[i],
+                           stream_bytes=p.stream_bytes[i])
                 for i, name in enumerate(KERNEL_CLASSES)}

@@ -112,13 +112,14 @@ struct varco_ctx {
     varco_stats stats{};
     VarcoProfiler prof;
     double prof_ms[VARCO_K_COUNT] = {}, prof_bytes[VARCO_K_COUNT] = {}, prof_flops[VARCO_K_COUNT] = {};
+    double prof_stream_bytes[VARCO_K_COUNT] = {};
     int64_t prof_launches[VARCO_K_COUNT] = {};
     mutable std::string error;
     double elem_bytes() const { return dtype == VARCO_BF16 ? 2.0 : 4.0; }
-    LaunchTag tag(int cls, double bytes, double flops) {
+    LaunchTag tag(int cls, double bytes, double flops, double stream_bytes = -1.0) {
         LaunchTag t;
         t.prof = prof.on ? &prof : nullptr;
-        t.cls = cls, t.bytes = bytes, t.flops = flops;
+        t.cls = cls, t.bytes = bytes, t.flops = flops, t.stream_bytes = stream_bytes;
         return t;
     }
 };
@@ -816,8 +817,11 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double es = ctx->elem_bytes();
     const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
                              double(d.n_halo) * rule.k * es;
+    // the same without any cache between the entries of different rows: one source row fetched per entry
+    const double agg_stream = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + double(d.n_local) * fi * es +
+                              double(ps.nnz_t_local) * fi * es + double(d.nnz - ps.nnz_t_local) * rule.k * es;
     VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, ps.edges, nullptr, d.vals, x_local, z_in, ps.z_rows, rule, m_saved, 0, ws.spmm, st,
-                                     ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0)));
+                                     ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0, agg_stream)));
     // transform + nonlinearity
     GemmArgs g;
     g.m = d.n_local, g.n = fo, g.k = fi;
@@ -913,8 +917,9 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
     const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
+    const double tl_stream = tl_bytes + (double(ps.nnz_t_local) - double(nl)) * fi * es;   // a source row per entry
     VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, 0, dense_rule, dx_local,
-                                     0, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
+                                     0, ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0, tl_stream)));
     if (d.n_halo > 0 && rule.k > 0) {   // k = 0: nothing is handed back
         if (rule.k == rule.width) {
             VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, ws.dm, nullptr, 0, dense_rule,
@@ -972,8 +977,10 @@ extern "C" int32_t varco_aggregate_fwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     const double es = ctx->elem_bytes();
     const double bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
                          double(d.n_halo) * rule.k * es;
+    const double stream_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + double(d.n_local) * fi * es +
+                                double(ps.nnz_t_local) * fi * es + double(d.nnz - ps.nnz_t_local) * rule.k * es;
     VARCO_HIP(ctx, varco_launch_spmm(ctx->dtype, ps.fwd, ps.edges, nullptr, d.vals, y_local, z_in, ps.z_rows, rule, y_out, 0, wsp->spmm,
-                                     st, ctx->tag(VARCO_K_AGG_FWD, bytes, 0)));
+                                     st, ctx->tag(VARCO_K_AGG_FWD, bytes, 0, stream_bytes)));
     ctx->stats.fwd_elems[layer] += int64_t(d.n_halo) * rule.k;
     ctx->stats.full_fwd_elems[layer] += int64_t(d.n_halo) * fi;
     return VARCO_OK;
@@ -1005,8 +1012,9 @@ extern "C" int32_t varco_aggregate_bwd(varco_ctx* ctx, int32_t tap, int32_t q, c
     const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fi * es;
     const double th_out_bytes = (double(d.n_halo) + 1.0) * 4.0 + double(d.n_halo) * rule.k * es;
     const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + double(nl) * fi * es + th_out_bytes;
+    const double tl_stream = tl_bytes + (double(ps.nnz_t_local) - double(nl)) * fi * es;
     VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, 0, dense_rule, g_local, 0,
-                                     ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0)));
+                                     ws.spmm, st, ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0, tl_stream)));
     if (d.n_halo > 0 && rule.k > 0) {
         if (rule.k == rule.width) {
             VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, g_out, nullptr, 0, dense_rule, dz_halo,
@@ -1288,6 +1296,7 @@ extern "C" int32_t varco_profile_read(varco_ctx* ctx, varco_profile* out, int32_
         VARCO_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof.events[r.start], ctx->prof.events[r.stop]));
         ctx->prof_ms[r.cls] += ms;
         ctx->prof_bytes[r.cls] += r.bytes;
+        ctx->prof_stream_bytes[r.cls] += r.stream_bytes;
         ctx->prof_flops[r.cls] += r.flops;
         ctx->prof_launches[r.cls] += 1;
     }
@@ -1300,7 +1309,8 @@ extern "C" int32_t varco_profile_read(varco_ctx* ctx, varco_profile* out, int32_
         out->ms[c] = ctx->prof_ms[c];
         out->bytes[c] = ctx->prof_bytes[c];
         out->flops[c] = ctx->prof_flops[c];
-        if (reset) ctx->prof_launches[c] = 0, ctx->prof_ms[c] = ctx->prof_bytes[c] = ctx->prof_flops[c] = 0.0;
+        out->stream_bytes[c] = ctx->prof_stream_bytes[c];
+        if (reset) ctx->prof_launches[c] = 0, ctx->prof_ms[c] = ctx->prof_bytes[c] = ctx->prof_flops[c] = ctx->prof_stream_bytes[c] = 0.0;
     }
     return VARCO_OK;
 }

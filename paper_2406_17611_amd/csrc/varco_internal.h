@@ -17,6 +17,7 @@ struct VarcoProfiler {
         int cls;
         int start, stop;     // indices into `events`
         double bytes, flops;
+        double stream_bytes;   // bytes when no cache serves a re-read (one source row per entry); = bytes for streaming kernels
     };
     bool on = false;
     std::vector<Rec> recs;
@@ -36,10 +37,10 @@ struct VarcoProfiler {
         events.push_back(e);
         return int(events.size()) - 1;
     }
-    void begin(int cls, hipStream_t st, double bytes, double flops) {
+    void begin(int cls, hipStream_t st, double bytes, double flops, double stream_bytes = -1.0) {
         if (!on) return;
         const int start = (last_stop >= 0 && last_stream == st) ? last_stop : record(st);
-        recs.push_back(Rec{cls, start, -1, bytes, flops});
+        recs.push_back(Rec{cls, start, -1, bytes, flops, stream_bytes < 0 ? bytes : stream_bytes});
         last_stop = -1;
     }
     void end(hipStream_t st) {
@@ -56,7 +57,8 @@ struct LaunchTag {
     VarcoProfiler* prof = nullptr;
     int cls = 0;
     double bytes = 0, flops = 0;
-    void begin(hipStream_t st) const { if (prof) prof->begin(cls, st, bytes, flops); }
+    double stream_bytes = -1;   // < 0: same as bytes
+    void begin(hipStream_t st) const { if (prof) prof->begin(cls, st, bytes, flops, stream_bytes); }
     void begin_as(int other, hipStream_t st, double other_bytes) const { if (prof) prof->begin(other, st, other_bytes, 0); }
     void end(hipStream_t st) const { if (prof) prof->end(st); }
 };

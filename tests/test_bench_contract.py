@@ -24,6 +24,24 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_traffic_table_covers_the_reported_kernel_of_both_profiled_workloads():
     bench = _bench_module()
     for workload in ("large_sage", "large_gcn_bf16"):
-        t = bench.measured_traffic(workload, "agg_fwd")
+        t, current = bench.measured_traffic(workload, "agg_fwd")
         assert t is not None and t > 1e8, workload
-    assert bench.measured_traffic("large_sage", "no_such_kernel") is None
+        assert current in (True, False)              # whether the counters were collected on this tree's kernel sources
+    assert bench.measured_traffic("large_sage", "no_such_kernel") == (None, None)
+
+
+def test_kernel_sources_hash_follows_the_sources(tmp_path, monkeypatch):
+    from paper_2406_17611_amd import profile_summary as ps
+    h = ps.kernel_sources_hash()
+    assert len(h) == 64 and h == ps.kernel_sources_hash()
+    import shutil
+    pkg = tmp_path / "pkg"
+    shutil.copytree(os.path.join(ROOT, "paper_2406_17611_amd", "csrc"), pkg / "csrc")
+    os.makedirs(tmp_path / "include")
+    shutil.copy(os.path.join(ROOT, "include", "varco.h"), tmp_path / "include" / "varco.h")
+    monkeypatch.setattr(ps, "HERE", str(pkg))
+    monkeypatch.setattr(ps, "ROOT", str(tmp_path))
+    assert ps.kernel_sources_hash() == h
+    with open(pkg / "csrc" / "elem.h", "a") as f:
+        f.write("// changed\n")
+    assert ps.kernel_sources_hash() != h

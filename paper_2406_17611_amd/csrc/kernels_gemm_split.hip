@@ -8,17 +8,17 @@
 // instructions that cover the same reduction steps. TERMS = 2 keeps x0 + x1 and three products (relative
 // error about 2^-16 per product); the library does not use it by default.
 //
-// A group of four wavefronts computes a 128 x 128 tile of C (128 x 64 for outputs at most 64 columns wide), a
-// wavefront 64 x 64 (32 x 64). A workgroup is two such groups with a tile each; while one multiplies, the
-// other fetches, expands and writes its next stage (see the kernel). A stage of 32 reduction steps is fetched
-// into registers one phase ahead, then expanded and written to LDS as TERMS planes of bf16 rows (one output
-// index per row, reduction index contiguous, 80-byte pitch).
+// A workgroup of four wavefronts computes a 128 x 128 tile of C (128 x 64 for outputs at most 64 columns wide), a
+// wavefront 64 x 64 (32 x 64); two workgroups are resident per compute unit (see the kernel). A stage of 32
+// reduction steps is fetched into registers one step ahead, then expanded and written to LDS as TERMS planes of
+// bf16 rows (one output index per row, reduction index contiguous, 80-byte pitch).
 //   "NT" products (transform, input gradient): A has the reduction index contiguous and is expanded here;
 //        B is the library's own expanded copy of the weights (varco_launch_prep_weight_split), zero-padded
 //        to whole tiles and copied as is.
 //   "TN" products (weight gradient, reduction over nodes): both operands have the node index as the slow
-//        one; a thread loads an 8 (nodes) x 4 (columns) block with eight 16-byte loads, expands it, transposes
-//        it in registers and writes four 16-byte LDS rows per plane. Half the threads serve A, half B.
+//        one; a thread loads an 8 (nodes) x 4 (columns) block with eight 16-byte loads and expands the values of
+//        two consecutive nodes of a column together, which yields the transposed (node index contiguous) words
+//        directly; it writes four 16-byte LDS rows per plane. Half the threads serve A, half B.
 // The ReLU mask of the backward pass is applied before the expansion, the activation in the epilogue.
 #include <type_traits>
 
@@ -52,8 +52,6 @@ struct SplitGemm {
     float* partial;
     int32_t tiles_m, tiles_n;
     int32_t inner, outer;            // tiles along the fast and the slow direction of the workgroup order
-    int32_t pair_inner;              // the two tiles of a workgroup are neighbours along the fast (1) or slow (0) direction
-    int32_t inner_units, outer_units;   // workgroups along either direction
 };
 
 
@@ -236,27 +234,24 @@ __device__ __forceinline__ void load_cols(const float* base, const float* gate, 
 
 template <int TERMS, int ROWS, bool GATE, bool HAS_GATE>
 __device__ __forceinline__ void store_cols(const ColRegs<HAS_GATE>& r, int b, uint16_t* s) {
-    uint32_t w[8][2][TERMS];                                  // [reduction step][output pair][term]
+    // An LDS row holds one output index with its 8 reduction steps contiguous, two steps per 32-bit word: the two
+    // values expanded together are steps 2 q and 2 q + 1 of one output index, which is the transposition itself.
+    float x[8][4];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-        float4 x = r.v[kk];
-        if (GATE) x = gate4(x, r.g[kk]);
-        expand_pair<TERMS>(x.x, x.y, w[kk][0]);
-        expand_pair<TERMS>(x.z, x.w, w[kk][1]);
+        float4 v = r.v[kk];
+        if (GATE) v = gate4(v, r.g[kk]);
+        x[kk][0] = v.x, x[kk][1] = v.y, x[kk][2] = v.z, x[kk][3] = v.w;
     }
     uint16_t* base = s + (b >> 2) * 4 * kPitch + (b & 3) * 8;
 #pragma unroll
-    for (int p = 0; p < TERMS; ++p) {
+    for (int ii = 0; ii < 4; ++ii) {                          // output index i + ii: its 8 reduction steps
+        uint32_t o[4][TERMS];
 #pragma unroll
-        for (int ii = 0; ii < 4; ++ii) {                      // output index i + ii: its 8 reduction steps
-            uint32_t o[4];
+        for (int q = 0; q < 4; ++q) expand_pair<TERMS>(x[2 * q][ii], x[2 * q + 1][ii], o[q]);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t e0 = w[2 * q][ii >> 1][p], e1 = w[2 * q + 1][ii >> 1][p];
-                o[q] = (ii & 1) ? ((e0 >> 16) | (e1 & 0xFFFF0000u)) : ((e0 & 0xFFFFu) | (e1 << 16));
-            }
-            *reinterpret_cast<uint4*>(base + p * ROWS * kPitch + ii * kPitch) = make_uint4(o[0], o[1], o[2], o[3]);
-        }
+        for (int p = 0; p < TERMS; ++p)
+            *reinterpret_cast<uint4*>(base + p * ROWS * kPitch + ii * kPitch) = make_uint4(o[0][p], o[1][p], o[2][p], o[3][p]);
     }
 }
 
@@ -285,54 +280,45 @@ __device__ __forceinline__ void workgroup_barrier() {
 // index contiguous and B an expanded weight copy. WM x WN wavefronts per tile, each TMB x TNB blocks of
 // 32 x 32. A_CH: floats per chunk of A (NT only). GATE masks A (NT) or B (TN).
 //
-// A workgroup is two groups of four wavefronts, each with a tile and LDS buffers of its own, that alternate
-// between two phases half a step apart: while one group multiplies the fragments of its current tile, the
-// other waits for its next tile's global loads, expands them and writes them to LDS. A compute unit's four
-// SIMDs each hold one wavefront of either group, so the matrix cores always have a wavefront in its multiply
-// phase while the conversions, LDS writes and load latency of the other are hidden behind it.
+// A workgroup is four wavefronts with one tile and one LDS stage (60 KB), so that two workgroups are resident
+// on a compute unit and each SIMD holds one wavefront of either. On this device the vector ALU and the matrix
+// unit of a SIMD do not run side by side (hardware counters: their busy times add up), so nothing is gained by
+// steering one wavefront's conversions under the other's products; what matters is that the SIMD always has a
+// wavefront that can issue, and that as few vector instructions as possible accompany the matrix instructions.
+// Two independent workgroups give the first: while one waits at a barrier, for its global loads, or stores its
+// tile, the other multiplies. (Two groups in lock step inside one 512-thread workgroup, the previous form, left
+// a tile's first fetch and epilogue uncovered and tied both groups to the slower one.)
 template <int TERMS, bool TN, int WM, int WN, int TMB, int TNB, int A_CH, bool GATE>
-__global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g) {
+__global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
     static_assert(TERMS == 2 || TERMS == 3, "two or three bf16 terms per operand");
     constexpr int BM = 32 * TMB * WM, BN = 32 * TNB * WN;
     static_assert(BM + BN <= kThreads, "one 8 x 4 block per thread in the TN layout");
-    __shared__ __attribute__((aligned(16))) uint16_t smem[2][TERMS * (BM + BN) * kPitch];
-    const int grp = threadIdx.x / kThreads, tid = threadIdx.x % kThreads;
-    uint16_t* const sa = smem[grp];
-    uint16_t* const sb = smem[grp] + TERMS * BM * kPitch;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[TERMS * (BM + BN) * kPitch];
+    const int tid = threadIdx.x;
+    uint16_t* const sa = smem;
+    uint16_t* const sb = smem + TERMS * BM * kPitch;
 
-    // workgroup -> pair of tiles: tiles that share streamed data go to one XCD (workgroups are dealt to the 8
-    // XCDs round-robin), so that the streamed operand is fetched into a single L2
+    // workgroup -> tile: tiles that share streamed data go to one XCD (workgroups are dealt to the 8 XCDs
+    // round-robin), so that the streamed operand is fetched into a single L2
     const int32_t xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
-    const int32_t in_u = within % g.inner_units, out_u = (within / g.inner_units) * 8 + xcd;
-    if (out_u >= g.outer_units) return;        // whole workgroup leaves together: no barrier is skipped
+    const int32_t in = within % g.inner, out = (within / g.inner) * 8 + xcd;
+    if (out >= g.outer) return;                // whole workgroup leaves together: no barrier is skipped
     const int32_t tiles1 = (g.k + BK - 1) / BK;
     const int32_t tiles2 = (g.k2 + BK - 1) / BK;
-    // tile and range of reduction tiles of either group (a group without a tile has an empty range)
-    auto tile_of = [&](int which, int32_t& in, int32_t& out, int32_t& t_begin, int32_t& t_end) {
-        in = g.pair_inner ? in_u * 2 + which : in_u;
-        out = g.pair_inner ? out_u : out_u * 2 + which;
-        t_begin = 0, t_end = tiles1 + tiles2;
-        if (g.split_k > 1) {
-            t_begin = out * g.tiles_per_split;
-            t_end = min(t_end, t_begin + g.tiles_per_split);
-        }
-        if (in >= g.inner || out >= g.outer) in = 0, out = 0, t_begin = 0, t_end = 0;
-    };
-    int32_t in, out, t_begin, t_end, o_in, o_out, o_begin, o_end;
-    tile_of(grp, in, out, t_begin, t_end);
-    tile_of(grp ^ 1, o_in, o_out, o_begin, o_end);
-    const int32_t my_steps = max(t_end - t_begin, 0);
-    const int32_t steps = max(my_steps, max(o_end - o_begin, 0));      // the same number in both groups
+    int32_t t_begin = 0, t_end = tiles1 + tiles2;
     int32_t tm, tn, z;
     if (g.split_k > 1) {
+        t_begin = out * g.tiles_per_split;
+        t_end = min(t_end, t_begin + g.tiles_per_split);
         z = out, tm = in / g.tiles_n, tn = in % g.tiles_n;
     } else {
         z = 0, tm = out, tn = in;
     }
+    const int32_t steps = max(t_end - t_begin, 0);
     const int32_t m0 = tm * BM, n0 = tn * BN;
 
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform: addresses built from it stay scalar
     const int wm = (wave / WN) * (32 * TMB), wn = (wave % WN) * (32 * TNB);
     const int lrow = lane & 31, lk = lane >> 5;
 
@@ -345,8 +331,9 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // staging registers and per-thread offsets of the two layouts (only one set is used per instantiation)
-    RowRegs<BM, A_CH, GATE && !TN> ra;
-    PrepRegs<TERMS, BN> rb;
+    constexpr int DEPTH = 1;                      // register sets = steps a fetch runs ahead of its use
+    RowRegs<BM, A_CH, GATE && !TN> ra_[DEPTH];
+    PrepRegs<TERMS, BN> rb_[DEPTH];
     ColRegs<GATE && TN> cr;           // a thread serves A or B, never both
     RowPlan<BM, A_CH> plan_a;
     PrepPlan<TERMS, BN> plan_b;
@@ -360,7 +347,10 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
         plan_b.init(tid, g.b.ld, g.b.plane);
     }
 
-    auto fetch = [&](int32_t t) {
+    auto fetch = [&](int32_t t, auto set) {
+        constexpr int SET = decltype(set)::value;
+        auto& ra = ra_[SET];
+        auto& rb = rb_[SET];
         const bool first = t < tiles1;
         const int32_t k0 = (first ? t : t - tiles1) * BK, k_left = (first ? g.k : g.k2) - k0;
         if constexpr (TN) {
@@ -383,7 +373,10 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
             load_prep<TERMS, BN>(bbase, plan_b, rb);
         }
     };
-    auto stash = [&]() {
+    auto stash = [&](auto set) {
+        constexpr int SET = decltype(set)::value;
+        auto& ra = ra_[SET];
+        auto& rb = rb_[SET];
         if constexpr (TN) {
             if (serves_a) store_cols<TERMS, BM, false>(cr, tid, sa);
             if (serves_b) store_cols<TERMS, BN, GATE>(cr, tid - BM, sb);
@@ -393,8 +386,6 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
         }
     };
     auto compute = [&]() {
-        // the multiplying wavefront goes first on its SIMD: the other group's conversions fill the gaps
-        __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
             const int koff = s * 16 + lk * 8;
@@ -415,76 +406,91 @@ __global__ __launch_bounds__(2 * kThreads, 2) void gemm_split_kernel(SplitGemm g
                 multiply<TMB, TNB, 2, 0>(fa, fb, acc);
             }
         }
-        __builtin_amdgcn_s_setprio(0);
     };
 
-    // Barrier k (k = 1, 2, ...) ends phase k. Group 0 writes tile `it` to LDS in phase 2 it + 1 and multiplies
-    // it in phase 2 it + 2; group 1 does the same one phase later. Both groups pass 2 steps + 1 barriers.
-    if (my_steps > 0) fetch(t_begin);
-    if (grp == 1) workgroup_barrier();
-    for (int32_t it = 0; it < steps; ++it) {
-        if (it < my_steps) {
-            stash();
-            if (it + 1 < my_steps) fetch(t_begin + it + 1);
-        }
+    // One LDS stage; a step's operands are fetched into registers DEPTH steps before they are expanded and written,
+    // after the previous step's fragments were read. (DEPTH = 2, a second register set, was measured and changes
+    // nothing: the compiler's wait-count tracking joins both sets' loads at the loop's back edge.)
+    using Set0 = std::integral_constant<int, 0>;
+    using Set1 = std::integral_constant<int, DEPTH - 1>;
+    auto step = [&](int32_t it, auto set) {
+        stash(set);
+        if (it + DEPTH < steps) fetch(t_begin + it + DEPTH, set);
         workgroup_barrier();
-        if (it < my_steps) compute();
-        workgroup_barrier();   // the tile's fragments have been read: the next one may overwrite them
+        compute();
+        workgroup_barrier();   // the stage's fragments have been read: the next one may overwrite them
+    };
+    if (steps > 0) fetch(t_begin, Set0{});
+    if (DEPTH > 1 && steps > 1) fetch(t_begin + 1, Set1{});
+    for (int32_t it = 0; it < steps; it += DEPTH) {
+        step(it, Set0{});
+        if (DEPTH > 1 && it + 1 < steps) step(it + 1, Set1{});
     }
-    if (grp == 0) workgroup_barrier();
-    if (my_steps == 0) return;         // a group without a tile; no barrier follows
+    if (steps == 0) return;
 
     // epilogue: accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32).
-    // Addresses are one 64-bit base per lane plus 32-bit multiples of the row pitch; a tile that lies wholly
-    // inside C (all but the last row and column of tiles) takes a path without per-element tests. When C is
-    // added to, the old values of a block are fetched by loads that are all issued before the first one is used
-    // (from clamped, always valid addresses), not one round trip per element.
+    // A tile that lies wholly inside C (all but the last row and column of tiles) is stored through one scalar
+    // base per output row plus one 32-bit lane offset (4 lk rows + lrow columns), so that the address arithmetic
+    // runs on the scalar unit and the vector unit only sees the loads, adds and stores; the edge tiles take the
+    // path with per-element tests and clamped addresses. When C is added to, the old values of a block are fetched
+    // by loads that are all issued before the first one is used, not one round trip per element.
     const bool to_partial = g.split_k > 1;
-    const int32_t col_base = n0 + wn + lrow;
     const int64_t pitch = to_partial ? int64_t(g.n) : g.ldc;
     float* const base = to_partial ? g.partial + int64_t(z) * g.m * g.n : g.c;
     const bool add_old = !to_partial && g.accumulate, relu = !to_partial && g.relu;
-    auto finish = [&](auto guard) {
-        constexpr bool GUARD = decltype(guard)::value;
-        float* const out0 = base + int64_t(m0 + wm) * pitch + col_base;      // interior tiles only
+    if (m0 + BM <= g.m && n0 + BN <= g.n) {
+        float* const tile = base + int64_t(m0 + wm) * pitch + (n0 + wn);               // scalar
+        const uint32_t lane_off = uint32_t(4 * lk) * uint32_t(pitch) + uint32_t(lrow);  // a tile spans < 2^32 elements
 #pragma unroll
         for (int i = 0; i < TMB; ++i) {
 #pragma unroll
             for (int j = 0; j < TNB; ++j) {
-                float* ptr[16];
-                bool ok[16];
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int32_t r = i * 32 + 4 * lk + 8 * (v >> 2) + (v & 3);        // row inside the wavefront's part
-                    if constexpr (GUARD) {
-                        const int32_t row = m0 + wm + r, col = col_base + j * 32;
-                        ok[v] = row < g.m && col < g.n;
-                        ptr[v] = base + int64_t(min(row, g.m - 1)) * pitch + min(col, g.n - 1);
-                    } else {
-                        ok[v] = true;
-                        ptr[v] = out0 + j * 32 + uint32_t(r) * uint32_t(pitch);        // a tile spans < 2^32 elements
-                    }
-                }
                 float old[16];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) old[v] = 0.f;
                 if (add_old) {
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) old[v] = *ptr[v];
+                    for (int v = 0; v < 16; ++v)
+                        old[v] = (tile + int64_t(i * 32 + 8 * (v >> 2) + (v & 3)) * pitch + j * 32)[lane_off];
                 }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     float x = acc[i][j][v] + old[v];
                     if (relu) x = fmaxf(x, 0.f);
-                    if (ok[v]) *ptr[v] = x;
+                    (tile + int64_t(i * 32 + 8 * (v >> 2) + (v & 3)) * pitch + j * 32)[lane_off] = x;
                 }
             }
         }
-    };
-    if (m0 + BM <= g.m && n0 + BN <= g.n)
-        finish(std::false_type{});
-    else
-        finish(std::true_type{});
+        return;
+    }
+    const int32_t col_base = n0 + wn + lrow;
+#pragma unroll
+    for (int i = 0; i < TMB; ++i) {
+#pragma unroll
+        for (int j = 0; j < TNB; ++j) {
+            float* ptr[16];
+            bool ok[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t row = m0 + wm + i * 32 + 4 * lk + 8 * (v >> 2) + (v & 3), col = col_base + j * 32;
+                ok[v] = row < g.m && col < g.n;
+                ptr[v] = base + int64_t(min(row, g.m - 1)) * pitch + min(col, g.n - 1);
+            }
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) old[v] = 0.f;
+            if (add_old) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) old[v] = *ptr[v];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float x = acc[i][j][v] + old[v];
+                if (relu) x = fmaxf(x, 0.f);
+                if (ok[v]) *ptr[v] = x;
+            }
+        }
+    }
 }
 
 // out[p][r][c] (bf16, `rows_padded` rows of `pitch` elements, zero beyond rows x cols) = term p of
@@ -600,10 +606,7 @@ hipError_t varco_launch_gemm_split(const GemmArgs& ga, hipStream_t stream, const
         g.inner = g.tiles_n;
         g.outer = g.tiles_m;
     }
-    g.pair_inner = g.inner >= 2 ? 1 : 0;
-    g.inner_units = g.pair_inner ? (g.inner + 1) / 2 : g.inner;
-    g.outer_units = g.pair_inner ? g.outer : (g.outer + 1) / 2;
-    const int64_t blocks = int64_t((g.outer_units + 7) / 8 * 8) * g.inner_units;
+    const int64_t blocks = int64_t((g.outer + 7) / 8 * 8) * g.inner;
     if (blocks > 0x7FFFFFFF) return hipErrorInvalidValue;
     const dim3 grid{unsigned(blocks)};
     *split_used = split;
@@ -616,11 +619,11 @@ hipError_t varco_launch_gemm_split(const GemmArgs& ga, hipStream_t stream, const
                 constexpr bool NR = decltype(nr)::value, GT = decltype(gt)::value;
                 constexpr int WM = NR ? 4 : 2, WN = NR ? 1 : 2, TMB = NR ? 1 : 2, TNB = 2;
                 if (tn) {
-                    hipLaunchKernelGGL((gemm_split_kernel<T, true, WM, WN, TMB, TNB, 4, GT>), grid, dim3(2 * kThreads), 0, stream, g);
+                    hipLaunchKernelGGL((gemm_split_kernel<T, true, WM, WN, TMB, TNB, 4, GT>), grid, dim3(kThreads), 0, stream, g);
                 } else if (a8) {
-                    hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 8, GT>), grid, dim3(2 * kThreads), 0, stream, g);
+                    hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 8, GT>), grid, dim3(kThreads), 0, stream, g);
                 } else {
-                    hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 4, GT>), grid, dim3(2 * kThreads), 0, stream, g);
+                    hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 4, GT>), grid, dim3(kThreads), 0, stream, g);
                 }
             });
         });

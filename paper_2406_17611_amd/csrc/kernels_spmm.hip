@@ -36,6 +36,7 @@ constexpr int agg_block(int mode) { return mode == 0 /* dense rows only */ ? kBl
 // Independent row loads issued back to back by the kernels that also take compressed rows (dense rows here,
 // compressed rows see sparse_phase): their register budget is the 64 of eight wavefronts per SIMD, or the 72 of
 // seven; resident wavefronts, each a chain of dependent round trips, are what their rate is made of.
+constexpr int kXcdRun = 32;       // consecutive workgroups of the work list that one XCD takes (see spmm_kernel)
 constexpr int kUnroll = 3;
 constexpr int kUnrollDense = 4;   // dense-only kernels have registers to spare
 
@@ -213,7 +214,13 @@ __global__ __launch_bounds__(agg_block(MODE)) void spmm_kernel(SpmmArgs<T> p) {
 
     // The wavefront's item and the records of its first batch are requested before the table is staged and the
     // workgroup meets at the barrier: three round trips in a row become little more than one.
-    const int32_t idx = blockIdx.x * kAggWaves + __builtin_amdgcn_readfirstlane(wave);   // uniform: the item sits in scalar registers
+    // Workgroups are dealt to the 8 XCDs round-robin; an XCD takes the work list in runs of kXcdRun consecutive
+    // workgroups (the grid is a multiple of 8 runs), so that rows next to each other - which on a graph with any
+    // locality share source rows - are aggregated through the same L2 at about the same time, while every XCD still
+    // sees the same mix of long and short rows (contiguous eighths put all split rows on one XCD: twice as slow).
+    const int32_t xcd = int32_t(blockIdx.x & 7u), seq = int32_t(blockIdx.x >> 3);
+    const int32_t block = ((seq / kXcdRun) * 8 + xcd) * kXcdRun + seq % kXcdRun;
+    const int32_t idx = block * kAggWaves + __builtin_amdgcn_readfirstlane(wave);   // uniform: the item sits in scalar registers
     const bool has_item = idx < p.n_items;
     SpmmItem it{};                      // empty range for a wavefront without an item
     if (has_item) it = p.items[idx];
@@ -786,7 +793,8 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
     while ((1 << a.lpe_log2) < a.ku && a.lpe_log2 < 6) ++a.lpe_log2;
     a.epi = std::max(1, std::min(64 >> a.lpe_log2, epi_cap));
     const int agg_waves = agg_block(halo ? kHalo : kDenseOnly) / 64;
-    const dim3 grid((plan.n_items + agg_waves - 1) / agg_waves);
+    const int32_t per_round = 8 * kXcdRun;                                         // see the kernel's XCD mapping
+    const dim3 grid(((plan.n_items + agg_waves - 1) / agg_waves + per_round - 1) / per_round * per_round);
     size_t lds_bytes = 0;
     if (halo && !full)
         lds_bytes = size_t(agg_waves) * a.epi * width * sizeof(float) + size_t(rule.n_units) * sizeof(uint16_t);

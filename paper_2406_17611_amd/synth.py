@@ -337,6 +337,19 @@ def make_workload(name: str) -> Workload:
         g = gcn_operator(2_449_029, u, v)
         return Workload(name, g, random_partition(g.n, 32, SEED_PART), 32, "gcn", (100, 512, 512, 47),
                         ((1, 1), (4, 1), (32, 1)), dtype="bf16")
+    # Evidence workloads (not configurations of the benchmark): the large graph's size, widths and ratio with a
+    # different structure, to tell what the aggregation kernels' rates owe to the input's locality.
+    if name == "large_sage_bfs8":        # the same graph, 8 contiguous chunks of a breadth-first order
+        u, v = _products_like_edges()
+        g = sage_mean_operator(2_449_029, u, v)
+        return Workload(name, g, bfs_contiguous_partition(g, 8), 8, "sage", (100, 256, 256, 47), ((8, 1),))
+    if name == "large_sage_banded8":     # every node linked to its 25 successors: 50 neighbours, all nearby; 8 id blocks
+        n, band = 2_449_029, 25
+        u = np.repeat(np.arange(n, dtype=np.int64), band)
+        v = u + np.tile(np.arange(1, band + 1, dtype=np.int64), n)
+        keep = v < n
+        g = sage_mean_operator(n, u[keep], v[keep])
+        return Workload(name, g, _equal_chunks(np.arange(n, dtype=np.int64), 8), 8, "sage", (100, 256, 256, 47), ((8, 1),))
     raise ValueError(f"unknown workload {name!r}")
 
 

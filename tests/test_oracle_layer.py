@@ -289,3 +289,39 @@ def test_tiny_config_shapes_and_single_layer_against_dense():
         cols = omask.kept_columns(p.halo_gid, 16, k, KEY, 0, 0)
         xo, _ = olayer.layer_forward(p, x[p.local_gid], z_all, cols, h1, None, olayer.RELU)
         assert _close(xo, want[p.local_gid])
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("ratio", [1, 4, 16])
+def test_transform_before_aggregate_is_the_same_layer(conv, ratio):
+    """Eq. (2) is associative in S and H: transforming the rows first (local rows as they are, remote rows after
+    decompression, i.e. k-sparse) and aggregating the narrow results gives the oracle's layer, forward and backward,
+    while what is exchanged stays the compressed X_{l-1}. Stated with dense matrices per partition:
+        X_out = rho( S_q [X_loc H1 ; X~_halo H1] + X_loc H0 )
+        G = S_q^T dZ;  dH1 = X_loc^T G_loc + X~_halo^T G_halo;  dX_loc = G_loc H1^T (+ dZ H0^T);
+        returned[s, j] = (G_halo H1^T)[s, pi(j)]"""
+    widths = (64, 12)                                   # a narrowing layer
+    g, part, parts, x, weights, r = _setup(conv, 240, 3, widths, seed=77)
+    h1, h0 = weights[0]
+    k = omask.keep_count(widths[0], ratio, 1)
+    z_all = np.vstack([olayer.compress(x[p.local_gid], p.boundary_rows,
+                                       omask.kept_columns(p.local_gid[p.boundary_rows], widths[0], k, KEY, 3, 0))
+                       for p in parts])
+    for p in parts:
+        cols = omask.kept_columns(p.halo_gid, widths[0], k, KEY, 3, 0)
+        xl, dxo = x[p.local_gid], r[p.local_gid]
+        xo, m = olayer.layer_forward(p, xl, z_all, cols, h1, h0, olayer.RELU)
+        dh1, dh0, dxl, dzh = olayer.layer_backward(p, dxo, xo, xl, m, cols, h1, h0, olayer.RELU, True)
+
+        s_q = np.zeros((p.n_local, p.n_local + p.n_halo))
+        rows = np.repeat(np.arange(p.n_local), np.diff(p.rowptr))
+        s_q[rows, p.colidx] = p.vals
+        x_halo = olayer.decompress(z_all[p.halo_zrow], cols, widths[0])
+        t = np.vstack([xl @ h1, x_halo @ h1])                       # transform first, at the output width
+        zpre = s_q @ t + (xl @ h0 if h0 is not None else 0.0)
+        _close(np.maximum(zpre, 0.0), xo)
+        dz = dxo * (zpre > 0)
+        gq = s_q.T @ dz                                             # aggregate the errors at the output width
+        _close(xl.T @ gq[:p.n_local] + x_halo.T @ gq[p.n_local:], dh1)
+        _close(gq[:p.n_local] @ h1.T + (dz @ h0.T if h0 is not None else 0.0), dxl)
+        _close((gq[p.n_local:] @ h1.T)[np.arange(p.n_halo)[:, None], cols], dzh)

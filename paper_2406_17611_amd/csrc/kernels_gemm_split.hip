@@ -161,8 +161,10 @@ __device__ __forceinline__ void store_rows(int tid, const RowRegs<ROWS, CH, GATE
     }
 }
 
-// ---- expanded bf16 weight copy [term][row][pitch]: chunks of 8 elements, copied unchanged ----
-// The copy is zero-padded to whole tiles (rows to kPrepRows, pitch to BK), so no chunk needs a bounds check.
+// ---- expanded bf16 weight copy: chunks of 8 elements, copied unchanged ----
+// The copy is stored by tile and stage, [row tile][stage of BK reduction steps][term][row in tile][BK], so that what
+// a workgroup fetches per step is one contiguous block (whole cache lines, one 1 KB run per wavefront load), and it
+// is zero-padded to whole tiles and stages, so no chunk needs a bounds check.
 template <int TERMS, int ROWS>
 struct PrepRegs {
     static constexpr int PER_ROW = BK / 8;
@@ -174,13 +176,13 @@ template <int TERMS, int ROWS>
 struct PrepPlan {
     static constexpr int PER_ROW = BK / 8;
     static constexpr int N = TERMS * ROWS * PER_ROW / kThreads;
-    uint32_t off[N];     // bytes from the tile base
-    __device__ __forceinline__ void init(int tid, int64_t pitch, int64_t plane) {
+    uint32_t off[N];     // bytes from the block's base
+    __device__ __forceinline__ void init(int tid) {
 #pragma unroll
         for (int h = 0; h < N; ++h) {
             const int c = tid + h * kThreads;
             const int p = c / (ROWS * PER_ROW), rc = c % (ROWS * PER_ROW);
-            off[h] = uint32_t(p * plane + tile_row(rc / PER_ROW) * pitch + (rc % PER_ROW) * 8) * 2u;
+            off[h] = uint32_t((p * ROWS + tile_row(rc / PER_ROW)) * BK + (rc % PER_ROW) * 8) * 2u;
         }
     }
 };
@@ -207,20 +209,19 @@ __device__ __forceinline__ void store_prep(int tid, const PrepRegs<TERMS, ROWS>&
 // eight consecutive lanes then write two LDS rows that are four rows apart, all four 16-byte chunks of each,
 // which touches every LDS bank once. Output indices beyond the matrix are clamped (their results are never
 // stored). In the last, partial tile of the reduction the node index is clamped and A is zeroed beyond it.
-// (HAS_GATE: the kernel masks one of its operands; GATE below: this operand is the masked one.)
-template <bool HAS_GATE>
+template <bool GATE>
 struct ColRegs {
     float4 v[8];
-    float4 g[HAS_GATE ? 8 : 1];
+    float4 g[GATE ? 8 : 1];
 };
 
 __device__ __forceinline__ uint32_t col_offset(int b, int32_t i0, int32_t extent) {
     return uint32_t(min(i0 + (b >> 2) * 4, extent - 4) - i0) * 4u;      // bytes; extent is a multiple of 4
 }
 
-template <bool GATE, bool TAIL, bool ZERO, bool HAS_GATE>
+template <bool GATE, bool TAIL, bool ZERO>
 __device__ __forceinline__ void load_cols(const float* base, const float* gate, int b, uint32_t col_off, uint32_t ld_bytes,
-                                          int32_t k_left, ColRegs<HAS_GATE>& r) {
+                                          int32_t k_left, ColRegs<GATE>& r) {
     const int kb = (b & 3) * 8;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
@@ -232,15 +233,15 @@ __device__ __forceinline__ void load_cols(const float* base, const float* gate, 
     }
 }
 
-template <int TERMS, int ROWS, bool GATE, bool HAS_GATE>
-__device__ __forceinline__ void store_cols(const ColRegs<HAS_GATE>& r, int b, uint16_t* s) {
+template <int TERMS, int ROWS, bool GATE>
+__device__ __forceinline__ void store_cols(const ColRegs<GATE>& r, int b, uint16_t* s) {
     // An LDS row holds one output index with its 8 reduction steps contiguous, two steps per 32-bit word: the two
     // values expanded together are steps 2 q and 2 q + 1 of one output index, which is the transposition itself.
     float x[8][4];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
         float4 v = r.v[kk];
-        if (GATE) v = gate4(v, r.g[kk]);
+        if constexpr (GATE) v = gate4(v, r.g[kk]);
         x[kk][0] = v.x, x[kk][1] = v.y, x[kk][2] = v.z, x[kk][3] = v.w;
     }
     uint16_t* base = s + (b >> 2) * 4 * kPitch + (b & 3) * 8;
@@ -331,56 +332,29 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     // staging registers and per-thread offsets of the two layouts (only one set is used per instantiation)
-    constexpr int DEPTH = 1;                      // register sets = steps a fetch runs ahead of its use
-    RowRegs<BM, A_CH, GATE && !TN> ra_[DEPTH];
-    PrepRegs<TERMS, BN> rb_[DEPTH];
-    ColRegs<GATE && TN> cr;           // a thread serves A or B, never both
+    RowRegs<BM, A_CH, GATE && !TN> ra;
+    PrepRegs<TERMS, BN> rb;
     RowPlan<BM, A_CH> plan_a;
     PrepPlan<TERMS, BN> plan_b;
-    const bool serves_a = tid < BM, serves_b = tid >= BM && tid < BM + BN;   // TN: uniform per wavefront
-    uint32_t col_off = 0;
-    if constexpr (TN) {
-        if (serves_a) col_off = col_offset(tid, m0, g.m);
-        if (serves_b) col_off = col_offset(tid - BM, n0, g.n);
-    } else {
+    if constexpr (!TN) {
         plan_a.init(tid, m0, g.m, g.a.ld);        // a chained second product has the same leading dimensions
-        plan_b.init(tid, g.b.ld, g.b.plane);
+        plan_b.init(tid);
     }
 
-    auto fetch = [&](int32_t t, auto set) {
-        constexpr int SET = decltype(set)::value;
-        auto& ra = ra_[SET];
-        auto& rb = rb_[SET];
+    auto fetch = [&](int32_t t) {                 // NT
         const bool first = t < tiles1;
         const int32_t k0 = (first ? t : t - tiles1) * BK, k_left = (first ? g.k : g.k2) - k0;
-        if constexpr (TN) {
-            const float* abase = static_cast<const float*>(g.a.ptr) + int64_t(k0) * g.a.ld + m0;
-            const float* bbase = static_cast<const float*>(g.b.ptr) + int64_t(k0) * g.b.ld + n0;
-            const float* gbase = GATE ? g.b.gate + int64_t(k0) * g.b.ld + n0 : nullptr;
-            const uint32_t lda = uint32_t(g.a.ld) * 4u, ldb = uint32_t(g.b.ld) * 4u;
-            if (k_left >= BK) {
-                if (serves_a) load_cols<false, false, false>(abase, nullptr, tid, col_off, lda, k_left, cr);
-                if (serves_b) load_cols<GATE, false, false>(bbase, gbase, tid - BM, col_off, ldb, k_left, cr);
-            } else {
-                if (serves_a) load_cols<false, true, true>(abase, nullptr, tid, col_off, lda, k_left, cr);
-                if (serves_b) load_cols<GATE, true, false>(bbase, gbase, tid - BM, col_off, ldb, k_left, cr);
-            }
-        } else {
-            const float* abase = static_cast<const float*>(first ? g.a.ptr : g.a2.ptr) + int64_t(m0) * g.a.ld + k0;
-            const float* gbase = GATE ? g.a.gate + int64_t(m0) * g.a.ld + k0 : nullptr;   // never with a second product
-            const uint16_t* bbase = static_cast<const uint16_t*>(first ? g.b.ptr : g.b2.ptr) + int64_t(n0) * g.b.ld + k0;
+        const float* abase = static_cast<const float*>(first ? g.a.ptr : g.a2.ptr) + int64_t(m0) * g.a.ld + k0;
+        const float* gbase = GATE ? g.a.gate + int64_t(m0) * g.a.ld + k0 : nullptr;   // never with a second product
+        const uint16_t* bbase = static_cast<const uint16_t*>(first ? g.b.ptr : g.b2.ptr) +
+                                (int64_t(tn) * (g.b.ld / BK) + k0 / BK) * (TERMS * BN * BK);      // g.b.ld: padded reduction length
+        if constexpr (!TN) {
             load_rows<BM, A_CH, GATE>(tid, abase, gbase, plan_a, k_left, ra);
             load_prep<TERMS, BN>(bbase, plan_b, rb);
         }
     };
-    auto stash = [&](auto set) {
-        constexpr int SET = decltype(set)::value;
-        auto& ra = ra_[SET];
-        auto& rb = rb_[SET];
-        if constexpr (TN) {
-            if (serves_a) store_cols<TERMS, BM, false>(cr, tid, sa);
-            if (serves_b) store_cols<TERMS, BN, GATE>(cr, tid - BM, sb);
-        } else {
+    auto stash = [&]() {                          // NT
+        if constexpr (!TN) {
             store_rows<TERMS, BM, A_CH, GATE>(tid, ra, sa);
             store_prep<TERMS, BN>(tid, rb, sb);
         }
@@ -408,23 +382,51 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
         }
     };
 
-    // One LDS stage; a step's operands are fetched into registers DEPTH steps before they are expanded and written,
-    // after the previous step's fragments were read. (DEPTH = 2, a second register set, was measured and changes
-    // nothing: the compiler's wait-count tracking joins both sets' loads at the loop's back edge.)
-    using Set0 = std::integral_constant<int, 0>;
-    using Set1 = std::integral_constant<int, DEPTH - 1>;
-    auto step = [&](int32_t it, auto set) {
-        stash(set);
-        if (it + DEPTH < steps) fetch(t_begin + it + DEPTH, set);
-        workgroup_barrier();
-        compute();
-        workgroup_barrier();   // the stage's fragments have been read: the next one may overwrite them
+    // One LDS stage: a step's operands are fetched into registers while the previous step is multiplied, then
+    // expanded and written once its fragments have been read. (A second register set, fetching two steps ahead,
+    // was measured and changes nothing.)
+    auto pipeline = [&](auto&& fetch_fn, auto&& stash_fn) {
+        if (steps > 0) fetch_fn(t_begin);
+        for (int32_t it = 0; it < steps; ++it) {
+            stash_fn();
+            if (it + 1 < steps) fetch_fn(t_begin + it + 1);
+            workgroup_barrier();
+            compute();
+            workgroup_barrier();   // the stage's fragments have been read: the next one may overwrite them
+        }
     };
-    if (steps > 0) fetch(t_begin, Set0{});
-    if (DEPTH > 1 && steps > 1) fetch(t_begin + 1, Set1{});
-    for (int32_t it = 0; it < steps; it += DEPTH) {
-        step(it, Set0{});
-        if (DEPTH > 1 && it + 1 < steps) step(it + 1, Set1{});
+    if constexpr (TN) {
+        // Every wavefront serves 8 x 4 blocks of one operand only (BM and BN are multiples of 64), so the role is
+        // a scalar and each role gets a loop of its own: one shared loop with per-thread role tests made the
+        // compiler copy the 32 staging registers between the paths every step.
+        const int role = __builtin_amdgcn_readfirstlane(tid < BM ? 0 : (tid < BM + BN ? 1 : 2));
+        auto run = [&](auto is_a) {
+            constexpr bool A = decltype(is_a)::value;
+            constexpr bool G = GATE && !A;
+            ColRegs<G> cr;
+            const int b = A ? tid : tid - BM;
+            const uint32_t col_off = A ? col_offset(b, m0, g.m) : col_offset(b, n0, g.n);
+            const SplitOperand& op = A ? g.a : g.b;
+            const uint32_t ld_bytes = uint32_t(op.ld) * 4u;
+            auto fetch_cols = [&](int32_t t) {
+                const int32_t k0 = t * BK, k_left = g.k - k0;
+                const float* base = static_cast<const float*>(op.ptr) + int64_t(k0) * op.ld + (A ? m0 : n0);
+                const float* gbase = G ? op.gate + int64_t(k0) * op.ld + n0 : nullptr;
+                if (k_left >= BK)
+                    load_cols<G, false, A>(base, gbase, b, col_off, ld_bytes, k_left, cr);
+                else
+                    load_cols<G, true, A>(base, gbase, b, col_off, ld_bytes, k_left, cr);
+            };
+            pipeline(fetch_cols, [&]() { store_cols<TERMS, A ? BM : BN, G>(cr, b, A ? sa : sb); });
+        };
+        if (role == 0)
+            run(std::true_type{});
+        else if (role == 1)
+            run(std::false_type{});
+        else
+            pipeline([](int32_t) {}, []() {});
+    } else {
+        pipeline(fetch, stash);
     }
     if (steps == 0) return;
 
@@ -493,22 +495,25 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
     }
 }
 
-// out[p][r][c] (bf16, `rows_padded` rows of `pitch` elements, zero beyond rows x cols) = term p of
-// (transpose ? h[c][r] : h[r][c]).
+// Expanded copy of (transpose ? h[c][r] : h[r][c]), r < rows, c < cols, zero beyond, in the tiled layout the product
+// kernel fetches: element (term p, row r, column c) sits at
+//   (((r / bn) * (pitch / BK) + c / BK) * TERMS + p) * bn * BK + (r % bn) * BK + c % BK,
+// bn = rows of a B tile (64 for at most 64 rows, else 128), rows padded to `rows_padded`, columns to `pitch`.
 template <int TERMS>
 __global__ __launch_bounds__(kThreads) void prep_weight_split_kernel(const float* __restrict__ h, int64_t ld, int32_t rows,
                                                                      int32_t cols, int32_t rows_padded, int32_t pitch,
-                                                                     int32_t transpose, uint16_t* __restrict__ out) {
+                                                                     int32_t bn, int32_t transpose, uint16_t* __restrict__ out) {
     const int64_t idx = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    const int64_t plane = int64_t(rows_padded) * pitch;
-    if (idx >= plane) return;
+    if (idx >= int64_t(rows_padded) * pitch) return;
     const int32_t r = int32_t(idx / pitch), c = int32_t(idx % pitch);
     float x = 0.f;
     if (r < rows && c < cols) x = transpose ? h[int64_t(c) * ld + r] : h[int64_t(r) * ld + c];
+    const int64_t block = (int64_t(r / bn) * (pitch / BK) + c / BK) * TERMS;
+    const int32_t inside = (r % bn) * BK + c % BK;
 #pragma unroll
     for (int p = 0; p < TERMS; ++p) {
         const uint16_t t = float_to_bf16(x);
-        out[p * plane + idx] = t;
+        out[(block + p) * bn * BK + inside] = t;
         x -= __uint_as_float(uint32_t(t) << 16);
     }
 }
@@ -532,12 +537,13 @@ hipError_t varco_launch_prep_weight_split(int terms, const float* h, int64_t ld,
     if (terms != 2 && terms != 3) return hipErrorInvalidValue;
     if (rows_padded < rows || rows_padded % kPrepRows != 0 || pitch < cols || pitch % BK != 0) return hipErrorInvalidValue;
     const dim3 grid(unsigned((total + kThreads - 1) / kThreads));
+    const int32_t bn = rows <= 64 ? 64 : 128;      // the product kernel's B tile for this many output columns
     if (terms == 3)
         hipLaunchKernelGGL(prep_weight_split_kernel<3>, grid, dim3(kThreads), 0, stream, h, ld, rows, cols, rows_padded,
-                           pitch, transpose ? 1 : 0, static_cast<uint16_t*>(out));
+                           pitch, bn, transpose ? 1 : 0, static_cast<uint16_t*>(out));
     else
         hipLaunchKernelGGL(prep_weight_split_kernel<2>, grid, dim3(kThreads), 0, stream, h, ld, rows, cols, rows_padded,
-                           pitch, transpose ? 1 : 0, static_cast<uint16_t*>(out));
+                           pitch, bn, transpose ? 1 : 0, static_cast<uint16_t*>(out));
     return hipGetLastError();
 }
 

@@ -206,8 +206,9 @@ hipError_t varco_launch_prep_weight(const float* h, int64_t ld, int32_t rows, in
 // the bf16 path above.
 bool varco_gemm_split_usable(const GemmArgs& g);
 hipError_t varco_launch_gemm_split(const GemmArgs& g, hipStream_t stream, const LaunchTag& tag, int32_t* split_used);
-// out[p][r][c] (bf16; rows_padded rows, a multiple of 128, of pitch elements, a multiple of 32; zero beyond
-// rows x cols) = term p of the expansion of (transpose ? h[c][r] : h[r][c]).
+// Expanded copy of (transpose ? h[c][r] : h[r][c]) (bf16 terms; rows padded to rows_padded, a multiple of 128, columns
+// to pitch, a multiple of 32; zero beyond rows x cols), stored by row tile and stage of 32 columns as the product
+// kernel fetches it (layout: kernels_gemm_split.hip). Same size as a plain [term][row][pitch] copy.
 hipError_t varco_launch_prep_weight_split(int terms, const float* h, int64_t ld, int32_t rows, int32_t cols,
                                           int32_t rows_padded, int32_t pitch, bool transpose, void* out, hipStream_t stream);
 

@@ -113,8 +113,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large_sage")
     ap.add_argument("--ratio", default=None, help="num/den, default: the configuration's ratio")
-    ap.add_argument("--streams", type=int, default=1,
-                    help="HIP streams the partitions of a layer are dealt to (kernels of different partitions overlap)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams the partitions of a layer are dealt to in the timed steps (kernels of different "
+                         "partitions overlap; the per-kernel pass that follows always uses one stream)")
     ap.add_argument("--matmul-terms", type=int, default=None, choices=[0, 2, 3],
                     help="fp32 storage only: form of the dense products (library default 3; 0 = fp32 matrix instructions; "
                          "2 = lower precision, not a valid headline setting)")
@@ -204,18 +205,20 @@ def main():
         dt = time.perf_counter() - t0
         stats = net.ctx.stats()
         # per-kernel table and roofline: a second pass of the same steps with every launch bracketed by HIP events
-        # on its launch stream (outside the headline's timed region: the brackets cost about 1 % of a step)
-        prof = {}
-        profiled_ms_per_step = None
-        if args.streams == 1:
-            net.ctx.profile_enable(True)
-            t1 = time.perf_counter()
-            for s in range(args.steps):
-                net.step(args.warmup + args.steps + s, ratio)
-            torch.cuda.synchronize()
-            profiled_ms_per_step = (time.perf_counter() - t1) * 1e3 / args.steps
-            prof = net.ctx.profile_read()
-            net.ctx.profile_enable(False)
+        # on its launch stream (outside the headline's timed region: the brackets cost about 1 % of a step),
+        # and on one stream: with kernels of two partitions overlapping, a launch's bracket would time both
+        net.use_streams(1)
+        net.step(args.warmup + args.steps, ratio)
+        torch.cuda.synchronize()
+        net.ctx.profile_enable(True)
+        t1 = time.perf_counter()
+        for s in range(args.steps):
+            net.step(args.warmup + args.steps + 1 + s, ratio)
+        torch.cuda.synchronize()
+        profiled_ms_per_step = (time.perf_counter() - t1) * 1e3 / args.steps
+        prof = net.ctx.profile_read()
+        net.ctx.profile_enable(False)
+        net.use_streams(args.streams)
     ms_per_step = dt * 1e3 / args.steps
     edges_per_step = L * net.nnz_total
     assert all(torch.isfinite(t).all().item() for t in net.dh1), "non-finite weight gradient"
@@ -272,7 +275,8 @@ def main():
                    "keep": [net.ctx.keep(l) for l in range(L)], "layers": L, "streams": args.streams,
                    "hip_graph": bool(args.graph),
                    "timed": f"{args.streams} stream{'s' if args.streams > 1 else ''}, " +
-                            ("HIP graph replay" if args.graph else "eager launches") + ", no per-launch events",
+                            ("HIP graph replay" if args.graph else "eager launches") + ", no per-launch events; "
+                            "per-kernel figures from a separate pass on one stream with HIP events around every launch",
                    "matmul_terms": (3 if args.matmul_terms is None else args.matmul_terms) if w.dtype == "f32" else None,
                    "edges_counted_per_step": edges_per_step},
         "roofline": roofline,

@@ -513,12 +513,15 @@ hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const Launc
     if (ga.m == 0 || ga.n == 0) return hipSuccess;
     if (small_k_usable(ga)) {
         tag.begin(stream);
+        hipError_t e = hipSuccess;
         if (ga.a.dtype == VARCO_BF16)
-            launch_small_k<bf16_t>(ga, stream);
+            e = varco_launch_gemm_short_k(ga, 1, stream);               // bf16 matrix instructions
+        else if (ga.f32_terms == 2 || ga.f32_terms == 3)
+            e = varco_launch_gemm_short_k(ga, ga.f32_terms, stream);    // fp32 products from bf16 terms
         else
-            launch_small_k<float>(ga, stream);
+            launch_small_k<float>(ga, stream);                          // fp32 matrix instructions
         tag.end(stream);
-        return hipGetLastError();
+        return e != hipSuccess ? e : hipGetLastError();
     }
     if (varco_gemm_bf16_usable(ga)) {
         int32_t split = 1;

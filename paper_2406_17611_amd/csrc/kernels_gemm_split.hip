@@ -495,6 +495,196 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------------
+// Short reductions on the bf16 matrix units: C (+)= A B^T with at most 64 reduction steps and densely stored
+// rows of A (the input gradient of the last layer: the reduction runs over the classes). Rows of, say, 47
+// elements are not 16-byte aligned, so a workgroup copies its 128 rows of A, one contiguous range of memory,
+// into LDS with 16-byte loads (masked and widened to fp32 on the way; the row pitch stays k). Each wavefront
+// owns 64 columns of C: their weights, expanded into TERMS bf16 terms, sit in registers as matrix operands for
+// the whole kernel; for each block of 32 rows the wavefront reads its 8 values per 16 reduction steps from LDS,
+// expands them in registers and issues the products. With fp32 matrix instructions (the previous form of this
+// kernel, still used when the context asks for them) the same product took 2.7 times the matrix-unit time and
+// was bound by it; this form is bound by writing C. TERMS = 1: bf16 storage (the values are bf16 already; the
+// weights are rounded to bf16 as for the other products of that storage type).
+constexpr int kShortRows = 128;
+constexpr int kEpiPitch = 68;      // floats per row of the epilogue's LDS block (64 + 4: rows start on different banks)
+
+template <typename T>
+__device__ __forceinline__ void load_chunk16(const T* p, float (&x)[16 / sizeof(T)]) {
+    if constexpr (sizeof(T) == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        x[0] = v.x, x[1] = v.y, x[2] = v.z, x[3] = v.w;
+    } else {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[2 * i] = __uint_as_float(u[i] << 16), x[2 * i + 1] = __uint_as_float(u[i] & 0xFFFF0000u);
+    }
+}
+
+// Eight consecutive values as TERMS bf16 fragments.
+template <int TERMS>
+__device__ __forceinline__ void expand8(const float (&x)[8], bf16x8 (&f)[3]) {
+    uint32_t w[4][TERMS];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) expand_pair<TERMS>(x[2 * q], x[2 * q + 1], w[q]);
+#pragma unroll
+    for (int p = 0; p < TERMS; ++p) f[p] = __builtin_bit_cast(bf16x8, make_uint4(w[0][p], w[1][p], w[2][p], w[3][p]));
+}
+template <>
+__device__ __forceinline__ void expand8<1>(const float (&x)[8], bf16x8 (&f)[3]) {
+    f[0] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]), pack_bf16(x[6], x[7])));
+}
+
+template <typename T, int KS, bool GATE, int TERMS>
+__global__ __launch_bounds__(kThreads, 2) void gemm_short_k_kernel(const T* __restrict__ a, const T* __restrict__ gate,
+                                                                   const float* __restrict__ b, int64_t ldb, T* __restrict__ c,
+                                                                   int64_t ldc, int32_t m, int32_t n, int32_t k,
+                                                                   int32_t accumulate) {
+    constexpr int VE = 16 / int(sizeof(T));                       // elements per 16-byte load
+    __shared__ __attribute__((aligned(16))) float tile[kShortRows * 16 * KS + 64];
+    __shared__ __attribute__((aligned(16))) float epi[4 * 32 * kEpiPitch];      // a 32 x 64 block per wavefront
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lcol = lane & 31, lk = lane >> 5;
+    const int32_t r0 = blockIdx.x * kShortRows, rows = min(kShortRows, m - r0);
+    const int32_t c0 = blockIdx.y * 256 + wave * 64;
+    // rows of C can be written 4 elements at a time: whole vectors inside the matrix, aligned
+    const bool vec_out = n % 4 == 0 && ldc % 4 == 0 && (reinterpret_cast<uintptr_t>(c) & (4 * sizeof(T) - 1)) == 0;
+
+    // weights of this wavefront's two column blocks: lane holds B[column][16 s + 8 lk .. + 7], expanded
+    bf16x8 w[2][KS][3];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int32_t col = c0 + cb * 32 + lcol;
+#pragma unroll
+        for (int s2 = 0; s2 < KS; ++s2) {
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int kk = 16 * s2 + 8 * lk + e;
+                x[e] = col < n && kk < k ? b[int64_t(col) * ldb + kk] : 0.f;
+            }
+            expand8<TERMS>(x, w[cb][s2]);
+        }
+    }
+
+    // the rows of this tile as one contiguous range, read in 16-byte chunks on 16-byte boundaries (the range
+    // may start `skew` elements into a chunk; A and its mask have the same skew, checked by the launcher)
+    const int32_t n_el = rows * k;
+    const T* src = a + int64_t(r0) * k;
+    const T* gsrc = GATE ? gate + int64_t(r0) * k : nullptr;
+    const int32_t skew = int32_t((reinterpret_cast<uintptr_t>(src) & 15u) / sizeof(T));
+    for (int32_t e0 = threadIdx.x * VE - skew; e0 < n_el; e0 += kThreads * VE) {
+        float x[VE], y[VE];
+        if (e0 >= 0 && e0 + VE <= n_el) {
+            load_chunk16<T>(src + e0, x);
+            if (GATE) load_chunk16<T>(gsrc + e0, y);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VE; ++i) {
+                const bool in = e0 + i >= 0 && e0 + i < n_el;
+                x[i] = in ? Elem<T>::load(src + e0 + i) : 0.f;
+                if (GATE) y[i] = in ? Elem<T>::load(gsrc + e0 + i) : 0.f;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < VE; ++i) {
+            if (GATE) x[i] = y[i] > 0.f ? x[i] : 0.f;
+            if (e0 + i >= 0 && e0 + i < n_el) tile[e0 + i] = x[i];
+        }
+    }
+    __syncthreads();
+    if (c0 >= n) return;               // no barrier follows
+
+    for (int rb = 0; rb * 32 < rows; ++rb) {
+        const int32_t lrow = min(rb * 32 + lcol, rows - 1);          // rows past the end repeat the last one; never stored
+        floatx16 acc[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < KS; ++s2) {
+            float x[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int kk = 16 * s2 + 8 * lk + e;
+                const float v = tile[lrow * k + kk];                 // in bounds: the tile has 64 spare floats
+                x[e] = kk < k ? v : 0.f;
+            }
+            bf16x8 fa[3];
+            expand8<TERMS>(x, fa);
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb) {
+                auto mul = [&](int pa, int pb) {
+                    acc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[pa], w[cb][s2][pb], acc[cb], 0, 0, 0);
+                };
+                mul(0, 0);
+                if constexpr (TERMS >= 2) {
+                    mul(0, 1);
+                    mul(1, 0);
+                }
+                if constexpr (TERMS == 3) {
+                    mul(1, 1);
+                    mul(0, 2);
+                    mul(2, 0);
+                }
+            }
+        }
+        // accumulator register v of a lane is element (8 * (v / 4) + 4 * (lane / 32) + v % 4, lane % 32): a lane holds
+        // one column. Stored that way a wavefront needs 32 store instructions of 256 bytes each per block of rows,
+        // and the kernel is bound by issuing them; so the block goes through LDS once and leaves as 4-element
+        // vectors along the rows (8 stores of 1 KB; the old values of C, when added to, come in the same way).
+        if (vec_out) {
+            float* ep = epi + wave * (32 * kEpiPitch);
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) ep[(8 * (v >> 2) + 4 * lk + (v & 3)) * kEpiPitch + cb * 32 + lcol] = acc[cb][v];
+            // same wavefront writes and reads: no barrier, the LDS operations of a wavefront complete in order
+            const int er = lane >> 4, ec = (lane & 15) * 4;
+            float4 old[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) old[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (accumulate) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int32_t row = min(rb * 32 + er + 4 * i, rows - 1);
+                    if (c0 + ec < n) old[i] = Elem<T>::load4(c + int64_t(r0 + row) * ldc + c0 + ec);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int32_t row = rb * 32 + er + 4 * i;
+                float4 x = *reinterpret_cast<const float4*>(ep + (er + 4 * i) * kEpiPitch + ec);
+                x.x += old[i].x, x.y += old[i].y, x.z += old[i].z, x.w += old[i].w;
+                if (row < rows && c0 + ec < n) Elem<T>::store4(c + int64_t(r0 + row) * ldc + c0 + ec, x);
+            }
+            continue;
+        }
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int32_t col = c0 + cb * 32 + lcol;
+            const int32_t row0 = rb * 32 + 4 * lk;
+            float old[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) old[v] = 0.f;
+            if (accumulate) {   // all loads issued before the first use, from clamped (always valid) addresses
+                const T* cbase = c + min(col, n - 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    old[v] = Elem<T>::load(cbase + int64_t(r0 + min(row0 + 8 * (v >> 2) + (v & 3), rows - 1)) * ldc);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t row = row0 + 8 * (v >> 2) + (v & 3);
+                if (row < rows && col < n) Elem<T>::store(c + int64_t(r0 + row) * ldc + col, acc[cb][v] + old[v]);
+            }
+        }
+    }
+}
+
 // Expanded copy of (transpose ? h[c][r] : h[r][c]), r < rows, c < cols, zero beyond, in the tiled layout the product
 // kernel fetches: element (term p, row r, column c) sits at
 //   (((r / bn) * (pitch / BK) + c / BK) * TERMS + p) * bn * BK + (r % bn) * BK + c % BK,
@@ -544,6 +734,48 @@ hipError_t varco_launch_prep_weight_split(int terms, const float* h, int64_t ld,
     else
         hipLaunchKernelGGL(prep_weight_split_kernel<2>, grid, dim3(kThreads), 0, stream, h, ld, rows, cols, rows_padded,
                            pitch, bn, transpose ? 1 : 0, static_cast<uint16_t*>(out));
+    return hipGetLastError();
+}
+
+namespace {
+template <typename U>
+struct TypeTag {
+    using type = U;
+};
+}  // namespace
+
+// Short reductions (see gemm_short_k_kernel): terms = 1 for bf16 storage, 2 or 3 for fp32 storage.
+hipError_t varco_launch_gemm_short_k(const GemmArgs& ga, int terms, hipStream_t stream) {
+    const dim3 grid(unsigned((ga.m + kShortRows - 1) / kShortRows), unsigned((ga.n + 255) / 256));
+    const int ks = (ga.k + 15) / 16;
+    if (ks < 1 || ks > 4) return hipErrorInvalidValue;
+    auto go = [&](auto type, auto ksc, auto gt, auto tc) {
+        using T = typename decltype(type)::type;
+        hipLaunchKernelGGL((gemm_short_k_kernel<T, decltype(ksc)::value, decltype(gt)::value, decltype(tc)::value>), grid,
+                           dim3(kThreads), 0, stream, static_cast<const T*>(ga.a.ptr), static_cast<const T*>(ga.a.gate),
+                           static_cast<const float*>(ga.b.ptr), ga.b.ld, static_cast<T*>(ga.c), ga.ldc, ga.m, ga.n, ga.k,
+                           ga.accumulate ? 1 : 0);
+    };
+    auto with_ks = [&](auto type, auto gt, auto tc) {
+        switch (ks) {
+            case 1: go(type, std::integral_constant<int, 1>{}, gt, tc); break;
+            case 2: go(type, std::integral_constant<int, 2>{}, gt, tc); break;
+            case 3: go(type, std::integral_constant<int, 3>{}, gt, tc); break;
+            default: go(type, std::integral_constant<int, 4>{}, gt, tc); break;
+        }
+    };
+    auto with_gate = [&](auto type, auto tc) {
+        if (ga.a.gate)
+            with_ks(type, std::true_type{}, tc);
+        else
+            with_ks(type, std::false_type{}, tc);
+    };
+    if (ga.a.dtype == VARCO_BF16)
+        with_gate(TypeTag<bf16_t>{}, std::integral_constant<int, 1>{});
+    else if (terms == 3)
+        with_gate(TypeTag<float>{}, std::integral_constant<int, 3>{});
+    else
+        with_gate(TypeTag<float>{}, std::integral_constant<int, 2>{});
     return hipGetLastError();
 }
 

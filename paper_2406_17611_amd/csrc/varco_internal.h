@@ -212,6 +212,10 @@ hipError_t varco_launch_gemm_split(const GemmArgs& g, hipStream_t stream, const 
 hipError_t varco_launch_prep_weight_split(int terms, const float* h, int64_t ld, int32_t rows, int32_t cols,
                                           int32_t rows_padded, int32_t pitch, bool transpose, void* out, hipStream_t stream);
 
+// C (+)= A B^T with at most 64 reduction steps on the bf16 matrix units (terms: 1 for bf16 storage, 2 or 3 bf16 terms
+// per fp32 operand); same operand contract as the fp32-instruction kernel of kernels_gemm.hip that it replaces.
+hipError_t varco_launch_gemm_short_k(const GemmArgs& g, int terms, hipStream_t stream);
+
 // Loss and update of a training iteration (kernels_train.hip). row_loss / row_correct: n_rows each; totals
 // (2 floats) may be null.
 hipError_t varco_launch_softmax_xent(int dtype, const void* logits, int64_t ld, const int32_t* labels, int64_t n_rows,

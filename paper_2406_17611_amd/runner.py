@@ -21,7 +21,7 @@ class PartitionedNetwork:
         another; streams are joined wherever a step needs all partitions (layer boundaries, owner-side sums)."""
         assert dtype in ("f32", "bf16")
         assert 1 <= n_streams <= 4
-        self.n_streams = n_streams
+        self.n_streams = self.max_streams = n_streams
         self.dtype = dtype
         self.act_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.device = torch.device(device)
@@ -84,13 +84,18 @@ class PartitionedNetwork:
                 self.ctx.prepare(st)
                 self._prepared.add(handle)
 
+    def use_streams(self, n: int):
+        """Issue the following steps on the first n of the network's streams (1 <= n <= n_streams)."""
+        assert 1 <= n <= self.max_streams
+        self.n_streams = n
+
     def _stream_set(self, stream):
         """The streams a step is issued on: the caller's (or torch's current) stream first, then the extra ones."""
         if self.n_streams == 1:
             return [stream]
         if self._streams is None:
-            self._streams = [torch.cuda.Stream(device=self.device) for _ in range(self.n_streams - 1)]
-        return [stream if stream is not None else torch.cuda.current_stream(self.device)] + self._streams
+            self._streams = [torch.cuda.Stream(device=self.device) for _ in range(self.max_streams - 1)]
+        return [stream if stream is not None else torch.cuda.current_stream(self.device)] + self._streams[:self.n_streams - 1]
 
     @staticmethod
     def _join(streams):
@@ -218,7 +223,7 @@ class PartitionedNetwork:
         # the partitions' weight gradients are summed (Algorithm 1): fold the per-stream accumulators
         if ns > 1:
             with torch.cuda.stream(streams[0]):
-                for extra1, extra0 in zip(self._dh1_extra, self._dh0_extra):
+                for extra1, extra0 in zip(self._dh1_extra[:ns - 1], self._dh0_extra[:ns - 1]):
                     for l in range(self.L):
                         vb.sum_gradients(self.dh1[l], extra1[l], streams[0])
                         extra1[l].zero_()

@@ -144,6 +144,34 @@ __device__ __forceinline__ void load_cols(const OperandDev& op, int32_t i0, int3
     }
 }
 
+// The same block for an operand whose rows are not 8-byte aligned or whose width is not a multiple of 4 (the
+// 47 class columns of the last layer): element loads; columns beyond the matrix repeat its last one, and their
+// products are never stored.
+template <int ROWS>
+__device__ __forceinline__ void load_cols_ragged(const OperandDev& op, int32_t i0, int32_t extent, int32_t k0, int32_t kmax,
+                                                 ColRegs<ROWS, false>& r) {
+    using R = ColRegs<ROWS, false>;
+    r.inside = 0u;
+#pragma unroll
+    for (int h = 0; h < R::N; ++h) {
+        const int b = threadIdx.x + h * kThreads;
+        const bool active = b < R::BLOCKS;
+        const int32_t i = i0 + (b % (ROWS / 4)) * 4;
+        const int32_t kb = k0 + (b / (ROWS / 4)) * 8;
+        int32_t col[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) col[e] = min(i + e, extent - 1);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const bool in = active && kb + kk < kmax;
+            const uint16_t* row = op.ptr + (in ? int64_t(kb + kk) * op.ld : 0);
+            const uint32_t x0 = row[col[0]], x1 = row[col[1]], x2 = row[col[2]], x3 = row[col[3]];
+            r.v[h][kk] = make_uint2(x0 | (x1 << 16), x2 | (x3 << 16));
+            r.inside |= in ? (1u << (h * 8 + kk)) : 0u;
+        }
+    }
+}
+
 template <int ROWS, bool GATE>
 __device__ __forceinline__ void store_cols(const ColRegs<ROWS, GATE>& r, uint16_t* s) {
     using R = ColRegs<ROWS, GATE>;
@@ -181,7 +209,9 @@ struct Stage {
     using Regs = std::conditional_t<TN, ColRegs<ROWS, GATE>, RowRegs<ROWS, CH, GATE>>;
     static __device__ __forceinline__ void load(const OperandDev& op, int32_t i0, int32_t extent, int32_t k0, int32_t kmax,
                                                 Regs& r) {
-        if constexpr (TN)
+        if constexpr (TN && CH == 1)
+            load_cols_ragged<ROWS>(op, i0, extent, k0, kmax, r);
+        else if constexpr (TN)
             load_cols<ROWS, GATE>(op, i0, extent, k0, kmax, r);
         else
             load_rows<ROWS, CH, GATE>(op, i0, extent, k0, kmax, r);
@@ -200,14 +230,16 @@ __device__ __forceinline__ bf16x8 fragment(const uint16_t* s, int row, int koff)
 
 // TN: both operands stored with the output index contiguous (weight gradient), else both with the reduction
 // index contiguous. WM x WN wavefronts, each TMB x TNB blocks of 32 x 32. A_CH: elements per global load of
-// A (NT only; B is the library's own padded weight copy, always 8). GATE masks A (NT) or B (TN).
+// A (NT; B is the library's own padded weight copy, always 8); in a TN product A_CH = 1 says that B is read
+// element by element (unaligned rows, never masked). GATE masks A (NT) or B (TN).
 // TC: bf16_t (activations) or float (weight gradients).
 template <typename TC, bool TN, int WM, int WN, int TMB, int TNB, int A_CH, bool GATE>
 __global__ __launch_bounds__(kThreads, 2) void gemm_bf16_kernel(GemmDev g) {
     constexpr int BM = 32 * TMB * WM, BN = 32 * TNB * WN;
     constexpr bool A_GATE = GATE && !TN, B_GATE = GATE && TN;
-    using StageA = Stage<TN, BM, A_CH, A_GATE>;
-    using StageB = Stage<TN, BN, 8, B_GATE>;
+    static_assert(!(TN && A_CH == 1 && GATE), "an operand read element by element is never masked");
+    using StageA = Stage<TN, BM, TN ? 8 : A_CH, A_GATE>;
+    using StageB = Stage<TN, BN, TN ? A_CH : 8, B_GATE>;
     __shared__ __attribute__((aligned(16))) uint16_t sa[2][BM * kPitch];
     __shared__ __attribute__((aligned(16))) uint16_t sb[2][BN * kPitch];
 
@@ -386,6 +418,13 @@ hipError_t varco_launch_prep_weight(const float* h, int64_t ld, int32_t rows, in
     return hipGetLastError();
 }
 
+namespace {
+// TN: B can be read four columns at a time.
+bool b_vector_ok(const GemmArgs& ga) {
+    return aligned_to(ga.b.ptr, 8) && aligned_to(ga.b.gate, 8) && ga.b.ld % 4 == 0 && ga.n % 4 == 0;
+}
+}  // namespace
+
 bool varco_gemm_bf16_usable(const GemmArgs& ga) {
     if (ga.m <= 0 || ga.n <= 0) return false;
     const bool a_kc = !ga.a.transposed, b_kc = ga.b.transposed;
@@ -401,7 +440,8 @@ bool varco_gemm_bf16_usable(const GemmArgs& ga) {
     }
     // TN: weight gradient
     if (b_kc || ga.b.dtype != VARCO_BF16 || ga.c_dtype != VARCO_F32 || ga.k2 > 0 || ga.a.gate) return false;
-    return ok8(ga.a) && ok8(ga.b) && ga.m % 4 == 0 && ga.n % 4 == 0;
+    if (!ok8(ga.a) || ga.m % 4 != 0) return false;
+    return b_vector_ok(ga) || (ga.n <= 64 && !ga.b.gate && aligned_to(ga.b.ptr, 2));   // else B element by element
 }
 
 hipError_t varco_launch_gemm_bf16(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag, int32_t* split_used) {
@@ -458,7 +498,10 @@ hipError_t varco_launch_gemm_bf16(const GemmArgs& ga, hipStream_t stream, const 
         with_flag(gate, [&](auto gt) {
             constexpr bool NR = decltype(nr)::value, GT = decltype(gt)::value;
             constexpr int WM = NR ? 4 : 2, WN = NR ? 1 : 2, TMB = NR ? 2 : 4, TNB = 2;
-            if (tn) {
+            if (tn && !b_vector_ok(ga)) {
+                if constexpr (NR && !GT)
+                    hipLaunchKernelGGL((gemm_bf16_kernel<float, true, WM, WN, TMB, TNB, 1, false>), grid, dim3(kThreads), 0, stream, g);
+            } else if (tn) {
                 hipLaunchKernelGGL((gemm_bf16_kernel<float, true, WM, WN, TMB, TNB, 8, GT>), grid, dim3(kThreads), 0, stream, g);
             } else if (a8) {
                 hipLaunchKernelGGL((gemm_bf16_kernel<bf16_t, false, WM, WN, TMB, TNB, 8, GT>), grid, dim3(kThreads), 0, stream, g);

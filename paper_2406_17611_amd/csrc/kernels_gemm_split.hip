@@ -233,6 +233,23 @@ __device__ __forceinline__ void load_cols(const float* base, const float* gate, 
     }
 }
 
+// The same block of an operand whose rows are not 16-byte aligned or whose width is not a multiple of 4 (the 47
+// class columns of the last layer): element loads; columns beyond the matrix repeat its last one (their products
+// are never stored), nodes beyond the reduction repeat the last one (the other operand is zero there).
+__device__ __forceinline__ void load_cols_ragged(const float* base, int b, int32_t i0, int32_t extent, uint32_t ld_bytes,
+                                                 int32_t k_left, ColRegs<false>& r) {
+    const int kb = (b & 3) * 8;
+    uint32_t off[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) off[e] = uint32_t(min(i0 + (b >> 2) * 4 + e, extent - 1) - i0) * 4u;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const uint32_t row = uint32_t(min(kb + kk, k_left - 1)) * ld_bytes;
+        r.v[kk] = make_float4(load_at<float>(base, row + off[0]), load_at<float>(base, row + off[1]),
+                              load_at<float>(base, row + off[2]), load_at<float>(base, row + off[3]));
+    }
+}
+
 template <int TERMS, int ROWS, bool GATE>
 __device__ __forceinline__ void store_cols(const ColRegs<GATE>& r, int b, uint16_t* s) {
     // An LDS row holds one output index with its 8 reduction steps contiguous, two steps per 32-bit word: the two
@@ -279,7 +296,8 @@ __device__ __forceinline__ void workgroup_barrier() {
 
 // TN: both operands stored with the output index contiguous (weight gradient), else A with the reduction
 // index contiguous and B an expanded weight copy. WM x WN wavefronts per tile, each TMB x TNB blocks of
-// 32 x 32. A_CH: floats per chunk of A (NT only). GATE masks A (NT) or B (TN).
+// 32 x 32. A_CH: floats per chunk of A (NT); in a TN product A_CH = 1 says that B is read element by element
+// (unaligned rows, never masked). GATE masks A (NT) or B (TN).
 //
 // A workgroup is four wavefronts with one tile and one LDS stage (60 KB), so that two workgroups are resident
 // on a compute unit and each SIMD holds one wavefront of either. On this device the vector ALU and the matrix
@@ -294,6 +312,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
     static_assert(TERMS == 2 || TERMS == 3, "two or three bf16 terms per operand");
     constexpr int BM = 32 * TMB * WM, BN = 32 * TNB * WN;
     static_assert(BM + BN <= kThreads, "one 8 x 4 block per thread in the TN layout");
+    static_assert(!(TN && A_CH == 1 && GATE), "an operand read element by element is never masked");
     __shared__ __attribute__((aligned(16))) uint16_t smem[TERMS * (BM + BN) * kPitch];
     const int tid = threadIdx.x;
     uint16_t* const sa = smem;
@@ -405,14 +424,17 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_split_kernel(SplitGemm g) {
             constexpr bool G = GATE && !A;
             ColRegs<G> cr;
             const int b = A ? tid : tid - BM;
-            const uint32_t col_off = A ? col_offset(b, m0, g.m) : col_offset(b, n0, g.n);
+            constexpr bool RAGGED = !A && A_CH == 1;
+            const uint32_t col_off = RAGGED ? 0u : (A ? col_offset(b, m0, g.m) : col_offset(b, n0, g.n));
             const SplitOperand& op = A ? g.a : g.b;
             const uint32_t ld_bytes = uint32_t(op.ld) * 4u;
             auto fetch_cols = [&](int32_t t) {
                 const int32_t k0 = t * BK, k_left = g.k - k0;
                 const float* base = static_cast<const float*>(op.ptr) + int64_t(k0) * op.ld + (A ? m0 : n0);
                 const float* gbase = G ? op.gate + int64_t(k0) * op.ld + n0 : nullptr;
-                if (k_left >= BK)
+                if constexpr (RAGGED)
+                    load_cols_ragged(base, b, n0, g.n, ld_bytes, k_left, cr);
+                else if (k_left >= BK)
                     load_cols<G, false, A>(base, gbase, b, col_off, ld_bytes, k_left, cr);
                 else
                     load_cols<G, true, A>(base, gbase, b, col_off, ld_bytes, k_left, cr);
@@ -779,6 +801,13 @@ hipError_t varco_launch_gemm_short_k(const GemmArgs& ga, int terms, hipStream_t 
     return hipGetLastError();
 }
 
+namespace {
+// TN: B can be read four columns at a time.
+bool b_vector_ok(const GemmArgs& ga) {
+    return aligned_to(ga.b.ptr, 16) && aligned_to(ga.b.gate, 16) && ga.b.ld % 4 == 0 && ga.n % 4 == 0;
+}
+}  // namespace
+
 bool varco_gemm_split_usable(const GemmArgs& ga) {
     if (ga.f32_terms != 2 && ga.f32_terms != 3) return false;
     if (ga.m <= 0 || ga.n <= 0) return false;
@@ -800,7 +829,8 @@ bool varco_gemm_split_usable(const GemmArgs& ga) {
     }
     // TN: weight gradient
     if (ga.b.transposed || ga.b.dtype != VARCO_F32 || ga.k2 > 0 || ga.a.gate) return false;
-    return ok16(ga.a) && ok16(ga.b) && ga.m % 4 == 0 && ga.n % 4 == 0;
+    if (!ok16(ga.a) || ga.m % 4 != 0) return false;
+    return b_vector_ok(ga) || (ga.n <= 64 && !ga.b.gate && aligned_to(ga.b.ptr, 4));   // else B element by element
 }
 
 hipError_t varco_launch_gemm_split(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag, int32_t* split_used) {
@@ -856,7 +886,10 @@ hipError_t varco_launch_gemm_split(const GemmArgs& ga, hipStream_t stream, const
                 constexpr int T = decltype(t3)::value ? 3 : 2;
                 constexpr bool NR = decltype(nr)::value, GT = decltype(gt)::value;
                 constexpr int WM = NR ? 4 : 2, WN = NR ? 1 : 2, TMB = NR ? 1 : 2, TNB = 2;
-                if (tn) {
+                if (tn && !b_vector_ok(ga)) {
+                    if constexpr (NR && !GT)
+                        hipLaunchKernelGGL((gemm_split_kernel<T, true, WM, WN, TMB, TNB, 1, false>), grid, dim3(kThreads), 0, stream, g);
+                } else if (tn) {
                     hipLaunchKernelGGL((gemm_split_kernel<T, true, WM, WN, TMB, TNB, 4, GT>), grid, dim3(kThreads), 0, stream, g);
                 } else if (a8) {
                     hipLaunchKernelGGL((gemm_split_kernel<T, false, WM, WN, TMB, TNB, 8, GT>), grid, dim3(kThreads), 0, stream, g);

@@ -617,6 +617,52 @@ __device__ __forceinline__ void segsum_body(const SegsumArgs<T>& p, const SpmmIt
     }
 }
 
+// bf16 rows, 8 elements (16 bytes) per lane and load: half as many, twice as wide loads as the 4-element form.
+struct Float8 {
+    float4 lo, hi;
+};
+__device__ __forceinline__ Float8 load8(const bf16_t* p) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    Float8 v;
+    v.lo = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xFFFF0000u), __uint_as_float(u.y << 16),
+                       __uint_as_float(u.y & 0xFFFF0000u));
+    v.hi = make_float4(__uint_as_float(u.z << 16), __uint_as_float(u.z & 0xFFFF0000u), __uint_as_float(u.w << 16),
+                       __uint_as_float(u.w & 0xFFFF0000u));
+    return v;
+}
+__device__ __forceinline__ void add8(Float8& a, const Float8& b) {
+    add_vec(a.lo, b.lo);
+    add_vec(a.hi, b.hi);
+}
+__device__ __forceinline__ void segsum_body8(const SegsumArgs<bf16_t>& p, const SpmmItem& it, int jl, int lpe) {
+    for (int ju = jl; ju < p.ku; ju += lpe) {
+        const bf16_t* src = p.prod + int64_t(it.e0 - p.prod_base) * p.k + ju * 8;
+        Float8 acc;
+        zero_vec(acc.lo), zero_vec(acc.hi);
+        int32_t n = it.e1 - it.e0;
+        for (; n >= 4; n -= 4) {
+            const Float8 v0 = load8(src), v1 = load8(src + p.k), v2 = load8(src + 2 * int64_t(p.k)), v3 = load8(src + 3 * int64_t(p.k));
+            add8(acc, v0), add8(acc, v1), add8(acc, v2), add8(acc, v3);
+            src += 4 * int64_t(p.k);
+        }
+        if (n > 0) {   // up to three rows left: fetched together (rows past the end re-read the first), added in order
+            const Float8 v0 = load8(src), v1 = load8(src + (n > 1 ? p.k : 0)), v2 = load8(src + (n > 2 ? 2 * int64_t(p.k) : 0));
+            add8(acc, v0);
+            if (n > 1) add8(acc, v1);
+            if (n > 2) add8(acc, v2);
+        }
+        if (it.dst < 0) {
+            bf16_t* dst = p.out + int64_t(it.row - p.row_base) * p.k + ju * 8;
+            Elem<bf16_t>::store4(dst, acc.lo);
+            Elem<bf16_t>::store4(dst + 4, acc.hi);
+        } else {
+            float* dst = p.partial + int64_t(it.dst) * p.k + ju * 8;
+            *reinterpret_cast<float4*>(dst) = acc.lo;
+            *reinterpret_cast<float4*>(dst + 4) = acc.hi;
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void halo_segsum_kernel(SegsumArgs<T> p) {
     const int lpe = 1 << p.lpe_log2;
@@ -624,6 +670,12 @@ __global__ __launch_bounds__(kBlock) void halo_segsum_kernel(SegsumArgs<T> p) {
     if (gidx >= p.n_items) return;
     const SpmmItem it = p.items[gidx];
     const int jl = threadIdx.x & (lpe - 1);
+    if constexpr (std::is_same_v<T, bf16_t>) {
+        if (p.ev == 8) {
+            segsum_body8(p, it, jl, lpe);
+            return;
+        }
+    }
     if (p.ev == 4)
         segsum_body<T, 4>(p, it, jl, lpe);
     else if (p.ev == 2)
@@ -910,7 +962,12 @@ hipError_t halo_grad_t(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, co
     b.row_base = row_base;
     b.partial = partial;
     b.ev = ev, b.ku = ku, b.lpe_log2 = lpe_log2;
-    const int64_t threads = int64_t(t_halo_plan.n_items) << lpe_log2;
+    if (std::is_same_v<T, bf16_t> && rule.k % 8 == 0 && aligned_to(prod, 16) && aligned_to(out, 16) && aligned_to(partial, 16)) {
+        b.ev = 8, b.ku = int(rule.k) / 8;      // the sums read 16 bytes per lane (the products above are written 4 elements at a time)
+        b.lpe_log2 = 0;
+        while ((1 << b.lpe_log2) < b.ku && b.lpe_log2 < 6) ++b.lpe_log2;
+    }
+    const int64_t threads = int64_t(t_halo_plan.n_items) << b.lpe_log2;
     sum_tag.begin(stream);
     hipLaunchKernelGGL(halo_segsum_kernel<T>, dim3(unsigned((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, b);
     sum_tag.end(stream);

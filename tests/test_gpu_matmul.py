@@ -106,6 +106,37 @@ def test_input_gradient_short_reduction(first_row, dtype):
         assert_close(gout.float().cpu().numpy(), ref, f"G0 + dZ H^T from row {first_row}", tol)
 
 
+@pytest.mark.parametrize("mode", ["f32x3", "f32x2", "bf16"])
+@pytest.mark.parametrize("fo", [47, 3, 1, 62])
+@pytest.mark.parametrize("first_row", [0, 1])
+def test_weight_gradient_of_unaligned_columns(first_row, fo, mode):
+    """Y^T dZ where dZ has a width that is no multiple of 4 and no activation mask (the class logits of the last
+    layer): its rows are not aligned, and the range may start at any row of a larger tensor. The reduction over
+    the rows spans several tiles, a ragged last tile and several workgroups."""
+    from oracle.rounding import round_bf16
+    n, fi = 2333, 256
+    rng = np.random.default_rng(300 + fo + first_row)
+    bf16 = mode == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    rnd = (lambda a: round_bf16(a).astype(np.float32)) if bf16 else (lambda a: a.astype(np.float32))
+    y = rnd(rng.standard_normal((n, fi)) * np.exp2(rng.integers(-4, 5, size=(n, fi))))
+    dz_all = rnd(rng.standard_normal((n + first_row, fo)) / n)
+    ctx = vb.Context([fi, fo], [vb.ACT_IDENTITY], vb.CONV_GCN, 1, KEY, vb.BF16 if bf16 else vb.F32)
+    if not bf16:
+        ctx.set_matmul_terms(3 if mode == "f32x3" else 2)
+    g = synth.small_random_graph(n, 3.0, "gcn", seed=5)
+    host = vb.partition_build(g.n, g.rowptr, g.colidx, g.vals, np.zeros(g.n, dtype=np.int32), 1)
+    ctx.register_partition(0, host[0])
+    ctx.prepare()
+    dh0 = rng.standard_normal((fi, fo)).astype(np.float32)
+    dh = dev(dh0)
+    ctx.transform_bwd_weight(0, dev(y, tdt), dev(dz_all, tdt)[first_row:], None, dh)      # adds to dh
+    torch.cuda.synchronize()
+    ref = dh0.astype(np.float64) + y.astype(np.float64).T @ dz_all[first_row:].astype(np.float64)
+    tol = 2.0 ** -14 if mode == "f32x2" else 8 * 2.0 ** -24 * np.sqrt(n)
+    assert_close(dh.cpu().numpy(), ref, f"dH0 + Y^T dZ, {fo} columns from row {first_row}", tol)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_weights_changed_between_steps_are_seen(dtype):
     """The library may keep converted copies of the weights during a step; after an in-place update and the

@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--matmul-terms", type=int, default=None, choices=[0, 2, 3],
                     help="fp32 storage only: form of the dense products (library default 3; 0 = fp32 matrix instructions; "
                          "2 = lower precision, not a valid headline setting)")
+    ap.add_argument("--transform-first", action="store_true",
+                    help="bf16 storage only: the last layer applies its weights before the aggregation "
+                         "(varco_set_layer_order); for comparing the two orders of eq. (2), not the headline setting")
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a HIP graph (no per-launch host work; per-kernel timing is not available)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -156,7 +159,8 @@ def main():
         f"boundary rows {sum(h.n_boundary for h in host)}")
     t0 = time.time()
     L = len(w.widths) - 1
-    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY, dtype=w.dtype, n_streams=args.streams)
+    net = PartitionedNetwork(host, w.widths, w.conv, synth.MASK_KEY, dtype=w.dtype, n_streams=args.streams,
+                             transform_first=(L - 1,) if args.transform_first else ())
     if args.matmul_terms is not None:
         net.ctx.set_matmul_terms(args.matmul_terms)
     net.set_inputs(synth.features(g.n, w.widths[0], synth.SEED_FEAT))
@@ -273,7 +277,7 @@ def main():
         "config": {"workload": w.name, "nodes": g.n, "directed_entries": g.nnz, "partitions": w.n_parts,
                    "conv": w.conv, "widths": list(w.widths), "ratio": f"{ratio[0]}/{ratio[1]}",
                    "keep": [net.ctx.keep(l) for l in range(L)], "layers": L, "streams": args.streams,
-                   "hip_graph": bool(args.graph),
+                   "hip_graph": bool(args.graph), "transform_first_layers": [L - 1] if args.transform_first else [],
                    "timed": f"{args.streams} stream{'s' if args.streams > 1 else ''}, " +
                             ("HIP graph replay" if args.graph else "eager launches") + ", no per-launch events; "
                             "per-kernel figures from a separate pass on one stream with HIP events around every launch",

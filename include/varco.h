@@ -59,6 +59,8 @@ enum {
 
 enum { VARCO_CONV_GCN = 0 /* single tap S */, VARCO_CONV_SAGE = 1 /* taps I (H0) and S (H1) */ };
 enum { VARCO_ACT_IDENTITY = 0, VARCO_ACT_RELU = 1 };
+/* Order of the two products of eq. (2) inside a layer call; see varco_set_layer_order. */
+enum { VARCO_ORDER_AGGREGATE_FIRST = 0 /* (S X) H */, VARCO_ORDER_TRANSFORM_FIRST = 1 /* S (X H) */ };
 enum { VARCO_F32 = 0, VARCO_BF16 = 1 /* activations and gradients stored as bf16, arithmetic in fp32 */ };
 
 #define VARCO_MAX_LAYERS 16
@@ -221,6 +223,21 @@ int32_t varco_compress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const
 int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t* gids, const int32_t* rows,
                          int64_t n_rows, const void* z, void* x, int64_t ldx, int32_t accumulate,
                          varco_stream stream);
+
+/* Order in which varco_layer_fwd / varco_layer_bwd of `layer` form the product S X H of eq. (2). The two orders are
+ * the same layer (the products associate); they differ in cost. VARCO_ORDER_AGGREGATE_FIRST (default) aggregates
+ * rows of width[layer] elements - the halo rows in compressed form, k elements each - and transforms the n_local
+ * sums. VARCO_ORDER_TRANSFORM_FIRST transforms every source row first - the local rows, and each halo row once from
+ * its k received elements (the exchange is the same compressed one) - and aggregates rows of width[layer+1]
+ * elements; the errors handed back are formed per halo row from the transposed aggregate, without a buffer of
+ * per-entry products. It pays for a narrowing layer whose halo rows are referred to often or kept nearly whole
+ * (k close to width[layer]); at high compression the default order moves fewer bytes.
+ * Supported for bf16 storage, an identity activation, width[layer+1] <= 64 and width[layer] a multiple of 16, at most 512 (the
+ * class-logit layer), else VARCO_ERR_UNSUPPORTED. A set-up call like varco_set_ratio: it may allocate and synchronise,
+ * and VARCO_ERR_STATE once the layer ran forward in the current step. In this order the forward call does not
+ * write m_saved (it may be NULL), and the backward call takes, as its m_saved argument, the z_in the forward call
+ * was given, still holding the same rows. */
+int32_t varco_set_layer_order(varco_ctx* ctx, int32_t layer, int32_t order);
 
 /* Forward of layer `layer` on partition q (Algorithm 1's forward pass: local nodes contribute their
  * activations as they are, nodes of other partitions their compressed ones):

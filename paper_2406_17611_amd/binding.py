@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libvarco.so")
 OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP = range(6)
 CONV_GCN, CONV_SAGE = 0, 1
 ACT_IDENTITY, ACT_RELU = 0, 1
+ORDER_AGGREGATE_FIRST, ORDER_TRANSFORM_FIRST = 0, 1
 F32 = 0
 BF16 = 1
 MAX_LAYERS = 16
@@ -24,7 +25,7 @@ MAX_LAYERS = 16
 EXPORTS = [
     "varco_partition_build", "varco_partition_view", "varco_partition_free",
     "varco_create", "varco_destroy", "varco_register_partition", "varco_prepare", "varco_last_error",
-    "varco_begin_step", "varco_set_ratio", "varco_set_matmul_terms", "varco_get_keep",
+    "varco_begin_step", "varco_set_ratio", "varco_set_matmul_terms", "varco_set_layer_order", "varco_get_keep",
     "varco_compress", "varco_decompress", "varco_layer_fwd", "varco_layer_bwd",
     "varco_accumulate_returned", "varco_get_stats", "varco_reset_stats", "varco_profile_enable", "varco_profile_read",
     "varco_calibration_copy", "varco_sum_gradients", "varco_softmax_xent", "varco_sgd_step", "varco_schedule_ratio",
@@ -92,6 +93,7 @@ def lib() -> C.CDLL:
         L.varco_last_error.restype = C.c_char_p
         L.varco_begin_step.argtypes = [vp, u64]
         L.varco_set_matmul_terms.argtypes = [vp, C.c_int32]
+        L.varco_set_layer_order.argtypes = [vp, i32, i32]
         L.varco_set_ratio.argtypes = [vp, i32, u32, u32]
         L.varco_get_keep.argtypes = [vp, i32, C.POINTER(i32)]
         L.varco_compress.argtypes = [vp, i32, vp, vp, i64, vp, i64, vp, vp]
@@ -304,6 +306,9 @@ class Context:
 
     def set_matmul_terms(self, terms: int):
         _check(lib().varco_set_matmul_terms(self._h, terms), self._h)
+
+    def set_layer_order(self, layer: int, order: int):
+        _check(lib().varco_set_layer_order(self._h, layer, order), self._h)
 
     def set_ratio(self, layer: int, num: int, den: int = 1):
         _check(lib().varco_set_ratio(self._h, layer, num, den), self._h)

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvarco.so")
-SOURCES = ["varco_api.hip", "kernels_compress.hip", "kernels_spmm.hip", "kernels_gemm.hip", "kernels_gemm_bf16.hip", "kernels_gemm_split.hip", "kernels_train.hip", "partition_builder.cpp"]
+SOURCES = ["varco_api.hip", "kernels_compress.hip", "kernels_spmm.hip", "kernels_gemm.hip", "kernels_gemm_bf16.hip", "kernels_gemm_split.hip", "kernels_halo_transform.hip", "kernels_train.hip", "partition_builder.cpp"]
 # -packed-fp32-ops is switched off for every device compilation of this library (packed fp32 forms have
 # produced wrong values on the target boxes); the host pass does not know the feature and says so.
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",

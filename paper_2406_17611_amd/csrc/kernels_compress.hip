@@ -183,6 +183,21 @@ unsigned grid_for(int64_t n_rows, int g_log2) {
     return unsigned(blocks);
 }
 
+// Per halo row: its position rule (element j sits at position (a j + b) mod width) and its row in the compressed
+// buffer, for the kernels that transform halo rows from their received elements.
+__global__ __launch_bounds__(kBlock) void halo_rows_kernel(MaskRule rule, const int32_t* __restrict__ gids,
+                                                           const int32_t* __restrict__ zrow, int32_t n,
+                                                           uint2* __restrict__ out) {
+    const int32_t s = blockIdx.x * kBlock + threadIdx.x;
+    if (s >= n) return;
+    uint32_t ab = 1u << 16;                       // every element kept: position c holds element c
+    if (rule.k < rule.width) {
+        const MaskAffine m = varco_affine(rule, uint32_t(gids[s]));
+        ab = (m.a << 16) | m.b;
+    }
+    out[s] = make_uint2(ab, uint32_t(zrow[s]));
+}
+
 template <typename T>
 hipError_t launch_compress_t(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows, const void* x,
                              int64_t ldx, void* z, hipStream_t stream) {
@@ -269,6 +284,14 @@ hipError_t varco_launch_accumulate_returned(int dtype, const MaskRule& rule, con
                              : launch_accumulate_t<float>(rule, gids, rows, n_rows, ptr, src, returned, x, ldx, stream);
     tag.end(stream);
     return e;
+}
+
+hipError_t varco_launch_halo_rows(const MaskRule& rule, const int32_t* gids, const int32_t* zrow, int32_t n, uint2* out,
+                                  hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(halo_rows_kernel, dim3(unsigned((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, rule, gids, zrow,
+                       n, out);
+    return hipGetLastError();
 }
 
 hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream) {

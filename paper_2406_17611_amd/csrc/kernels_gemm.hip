@@ -509,6 +509,17 @@ hipError_t launch_reduce(const GemmArgs& ga, int32_t split, hipStream_t stream, 
 
 }  // namespace
 
+hipError_t varco_launch_gemm_reduce(const float* partial, int32_t slabs, int32_t m, int32_t n, float* c, int64_t ldc,
+                                    bool accumulate, hipStream_t stream, const LaunchTag& tag) {
+    if (slabs <= 0 || m <= 0 || n <= 0) return hipSuccess;
+    GemmArgs ga;
+    ga.m = m, ga.n = n;
+    ga.partial = const_cast<float*>(partial);
+    ga.c = c, ga.ldc = ldc, ga.c_dtype = VARCO_F32;
+    ga.accumulate = accumulate;
+    return launch_reduce(ga, slabs, stream, tag);
+}
+
 hipError_t varco_launch_gemm(const GemmArgs& ga, hipStream_t stream, const LaunchTag& tag) {
     if (ga.m == 0 || ga.n == 0) return hipSuccess;
     if (small_k_usable(ga)) {

@@ -29,6 +29,7 @@ struct LayerState {
     uint16_t* units = nullptr;       // device
     uint16_t* units_inv = nullptr;   // device
     bool ran_forward = false;        // in the current step
+    int32_t order = VARCO_ORDER_AGGREGATE_FIRST;
 };
 
 struct PartState {
@@ -54,6 +55,8 @@ struct Workspace {
     float* gemm = nullptr;      size_t gemm_elems = 0;      // split-K partial products
     float* prod = nullptr;      size_t prod_elems = 0;      // halo-gradient products: (halo entries) x k elements
     float* w = nullptr;         size_t w_elems = 0;         // converted copies of the weights, one slot per (layer, weight, orientation)
+    float* tf = nullptr;        size_t tf_elems = 0;        // transform-first layers: [Y_loc ; Y_halo], (n_local + n_halo) x width[l+1]
+    float* hrows = nullptr;     size_t hrows_elems = 0;     // and one record (two words) per halo row
     struct WeightTag {          // what a slot holds: made from `h` during step epoch `epoch` in the form `terms`
         const void* h = nullptr;
         uint64_t epoch = 0;
@@ -338,6 +341,19 @@ size_t prod_need(const varco_ctx* ctx) {
     return (size_t(entries) * size_t(k) * size_t(ctx->elem_bytes()) + 3) / 4;
 }
 
+// Floats of the two buffers of the layers that transform first: transformed rows of the local and halo nodes of the
+// largest registered partition at the widest such layer's output, and a two-word record per halo row.
+void transform_first_need(const varco_ctx* ctx, size_t* rows_out, size_t* records_out) {
+    int32_t fo = 0;
+    for (int32_t l = 0; l < ctx->n_layers; ++l)
+        if (ctx->layers[l].order == VARCO_ORDER_TRANSFORM_FIRST) fo = std::max(fo, ctx->widths[l + 1]);
+    int64_t rows = 0, halo = 0;
+    for (const PartState& ps : ctx->parts)
+        if (ps.registered) rows = std::max(rows, int64_t(ps.d.n_local) + ps.d.n_halo), halo = std::max<int64_t>(halo, ps.d.n_halo);
+    *rows_out = fo ? (size_t(rows) * size_t(fo) * size_t(ctx->elem_bytes()) + 3) / 4 : 0;
+    *records_out = fo ? size_t(halo) * 2 : 0;
+}
+
 // Brings one workspace set up to what the registered partitions and the current ratios need (host side of
 // varco_prepare, varco_set_ratio and varco_register_partition: may synchronise the device).
 int32_t size_workspace(varco_ctx* ctx, Workspace& ws) {
@@ -347,6 +363,10 @@ int32_t size_workspace(varco_ctx* ctx, Workspace& ws) {
     VARCO_HIP(ctx, grow(ws.w, ws.w_elems, ctx->need_w));
     const size_t prod = prod_need(ctx);
     if (prod > ws.prod_elems) VARCO_HIP(ctx, grow(ws.prod, ws.prod_elems, prod + prod / 4));   // head-room: schedules raise k step by step
+    size_t tf_rows = 0, tf_records = 0;
+    transform_first_need(ctx, &tf_rows, &tf_records);
+    VARCO_HIP(ctx, grow(ws.tf, ws.tf_elems, tf_rows));
+    VARCO_HIP(ctx, grow(ws.hrows, ws.hrows_elems, tf_records));
     if (ws.w_tags.empty()) ws.w_tags.resize(size_t(ctx->n_layers) * 4);
     return VARCO_OK;
 }
@@ -510,7 +530,7 @@ extern "C" int32_t varco_destroy(varco_ctx* ctx) {
     }
     for (PartState& ps : ctx->parts) free_part(ps);
     for (Workspace& w : ctx->ws)
-        for (float* p : {w.dm, w.spmm, w.gemm, w.prod, w.w})
+        for (float* p : {w.dm, w.spmm, w.gemm, w.prod, w.w, w.tf, w.hrows})
             if (p) (void)hipFree(p);
     if (ctx->d_flags) (void)hipFree(ctx->d_flags);
     if (ctx->d_step) (void)hipFree(ctx->d_step);
@@ -722,6 +742,23 @@ extern "C" int32_t varco_set_matmul_terms(varco_ctx* ctx, int32_t terms) {
     return VARCO_OK;
 }
 
+extern "C" int32_t varco_set_layer_order(varco_ctx* ctx, int32_t layer, int32_t order) {
+    if (int32_t rc = check_layer(ctx, layer, "varco_set_layer_order")) return rc;
+    if (order != VARCO_ORDER_AGGREGATE_FIRST && order != VARCO_ORDER_TRANSFORM_FIRST)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_layer_order: unknown order");
+    if (ctx->layers[layer].ran_forward)
+        return varco_fail(ctx, VARCO_ERR_STATE, "varco_set_layer_order: the layer already ran forward in this step; call varco_begin_step first");
+    if (order == VARCO_ORDER_TRANSFORM_FIRST) {
+        const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1];
+        if (ctx->dtype != VARCO_BF16 || ctx->act[layer] != VARCO_ACT_IDENTITY || fo > 64 || fi % 16 != 0 || fi > 512)
+            return varco_fail(ctx, VARCO_ERR_UNSUPPORTED,
+                              "varco_set_layer_order: transform-first needs bf16 storage, an identity activation, at most 64 "
+                              "output columns and an input width that is a multiple of 16 and at most 512");
+    }
+    ctx->layers[layer].order = order;
+    return size_all_workspaces(ctx);
+}
+
 extern "C" int32_t varco_set_ratio(varco_ctx* ctx, int32_t layer, uint32_t num, uint32_t den) {
     if (!ctx) return varco_fail(nullptr, VARCO_ERR_INVALID_ARG, "varco_set_ratio: null context");
     if (layer < -1 || layer >= ctx->n_layers) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_set_ratio: layer out of range");
@@ -786,6 +823,170 @@ extern "C" int32_t varco_decompress(varco_ctx* ctx, int32_t layer, const int32_t
     return VARCO_OK;
 }
 
+namespace {
+
+HaloTransform halo_transform(const varco_partition_desc& d, const MaskRule& rule, const void* z, const Workspace& ws, int32_t fo) {
+    HaloTransform h;
+    h.z = z;
+    h.rec = reinterpret_cast<const uint2*>(ws.hrows);
+    h.n = d.n_halo;
+    h.width = rule.width, h.k = rule.k, h.width_magic = rule.width_magic;
+    h.fo = fo;
+    return h;
+}
+
+int32_t transform_first_fits(varco_ctx* ctx, const PartState& ps, const Workspace& ws, int32_t fo, const char* fn) {
+    const size_t rows = (size_t(int64_t(ps.d.n_local) + ps.d.n_halo) * size_t(fo) * size_t(ctx->elem_bytes()) + 3) / 4;
+    if (rows <= ws.tf_elems && size_t(ps.d.n_halo) * 2 <= ws.hrows_elems) return VARCO_OK;
+    std::string m = std::string(fn) + ": the stream's workspace is too small; call varco_prepare";
+    return varco_fail(ctx, VARCO_ERR_STATE, m.c_str());
+}
+
+// Split of a weight-gradient product's reduction that the stream's partial buffer holds.
+int32_t wgrad_split(const Workspace& ws, const GemmArgs& g, int64_t rows) {
+    int64_t split = gemm_split_for(g.m, g.n, rows, gemm_kind(g));
+    const int64_t fit = int64_t(ws.gemm_elems / (size_t(g.m) * size_t(g.n)));
+    return int32_t(std::max<int64_t>(1, std::min(split, fit)));
+}
+
+// The layer of eq. (2) with the transform applied before the aggregation, x_out = S_q [X_loc H1 ; X~_halo H1] (+ X_loc H0):
+// every source row is transformed once - a halo row from its k received elements - and rows of width[layer+1]
+// elements are aggregated.
+int32_t layer_fwd_transform_first(varco_ctx* ctx, const PartState& ps, Workspace& ws, int32_t layer, const MaskRule& rule,
+                                  const void* x_local, const void* z_in, const void* h1, const void* h0, void* x_out,
+                                  hipStream_t st) {
+    const varco_partition_desc& d = ps.d;
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1], nl = d.n_local, nh = d.n_halo;
+    const int dt = ctx->dtype;
+    const double es = ctx->elem_bytes();
+    if (nl == 0) return VARCO_OK;
+    if (int32_t rc = transform_first_fits(ctx, ps, ws, fo, "varco_layer_fwd")) return rc;
+    char* const y_all = reinterpret_cast<char*>(ws.tf);
+    GemmArgs g;
+    g.m = nl, g.n = fo, g.k = fi;
+    g.a.ptr = x_local, g.a.ld = fi, g.a.dtype = dt;
+    g.b.ptr = h1, g.b.ld = fo;
+    g.c = y_all, g.ldc = fo, g.c_dtype = dt;
+    VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h1, fi, fo, true, 0, false, st, g));
+    VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * nl * double(fo) * fi)));
+    if (nh > 0) {   // k = 0 (no communication): rows of zeros
+        ctx->prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
+        VARCO_HIP(ctx, varco_launch_halo_rows(rule, d.halo_gid, d.halo_zrow, nh, reinterpret_cast<uint2*>(ws.hrows), st));
+        // rows of z once, the transformed rows once; the weights stay on chip
+        const LaunchTag tag = ctx->tag(VARCO_K_GEMM_FWD, double(nh) * (rule.k + fo) * es + 8.0 * nh, 2.0 * nh * double(fo) * rule.k);
+        tag.begin(st);
+        const hipError_t e = varco_launch_halo_transform_fwd(halo_transform(d, rule, z_in, ws, fo), g.b_prep, int32_t(g.b_prep_ld),
+                                                             y_all + size_t(nl) * fo * size_t(es), st);
+        tag.end(st);
+        VARCO_HIP(ctx, e);
+    }
+    // entries, row pointer, the transformed rows once, the output once
+    const double agg_bytes = double(d.nnz) * 8.0 + (double(nl) + 1.0) * 4.0 + (2.0 * double(nl) + nh) * fo * es;
+    const double agg_stream = double(d.nnz) * 8.0 + (double(nl) + 1.0) * 4.0 + (double(nl) + double(d.nnz)) * fo * es;
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.fwd, nullptr, d.colidx, d.vals, y_all, nullptr, 0, full_rule(fo), x_out, 0, ws.spmm, st,
+                                     ctx->tag(VARCO_K_AGG_FWD, agg_bytes, 0, agg_stream)));
+    if (ctx->conv == VARCO_CONV_SAGE) {   // self tap
+        GemmArgs g0;
+        g0.m = nl, g0.n = fo, g0.k = fi;
+        g0.a.ptr = x_local, g0.a.ld = fi, g0.a.dtype = dt;
+        g0.b.ptr = h0, g0.b.ld = fo;
+        g0.c = x_out, g0.ldc = fo, g0.c_dtype = dt;
+        g0.accumulate = true;
+        VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h0, fi, fo, true, 1, false, st, g0));
+        VARCO_HIP(ctx, varco_launch_gemm(g0, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * nl * double(fo) * fi)));
+    }
+    return VARCO_OK;
+}
+
+// Its gradient: [dY_loc ; dY_halo] = S_q^T dZ at width[layer+1]; dH1 += X_loc^T dY_loc + X~_halo^T dY_halo;
+// dX_loc = dY_loc H1^T; the errors handed back are dY_halo H1^T at each halo row's kept positions. z_in: the compressed
+// rows the forward call read.
+int32_t layer_bwd_transform_first(varco_ctx* ctx, const PartState& ps, Workspace& ws, int32_t layer, const void* dz,
+                                  const void* x_local, const void* z_in, const void* h1, const void* h0, void* dh1, void* dh0,
+                                  void* dx_local, void* dz_halo, hipStream_t st) {
+    const varco_partition_desc& d = ps.d;
+    const int32_t fi = ctx->widths[layer], fo = ctx->widths[layer + 1], nl = d.n_local, nh = d.n_halo;
+    const int dt = ctx->dtype;
+    const double es = ctx->elem_bytes();
+    const bool sage = ctx->conv == VARCO_CONV_SAGE;
+    const MaskRule rule = make_rule(ctx, layer);
+    const bool halo = nh > 0 && rule.k > 0;
+    if (halo && !z_in)
+        return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: a transform-first layer takes the forward call's z_in as m_saved");
+    if (int32_t rc = transform_first_fits(ctx, ps, ws, fo, "varco_layer_bwd")) return rc;
+    char* const dy_all = reinterpret_cast<char*>(ws.tf);
+    char* const dy_halo = dy_all + size_t(nl) * fo * size_t(es);
+    const MaskRule narrow = full_rule(fo);
+    const double tl_bytes = double(ps.nnz_t_local) * 8.0 + (double(nl) + 1.0) * 4.0 + 2.0 * double(nl) * fo * es;
+    const double tl_stream = tl_bytes + (double(ps.nnz_t_local) - double(nl)) * fo * es;
+    VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_local, nullptr, d.t_colidx, d.t_vals, dz, nullptr, 0, narrow, dy_all, 0, ws.spmm, st,
+                                     ctx->tag(VARCO_K_AGG_BWD_LOCAL, tl_bytes, 0, tl_stream)));
+    if (halo) {
+        const double th_bytes = double(d.nnz - ps.nnz_t_local) * 8.0 + (double(nh) + 1.0) * 4.0 + (double(nl) + nh) * fo * es;
+        VARCO_HIP(ctx, varco_launch_spmm(dt, ps.t_halo, nullptr, d.t_colidx, d.t_vals, dz, nullptr, 0, narrow, dy_halo, nl, ws.spmm,
+                                         st, ctx->tag(VARCO_K_AGG_BWD_HALO, th_bytes, 0)));
+        ctx->prof.interrupt();   // an untimed launch: the next bracketed launch records a start event of its own
+        VARCO_HIP(ctx, varco_launch_halo_rows(rule, d.halo_gid, d.halo_zrow, nh, reinterpret_cast<uint2*>(ws.hrows), st));
+    }
+    // weight gradients
+    {
+        GemmArgs g;
+        g.m = fi, g.n = fo, g.k = nl;
+        g.a.ptr = x_local, g.a.ld = fi, g.a.transposed = true, g.a.dtype = dt;
+        g.b.ptr = dy_all, g.b.ld = fo, g.b.dtype = dt;
+        g.c = dh1, g.ldc = fo;
+        g.accumulate = true;
+        g.partial = ws.gemm;
+        g.split_k = wgrad_split(ws, g, nl);
+        VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl))));
+        if (sage) {
+            g.b.ptr = dz, g.c = dh0;
+            g.split_k = wgrad_split(ws, g, nl);
+            VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_WGRAD, 0, 2.0 * fi * fo * double(nl))));
+        }
+        if (halo) {   // + X~_halo^T dY_halo: per-workgroup shares, then the fixed-order sum
+            const LaunchTag tag = ctx->tag(VARCO_K_GEMM_WGRAD, double(nh) * (rule.k + fo) * es + 8.0 * nh,
+                                           2.0 * double(rule.k) * fo * double(nh));
+            int32_t slabs = 0;
+            tag.begin(st);
+            const hipError_t e = varco_launch_halo_transform_wgrad(halo_transform(d, rule, z_in, ws, fo), dy_halo, ws.gemm,
+                                                                   int64_t(ws.gemm_elems), &slabs, st);
+            tag.end(st);
+            VARCO_HIP(ctx, e);
+            VARCO_HIP(ctx, varco_launch_gemm_reduce(ws.gemm, slabs, fi, fo, static_cast<float*>(dh1), fo, true, st, tag));
+        }
+    }
+    if (!dx_local) return VARCO_OK;
+    {   // dX_loc = dY_loc H1^T (+ dZ H0^T)
+        GemmArgs g;
+        g.m = nl, g.n = fi, g.k = fo;
+        g.a.ptr = dy_all, g.a.ld = fo, g.a.dtype = dt;
+        g.b.ptr = h1, g.b.ld = fo, g.b.transposed = true;
+        g.c = dx_local, g.ldc = fi, g.c_dtype = dt;
+        VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
+        if (sage) {
+            g.a.ptr = dz, g.b.ptr = h0, g.accumulate = true;
+            VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_DGRAD, 0, 2.0 * fi * fo * double(nl))));
+        }
+        if (halo) {   // dY_halo H1^T at the kept positions only, straight into compressed form
+            GemmArgs gw;              // (carries the slot of the weights' bf16 copy [position][column])
+            VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h1, fi, fo, false, 0, false, st, gw));
+            const LaunchTag tag = ctx->tag(VARCO_K_GEMM_DGRAD, double(nh) * (rule.k + fo) * es + 8.0 * nh,
+                                           2.0 * double(rule.k) * fo * double(nh));
+            tag.begin(st);
+            const hipError_t e = varco_launch_halo_transform_bwd(halo_transform(d, rule, z_in, ws, fo), dy_halo, gw.b_prep,
+                                                                 int32_t(gw.b_prep_ld), dz_halo, st);
+            tag.end(st);
+            VARCO_HIP(ctx, e);
+            ctx->stats.bwd_elems[layer] += int64_t(nh) * rule.k;
+            ctx->stats.full_bwd_elems[layer] += int64_t(nh) * fi;
+        }
+    }
+    return VARCO_OK;
+}
+
+}  // namespace
+
 extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_local, const void* z_in,
                                    const void* h1, const void* h0, void* x_out, void* z_out, void* m_saved,
                                    varco_stream stream) {
@@ -795,7 +996,8 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const PartState& ps = ctx->parts[q];
     const varco_partition_desc& d = ps.d;
     const bool sage = ctx->conv == VARCO_CONV_SAGE;
-    if (!h1 || (d.n_local > 0 && (!x_local || !x_out || !m_saved)))
+    const bool transform_first = ctx->layers[layer].order == VARCO_ORDER_TRANSFORM_FIRST;
+    if (!h1 || (d.n_local > 0 && (!x_local || !x_out || (!m_saved && !transform_first))))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: null pointer");
     if (sage && !h0) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: h0 is required for the SAGE convolution");
     if (!sage && h0) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_fwd: h0 must be null for the single-tap convolution");
@@ -812,9 +1014,12 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const MaskRule rule = make_rule(ctx, layer);
     ctx->layers[layer].ran_forward = true;
 
-    // aggregate: local rows dense, halo rows straight from the owners' compressed buffers
     const int dt = ctx->dtype;
     const double es = ctx->elem_bytes();
+    if (transform_first) {
+        if (int32_t rc = layer_fwd_transform_first(ctx, ps, ws, layer, rule, x_local, z_in, h1, h0, x_out, st)) return rc;
+    } else {
+    // aggregate: local rows dense, halo rows straight from the owners' compressed buffers
     const double agg_bytes = double(d.nnz) * 8.0 + (double(d.n_local) + 1.0) * 4.0 + 2.0 * double(d.n_local) * fi * es +
                              double(d.n_halo) * rule.k * es;
     // the same without any cache between the entries of different rows: one source row fetched per entry
@@ -839,6 +1044,7 @@ extern "C" int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, con
         if (sage) VARCO_HIP(ctx, prep_weight(ctx, ws, layer, h0, fi, fo, true, 1, true, st, g));
     }
     VARCO_HIP(ctx, varco_launch_gemm(g, st, ctx->tag(VARCO_K_GEMM_FWD, 0, 2.0 * g.m * g.n * (double(g.k) + g.k2))));
+    }
     // boundary rows of the output, compressed for the next layer's exchange
     if (z_out && d.n_boundary > 0 && ctx->layers[layer + 1].k > 0) {
         ctx->layers[layer + 1].ran_forward = true;   // its positions are now in use
@@ -861,7 +1067,8 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     const PartState& ps = ctx->parts[q];
     const varco_partition_desc& d = ps.d;
     const bool sage = ctx->conv == VARCO_CONV_SAGE;
-    if (!h1 || !dh1 || (d.n_local > 0 && (!dx_out || !x_out || !x_local || !m_saved)))
+    const bool transform_first = ctx->layers[layer].order == VARCO_ORDER_TRANSFORM_FIRST;
+    if (!h1 || !dh1 || (d.n_local > 0 && (!dx_out || !x_out || !x_local || (!m_saved && !transform_first))))
         return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: null pointer");
     if (sage && (!h0 || !dh0)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: h0 and dh0 are required for the SAGE convolution");
     if (!sage && (h0 || dh0)) return varco_fail(ctx, VARCO_ERR_INVALID_ARG, "varco_layer_bwd: h0 and dh0 must be null for the single-tap convolution");
@@ -879,6 +1086,8 @@ extern "C" int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, con
     Workspace* wsp = nullptr;
     if (int32_t rc = workspace_for(ctx, st, &wsp, "varco_layer_bwd")) return rc;
     Workspace& ws = *wsp;
+    if (transform_first)
+        return layer_bwd_transform_first(ctx, ps, ws, layer, dx_out, x_local, m_saved, h1, h0, dh1, dh0, dx_local, dz_halo, st);
 
     // weight gradients: reductions over the partition's rows, split over workgroups
     {

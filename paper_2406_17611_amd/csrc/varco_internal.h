@@ -122,6 +122,11 @@ hipError_t varco_launch_accumulate_returned(int dtype, const MaskRule& rule, con
 hipError_t varco_launch_calibration_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream);
 hipError_t varco_launch_sum_gradients(float* dst, const float* src, int64_t n, hipStream_t stream);
 
+// out[s] = {(a << 16) | b of node gids[s] under `rule` (1 << 16, the identity, when every element is kept), zrow[s]}:
+// element j of halo row s sits at position (a j + b) mod width; the per-row records of HaloTransform.
+hipError_t varco_launch_halo_rows(const MaskRule& rule, const int32_t* gids, const int32_t* zrow, int32_t n, uint2* out,
+                                  hipStream_t stream);
+
 // Device-resident step state: *d_step = the step (set to `value` when set != 0, else incremented), and
 // table[2 t], table[2 t + 1] = the two key words of tap address t (0 .. 255) for that step and `key`.
 hipError_t varco_launch_step_table(uint64_t* d_step, uint32_t* table, uint64_t key, int set, uint64_t value,
@@ -192,6 +197,29 @@ struct GemmArgs {
     float* partial = nullptr;     // split_k * m * n floats
 };
 hipError_t varco_launch_gemm(const GemmArgs& g, hipStream_t stream, const LaunchTag& tag);
+// c (+)= sum over s < slabs of partial[s][m x n], in a fixed order (the second pass of every split reduction).
+hipError_t varco_launch_gemm_reduce(const float* partial, int32_t slabs, int32_t m, int32_t n, float* c, int64_t ldc,
+                                    bool accumulate, hipStream_t stream, const LaunchTag& tag);
+
+// The halo rows of a partition as an exchange delivered them (kernels_halo_transform.hip; bf16 storage): row s holds
+// the k elements z[rec[s].y * k + j] at positions (a j + b) mod width, (a << 16) | b = rec[s].x, of a width-wide row
+// that is zero elsewhere. width: a multiple of 16, at most 512; fo <= 64 columns on the other side of the weights.
+struct HaloTransform {
+    const void* z = nullptr;
+    const uint2* rec = nullptr;
+    int32_t n = 0;
+    uint32_t width = 0, k = 0, width_magic = 0;
+    int32_t fo = 0;
+};
+// y[s, :] = X~[s, :] H (n x fo, bf16), H as its bf16 copy wt[column][position] (pitch wpitch).
+hipError_t varco_launch_halo_transform_fwd(const HaloTransform& h, const void* wt, int32_t wpitch, void* y, hipStream_t stream);
+// dz[s, j] = (dy[s, :] H^T)[position of j] (n x k, bf16), H as its bf16 copy wr[position][column] (pitch cpitch).
+hipError_t varco_launch_halo_transform_bwd(const HaloTransform& h, const void* dy, const void* wr, int32_t cpitch, void* dz,
+                                           hipStream_t stream);
+// partial[g][width x fo] = workgroup g's share of X~^T dy; *slabs = number of shares written (sum them with
+// varco_launch_gemm_reduce). partial_elems: floats the buffer holds.
+hipError_t varco_launch_halo_transform_wgrad(const HaloTransform& h, const void* dy, float* partial, int64_t partial_elems,
+                                             int32_t* slabs, hipStream_t stream);
 
 // bf16 matrix-core path (bf16 operands, fp32 accumulation). `usable` says whether the shapes, types and
 // alignments of `g` fit it; the launcher runs the product kernel only and reports the number of reduction

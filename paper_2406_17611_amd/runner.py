@@ -14,11 +14,12 @@ from . import binding as vb
 
 class PartitionedNetwork:
     def __init__(self, host_parts, widths, conv: str, mask_key: int, device="cuda", need_backward=True, dtype="f32",
-                 n_streams=1):
+                 n_streams=1, transform_first=()):
         """dtype: storage of activations, messages and their gradients ("f32" or "bf16"); weights and weight
         gradients are always fp32. n_streams > 1: the partitions of a layer are dealt to that many HIP
         streams, so that the matrix-core-bound kernels of one partition overlap the memory-bound kernels of
-        another; streams are joined wherever a step needs all partitions (layer boundaries, owner-side sums)."""
+        another; streams are joined wherever a step needs all partitions (layer boundaries, owner-side sums).
+        transform_first: layers whose calls apply the weights before the aggregation (varco_set_layer_order)."""
         assert dtype in ("f32", "bf16")
         assert 1 <= n_streams <= 4
         self.n_streams = self.max_streams = n_streams
@@ -34,6 +35,9 @@ class PartitionedNetwork:
         self.ctx = vb.Context(self.widths, act, vb.CONV_SAGE if conv == "sage" else vb.CONV_GCN, self.P, mask_key,
                               vb.BF16 if dtype == "bf16" else vb.F32)
         self.dev_parts = [self.ctx.register_partition(q, hp, self.device) for q, hp in enumerate(host_parts)]
+        self.transform_first = frozenset(transform_first)
+        for l in self.transform_first:
+            self.ctx.set_layer_order(l, vb.ORDER_TRANSFORM_FIRST)
 
         self.n_local = [hp.n_local for hp in host_parts]
         self.n_halo = [hp.n_halo for hp in host_parts]
@@ -210,7 +214,9 @@ class PartitionedNetwork:
                     dzh = self.dz_halo[l][int(self.halo_off[q]) * k:]
                 dh1 = self.dh1[l] if si == 0 else self._dh1_extra[si - 1][l]
                 dh0 = self.dh0[l] if si == 0 else self._dh0_extra[si - 1][l]
-                ctx.layer_bwd(l, q, self.dx[l + 1][r], self.x[l + 1][r], self.x[l][r], self.m[l][r], self.h1[l],
+                # what the forward call saved: the aggregated rows, or (transform-first) the compressed rows it read
+                saved = self.z[l] if l in self.transform_first else self.m[l][r]
+                ctx.layer_bwd(l, q, self.dx[l + 1][r], self.x[l + 1][r], self.x[l][r], saved, self.h1[l],
                               self.h0[l], dh1, dh0, self.dx[l][r] if need else None, dzh, streams[si])
             self._join(streams)         # all consumers' returned rows and all local gradients of the layer exist
             if need:

@@ -56,9 +56,25 @@ def check_partition_indexing(large, q):
         assert np.array_equal(getattr(hp, name), getattr(op, name)), name
 
 
-def check_layer(large, layer, ratio, tol, dh_cols=None, consumer=5):
+def check_layer(large, layer, ratio, tol, dh_cols=None, consumer=5, transform_first=False):
     """Forward then backward of one layer over all partitions on synthetic inputs; `dh_cols`: check that many
-    sampled columns of the weight gradients instead of all of them."""
+    sampled columns of the weight gradients instead of all of them. transform_first: the device forms S (X H)
+    instead of (S X) H (same oracle); its weight gradient then depends on the true aggregates, which the oracle
+    has for the sampled rows only, so it is checked in a second backward pass whose upstream gradient is zero
+    outside those rows."""
+    ctx = large["net"].ctx
+    if not transform_first:
+        return _check_layer(large, layer, ratio, tol, dh_cols, consumer, False)
+    ctx.begin_step(0)
+    ctx.set_layer_order(layer, vb.ORDER_TRANSFORM_FIRST)
+    try:
+        return _check_layer(large, layer, ratio, tol, dh_cols, consumer, True)
+    finally:
+        ctx.begin_step(1)
+        ctx.set_layer_order(layer, vb.ORDER_AGGREGATE_FIRST)
+
+
+def _check_layer(large, layer, ratio, tol, dh_cols, consumer, transform_first):
     w, g, host, net, order, st = (large[k] for k in ("w", "g", "host", "net", "order", "st"))
     part = w.part
     L = net.L
@@ -98,7 +114,8 @@ def check_layer(large, layer, ratio, tol, dh_cols=None, consumer=5):
     arena_of[order] = np.arange(g.n)
     m_ref, xo_ref = osamp.forward_rows(g.rowptr, g.colidx, g.vals, part, x, nodes, k, KEY, step, layer, h1, h0, relu)
     rows_dev = torch.from_numpy(arena_of[nodes]).cuda()
-    assert_close(net.m[layer][rows_dev].float().cpu().numpy(), m_ref, f"layer {layer} M rows", tol)
+    if not transform_first:
+        assert_close(net.m[layer][rows_dev].float().cpu().numpy(), m_ref, f"layer {layer} M rows", tol)
     assert_close(net.x[layer + 1][rows_dev].float().cpu().numpy(), xo_ref, f"layer {layer} X_out rows", tol)
     # compressed boundary rows are copies: bit-exact on a sample of owners' rows
     for p in (0, net.P - 1):
@@ -121,7 +138,8 @@ def check_layer(large, layer, ratio, tol, dh_cols=None, consumer=5):
     for q in range(net.P):
         r = net.rows(q)
         dzh = net.dz_halo[layer][int(net.halo_off[q]) * k:] if need else None
-        ctx.layer_bwd(layer, q, net.dx[layer + 1][r], net.x[layer + 1][r], net.x[layer][r], net.m[layer][r],
+        ctx.layer_bwd(layer, q, net.dx[layer + 1][r], net.x[layer + 1][r], net.x[layer][r],
+                      net.z[layer] if transform_first else net.m[layer][r],
                       net.h1[layer], net.h0[layer], net.dh1[layer], net.dh0[layer],
                       net.dx[layer][r] if need else None, dzh)
     if need:
@@ -136,7 +154,8 @@ def check_layer(large, layer, ratio, tol, dh_cols=None, consumer=5):
     dz = dxo[:, cols].astype(np.float64)
     if relu:
         dz *= xout[:, cols] > 0
-    assert_close(net.dh1[layer].cpu().numpy()[:, cols], msav.astype(np.float64).T @ dz, f"layer {layer} dH1")
+    if not transform_first:
+        assert_close(net.dh1[layer].cpu().numpy()[:, cols], msav.astype(np.float64).T @ dz, f"layer {layer} dH1")
     if sage:
         assert_close(net.dh0[layer].cpu().numpy()[:, cols], x.astype(np.float64).T @ dz, f"layer {layer} dH0")
     del dz
@@ -153,3 +172,18 @@ def check_layer(large, layer, ratio, tol, dh_cols=None, consumer=5):
         got = net.dz_halo[layer][int(net.halo_off[q]) * k:int(net.halo_off[q + 1]) * k].reshape(hp.n_halo, k)
         assert_close(got[torch.from_numpy(pick).cuda()].float().cpu().numpy(), ret_ref,
                      f"layer {layer} returned rows", tol)
+    if transform_first:
+        # weight gradient of the aggregated tap: upstream gradient on the sampled rows only, whose aggregates the
+        # oracle computed above (the layer has no gate: transform-first is limited to identity activations)
+        assert not relu
+        sparse = np.zeros_like(dxo)
+        sparse[nodes] = dxo[nodes]
+        _to_arena(net.dx[layer + 1], sparse, order)
+        net.zero_grads()
+        for q in range(net.P):
+            r = net.rows(q)
+            ctx.layer_bwd(layer, q, net.dx[layer + 1][r], net.x[layer + 1][r], net.x[layer][r], net.z[layer],
+                          net.h1[layer], net.h0[layer], net.dh1[layer], net.dh0[layer], None, None)
+        torch.cuda.synchronize()
+        assert_close(net.dh1[layer].cpu().numpy(), m_ref.astype(np.float64).T @ dxo[nodes].astype(np.float64),
+                     f"layer {layer} dH1 from the sampled rows", tol)

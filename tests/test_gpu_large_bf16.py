@@ -29,3 +29,10 @@ def test_partition_indexing_of_one_partition_is_bit_exact(large):
 @pytest.mark.parametrize("layer", [0, 1, 2])
 def test_layer_forward_and_backward_on_sampled_rows(large, layer, ratio):
     lc.check_layer(large, layer, ratio, BF16_TOL, dh_cols=64, consumer=21)
+
+
+@pytest.mark.parametrize("ratio", [(1, 1), (4, 1)])
+def test_class_layer_with_the_transform_before_the_aggregation(large, ratio):
+    # eq. (2) in the other order on the 512 -> 47 layer: the halo rows are transformed from their received elements
+    # and rows of 47 elements are aggregated; same oracle rows, same counts
+    lc.check_layer(large, 2, ratio, BF16_TOL, consumer=21, transform_first=True)

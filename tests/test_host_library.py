@@ -224,6 +224,25 @@ def test_schedules_match_the_oracle_exactly():
         assert e.value.code == vb.ERR_INVALID_ARG
 
 
+def test_layer_order_is_accepted_only_where_the_kernels_cover_it():
+    L = vb.lib()
+    ctx = vb.Context([100, 512, 47], [1, 0], vb.CONV_GCN, 2, 1, vb.BF16)
+    assert L.varco_set_layer_order(ctx._h, 1, vb.ORDER_TRANSFORM_FIRST) == vb.OK
+    assert L.varco_set_layer_order(ctx._h, 1, vb.ORDER_AGGREGATE_FIRST) == vb.OK
+    assert L.varco_set_layer_order(ctx._h, 1, 2) == vb.ERR_INVALID_ARG
+    assert L.varco_set_layer_order(ctx._h, 2, vb.ORDER_TRANSFORM_FIRST) == vb.ERR_INVALID_ARG      # no such layer
+    assert L.varco_set_layer_order(ctx._h, 0, vb.ORDER_TRANSFORM_FIRST) == vb.ERR_UNSUPPORTED      # ReLU layer, 512 outputs
+    assert L.varco_set_layer_order(None, 0, 0) == vb.ERR_INVALID_ARG
+    ctx.close()
+    ctx = vb.Context([100, 512, 47], [1, 0], vb.CONV_GCN, 2, 1, vb.F32)
+    assert L.varco_set_layer_order(ctx._h, 1, vb.ORDER_TRANSFORM_FIRST) == vb.ERR_UNSUPPORTED      # fp32 storage
+    assert b"bf16" in vb.lib().varco_last_error(ctx._h)
+    ctx.close()
+    ctx = vb.Context([100, 510, 47], [1, 0], vb.CONV_SAGE, 2, 1, vb.BF16)
+    assert L.varco_set_layer_order(ctx._h, 1, vb.ORDER_TRANSFORM_FIRST) == vb.ERR_UNSUPPORTED      # width not a multiple of 4
+    ctx.close()
+
+
 def test_host_checkable_errors_of_the_building_block_and_training_calls():
     ctx = vb.Context([8, 4, 3], [1, 0], vb.CONV_SAGE, 2, 1)
     L = vb.lib()

@@ -3,7 +3,7 @@ the entry of profiles/hbm_traffic.json that bench.py reports as `roofline.traffi
 
 The three runs (on the GPU machine, from /tmp with TMPDIR=/tmp; <out> is any directory; one counter per run):
 
-  rocprofv3 --kernel-trace --stats --output-format csv -d <out> -o trace -- python3 bench.py --workload W --steps 3 --warmup 1 --no-cpu-baseline > <out>/trace_bench.json
+  rocprofv3 --kernel-trace --stats --output-format csv -d <out> -o trace -- python3 bench.py --workload W --steps 3 --warmup 1 --streams 1 --no-cpu-baseline > <out>/trace_bench.json
   rocprofv3 --pmc FETCH_SIZE --output-format csv -d <out> -o fetch -- python3 bench.py --workload W --steps 1 --warmup 1 --no-cpu-baseline
   rocprofv3 --pmc WRITE_SIZE --output-format csv -d <out> -o write -- python3 bench.py --workload W --steps 1 --warmup 1 --no-cpu-baseline
 
@@ -81,12 +81,14 @@ def summarise(workload: str, out_dir: str) -> dict:
     desc = (f"workload {workload} ({cfg['nodes']} nodes, {cfg['directed_entries']} directed entries, {cfg['partitions']} "
             f"partitions, {cfg['conv']} {'-'.join(map(str, cfg['widths']))}, ratio {cfg['ratio']})")
     cmd = ("cd /tmp && export TMPDIR=/tmp && rocprofv3 {what} --output-format csv -d <out> -o {name} -- python3 "
-           f"/root/repo/bench.py --workload {workload} --steps {{steps}} --warmup 1 --no-cpu-baseline")
+           f"/root/repo/bench.py --workload {workload} --steps {{steps}} --warmup 1{{extra}} --no-cpu-baseline")
     with open(_find(out_dir, "trace_kernel_stats.csv")) as f:
         rows = list(csv.DictReader(f))
     with open(os.path.join(prof_dir, f"{workload}_kernel_stats.txt"), "w") as f:
         f.write(f"rocprofv3 kernel statistics, bench.py on {desc}, MI355X;\n1 warm-up + 3 timed + 3 event-bracketed "
-                f"steps (7 steps of launches).\ncommand: {cmd.format(what='--kernel-trace --stats', name='trace', steps=3)}\n"
+                f"steps (7 steps of launches), all on one stream, so that no two launches overlap and the averages\nbelow are those of "
+                f"kernels that have the device to themselves (the headline configuration deals the partitions to two streams).\n"
+                f"command: {cmd.format(what='--kernel-trace --stats', name='trace', steps=3, extra=' --streams 1')}\n"
                 f"summary written by: python -m paper_2406_17611_amd.profile_summary {workload} <out>\n\n")
         f.write(f"{'kernel':78s} {'calls':>6s} {'total ms':>10s} {'avg us':>10s} {'%':>6s}\n")
         for r in rows:
@@ -117,8 +119,8 @@ def summarise(workload: str, out_dir: str) -> dict:
     with open(os.path.join(prof_dir, f"{workload}_hbm_traffic.txt"), "w") as f:
         f.write(f"HBM-side traffic per kernel launch from rocprofv3 hardware counters, bench.py on {desc}, MI355X.\n"
                 "commands (one counter per run; 1 warm-up + 1 timed + 1 event-bracketed step):\n"
-                f"  {cmd.format(what='--pmc FETCH_SIZE', name='fetch', steps=1)}\n"
-                f"  {cmd.format(what='--pmc WRITE_SIZE', name='write', steps=1)}\n"
+                f"  {cmd.format(what='--pmc FETCH_SIZE', name='fetch', steps=1, extra='')}\n"
+                f"  {cmd.format(what='--pmc WRITE_SIZE', name='write', steps=1, extra='')}\n"
                 f"summary written by: python -m paper_2406_17611_amd.profile_summary {workload} <out>\n"
                 f"kernel sources (sha256 of csrc/ and include/varco.h): {kernel_sources_hash()}\n\n")
         f.write(f"calibration: the library's plain copy of {CAL_BYTES} bytes (calibration_copy_kernel) reads FETCH_SIZE = "

@@ -51,35 +51,89 @@ __device__ __forceinline__ bf16x8 fragment(const uint16_t* p) { return __builtin
 
 enum { kScatter = 0, kClear = 1, kGather = 2 };
 
+// Element (position, row) of the transposed tile. The lanes that scatter one row write positions that differ by
+// multiples of 8, i.e. by multiples of 160 words with the 80-byte pitch: all in one LDS bank. So the four groups of
+// 8 rows of a position are stored in an order that depends on the position (bits 3-4), which spreads those writes
+// over four banks; a fragment (8 consecutive rows of one position) stays one aligned 16-byte read.
+__device__ __forceinline__ int transposed_cell(int pos, int r) {
+    return pos * kPitchT + ((((r >> 3) ^ (pos >> 3)) & 3) << 3) + (r & 7);
+}
+
+// What a thread needs of the first kAhead chunks it walks in a tile (chunks of 8 elements): the rows' rules and, for
+// a scatter, the compressed elements. Fetched one tile ahead, so that the loads are in flight while the previous tile
+// is multiplied, stored and cleared; a tile of 64 rows of up to 128 kept elements is covered entirely.
+constexpr int kAhead = 4;
+struct Ahead {
+    uint4 data[kAhead];
+    uint32_t ab[kAhead];
+};
+
+template <bool WITH_DATA>
+__device__ __forceinline__ void fetch_ahead(const HaloRows& p, int32_t row0, int32_t rows, Ahead& f) {
+    const int32_t per_row = int32_t(p.k) / 8;
+    const int32_t total = rows * per_row;
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) {
+        const int32_t idx = threadIdx.x + i * kThreads;
+        f.ab[i] = 0u;
+        f.data[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (idx < total) {
+            const int32_t r = idx / per_row;
+            const uint2 rec = p.rec[row0 + r];
+            f.ab[i] = rec.x;
+            if constexpr (WITH_DATA)
+                f.data[i] = *reinterpret_cast<const uint4*>(p.z + int64_t(rec.y) * p.k + uint32_t(idx - r * per_row) * 8u);
+        }
+    }
+}
+
 // Walks the kept elements of rows [row0, row0 + rows) in chunks of VEC (8 when k is a multiple of 8 and the buffers
 // are 16-byte aligned, else 1): kScatter writes them into the dense tile, kClear writes zeros to the same places,
 // kGather reads the tile at those places and stores the compressed rows to `out`. TRANSPOSED: the tile is
-// [position][row] instead of [row][position].
+// [position][row] instead of [row][position]. ahead (VEC = 8 only): what fetch_ahead brought for this tile; the
+// chunks it covers need no loads here.
 template <int VEC, int MODE, bool TRANSPOSED>
-__device__ __forceinline__ void walk_rows(const HaloRows& p, int32_t row0, int32_t rows, uint16_t* tile, uint16_t* out) {
+__device__ __forceinline__ void walk_rows(const HaloRows& p, int32_t row0, int32_t rows, uint16_t* tile, uint16_t* out,
+                                          const Ahead* ahead = nullptr) {
     const int32_t per_row = int32_t(p.k) / VEC;
     const int32_t total = rows * per_row;
-    for (int32_t idx = threadIdx.x; idx < total; idx += kThreads) {
+    auto chunk = [&](int32_t idx, bool have, uint32_t ab_have, const uint4& data_have) {
         const int32_t r = idx / per_row;
         const uint32_t j0 = uint32_t(idx - r * per_row) * VEC;
-        const uint2 rec = p.rec[row0 + r];
-        const uint32_t a = rec.x >> 16;
-        uint32_t pos = position(p, rec.x, j0);
+        uint32_t ab = ab_have;
+        int64_t zrow = 0;
+        if (!have) {
+            const uint2 rec = p.rec[row0 + r];
+            ab = rec.x, zrow = rec.y;
+        }
+        const uint32_t a = ab >> 16;
+        uint32_t pos = position(p, ab, j0);
+        if constexpr (VEC == 8 && !TRANSPOSED) {
+            if (p.k == p.width) {   // every element kept: position j holds element j, a chunk is 16 contiguous bytes on both sides
+                uint4* cell = reinterpret_cast<uint4*>(tile + r * kPitch + int32_t(j0));
+                if constexpr (MODE == kScatter)
+                    *cell = have ? data_have : *reinterpret_cast<const uint4*>(p.z + zrow * p.k + j0);
+                else if constexpr (MODE == kClear)
+                    *cell = make_uint4(0u, 0u, 0u, 0u);
+                else
+                    *reinterpret_cast<uint4*>(out + int64_t(row0 + r) * p.k + j0) = *cell;
+                return;
+            }
+        }
         uint16_t v[VEC];
         if constexpr (MODE == kScatter) {
-            const uint16_t* src = p.z + int64_t(rec.y) * p.k + j0;
             if constexpr (VEC == 8) {
-                const uint4 u = *reinterpret_cast<const uint4*>(src);
+                const uint4 u = have ? data_have : *reinterpret_cast<const uint4*>(p.z + zrow * p.k + j0);
                 const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = uint16_t(w[e >> 1] >> (16 * (e & 1)));
             } else {
-                v[0] = src[0];
+                v[0] = p.z[zrow * p.k + j0];
             }
         }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            uint16_t* cell = tile + (TRANSPOSED ? int32_t(pos) * kPitchT + r : r * kPitch + int32_t(pos));
+            uint16_t* cell = tile + (TRANSPOSED ? transposed_cell(int32_t(pos), r) : r * kPitch + int32_t(pos));
             if constexpr (MODE == kScatter)
                 *cell = v[e];
             else if constexpr (MODE == kClear)
@@ -100,6 +154,29 @@ __device__ __forceinline__ void walk_rows(const HaloRows& p, int32_t row0, int32
                 dst[0] = v[0];
             }
         }
+    };
+    int32_t idx = threadIdx.x;
+    if constexpr (VEC == 8) {
+        if (ahead) {
+#pragma unroll
+            for (int i = 0; i < kAhead; ++i) {
+                if (idx < total) chunk(idx, true, ahead->ab[i], ahead->data[i]);
+                idx += kThreads;
+            }
+        }
+    }
+    const uint4 none = make_uint4(0u, 0u, 0u, 0u);
+    for (; idx < total; idx += kThreads) chunk(idx, false, 0u, none);
+}
+
+// The elements of a tile of dY that a thread copies into LDS (the tile's rows are one contiguous range of `count`
+// elements), fetched one tile ahead; N covers the largest tile (rows x 64 columns).
+template <int N>
+__device__ __forceinline__ void fetch_dy(const uint16_t* __restrict__ src, int32_t count, uint16_t (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const int32_t e = threadIdx.x + i * kThreads;
+        v[i] = e < count ? src[e] : uint16_t(0);
     }
 }
 
@@ -127,10 +204,15 @@ __global__ __launch_bounds__(kThreads, 2) void halo_transform_fwd_kernel(HaloRow
     zero_lds(tile, kTile * kPitch);
     __syncthreads();
     const int32_t n_tiles = (p.n + kTile - 1) / kTile;
+    Ahead next, cur;
+    if (VEC == 8 && int32_t(blockIdx.x) < n_tiles) fetch_ahead<true>(p, blockIdx.x * kTile, min(kTile, p.n - int32_t(blockIdx.x) * kTile), next);
     for (int32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int32_t row0 = t * kTile, rows = min(kTile, p.n - row0);
-        walk_rows<VEC, kScatter, false>(p, row0, rows, tile, nullptr);
+        cur = next;
+        walk_rows<VEC, kScatter, false>(p, row0, rows, tile, nullptr, VEC == 8 ? &cur : nullptr);
         __syncthreads();
+        const int32_t tn = t + int32_t(gridDim.x);
+        if (VEC == 8 && tn < n_tiles) fetch_ahead<true>(p, tn * kTile, min(kTile, p.n - tn * kTile), next);
         floatx16 acc;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -145,7 +227,7 @@ __global__ __launch_bounds__(kThreads, 2) void halo_transform_fwd_kernel(HaloRow
             if (r < rows && col < p.fo) y[int64_t(row0 + r) * p.fo + col] = float_to_bf16(acc[v]);
         }
         __syncthreads();                           // every fragment has been read
-        walk_rows<VEC, kClear, false>(p, row0, rows, tile, nullptr);
+        walk_rows<VEC, kClear, false>(p, row0, rows, tile, nullptr, VEC == 8 ? &cur : nullptr);
         __syncthreads();
     }
 }
@@ -177,15 +259,30 @@ __global__ __launch_bounds__(kThreads, 2) void halo_transform_bwd_kernel(HaloRow
     zero_lds(dtile, kTile * kPitchC);
     __syncthreads();
     const int32_t n_tiles = (p.n + kTile - 1) / kTile;
+    constexpr int kDy = kTile * 64 / kThreads;     // elements of a tile of dY per thread
+    uint16_t dnext[kDy];
+    Ahead next, cur;
+    auto fetch_tile = [&](int32_t t) {
+        const int32_t row0 = t * kTile, rows = min(kTile, p.n - row0);
+        fetch_dy<kDy>(dy + int64_t(row0) * p.fo, rows * p.fo, dnext);
+        if (VEC == 8) fetch_ahead<false>(p, row0, rows, next);
+    };
+    if (int32_t(blockIdx.x) < n_tiles) fetch_tile(blockIdx.x);
     for (int32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int32_t row0 = t * kTile, rows = min(kTile, p.n - row0);
         // the tile's rows of dY are one contiguous range (columns beyond fo stay zero; rows beyond the tile keep an
         // older tile's values, and their results are never read)
-        for (int32_t i = threadIdx.x; i < rows * p.fo; i += kThreads) {
-            const int32_t r = i / p.fo;
-            dtile[r * kPitchC + (i - r * p.fo)] = dy[int64_t(row0) * p.fo + i];
+#pragma unroll
+        for (int i = 0; i < kDy; ++i) {
+            const int32_t e = threadIdx.x + i * kThreads;
+            if (e < rows * p.fo) {
+                const int32_t r = e / p.fo;
+                dtile[r * kPitchC + (e - r * p.fo)] = dnext[i];
+            }
         }
+        cur = next;
         __syncthreads();
+        if (t + int32_t(gridDim.x) < n_tiles) fetch_tile(t + gridDim.x);
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             bf16x8 fa[4];
@@ -208,7 +305,7 @@ __global__ __launch_bounds__(kThreads, 2) void halo_transform_bwd_kernel(HaloRow
             }
         }
         __syncthreads();
-        walk_rows<VEC, kGather, false>(p, row0, rows, tile, dz);
+        walk_rows<VEC, kGather, false>(p, row0, rows, tile, dz, VEC == 8 ? &cur : nullptr);
         __syncthreads();                           // the next tile overwrites both LDS blocks
     }
 }
@@ -234,14 +331,29 @@ __global__ __launch_bounds__(kThreads, 2) void halo_transform_wgrad_kernel(HaloR
     zero_lds(dtile, 64 * kPitchT);
     __syncthreads();
     const int32_t n_tiles = (p.n + kTileT - 1) / kTileT;
+    constexpr int kDy = kTileT * 64 / kThreads;    // elements of a tile of dY per thread
+    uint16_t dnext[kDy];
+    Ahead next, cur;
+    auto fetch_tile = [&](int32_t t) {
+        const int32_t row0 = t * kTileT, rows = min(kTileT, p.n - row0);
+        fetch_dy<kDy>(dy + int64_t(row0) * p.fo, rows * p.fo, dnext);      // rows beyond the tile: zeros
+        if (VEC == 8) fetch_ahead<true>(p, row0, rows, next);
+    };
+    if (int32_t(blockIdx.x) < n_tiles) fetch_tile(blockIdx.x);
     for (int32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
         const int32_t row0 = t * kTileT, rows = min(kTileT, p.n - row0);
-        walk_rows<VEC, kScatter, true>(p, row0, rows, tile, nullptr);
-        for (int32_t i = threadIdx.x; i < kTileT * p.fo; i += kThreads) {      // rows beyond the tile: zeros
-            const int32_t r = i / p.fo, c = i - r * p.fo;
-            dtile[c * kPitchT + r] = r < rows ? dy[int64_t(row0) * p.fo + i] : uint16_t(0);
+        cur = next;
+        walk_rows<VEC, kScatter, true>(p, row0, rows, tile, nullptr, VEC == 8 ? &cur : nullptr);
+#pragma unroll
+        for (int i = 0; i < kDy; ++i) {
+            const int32_t e = threadIdx.x + i * kThreads;
+            if (e < kTileT * p.fo) {
+                const int32_t r = e / p.fo;
+                dtile[(e - r * p.fo) * kPitchT + r] = dnext[i];
+            }
         }
         __syncthreads();
+        if (t + int32_t(gridDim.x) < n_tiles) fetch_tile(t + gridDim.x);
 #pragma unroll
         for (int s = 0; s < kTileT / 16; ++s) {
             bf16x8 fb[2];
@@ -249,13 +361,13 @@ __global__ __launch_bounds__(kThreads, 2) void halo_transform_wgrad_kernel(HaloR
             for (int c = 0; c < 2; ++c) fb[c] = fragment(dtile + (c * 32 + lrow) * kPitchT + 16 * s + 8 * lk);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const bf16x8 fa = fragment(tile + (wave * 128 + b * 32 + lrow) * kPitchT + 16 * s + 8 * lk);
+                const bf16x8 fa = fragment(tile + transposed_cell(wave * 128 + b * 32 + lrow, 16 * s + 8 * lk));
 #pragma unroll
                 for (int c = 0; c < 2; ++c) acc[b][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[c], acc[b][c], 0, 0, 0);
             }
         }
         __syncthreads();
-        walk_rows<VEC, kClear, true>(p, row0, rows, tile, nullptr);
+        walk_rows<VEC, kClear, true>(p, row0, rows, tile, nullptr, VEC == 8 ? &cur : nullptr);
         __syncthreads();
     }
     float* out = partial + int64_t(blockIdx.x) * p.width * p.fo;

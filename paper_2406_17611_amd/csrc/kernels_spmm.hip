@@ -448,6 +448,48 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const SpmmSplit* spl
     }
 }
 
+// The same for rows whose width is a multiple of 4: a launch ends with its longest split row (a hub's hundreds of
+// partial rows, one dependent chain per thread above), so here the four wavefronts of the workgroup each sum a
+// contiguous quarter of the slots, 4 columns per lane and 8 loads in flight, and the quarters are added in wavefront
+// order: a fixed order as well, with a chain a quarter as long.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void spmm_fixup4_kernel(const SpmmSplit* splits, int32_t n_splits,
+                                                             const float* partial, T* out, int32_t row_base,
+                                                             int32_t width) {
+    __shared__ float4 part[kWaves][64];
+    const int32_t s = blockIdx.x;
+    if (s >= n_splits) return;          // whole workgroup
+    const SpmmSplit sp = splits[s];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int32_t per = (sp.count + kWaves - 1) / kWaves;
+    const int32_t i0 = min(wave * per, sp.count), i1 = min(i0 + per, sp.count);
+    for (int32_t c0 = 0; c0 < width; c0 += 256) {
+        const int32_t c = c0 + 4 * lane;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (c < width) {
+            const float* src = partial + int64_t(sp.first) * width + c;
+            int32_t i = i0;
+            for (; i + 8 <= i1; i += 8) {
+                float4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4*>(src + int64_t(i + u) * width);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) add_vec(acc, v[u]);
+            }
+            for (; i < i1; ++i) add_vec(acc, *reinterpret_cast<const float4*>(src + int64_t(i) * width));
+        }
+        part[wave][lane] = acc;
+        __syncthreads();
+        if (wave == 0 && c < width) {
+            float4 x = part[0][lane];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) add_vec(x, part[w][lane]);
+            store_vec<T, 4>(out + int64_t(sp.row - row_base) * width + c, x);
+        }
+        __syncthreads();                // the next column group reuses the block
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------
 // Transposed aggregation for halo rows, produced directly in compressed form:
 //     dz_halo[s, j] = sum over local rows i of S[i, halo s] * dM[i, pi_v(j)],  j < k,  v = node of slot s.
@@ -869,8 +911,12 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
         // the split records, every fp32 partial row once, every split row written once
         tag.begin_as(VARCO_K_REDUCE, stream, 16.0 * plan.n_splits + 4.0 * double(plan.n_partials) * width +
                                                  double(sizeof(T)) * plan.n_splits * width);
-        hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
-                           partial, out, row_base, width);
+        if (vec4)
+            hipLaunchKernelGGL(spmm_fixup4_kernel<T>, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
+                               partial, out, row_base, width);
+        else
+            hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(plan.n_splits), dim3(kBlock), 0, stream, plan.splits, plan.n_splits,
+                               partial, out, row_base, width);
         tag.end(stream);
         err = hipGetLastError();
     }
@@ -976,8 +1022,12 @@ hipError_t halo_grad_t(const SpmmPlan& fwd_plan, const SpmmPlan& t_halo_plan, co
     if (t_halo_plan.n_splits > 0) {
         tag.begin_as(VARCO_K_REDUCE, stream, 16.0 * t_halo_plan.n_splits + 4.0 * double(t_halo_plan.n_partials) * rule.k +
                                                  double(sizeof(T)) * t_halo_plan.n_splits * rule.k);
-        hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
-                           t_halo_plan.n_splits, partial, out, row_base, int32_t(rule.k));
+        if (ev == 4)
+            hipLaunchKernelGGL(spmm_fixup4_kernel<T>, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
+                               t_halo_plan.n_splits, partial, out, row_base, int32_t(rule.k));
+        else
+            hipLaunchKernelGGL(spmm_fixup_kernel<T>, dim3(t_halo_plan.n_splits), dim3(kBlock), 0, stream, t_halo_plan.splits,
+                               t_halo_plan.n_splits, partial, out, row_base, int32_t(rule.k));
         tag.end(stream);
         err = hipGetLastError();
     }

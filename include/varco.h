@@ -248,7 +248,8 @@ int32_t varco_set_layer_order(varco_ctx* ctx, int32_t layer, int32_t order);
  * partition order (the on-device stand-in for the exchange; may be NULL when n_halo = 0); h1, h0:
  * width[layer] x width[layer+1] (h0 NULL for GCN, required for SAGE); m_saved is written and must be kept
  * for the backward call; z_out may be NULL (must be NULL on the last layer).
- * Counts n_halo * k_layer elements as handed off forward. */
+ * Counts n_halo * k_layer elements as handed off forward. (A layer set to VARCO_ORDER_TRANSFORM_FIRST computes the
+ * same x_out as S_q [x_local h1 ; x~_halo h1] and leaves m_saved alone: see varco_set_layer_order.) */
 int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_local, const void* z_in,
                         const void* h1, const void* h0, void* x_out, void* z_out, void* m_saved,
                         varco_stream stream);
@@ -261,7 +262,8 @@ int32_t varco_layer_fwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* x_
  * dh1/dh0 are accumulated into (the sum over partitions is the cross-machine sum of Section III); dx_local
  * (n_local x width[layer]) and dz_halo (n_halo x k_layer) are overwritten. dx_local = NULL skips the input
  * gradient (first layer); dz_halo must then be NULL too. The owners add dz_halo with varco_decompress
- * (accumulate = 1). Counts n_halo * k_layer elements as handed off backward when dz_halo is produced. */
+ * (accumulate = 1). Counts n_halo * k_layer elements as handed off backward when dz_halo is produced. (A layer set to
+ * VARCO_ORDER_TRANSFORM_FIRST produces the same results from x_local and the forward call's z_in, passed as m_saved.) */
 int32_t varco_layer_bwd(varco_ctx* ctx, int32_t layer, int32_t q, const void* dx_out, const void* x_out,
                         const void* x_local, const void* m_saved, const void* h1, const void* h0, void* dh1,
                         void* dh0, void* dx_local, void* dz_halo, varco_stream stream);

@@ -18,12 +18,13 @@ BF16_TOL = 2.0 ** -7   # norm-wise bound with bf16 storage: at most four roundin
 
 
 def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, layer=1, dtype="f32", z_row_shift=0,
-                    registered_before=None):
+                    registered_before=None, transform_first=False):
     """dtype "bf16": every activation / message / gradient tensor handed to the library is bf16 (the inputs
     are bf16 values, so both sides start from identical numbers); weights and weight gradients stay fp32.
     z_row_shift: the library's partitions address the compressed buffer that many rows further in (the rows
     before stay unused), the oracle's are unchanged. registered_before: partitions of another graph that are
-    registered under the same numbers first, and replaced."""
+    registered under the same numbers first, and replaced. transform_first: the layer runs as S (X H) (same oracle;
+    no aggregated rows M on the device, the backward call is given the compressed buffer again)."""
     host, orc = both_partitions(g, part, n_parts)
     for hp in host:
         hp.halo_zrow = (hp.halo_zrow.astype(np.int64) + z_row_shift).astype(np.int32)
@@ -44,6 +45,8 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
     ctx.prepare()
     ctx.begin_step(step)
     ctx.set_ratio(layer, *ratio)
+    if transform_first:
+        ctx.set_layer_order(layer, vb.ORDER_TRANSFORM_FIRST)
     k = ctx.keep(layer)
     assert k == omask.keep_count(fi, *ratio)
 
@@ -78,8 +81,9 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
         xld = dev(xl, tdt)
         xo = torch.full((p.n_local, fo), float("nan"), dtype=tdt, device="cuda")
         ms = torch.full((p.n_local, fi), float("nan"), dtype=tdt, device="cuda")
-        ctx.layer_fwd(layer, q, xld, z_dev, h1d, h0d, xo, None, ms)
-        assert_close(ms.float().cpu().numpy(), m_ref, f"M q={q}", tol)
+        ctx.layer_fwd(layer, q, xld, z_dev, h1d, h0d, xo, None, None if transform_first else ms)
+        if not transform_first:
+            assert_close(ms.float().cpu().numpy(), m_ref, f"M q={q}", tol)
         assert_close(xo.float().cpu().numpy(), xo_ref, f"X_out q={q}", tol)
 
         # backward on synthetic upstream gradient, with the oracle's own x_out / m as saved tensors
@@ -92,14 +96,15 @@ def _run_layer_case(g, part, n_parts, conv, fi, fo, ratio, act, seed, step=3, la
             dh0_ref += r0
         dxl = torch.full((p.n_local, fi), float("nan"), dtype=tdt, device="cuda")
         dzh = torch.full((max(p.n_halo, 1), k), float("nan"), dtype=tdt, device="cuda")
-        ctx.layer_bwd(layer, q, dev(d, tdt), dev(xo32, tdt), xld, dev(m32, tdt), h1d, h0d, dh1_dev, dh0_dev, dxl,
-                      dzh if p.n_halo else None)
+        ctx.layer_bwd(layer, q, dev(d, tdt), dev(xo32, tdt), xld, z_dev if transform_first else dev(m32, tdt), h1d, h0d,
+                      dh1_dev, dh0_dev, dxl, dzh if p.n_halo else None)
         assert_close(dxl.float().cpu().numpy(), rdx, f"dX_local q={q}", tol)
         if p.n_halo:
             assert_close(dzh.float().cpu().numpy(), rdz, f"dZ_halo q={q}", tol)
         halo_rows += p.n_halo
-    # weight gradients: fp32 sums of products of stored values, no storage rounding on either side
-    assert_close(dh1_dev.cpu().numpy(), dh1_ref, "dH1 summed over partitions")
+    # weight gradients: fp32 sums of products of stored values, no storage rounding on either side (transform first: the
+    # transposed aggregate that enters the product is a stored bf16 tensor)
+    assert_close(dh1_dev.cpu().numpy(), dh1_ref, "dH1 summed over partitions", tol if transform_first else TOL)
     if sage:
         assert_close(dh0_dev.cpu().numpy(), dh0_ref, "dH0 summed over partitions")
     st = ctx.stats()
@@ -201,6 +206,35 @@ def test_layer_parity_after_a_partition_is_registered_again(dtype):
     g = synth.small_random_graph(1300, 7.0, "sage", seed=22)
     part = synth.random_partition(g.n, 3, seed=9)
     _run_layer_case(g, part, 3, "sage", 96, 40, (4, 1), vb.ACT_RELU, seed=5, dtype=dtype, registered_before=host_before)
+
+
+@pytest.mark.parametrize("conv", ["gcn", "sage"])
+@pytest.mark.parametrize("fi,fo,ratio", [(128, 47, (4, 1)), (512, 47, (1, 1)), (512, 33, (32, 1)), (64, 16, (3, 1)),
+                                         (256, 64, (16, 1)), (16, 1, (2, 1))])
+def test_layer_parity_in_the_transform_first_order(conv, fi, fo, ratio):
+    # widths up to the limit of the halo kernels, outputs that are no multiple of anything, k a multiple of 8 (16-byte
+    # chunks) and not (22 of 64: element by element), every element kept (dense copy), several tiles and a ragged last one
+    g = synth.small_random_graph(1500, 9.0, conv, seed=fi + fo)
+    part = synth.random_partition(g.n, 3, seed=fi)
+    _run_layer_case(g, part, 3, conv, fi, fo, ratio, vb.ACT_IDENTITY, seed=fi * fo, dtype="bf16", transform_first=True)
+
+
+def test_transform_first_edge_cases():
+    # rows split over wavefronts in all three blocks; no halo at all; a partition that owns nothing and empty rows;
+    # compressed rows far into the buffer (64-bit offsets)
+    g = hub_graph(6000, 4, 1500, 6.0, "gcn", seed=9)
+    _run_layer_case(g, synth.random_partition(g.n, 4, seed=10), 4, "gcn", 128, 47, (4, 1), vb.ACT_IDENTITY, seed=11,
+                    dtype="bf16", transform_first=True)
+    g = synth.small_random_graph(900, 8.0, "gcn", seed=2)
+    _run_layer_case(g, np.zeros(g.n, dtype=np.int32), 1, "gcn", 64, 16, (4, 1), vb.ACT_IDENTITY, seed=3, dtype="bf16",
+                    transform_first=True)
+    g = synth.small_random_graph(400, 1.2, "sage", seed=4)
+    part = synth.random_partition(g.n, 2, seed=1).astype(np.int32)
+    part[part == 1] = 2
+    _run_layer_case(g, part, 3, "sage", 32, 16, (2, 1), vb.ACT_IDENTITY, seed=5, dtype="bf16", transform_first=True)
+    g = synth.small_random_graph(1200, 8.0, "gcn", seed=12)
+    _run_layer_case(g, synth.random_partition(g.n, 3, seed=13), 3, "gcn", 512, 47, (1, 1), vb.ACT_IDENTITY, seed=14,
+                    dtype="bf16", z_row_shift=(1 << 22) + 5, transform_first=True)
 
 
 def test_layer_parity_single_partition_has_no_exchange():

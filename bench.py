@@ -29,7 +29,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0 # MI355X dense bf16 matrix rate
 HBM_CLASSES = ("compress", "decompress", "agg_fwd", "agg_bwd_local", "agg_bwd_halo", "agg_bwd_halo_sum", "reduce")
 MFMA_CLASSES = ("gemm_fwd", "gemm_wgrad", "gemm_dgrad")
 DEFAULT_RATIO = {"tiny": (4, 1), "medium": (8, 1), "medium_bfs16": (1584 - 15 * 50, 99), "large_sage": (8, 1),
-                 "large_gcn_bf16": (4, 1), "large_sage_bfs8": (8, 1), "large_sage_banded8": (8, 1)}
+                 "large_gcn_bf16": (4, 1), "large_sage_bfs8": (8, 1), "large_sage_banded8": (8, 1), "large_gcn_bf16_p4": (4, 1)}
 
 
 def log(*a):

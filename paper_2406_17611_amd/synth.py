@@ -350,6 +350,12 @@ def make_workload(name: str) -> Workload:
         keep = v < n
         g = sage_mean_operator(n, u[keep], v[keep])
         return Workload(name, g, _equal_chunks(np.arange(n, dtype=np.int64), 8), 8, "sage", (100, 256, 256, 47), ((8, 1),))
+    # The bf16 configuration's graph, widths and storage cut into 4 instead of 32 random parts: a quarter of the entries
+    # local and a dozen entries per halo row, to show where the order of eq. (2)'s two products matters.
+    if name == "large_gcn_bf16_p4":
+        u, v = _products_like_edges()
+        g = gcn_operator(2_449_029, u, v)
+        return Workload(name, g, random_partition(g.n, 4, SEED_PART), 4, "gcn", (100, 512, 512, 47), ((4, 1),), dtype="bf16")
     raise ValueError(f"unknown workload {name!r}")
 
 

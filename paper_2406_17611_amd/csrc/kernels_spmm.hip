@@ -90,6 +90,7 @@ struct SpmmArgs {
     int32_t ku;               // loads per compressed row = k / ev
     int32_t lpe_log2;         // lanes that share one compressed row = 1 << lpe_log2 (>= min(ku, 64))
     int32_t epi;              // compressed rows handled per instruction = private LDS rows per wavefront
+    int32_t swizzle;          // private rows hold position q at q ^ ((q >> 5) & 3) (see sparse_phase)
 };
 
 // N consecutive stored elements as they come from memory (bf16 stays packed until it is used).
@@ -127,7 +128,12 @@ struct Stored<bf16_t, 1> {
 // Z32: every element of the compressed buffer lies below 2^32 bytes, so a row's address is the (uniform) base
 // plus a 32-bit offset: one address register per gather in flight instead of two, which is what decides how
 // many wavefronts fit a SIMD here. `srow` then holds the row's element offset (row * k), not the row.
-template <typename T, int EV, bool Z32>
+// SWZ: the lanes of one entry step through its stored elements EV at a time, so at one instruction their positions
+// differ by multiples of EV * a: with 16 or more lanes per entry, lanes 8 (EV = 4) apart meet in one LDS bank at
+// different addresses, a 4-way conflict on every access of a 512-wide row. Their positions differ by odd multiples
+// of 32, so folding bits 5-6 of the position into bits 0-1 of the address (which the lanes of an instruction share)
+// separates them; the row is read back through the same map.
+template <typename T, int EV, bool Z32, bool SWZ>
 __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int nd, int ns, int32_t srow, float w,
                                              uint32_t mab, float* lpriv) {
     using S = typename Stored<T, EV>::type;
@@ -180,6 +186,10 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int
                     for (int i = 1; i < EV; ++i) {
                         q[i] = q[i - 1] + a;
                         if (q[i] >= width) q[i] -= width;
+                    }
+                    if constexpr (SWZ) {
+#pragma unroll
+                        for (int i = 0; i < EV; ++i) q[i] ^= (q[i] >> 5) & 3u;
                     }
 #pragma unroll
                     for (int i = 0; i < EV; ++i) cur[i] = row[q[i]];          // distinct positions of one entry
@@ -306,12 +316,14 @@ __global__ __launch_bounds__(agg_block(MODE)) void spmm_kernel(SpmmArgs<T> p) {
 
         if (ns > 0) {
             any_sparse = true;
-            if (p.ev == 4)
-                sparse_phase<T, 4, Z32>(p, lane, nd, ns, srow, w, mab, lpriv);
+            if (p.ev == 4 && p.swizzle)
+                sparse_phase<T, 4, Z32, true>(p, lane, nd, ns, srow, w, mab, lpriv);
+            else if (p.ev == 4)
+                sparse_phase<T, 4, Z32, false>(p, lane, nd, ns, srow, w, mab, lpriv);
             else if (p.ev == 2)
-                sparse_phase<T, 2, Z32>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 2, Z32, false>(p, lane, nd, ns, srow, w, mab, lpriv);
             else
-                sparse_phase<T, 1, Z32>(p, lane, nd, ns, srow, w, mab, lpriv);
+                sparse_phase<T, 1, Z32, false>(p, lane, nd, ns, srow, w, mab, lpriv);
         }
     }
 
@@ -327,8 +339,19 @@ __global__ __launch_bounds__(agg_block(MODE)) void spmm_kernel(SpmmArgs<T> p) {
             const int col = VEC * (t + lpr * m);
             if (col < width) {
                 V v = acc[m];
-                if (any_sparse)
-                    for (int sub = 0; sub < p.epi; ++sub) add_vec(v, *reinterpret_cast<const V*>(lpriv + sub * width + col));
+                if (any_sparse) {
+                    for (int sub = 0; sub < p.epi; ++sub) {
+                        V x = *reinterpret_cast<const V*>(lpriv + sub * width + col);
+                        if constexpr (VEC == 4) {
+                            if (p.swizzle) {        // element i of the group of 4 sits at i ^ s
+                                const int sw = (col >> 5) & 3;
+                                const float e[4] = {x.x, x.y, x.z, x.w};
+                                x = make_float4(e[sw], e[1 ^ sw], e[2 ^ sw], e[3 ^ sw]);
+                            }
+                        }
+                        add_vec(v, x);
+                    }
+                }
                 if (it.dst < 0)
                     store_vec<T, VEC>(p.out + int64_t(it.row - p.row_base) * width + col, v);
                 else
@@ -886,6 +909,8 @@ hipError_t spmm_t(const SpmmPlan& plan, const VarcoEdge* edge, const int32_t* co
     a.lpe_log2 = 0;
     while ((1 << a.lpe_log2) < a.ku && a.lpe_log2 < 6) ++a.lpe_log2;
     a.epi = std::max(1, std::min(64 >> a.lpe_log2, epi_cap));
+    // 16 or more lanes per compressed row, 4 elements each, rows of whole 128-position blocks read back 4 at a time
+    a.swizzle = halo && !full && a.ev == 4 && a.lpe_log2 >= 4 && vec4 && width % 128 == 0 ? 1 : 0;
     const int agg_waves = agg_block(halo ? kHalo : kDenseOnly) / 64;
     const int32_t per_round = 8 * kXcdRun;                                         // see the kernel's XCD mapping
     const dim3 grid(((plan.n_items + agg_waves - 1) / agg_waves + per_round - 1) / per_round * per_round);

@@ -113,9 +113,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large_sage")
     ap.add_argument("--ratio", default=None, help="num/den, default: the configuration's ratio")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=None,
                     help="HIP streams the partitions of a layer are dealt to in the timed steps (kernels of different "
-                         "partitions overlap; the per-kernel pass that follows always uses one stream)")
+                         "partitions overlap; the per-kernel pass that follows always uses one stream). Default: 2, "
+                         "or 1 for a workload of two partitions (a step of a few hundred microseconds, where the joins cost more than the overlap gains)")
     ap.add_argument("--matmul-terms", type=int, default=None, choices=[0, 2, 3],
                     help="fp32 storage only: form of the dense products (library default 3; 0 = fp32 matrix instructions; "
                          "2 = lower precision, not a valid headline setting)")
@@ -140,6 +141,8 @@ def main():
     t0 = time.time()
     w = synth.make_workload(args.workload)
     g = w.graph
+    if args.streams is None:
+        args.streams = 1 if w.n_parts <= 2 else 2
     log(f"[bench] workload {w.name}: n={g.n} nnz={g.nnz} P={w.n_parts} conv={w.conv} widths={w.widths} "
         f"ratio={ratio} (generated in {time.time() - t0:.1f}s)")
     if args.cpu_baseline_only:

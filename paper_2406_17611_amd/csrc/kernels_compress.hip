@@ -2,6 +2,8 @@
 // each node vector; decode by writing them in place and zero elsewhere (no rescale). Pure data movement:
 // HBM-bound, no index bytes are stored or read. A power-of-two group of lanes serves one row, so that
 // narrow messages (k of 4..32) still fill the 64-wide wavefront with several rows.
+#include <algorithm>
+
 #include "elem.h"
 #include "mask_device.h"
 
@@ -35,6 +37,35 @@ __global__ __launch_bounds__(kBlock) void compress_kernel(MaskRule rule, const i
             const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
             for (uint32_t j = gl; j < rule.k; j += g) zr[j] = xr[varco_position(rule, m, j)];
         }
+    }
+}
+
+// bf16 rows: picking the kept elements straight from memory is 64 scattered 2-byte loads per instruction, which the
+// vector memory unit takes about one per cycle. Here a wavefront copies the row into LDS with 16-byte loads (a
+// 512-wide row is one instruction), picks from there, two elements per lane, and writes 4 bytes per lane.
+// Needs width % 8 == 0, width <= kStagedWidth, k even, 16-byte aligned rows of x and 4-byte aligned rows of z.
+constexpr int kStagedWidth = 2048;
+__global__ __launch_bounds__(kBlock) void compress_staged_kernel(MaskRule rule, const int32_t* __restrict__ gids,
+                                                                 const int32_t* __restrict__ rows, int64_t n_rows,
+                                                                 const uint16_t* __restrict__ x, int64_t ldx,
+                                                                 uint16_t* __restrict__ z) {
+    __shared__ __attribute__((aligned(16))) uint16_t staged[kBlock / 64][kStagedWidth];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint16_t* row_lds = staged[wave];
+    const int64_t stride = int64_t(gridDim.x) * (kBlock / 64);
+    for (int64_t row = int64_t(blockIdx.x) * (kBlock / 64) + wave; row < n_rows; row += stride) {
+        const uint16_t* xr = x + (rows ? int64_t(rows[row]) : row) * ldx;
+        for (uint32_t c = lane * 8; c < rule.width; c += 512) *reinterpret_cast<uint4*>(row_lds + c) = *reinterpret_cast<const uint4*>(xr + c);
+        const MaskAffine m = varco_affine(rule, uint32_t(gids[row]));
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // the wavefront's own LDS writes, then its reads
+        uint16_t* zr = z + row * int64_t(rule.k);
+        for (uint32_t j = 2 * lane; j < rule.k; j += 128) {
+            const uint32_t p0 = varco_position(rule, m, j);
+            uint32_t p1 = p0 + m.a;
+            if (p1 >= rule.width) p1 -= rule.width;
+            *reinterpret_cast<uint32_t*>(zr + j) = uint32_t(row_lds[p0]) | (uint32_t(row_lds[p1]) << 16);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");     // reads done before the next row overwrites the buffer
     }
 }
 
@@ -201,6 +232,13 @@ __global__ __launch_bounds__(kBlock) void halo_rows_kernel(MaskRule rule, const 
 template <typename T>
 hipError_t launch_compress_t(const MaskRule& rule, const int32_t* gids, const int32_t* rows, int64_t n_rows, const void* x,
                              int64_t ldx, void* z, hipStream_t stream) {
+    if (sizeof(T) == 2 && rule.k < rule.width && rule.k % 2 == 0 && rule.width % 8 == 0 && rule.width <= uint32_t(kStagedWidth) &&
+        ldx % 8 == 0 && (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && (reinterpret_cast<uintptr_t>(z) & 3u) == 0) {
+        const int64_t blocks = std::min<int64_t>((n_rows + kBlock / 64 - 1) / (kBlock / 64), 256 * 8);
+        hipLaunchKernelGGL(compress_staged_kernel, dim3(unsigned(blocks)), dim3(kBlock), 0, stream, rule, gids, rows, n_rows,
+                           static_cast<const uint16_t*>(x), ldx, static_cast<uint16_t*>(z));
+        return hipGetLastError();
+    }
     const int gl = group_log2(rule.k);
     hipLaunchKernelGGL(compress_kernel<T>, dim3(grid_for(n_rows, gl)), dim3(kBlock), 0, stream, rule, gids, rows, n_rows,
                        static_cast<const T*>(x), ldx, static_cast<T*>(z), gl);

@@ -133,7 +133,9 @@ struct Stored<bf16_t, 1> {
 // different addresses, a 4-way conflict on every access of a 512-wide row. Their positions differ by odd multiples
 // of 32, so folding bits 5-6 of the position into bits 0-1 of the address (which the lanes of an instruction share)
 // separates them; the row is read back through the same map.
-template <typename T, int EV, bool Z32, bool SWZ>
+// POW2: the width is a power of two, so positions wrap with a mask instead of a division by multiplication and
+// conditional subtractions (the kernel is bound by its vector instructions once the conflicts are gone).
+template <typename T, int EV, bool Z32, bool SWZ, bool POW2 = false>
 __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int nd, int ns, int32_t srow, float w,
                                              uint32_t mab, float* lpriv) {
     using S = typename Stored<T, EV>::type;
@@ -181,11 +183,17 @@ __device__ __forceinline__ void sparse_phase(const SpmmArgs<T>& p, int lane, int
                 if (act) {
                     uint32_t q[EV];
                     float cur[EV];
-                    q[0] = varco_mod_width(__umul24(a, uint32_t(j)) + (ab >> 16), width, p.rule.width_magic);
+                    if constexpr (POW2) {
+                        q[0] = (__umul24(a, uint32_t(j)) + (ab >> 16)) & (width - 1u);
 #pragma unroll
-                    for (int i = 1; i < EV; ++i) {
-                        q[i] = q[i - 1] + a;
-                        if (q[i] >= width) q[i] -= width;
+                        for (int i = 1; i < EV; ++i) q[i] = (q[i - 1] + a) & (width - 1u);
+                    } else {
+                        q[0] = varco_mod_width(__umul24(a, uint32_t(j)) + (ab >> 16), width, p.rule.width_magic);
+#pragma unroll
+                        for (int i = 1; i < EV; ++i) {
+                            q[i] = q[i - 1] + a;
+                            if (q[i] >= width) q[i] -= width;
+                        }
                     }
                     if constexpr (SWZ) {
 #pragma unroll
@@ -316,7 +324,9 @@ __global__ __launch_bounds__(agg_block(MODE)) void spmm_kernel(SpmmArgs<T> p) {
 
         if (ns > 0) {
             any_sparse = true;
-            if (p.ev == 4 && p.swizzle)
+            if (p.ev == 4 && p.swizzle && (width & (width - 1)) == 0)
+                sparse_phase<T, 4, Z32, true, true>(p, lane, nd, ns, srow, w, mab, lpriv);
+            else if (p.ev == 4 && p.swizzle)
                 sparse_phase<T, 4, Z32, true>(p, lane, nd, ns, srow, w, mab, lpriv);
             else if (p.ev == 4)
                 sparse_phase<T, 4, Z32, false>(p, lane, nd, ns, srow, w, mab, lpriv);

@@ -85,8 +85,8 @@ def summarise(workload: str, out_dir: str) -> dict:
     with open(_find(out_dir, "trace_kernel_stats.csv")) as f:
         rows = list(csv.DictReader(f))
     with open(os.path.join(prof_dir, f"{workload}_kernel_stats.txt"), "w") as f:
-        f.write(f"rocprofv3 kernel statistics, bench.py on {desc}, MI355X;\n1 warm-up + 3 timed + 3 event-bracketed "
-                f"steps (7 steps of launches), all on one stream, so that no two launches overlap and the averages\nbelow are those of "
+        f.write(f"rocprofv3 kernel statistics, bench.py on {desc}, MI355X;\n1 warm-up + 3 timed + 1 untimed + 3 event-bracketed "
+                f"steps (8 steps of launches), all on one stream, so that no two launches overlap and the averages\nbelow are those of "
                 f"kernels that have the device to themselves (the headline configuration deals the partitions to two streams).\n"
                 f"command: {cmd.format(what='--kernel-trace --stats', name='trace', steps=3, extra=' --streams 1')}\n"
                 f"summary written by: python -m paper_2406_17611_amd.profile_summary {workload} <out>\n\n")
@@ -118,7 +118,7 @@ def summarise(workload: str, out_dir: str) -> dict:
     per_class = collections.defaultdict(lambda: [0.0, 0.0, 0])
     with open(os.path.join(prof_dir, f"{workload}_hbm_traffic.txt"), "w") as f:
         f.write(f"HBM-side traffic per kernel launch from rocprofv3 hardware counters, bench.py on {desc}, MI355X.\n"
-                "commands (one counter per run; 1 warm-up + 1 timed + 1 event-bracketed step):\n"
+                "commands (one counter per run; 1 warm-up + 1 timed + 1 untimed + 1 event-bracketed step):\n"
                 f"  {cmd.format(what='--pmc FETCH_SIZE', name='fetch', steps=1, extra='')}\n"
                 f"  {cmd.format(what='--pmc WRITE_SIZE', name='write', steps=1, extra='')}\n"
                 f"summary written by: python -m paper_2406_17611_amd.profile_summary {workload} <out>\n"

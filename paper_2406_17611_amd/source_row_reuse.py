@@ -20,7 +20,8 @@ from . import synth
 CACHE_MB = (0.5, 1, 2, 4, 8, 16, 64, 256)
 
 
-def reuse_table(w: synth.Workload, p: int, width: int, ratio: int, elem_bytes: int) -> list[str]:
+def reuse_counts(w: synth.Workload, p: int, width: int, ratio: int, elem_bytes: int) -> dict:
+    """Per distinct source row of partition p: references and bytes; plus the entry count and the local share."""
     g, part = w.graph, np.asarray(w.part)
     rows = np.nonzero(part == p)[0]
     lens = (g.rowptr[rows + 1] - g.rowptr[rows]).astype(np.int64)
@@ -32,11 +33,17 @@ def reuse_table(w: synth.Workload, p: int, width: int, ratio: int, elem_bytes: i
     local = part[src] == p
     k = max(1, width // ratio)
     row_bytes = np.where(local, width * elem_bytes, k * elem_bytes).astype(np.int64)
-    streaming = int((refs * row_bytes).sum())
-    out = [f"workload {w.name}, partition {p} of {w.n_parts}, width {width}, k {k}, {elem_bytes} bytes per element",
-           f"entries {total} ({100.0 * local[np.searchsorted(src, cols)].mean():.1f} % refer to local rows), "
-           f"distinct source rows {len(src)} ({int(local.sum())} local, {int((~local).sum())} halo)",
-           f"source-row bytes: {streaming / 1e9:.3f} GB with one fetch per entry, {row_bytes.sum() / 1e9:.3f} GB with one "
+    return {"entries": total, "local_entries": int(refs[local].sum()), "k": k, "refs": refs, "row_bytes": row_bytes,
+            "local": local, "per_entry_bytes": int((refs * row_bytes).sum()), "per_row_bytes": int(row_bytes.sum())}
+
+
+def reuse_table(w: synth.Workload, p: int, width: int, ratio: int, elem_bytes: int) -> list[str]:
+    c = reuse_counts(w, p, width, ratio, elem_bytes)
+    refs, row_bytes, local, streaming = c["refs"], c["row_bytes"], c["local"], c["per_entry_bytes"]
+    out = [f"workload {w.name}, partition {p} of {w.n_parts}, width {width}, k {c['k']}, {elem_bytes} bytes per element",
+           f"entries {c['entries']} ({100.0 * c['local_entries'] / max(1, c['entries']):.1f} % refer to local rows), "
+           f"distinct source rows {len(refs)} ({int(local.sum())} local, {int((~local).sum())} halo)",
+           f"source-row bytes: {streaming / 1e9:.3f} GB with one fetch per entry, {c['per_row_bytes'] / 1e9:.3f} GB with one "
            f"fetch per row",
            f"references per source row: median {int(np.median(refs))}, 90 % {int(np.quantile(refs, .9))}, "
            f"99 % {int(np.quantile(refs, .99))}, 99.9 % {int(np.quantile(refs, .999))}, max {int(refs.max())}",

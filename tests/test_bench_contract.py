@@ -45,3 +45,30 @@ def test_kernel_sources_hash_follows_the_sources(tmp_path, monkeypatch):
     with open(pkg / "csrc" / "elem.h", "a") as f:
         f.write("// changed\n")
     assert ps.kernel_sources_hash() != h
+
+
+def test_source_row_reuse_counts_match_a_direct_count():
+    """The reuse count's totals against a plain loop over one partition's rows of the smallest workload."""
+    import numpy as np
+    from paper_2406_17611_amd import source_row_reuse, synth
+
+    w = synth.make_workload("tiny")
+    width, ratio, p = 16, 4, 0
+    g, part = w.graph, np.asarray(w.part)
+    per_entry, entries, local_entries = 0, 0, 0
+    seen = {}
+    for i in np.nonzero(part == p)[0]:
+        for c in g.colidx[g.rowptr[i]:g.rowptr[i + 1]]:
+            b = (width if part[c] == p else width // ratio) * 4
+            per_entry += b
+            entries += 1
+            local_entries += int(part[c] == p)
+            seen[int(c)] = b
+    c = source_row_reuse.reuse_counts(w, p, width, ratio, 4)
+    assert (c["entries"], c["local_entries"]) == (entries, local_entries) and entries > 0
+    assert c["per_entry_bytes"] == per_entry and c["per_row_bytes"] == sum(seen.values())
+    assert len(c["refs"]) == len(seen) and int(c["refs"].sum()) == entries
+    lines = source_row_reuse.reuse_table(w, p, width, ratio, 4)
+    assert f"distinct source rows {len(seen)} " in lines[1]
+    shares = [float(l.split()[-1]) for l in lines[6:]]
+    assert shares == sorted(shares) and all(0.0 <= s <= 1.0 for s in shares)
